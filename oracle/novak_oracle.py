@@ -1,0 +1,216 @@
+"""CPU oracle of the NOVAK per-parameter update step.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, by-eye-checkable statement of what one optimizer step computes, written from the
+paper's equations (section 4, Eq. 1-31; the ten-phase order of section 5.1 and Table 2).  It shares
+no code with the HIP path.  Nothing in the product may import it: only tests, the smoke check and
+the benchmark's cpu_baseline leg do.
+
+Arithmetic is IEEE double throughout.  `state_dtype=np.float32` (the default) rounds theta, m, v and
+the slow weights to fp32 once at the end of every step / sync, which is what "fp32 steps" means;
+`state_dtype=np.float64` gives the all-double trajectory used to separate algorithm from rounding.
+
+Readings taken where the paper is silent or inconsistent (each is a named switch or stated here):
+  * unrect_fallback: what the step is while rho_t < 5 (Eq. 8 only gives alpha_eff = alpha/(1-beta1^t)
+    and never says the sqrt(v_hat) denominator is dropped).  "adam_denom" keeps the denominator with
+    r_t = 1 (the paper's Eq. 24 taken literally); "sgdm" drops it (theta -= alpha*m_hat, the original
+    RAdam behaviour).
+  * The 1/(1-beta1^t) of Eq. 8 and the m_hat of Eq. 24 are the same bias correction; applied once.
+  * Lookahead "memory_efficient": slow_new = slow_0 + alpha_LA * (1/k) * sum_{i=1..k}(theta_i - slow_0),
+    the mean over ALL k fast iterates of the window (Theorem 6.2 proof, text under Eq. 29, section
+    7.2).  The literal Eq. 29 (sum of negated single-step updates) contradicts Eq. 30's 1/k and the
+    four restatements, and is not used.  "basic" is standard Lookahead: slow_0 + alpha_LA*(theta_k - slow_0).
+  * Sync happens after the steps with t mod k == 0, t counted from 1; the window starts at theta_0.
+    A sync does not touch m or v.
+  * decoupled_decay = False is listed by the paper with no formula; read as classic coupled L2,
+    g <- g + lambda*theta before everything else.  parity unpinned by the paper (pinned only against
+    torch.optim.Adam's weight_decay semantics).
+  * beta_n has no default in the paper.  parity unpinned by the paper for its value; callers pass it.
+  * nesterov "true": the gradient handed in is already the one evaluated at the extrapolated point
+    (Eq. 10-11 need a model); the moment pipeline of Eq. 24 then runs as for "none".
+  * nesterov "classical": Eq. 16 literally (blend of un-normalised m_hat with the normalised u).
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+
+NESTEROV_MODES = ("none", "approx", "classical", "true")
+LOOKAHEAD_MODES = ("none", "memory_efficient", "basic")
+UNRECT_FALLBACKS = ("adam_denom", "sgdm")
+
+
+@dataclass
+class Hyper:
+    """Hyper-parameters of Algorithm 1's header (section 5.2)."""
+    lr: float = 1e-3
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    weight_decay: float = 0.0
+    beta_n: float = 0.9
+    la_alpha: float = 0.5
+    la_k: int = 5
+    rectified: bool = True
+    decoupled_decay: bool = True
+    nesterov: str = "approx"
+    lookahead: str = "memory_efficient"
+    unrect_fallback: str = "adam_denom"
+
+    def __post_init__(self):
+        assert self.nesterov in NESTEROV_MODES
+        assert self.lookahead in LOOKAHEAD_MODES
+        assert self.unrect_fallback in UNRECT_FALLBACKS
+
+
+@dataclass
+class StepScalars:
+    """Per-step scalars shared by every element (Phases 5-6)."""
+    bc1: float          # 1 - beta1^t            (Eq. 5)
+    bc2: float          # 1 - beta2^t            (Eq. 5)
+    rho_inf: float      # Eq. 6
+    rho_t: float        # Eq. 7
+    rectified_now: bool  # rho_t >= 5 and rectification enabled
+    r_t: float          # Eq. 9, or 1 when not rectified_now
+    denom_on: bool      # whether u carries the sqrt(v_hat)+eps denominator
+    step_size: float    # alpha * r_t            (Eq. 24a with lambda_trust = alpha_auto = 1)
+    decay: float        # 1 - alpha*lambda       (Eq. 18), or 1 when decay is coupled
+
+
+def one_minus_pow(beta: float, t: int) -> float:
+    """1 - beta^t, through the logarithm as section 5.8 prescribes: 1 - exp(t*log(beta))."""
+    if beta == 0.0:
+        return 1.0
+    return -math.expm1(t * math.log(beta))
+
+
+def step_scalars(h: Hyper, t: int) -> StepScalars:
+    """Scalars of step t (t = 1 on the first step; Eq. 5 is undefined at t = 0)."""
+    assert t >= 1
+    bc1 = one_minus_pow(h.beta1, t)
+    bc2 = one_minus_pow(h.beta2, t)
+    rho_inf = 2.0 / (1.0 - h.beta2) - 1.0                                  # Eq. 6
+    beta2_t = 1.0 - bc2
+    rho_t = rho_inf - 2.0 * t * beta2_t / bc2                              # Eq. 7
+    r_t, rect_now, denom_on = 1.0, False, True
+    if h.rectified:
+        if rho_t >= 5.0:                                                   # Eq. 8, first case
+            rect_now = True
+            r_t = math.sqrt((rho_t - 4.0) * (rho_t - 2.0) * rho_inf /
+                            ((rho_inf - 4.0) * (rho_inf - 2.0) * rho_t))   # Eq. 9
+        else:                                                              # Eq. 8, second case
+            denom_on = (h.unrect_fallback == "adam_denom")
+    decay = 1.0 - h.lr * h.weight_decay if h.decoupled_decay else 1.0      # Eq. 18
+    return StepScalars(bc1, bc2, rho_inf, rho_t, rect_now, r_t, denom_on, h.lr * r_t, decay)
+
+
+@dataclass
+class TensorState:
+    """State of one parameter tensor (Table 3): theta, m, v and the lookahead window."""
+    theta: np.ndarray
+    m: np.ndarray
+    v: np.ndarray
+    slow0: Optional[np.ndarray] = None                 # theta_0^slow of the open window (Eq. 28)
+    window: List[np.ndarray] = field(default_factory=list)   # the fast iterates of the open window
+
+    @property
+    def dtype(self):
+        return self.theta.dtype
+
+
+def init_state(theta0: np.ndarray, h: Hyper, state_dtype=np.float32) -> TensorState:
+    """m_0 = v_0 = 0; with lookahead on, slow weights start at theta_0 (Eq. 28, section 5.8)."""
+    theta = np.array(theta0, dtype=state_dtype).reshape(-1).copy()
+    st = TensorState(theta, np.zeros_like(theta), np.zeros_like(theta))
+    if h.lookahead != "none":
+        st.slow0 = theta.copy()
+    return st
+
+
+def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper) -> StepScalars:
+    """One update of one tensor at step t (Phases 2-9), then record the iterate for lookahead.
+
+    `grad` holds the gradient values (any float dtype; bf16 gradients arrive as the fp32/fp64
+    numbers they exactly represent).  The sync of Phase 10 is a separate call: `lookahead_sync`.
+    """
+    s = step_scalars(h, t)
+    dt = st.dtype
+    theta = st.theta.astype(np.float64)
+    m_prev = st.m.astype(np.float64)
+    v_prev = st.v.astype(np.float64)
+    g = np.asarray(grad).reshape(-1).astype(np.float64)
+
+    if (not h.decoupled_decay) and h.weight_decay != 0.0:
+        g = g + h.weight_decay * theta                      # coupled L2 (reading; see header)
+    if h.nesterov == "approx":
+        g = g + h.beta_n * (g - m_prev)                     # Eq. 13; replaces g for both moments
+    m = h.beta1 * m_prev + (1.0 - h.beta1) * g              # Eq. 1
+    v = h.beta2 * v_prev + (1.0 - h.beta2) * g * g          # Eq. 2
+    m_hat = m / s.bc1                                       # Eq. 5
+    if s.denom_on:
+        v_hat = v / s.bc2                                   # Eq. 5
+        u = m_hat / (np.sqrt(v_hat) + h.eps)                # Eq. 17
+    else:
+        u = m_hat                                           # momentum-SGD fallback while rho_t < 5
+    if h.nesterov == "classical":
+        u = h.beta1 * m_hat + (1.0 - h.beta1) * u           # Eq. 16
+    theta = theta * s.decay - s.step_size * u               # Eq. 18 then Eq. 24
+
+    st.theta = theta.astype(dt)
+    st.m = m.astype(dt)
+    st.v = v.astype(dt)
+    if h.lookahead != "none":
+        st.window.append(st.theta.copy())
+    return s
+
+
+def sync_due(t: int, h: Hyper) -> bool:
+    """Phase 10: synchronise after the steps with t mod k == 0."""
+    return h.lookahead != "none" and t % h.la_k == 0
+
+
+def lookahead_sync(st: TensorState, h: Hyper) -> None:
+    """Eq. 30-31 at the end of a k-step window, from the stored iterates (the plain definition)."""
+    assert h.lookahead != "none"
+    assert len(st.window) == h.la_k, "sync is defined at the end of a full window"
+    slow0 = st.slow0.astype(np.float64)
+    if h.lookahead == "memory_efficient":
+        delta = np.zeros_like(slow0)
+        for th in st.window:                                # Delta = sum_i (theta_i - slow_0)
+            delta += th.astype(np.float64) - slow0
+        slow_new = slow0 + h.la_alpha * delta / h.la_k      # Eq. 30
+    else:                                                   # "basic": standard Lookahead
+        slow_new = slow0 + h.la_alpha * (st.window[-1].astype(np.float64) - slow0)
+    st.theta = slow_new.astype(st.dtype)                    # Eq. 31
+    st.slow0 = st.theta.copy()                              # new reference point, Delta reset
+    st.window = []
+
+
+def blend_buffer(st: TensorState, h: Hyper) -> np.ndarray:
+    """(1-alpha_LA)*slow_0 + (alpha_LA/k)*sum of the window's iterates so far, in double.
+
+    Not part of the method: an observable of the stored window that equals Eq. 30's right-hand side
+    once the window is full.  Tests use it to check single-buffer running-blend implementations.
+    """
+    slow0 = st.slow0.astype(np.float64)
+    acc = (1.0 - h.la_alpha) * slow0
+    for th in st.window:
+        acc = acc + (h.la_alpha / h.la_k) * th.astype(np.float64)
+    return acc
+
+
+def run(theta0_list, grads_fn, steps: int, h: Hyper, state_dtype=np.float32, t0: int = 0,
+        states: Optional[List[TensorState]] = None) -> List[TensorState]:
+    """Run `steps` steps over a list of tensors; grads_fn(t) returns the gradient list of step t."""
+    if states is None:
+        states = [init_state(th, h, state_dtype) for th in theta0_list]
+    for t in range(t0 + 1, t0 + steps + 1):
+        grads = grads_fn(t)
+        for st, g in zip(states, grads):
+            step(st, g, t, h)
+        if sync_due(t, h):
+            for st in states:
+                lookahead_sync(st, h)
+    return states
