@@ -1,0 +1,215 @@
+/*
+ * novak.h - C ABI of the MI355X (gfx950) implementation of the NOVAK optimizer's fused update step.
+ *
+ * What the library computes, per parameter element and per step t (t = 1 on the first step), in
+ * the paper's notation (section 4; phase order of section 5.1 / Table 2):
+ *
+ *   g~  = g + beta_n (g - m_{t-1})                         Nesterov approximation       (Eq. 13)
+ *   m_t = beta1 m_{t-1} + (1-beta1) g~                     first moment                 (Eq. 1)
+ *   v_t = beta2 v_{t-1} + (1-beta2) g~^2                   second moment                (Eq. 2)
+ *   m^  = m_t / (1-beta1^t),  v^ = v_t / (1-beta2^t)       bias correction              (Eq. 5)
+ *   u   = m^ / (sqrt(v^) + eps)                            update direction             (Eq. 17)
+ *   u   = beta1 m^ + (1-beta1) u                           classical Nesterov blend     (Eq. 16)
+ *   theta_t = theta_{t-1} (1 - alpha lambda) - alpha r_t u decoupled decay, then update (Eq. 18, 24, 24a)
+ *
+ * with the rectification schedule rho_inf, rho_t, r_t of Eq. 6-9 computed once per step on the
+ * host in double precision, and the lookahead slow-weight synchronisation of section 4.7 every
+ * la_k steps (Eq. 28-31; the averaging form stated in the proof of Theorem 6.2).
+ *
+ * All tensor memory is DEVICE memory owned by the caller (fp32, contiguous).  The library owns only
+ * the handle, its chunk table and a small gradient-pointer table.  Every call returns a status
+ * code; nothing throws or aborts across this boundary.  Calls on one handle must not overlap.
+ * Kernels are enqueued on the HIP stream the caller passes and return without synchronising.
+ */
+#ifndef NOVAK_H_
+#define NOVAK_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct novak_handle novak_handle;
+
+/* ---- status codes ------------------------------------------------------------------------- */
+enum {
+  NOVAK_OK = 0,
+  NOVAK_ERR_INVALID_ARG = 1,      /* a hyper-parameter breaks a rule of section 5.8 / 7.3, or a bad size */
+  NOVAK_ERR_NULL_POINTER = 2,     /* a required pointer is NULL */
+  NOVAK_ERR_MISALIGNED = 3,       /* a tensor pointer is not aligned to its element size */
+  NOVAK_ERR_BAD_STEP = 4,         /* step < 1, or not last step + 1 on this handle */
+  NOVAK_ERR_STATE = 5,            /* call not legal now (sync not due / sync pending / no lookahead) */
+  NOVAK_ERR_HIP = 6,              /* a HIP runtime call failed; see novak_last_error() */
+  NOVAK_ERR_NOT_IMPLEMENTED = 7,  /* a feature outside the update step was requested */
+  NOVAK_ERR_NO_MEMORY = 8
+};
+
+/* ---- enumerations of Algorithm 1's header (section 5.2) -------------------------------------- */
+enum { NOVAK_NESTEROV_NONE = 0, NOVAK_NESTEROV_APPROX = 1, NOVAK_NESTEROV_CLASSICAL = 2, NOVAK_NESTEROV_TRUE = 3 };
+enum { NOVAK_LOOKAHEAD_NONE = 0, NOVAK_LOOKAHEAD_MEMORY_EFFICIENT = 1, NOVAK_LOOKAHEAD_BASIC = 2 };
+/* What a step is while rho_t < 5 (Eq. 8 is silent about the denominator):
+ * ADAM_DENOM keeps u = m^/(sqrt(v^)+eps) with r_t = 1; SGDM uses u = m^ (original RAdam). */
+enum { NOVAK_UNRECT_ADAM_DENOM = 0, NOVAK_UNRECT_SGDM = 1 };
+/* Dual-mode control of section 7.1: FAST is the paper's fast path, RESEARCH its full-features mode. */
+enum { NOVAK_MODE_FAST = 0, NOVAK_MODE_RESEARCH = 1 };
+enum { NOVAK_GRAD_F32 = 0, NOVAK_GRAD_BF16 = 1 };
+
+/* warning bits reported by novak_validate_hparams / novak_get_info (section 7.3: downgrades warn) */
+enum {
+  NOVAK_WARN_TRUE_NESTEROV_DOWNGRADED = 1u << 0,  /* FAST + TRUE        -> APPROX           */
+  NOVAK_WARN_LOOKAHEAD_DOWNGRADED = 1u << 1       /* FAST + BASIC       -> MEMORY_EFFICIENT */
+};
+
+/* ---- hyper-parameters (host memory, plain data) -------------------------------------------------
+ * Rules checked (section 5.8 "Hyperparameter validation", section 7.3): lr > 0; beta1, beta2 in
+ * [0,1); weight_decay >= 0; beta_n in [0,1); la_k >= 1; eps > 0; beta2 < 1 - 1e-8 when rectified;
+ * la_alpha in (0,1] when lookahead is on (the paper's open bound at 1 is relaxed so that the
+ * alpha_LA = 1 fixed point can be exercised).  All values must be finite. */
+typedef struct novak_hparams {
+  size_t struct_size;      /* sizeof(novak_hparams); guards against layout mismatch */
+  double lr;               /* alpha   */
+  double beta1, beta2;     /* moment decay rates */
+  double eps;              /* epsilon, added outside the root (Eq. 17) */
+  double weight_decay;     /* lambda  */
+  double beta_n;           /* Nesterov coefficient of Eq. 13 (no default in the paper) */
+  double la_alpha;         /* alpha_LA */
+  int32_t la_k;            /* k: steps per lookahead window */
+  int32_t rectified;       /* 0/1: RAdam rectification (Eq. 6-9) */
+  int32_t decoupled_decay; /* 1: Eq. 18; 0: classic L2, g <- g + lambda*theta (a reading; paper gives no formula) */
+  int32_t nesterov_mode;   /* NOVAK_NESTEROV_*; TRUE means `grads` were evaluated at theta + beta_n m (Eq. 10-11) by the caller */
+  int32_t lookahead_mode;  /* NOVAK_LOOKAHEAD_* */
+  int32_t unrect_fallback; /* NOVAK_UNRECT_* */
+  int32_t mode;            /* NOVAK_MODE_* */
+  int32_t auto_sync;       /* 1: novak_step performs the sync itself, fused into the k-th step's pass */
+} novak_hparams;
+
+/* One parameter tensor.  All pointers are DEVICE pointers to contiguous fp32 arrays of `numel`
+ * elements, 4-byte aligned (16-byte alignment of every pointer selects the 128-bit path; any other
+ * alignment is handled element-wise).  They must stay valid and fixed until novak_destroy, and no
+ * two arrays may overlap.  numel == 0 is allowed.
+ *   la_buf: the single lookahead buffer; required unless lookahead is NONE.
+ *     MEMORY_EFFICIENT: running blend (1-alpha_LA)*slow_0 + (alpha_LA/k)*sum of the window's iterates,
+ *       which equals Eq. 30's right-hand side when the window is full (one buffer instead of the
+ *       Delta + theta_0^slow pair of Table 3).
+ *     BASIC: the slow weights theta^slow. */
+typedef struct novak_tensor_desc {
+  void *param;       /* theta, updated in place   */
+  void *exp_avg;     /* m, updated in place       */
+  void *exp_avg_sq;  /* v, updated in place       */
+  void *la_buf;      /* see above; may be NULL when lookahead is NONE */
+  int64_t numel;
+} novak_tensor_desc;
+
+/* Per-step scalars (Phases 5-6), as the host prologue computes them in double. */
+typedef struct novak_step_scalars {
+  double bc1, bc2;         /* 1-beta1^t, 1-beta2^t via -expm1(t log beta) (section 5.8) */
+  double rho_inf, rho_t;   /* Eq. 6, 7 */
+  double r_t;              /* Eq. 9, or 1 when rectification is off or rho_t < 5 */
+  double step_size;        /* alpha * r_t (Eq. 24a with lambda_trust = alpha_auto = 1) */
+  double decay;            /* 1 - alpha*lambda (Eq. 18), or 1 with coupled decay */
+  int32_t rectified_now;   /* rectified && rho_t >= 5 */
+  int32_t denom_on;        /* 0 only in the SGDM fallback while rho_t < 5 */
+} novak_step_scalars;
+
+/* One entry of the multi-tensor chunk table: `len` elements of tensor `tensor` starting at `offset`. */
+typedef struct novak_chunk {
+  int64_t offset;
+  int32_t tensor;
+  int32_t len;
+} novak_chunk;
+
+typedef struct novak_info {
+  size_t struct_size;
+  int32_t nesterov_mode;     /* effective, after the fast-path downgrade */
+  int32_t lookahead_mode;    /* effective */
+  uint32_t warnings;         /* NOVAK_WARN_* */
+  int32_t n_tensors;
+  int64_t n_chunks;
+  int64_t chunk_elems;
+  int64_t total_numel;
+  int64_t last_step;         /* 0 before the first step on this handle */
+  int32_t sync_due;          /* 1 between a k-th step and its novak_lookahead_sync (auto_sync off) */
+  int32_t device_id;
+} novak_info;
+
+/* tuning keys for novak_set_tuning */
+enum {
+  NOVAK_TUNE_CHUNK_ELEMS = 0,   /* elements per chunk-table entry; multiple of 1024, 1024..2^24 */
+  NOVAK_TUNE_NONTEMPORAL = 1    /* 0/1: non-temporal hints on the streaming loads and stores */
+};
+
+/* ---- host-only helpers (no GPU needed) -------------------------------------------------------- */
+
+/* Validates `hp` by the rules above and writes the effective hyper-parameters (after the fast-path
+ * downgrades of section 7.3) to `effective` and the NOVAK_WARN_* bits to `warnings` (either may be
+ * NULL).  Returns NOVAK_OK, NOVAK_ERR_NULL_POINTER or NOVAK_ERR_INVALID_ARG; RESEARCH-mode features
+ * outside the update step are not representable in novak_hparams, so nothing maps to
+ * NOT_IMPLEMENTED here. */
+int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, uint32_t *warnings);
+
+/* Scalars of step `step` (>= 1) for validated hyper-parameters (Eq. 5-9, 18, 24a).  Host memory. */
+int novak_compute_step_scalars(const novak_hparams *hp, int64_t step, novak_step_scalars *out);
+
+/* Cuts tensors of `numels[i]` elements into chunks of at most `chunk_elems` elements, in tensor
+ * order; a chunk never spans two tensors and empty tensors produce none.  Writes up to `capacity`
+ * entries to `out` (may be NULL with capacity 0 to query) and the total count to `n_chunks`. */
+int novak_plan_chunks(const int64_t *numels, int32_t n_tensors, int64_t chunk_elems,
+                      novak_chunk *out, int64_t capacity, int64_t *n_chunks);
+
+/* Algorithmic HBM bytes per parameter of one step (section 5.5: 4 streams read + 3 written, 4 B
+ * each; gradients 2 B when bf16; plus the lookahead buffer traffic of that step).  `window_pos` is
+ * the step's 1-based position in its lookahead window (ignored when lookahead is NONE);
+ * `fused_sync` says whether the k-th step also performs the sync. */
+double novak_bytes_per_param_step(int32_t lookahead_mode, int32_t grad_dtype, int32_t la_k,
+                                  int32_t window_pos, int32_t fused_sync);
+/* Algorithmic bytes per parameter of the separate sync kernel. */
+double novak_bytes_per_param_sync(int32_t lookahead_mode);
+
+const char *novak_status_string(int status);
+
+/* ---- device entry points ---------------------------------------------------------------------- */
+
+/* Validates and downgrades `hp`, checks every descriptor, builds the chunk table and uploads it to
+ * device `device_id`.  Allocates no parameter-sized memory and launches no kernel.  `tensors` is
+ * host memory and is copied.  n_tensors >= 0.  On failure *out is NULL. */
+int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor_desc *tensors,
+                 int32_t n_tensors, int32_t device_id);
+
+/* Eq. 28: writes the initial lookahead state from the current theta (la_buf <- theta) for every
+ * tensor.  Call once at the start of training; not when resuming with preserved buffers.
+ * NOVAK_ERR_STATE when lookahead is NONE. */
+int novak_lookahead_init(novak_handle *h, void *hip_stream);
+
+/* One optimizer step (Phases 2-9 and the lookahead accumulation of Phase 10) for all tensors in one
+ * kernel launch.  `grads` is a HOST array of n_tensors DEVICE pointers to the gradients (fp32, or
+ * bf16 bit patterns when grad_dtype is NOVAK_GRAD_BF16), contiguous, numel elements each, aligned
+ * to the element size.  `step` is t, 1-based; on a fresh handle any t >= 1 is accepted (resume),
+ * afterwards it must be the previous step + 1.  With lookahead on and auto_sync off, the step with
+ * t mod k == 0 leaves the handle in "sync due" state and the next call must be
+ * novak_lookahead_sync; with auto_sync on, that step applies Eq. 30-31 itself. */
+int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t step, void *hip_stream);
+
+/* Eq. 30-31 over all tensors in one launch: theta <- slow_new, and the buffer is left equal to the
+ * new slow weights.  Legal only when a sync is due. */
+int novak_lookahead_sync(novak_handle *h, void *hip_stream);
+
+/* Frees the handle and its tables (waits for nothing: the caller synchronises its stream first).
+ * NULL is a no-op. */
+int novak_destroy(novak_handle *h);
+
+int novak_get_info(const novak_handle *h, novak_info *info);
+
+/* Adjusts a launch parameter (NOVAK_TUNE_*); rebuilds the chunk table when needed.  Results do not
+ * depend on tuning values. */
+int novak_set_tuning(novak_handle *h, int32_t key, int64_t value);
+
+/* Text of the most recent failure on this handle (or of the last failed novak_create on this
+ * thread when h is NULL).  Never NULL; valid until the next call on the same handle/thread. */
+const char *novak_last_error(const novak_handle *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NOVAK_H_ */

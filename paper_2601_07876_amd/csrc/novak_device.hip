@@ -1,0 +1,650 @@
+// Device part of the NOVAK update-step library for gfx950 (MI355X): the fused single-pass update
+// kernel over a multi-tensor chunk table, the lookahead sync / init kernels, and the C entry
+// points that launch them.
+//
+// The step is HBM-bound (section 5.5 of the paper: 4 streams read, 3 written per element, a few
+// dozen flops), so the kernel is built around memory streams, not arithmetic:
+//   * one workgroup (4 wave64) per chunk-table entry; a chunk never spans tensors;
+//   * each lane moves 128 bits per stream per access (4 fp32; 4 bf16 gradients = 64 bits), four
+//     accesses per stream are issued back to back before any arithmetic so that ~16 KB per wave
+//     are in flight;
+//   * per-step scalars arrive as kernel arguments (SGPRs); nothing is read from memory except the
+//     chunk entry, five base pointers and the streams themselves;
+//   * streams are touched exactly once per step, so loads and stores may carry non-temporal hints.
+// Arithmetic is IEEE fp32 with explicit FMAs (compiled with -ffp-contract=off, no fast-math);
+// square root and division are the correctly rounded ones.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "novak_internal.h"
+
+namespace {
+
+constexpr int kBlock = 256;   // 4 wave64 per workgroup
+constexpr int kUnroll = 4;    // independent 128-bit accesses per stream in flight per lane
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+
+// lookahead work done inside the step kernel (which extra stream is read / written)
+enum : int {
+  LA_OFF = 0,          // no lookahead traffic in this step
+  LA_FIRST = 1,        // first step of a window:  A  = c0*theta_in + c1*theta_new      (A written)
+  LA_MID = 2,          // later steps:             A += c1*theta_new                    (A read, written)
+  LA_LAST_FUSED = 3,   // k-th step, sync fused:   theta_out = A + c1*theta_new         (A read)
+  LA_BASIC_FUSED = 4   // k-th step, basic mode:   S = c1*theta_new + c0*S; theta_out=S (S read, written)
+};
+
+enum : uint32_t { F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u };
+
+struct Tables {
+  const novak_chunk *chunks;
+  float *const *param;
+  float *const *m;
+  float *const *v;
+  float *const *la;
+  const void *const *grad;
+};
+
+// Per-step scalars, rounded once from the host's double values.
+struct Consts {
+  float omb1, omb2;      // 1-beta1, 1-beta2
+  float beta1, beta_n;
+  float inv_bc1, inv_bc2;
+  float eps;
+  float step_size;       // alpha * r_t
+  float lr_wd;           // alpha * lambda (decoupled) or 0
+  float wd;              // lambda (coupled) or 0
+  float la_c0, la_c1;    // lookahead blend coefficients (meaning depends on the LA phase)
+  uint32_t flags;
+};
+
+__device__ __forceinline__ float bf16_to_f32(unsigned short b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+
+// One element of the update.  `la` is the lookahead buffer value (read when the phase reads it,
+// returned updated when the phase writes it).
+template <int LA>
+__device__ __forceinline__ void update_one(float &th, float g, float &m, float &v, float &la, const Consts &c) {
+  const float th_in = th;
+  if (c.flags & F_COUPLED) g = __builtin_fmaf(c.wd, th_in, g);          // classic L2 reading
+  if (c.flags & F_APPROX) g = __builtin_fmaf(c.beta_n, g - m, g);       // Eq. 13
+  m = __builtin_fmaf(c.omb1, g - m, m);                                 // Eq. 1:  m + (1-b1)(g - m)
+  v = __builtin_fmaf(c.omb2, __builtin_fmaf(g, g, -v), v);              // Eq. 2:  v + (1-b2)(g^2 - v)
+  const float m_hat = m * c.inv_bc1;                                    // Eq. 5
+  float u = m_hat;
+  if (c.flags & F_DENOM) {
+    const float v_hat = v * c.inv_bc2;                                  // Eq. 5
+    u = m_hat / (__builtin_sqrtf(v_hat) + c.eps);                       // Eq. 17
+  }
+  if (c.flags & F_CLASSICAL) u = __builtin_fmaf(c.beta1, m_hat, c.omb1 * u);   // Eq. 16
+  // Eq. 18 + Eq. 24 in additive form: one rounding at theta's magnitude per step
+  const float th_new = th_in - __builtin_fmaf(c.step_size, u, c.lr_wd * th_in);
+  th = th_new;
+  if (LA == LA_FIRST) {
+    la = __builtin_fmaf(c.la_c1, th_new, c.la_c0 * th_in);
+  } else if (LA == LA_MID) {
+    la = __builtin_fmaf(c.la_c1, th_new, la);
+  } else if (LA == LA_LAST_FUSED) {
+    th = __builtin_fmaf(c.la_c1, th_new, la);                           // Eq. 30-31
+  } else if (LA == LA_BASIC_FUSED) {
+    la = __builtin_fmaf(c.la_c1, th_new, c.la_c0 * la);
+    th = la;
+  }
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ T ld(const T *p) {
+  if (NT) return __builtin_nontemporal_load(p);
+  return *p;
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void st(T *p, T x) {
+  if (NT) __builtin_nontemporal_store(x, p);
+  else *p = x;
+}
+
+template <typename GradV>
+__device__ __forceinline__ f32x4 grad_to_f32(GradV g);
+template <>
+__device__ __forceinline__ f32x4 grad_to_f32<f32x4>(f32x4 g) { return g; }
+template <>
+__device__ __forceinline__ f32x4 grad_to_f32<u16x4>(u16x4 g) {
+  f32x4 r;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) r[k] = bf16_to_f32(g[k]);
+  return r;
+}
+
+template <int LA>
+__device__ __forceinline__ void update_vec(f32x4 &th, f32x4 g, f32x4 &m, f32x4 &v, f32x4 &la, const Consts &c) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    float th_k = th[k], m_k = m[k], v_k = v[k], la_k = la[k];
+    update_one<LA>(th_k, g[k], m_k, v_k, la_k, c);
+    th[k] = th_k; m[k] = m_k; v[k] = v_k; la[k] = la_k;
+  }
+}
+
+constexpr bool la_reads(int la) { return la == LA_MID || la == LA_LAST_FUSED || la == LA_BASIC_FUSED; }
+constexpr bool la_writes(int la) { return la == LA_FIRST || la == LA_MID || la == LA_BASIC_FUSED; }
+
+// GradS: scalar gradient type (float or unsigned short holding bf16 bits); GradV its 4-vector.
+template <typename GradS, typename GradV, int LA, bool NT>
+__global__ __launch_bounds__(kBlock) void novak_step_kernel(Tables tb, Consts c) {
+  const novak_chunk ch = tb.chunks[blockIdx.x];
+  const int len = ch.len;
+  float *__restrict__ th_p = tb.param[ch.tensor] + ch.offset;
+  float *__restrict__ m_p = tb.m[ch.tensor] + ch.offset;
+  float *__restrict__ v_p = tb.v[ch.tensor] + ch.offset;
+  const GradS *__restrict__ g_p = static_cast<const GradS *>(tb.grad[ch.tensor]) + ch.offset;
+  float *__restrict__ la_p = nullptr;
+  if (LA != LA_OFF) la_p = tb.la[ch.tensor] + ch.offset;
+
+  uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) |
+                   reinterpret_cast<uintptr_t>(v_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
+  mis |= reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1);
+
+  int done = 0;   // elements [0, done) handled by the vector path
+  if (mis == 0) {
+    const int nvec = len >> 2;
+    const f32x4 *th4 = reinterpret_cast<const f32x4 *>(th_p);
+    const f32x4 *m4 = reinterpret_cast<const f32x4 *>(m_p);
+    const f32x4 *v4 = reinterpret_cast<const f32x4 *>(v_p);
+    const f32x4 *la4 = reinterpret_cast<const f32x4 *>(la_p);
+    const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
+    int i = threadIdx.x;
+    for (; i + (kUnroll - 1) * kBlock < nvec; i += kUnroll * kBlock) {
+      f32x4 th[kUnroll], m[kUnroll], v[kUnroll], la[kUnroll];
+      GradV g[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int j = i + u * kBlock;
+        th[u] = ld<NT>(th4 + j);
+        g[u] = ld<NT>(g4 + j);
+        m[u] = ld<NT>(m4 + j);
+        v[u] = ld<NT>(v4 + j);
+        if (la_reads(LA)) la[u] = ld<NT>(la4 + j);
+      }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int j = i + u * kBlock;
+        update_vec<LA>(th[u], grad_to_f32<GradV>(g[u]), m[u], v[u], la[u], c);
+        st<NT>(const_cast<f32x4 *>(th4) + j, th[u]);
+        st<NT>(const_cast<f32x4 *>(m4) + j, m[u]);
+        st<NT>(const_cast<f32x4 *>(v4) + j, v[u]);
+        if (la_writes(LA)) st<NT>(const_cast<f32x4 *>(la4) + j, la[u]);
+      }
+    }
+    for (; i < nvec; i += kBlock) {
+      f32x4 th = ld<NT>(th4 + i), m = ld<NT>(m4 + i), v = ld<NT>(v4 + i), la;
+      GradV g = ld<NT>(g4 + i);
+      if (la_reads(LA)) la = ld<NT>(la4 + i);
+      update_vec<LA>(th, grad_to_f32<GradV>(g), m, v, la, c);
+      st<NT>(const_cast<f32x4 *>(th4) + i, th);
+      st<NT>(const_cast<f32x4 *>(m4) + i, m);
+      st<NT>(const_cast<f32x4 *>(v4) + i, v);
+      if (la_writes(LA)) st<NT>(const_cast<f32x4 *>(la4) + i, la);
+    }
+    done = nvec << 2;
+  }
+  // element-wise path: the < 4 element tail of an aligned chunk, or a whole unaligned chunk
+  for (int i = done + threadIdx.x; i < len; i += kBlock) {
+    float th = th_p[i], m = m_p[i], v = v_p[i], la = 0.0f, g;
+    if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
+    else g = g_p[i];
+    if (la_reads(LA)) la = la_p[i];
+    update_one<LA>(th, g, m, v, la, c);
+    th_p[i] = th;
+    m_p[i] = m;
+    v_p[i] = v;
+    if (la_writes(LA)) la_p[i] = la;
+  }
+}
+
+// Lookahead kernels over the same chunk table.
+//   SYNC_ME:    theta <- A                       (A already holds Eq. 30's right-hand side)
+//   SYNC_BASIC: S <- c1*theta + c0*S; theta <- S (standard Lookahead interpolation)
+//   INIT:       buffer <- theta                  (Eq. 28)
+enum : int { SYNC_ME = 0, SYNC_BASIC = 1, LA_INIT = 2 };
+
+template <int OP>
+__device__ __forceinline__ void la_one(float &th, float &la, float c0, float c1) {
+  if (OP == SYNC_ME) th = la;
+  else if (OP == SYNC_BASIC) { la = __builtin_fmaf(c1, th, c0 * la); th = la; }
+  else la = th;
+}
+
+template <int OP, bool NT>
+__global__ __launch_bounds__(kBlock) void novak_lookahead_kernel(Tables tb, float c0, float c1) {
+  const novak_chunk ch = tb.chunks[blockIdx.x];
+  const int len = ch.len;
+  float *__restrict__ th_p = tb.param[ch.tensor] + ch.offset;
+  float *__restrict__ la_p = tb.la[ch.tensor] + ch.offset;
+  const uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
+  int done = 0;
+  if (mis == 0) {
+    const int nvec = len >> 2;
+    f32x4 *th4 = reinterpret_cast<f32x4 *>(th_p);
+    f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
+    for (int i = threadIdx.x; i < nvec; i += kBlock) {
+      f32x4 th, la;
+      if (OP != SYNC_ME) th = ld<NT>(th4 + i);
+      if (OP != LA_INIT) la = ld<NT>(la4 + i);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        float th_k = th[k], la_k = la[k];
+        la_one<OP>(th_k, la_k, c0, c1);
+        th[k] = th_k; la[k] = la_k;
+      }
+      if (OP != LA_INIT) st<NT>(th4 + i, th);
+      if (OP != SYNC_ME) st<NT>(la4 + i, la);
+    }
+    done = nvec << 2;
+  }
+  for (int i = done + threadIdx.x; i < len; i += kBlock) {
+    float th = 0.0f, la = 0.0f;
+    if (OP != SYNC_ME) th = th_p[i];
+    if (OP != LA_INIT) la = la_p[i];
+    la_one<OP>(th, la, c0, c1);
+    if (OP != LA_INIT) th_p[i] = th;
+    if (OP != SYNC_ME) la_p[i] = la;
+  }
+}
+
+thread_local std::string g_create_error = "";
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// handle
+// ------------------------------------------------------------------------------------------------
+struct novak_handle {
+  novak_hparams hp;                 // effective hyper-parameters
+  uint32_t warnings = 0;
+  int32_t device_id = 0;
+  std::vector<novak_tensor_desc> tensors;
+  std::vector<int64_t> numels;
+  int64_t total_numel = 0;
+  int64_t chunk_elems = NOVAK_CHUNK_DEFAULT;
+  int64_t n_chunks = 0;
+  int nontemporal = 1;
+  int64_t last_step = 0;
+  int sync_due = 0;
+  // device-side tables (owned)
+  novak_chunk *d_chunks = nullptr;
+  void *d_ptrs = nullptr;           // 5 arrays of n_tensors pointers: param, m, v, la, grad
+  // pinned staging ring for the per-step gradient pointer list
+  static constexpr int kRing = 4;
+  void **h_ring = nullptr;
+  hipEvent_t ring_ev[kRing] = {};
+  bool ring_used[kRing] = {};
+  int ring_next = 0;
+  std::vector<void *> last_grads;
+  bool grads_uploaded = false;
+  std::string error;
+};
+
+namespace {
+
+int fail(novak_handle *h, int status, const std::string &msg) {
+  if (h) h->error = msg;
+  else g_create_error = msg;
+  return status;
+}
+
+int fail_hip(novak_handle *h, hipError_t e, const char *what) {
+  return fail(h, NOVAK_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define NOVAK_HIP(h, call)                                   \
+  do {                                                       \
+    hipError_t e_ = (call);                                  \
+    if (e_ != hipSuccess) return fail_hip((h), e_, #call);   \
+  } while (0)
+
+// RAII: make the handle's device current for the duration of a call, then restore.
+struct DeviceScope {
+  int prev = -1;
+  bool switched = false;
+  hipError_t enter(int dev) {
+    hipError_t e = hipGetDevice(&prev);
+    if (e != hipSuccess) return e;
+    if (prev != dev) {
+      e = hipSetDevice(dev);
+      if (e != hipSuccess) return e;
+      switched = true;
+    }
+    return hipSuccess;
+  }
+  ~DeviceScope() {
+    if (switched) (void)hipSetDevice(prev);
+  }
+};
+
+Tables tables_of(const novak_handle *h) {
+  const size_t n = h->tensors.size();
+  char *base = static_cast<char *>(h->d_ptrs);
+  Tables tb;
+  tb.chunks = h->d_chunks;
+  tb.param = reinterpret_cast<float *const *>(base);
+  tb.m = reinterpret_cast<float *const *>(base + 1 * n * sizeof(void *));
+  tb.v = reinterpret_cast<float *const *>(base + 2 * n * sizeof(void *));
+  tb.la = reinterpret_cast<float *const *>(base + 3 * n * sizeof(void *));
+  tb.grad = reinterpret_cast<const void *const *>(base + 4 * n * sizeof(void *));
+  return tb;
+}
+
+void free_device_tables(novak_handle *h) {
+  if (h->d_chunks) (void)hipFree(h->d_chunks);
+  h->d_chunks = nullptr;
+}
+
+// (Re)build and upload the chunk table for the current chunk_elems.  Synchronous.
+int build_chunk_table(novak_handle *h) {
+  int64_t n = 0;
+  int rc = novak_plan_chunks(h->numels.data(), static_cast<int32_t>(h->numels.size()), h->chunk_elems, nullptr, 0, &n);
+  if (rc != NOVAK_OK) return fail(h, rc, "chunk planning failed");
+  if (n > 0x7fffffffLL) return fail(h, NOVAK_ERR_INVALID_ARG, "too many chunks for one launch; raise chunk_elems");
+  std::vector<novak_chunk> table(static_cast<size_t>(n));
+  rc = novak_plan_chunks(h->numels.data(), static_cast<int32_t>(h->numels.size()), h->chunk_elems, table.data(), n, &n);
+  if (rc != NOVAK_OK) return fail(h, rc, "chunk planning failed");
+  free_device_tables(h);
+  h->n_chunks = n;
+  if (n > 0) {
+    NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_chunks), static_cast<size_t>(n) * sizeof(novak_chunk)));
+    NOVAK_HIP(h, hipMemcpy(h->d_chunks, table.data(), static_cast<size_t>(n) * sizeof(novak_chunk), hipMemcpyHostToDevice));
+  }
+  return NOVAK_OK;
+}
+
+template <typename GradS, typename GradV, bool NT>
+void launch_step_la(int la, dim3 grid, hipStream_t s, const Tables &tb, const Consts &c) {
+  switch (la) {
+    case LA_OFF: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_OFF, NT>), grid, dim3(kBlock), 0, s, tb, c); break;
+    case LA_FIRST: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_FIRST, NT>), grid, dim3(kBlock), 0, s, tb, c); break;
+    case LA_MID: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_MID, NT>), grid, dim3(kBlock), 0, s, tb, c); break;
+    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_LAST_FUSED, NT>), grid, dim3(kBlock), 0, s, tb, c); break;
+    default: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_BASIC_FUSED, NT>), grid, dim3(kBlock), 0, s, tb, c); break;
+  }
+}
+
+void launch_step(int grad_dtype, bool nt, int la, dim3 grid, hipStream_t s, const Tables &tb, const Consts &c) {
+  if (grad_dtype == NOVAK_GRAD_BF16) {
+    if (nt) launch_step_la<unsigned short, u16x4, true>(la, grid, s, tb, c);
+    else launch_step_la<unsigned short, u16x4, false>(la, grid, s, tb, c);
+  } else {
+    if (nt) launch_step_la<float, f32x4, true>(la, grid, s, tb, c);
+    else launch_step_la<float, f32x4, false>(la, grid, s, tb, c);
+  }
+}
+
+template <int OP>
+void launch_la(bool nt, dim3 grid, hipStream_t s, const Tables &tb, float c0, float c1) {
+  if (nt) hipLaunchKernelGGL((novak_lookahead_kernel<OP, true>), grid, dim3(kBlock), 0, s, tb, c0, c1);
+  else hipLaunchKernelGGL((novak_lookahead_kernel<OP, false>), grid, dim3(kBlock), 0, s, tb, c0, c1);
+}
+
+int launch_sync(novak_handle *h, hipStream_t s) {
+  if (h->n_chunks == 0) return NOVAK_OK;
+  const Tables tb = tables_of(h);
+  const dim3 grid(static_cast<unsigned>(h->n_chunks));
+  if (h->hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT) {
+    launch_la<SYNC_ME>(h->nontemporal != 0, grid, s, tb, 0.0f, 0.0f);
+  } else {
+    const float c1 = static_cast<float>(h->hp.la_alpha);
+    const float c0 = static_cast<float>(1.0 - h->hp.la_alpha);
+    launch_la<SYNC_BASIC>(h->nontemporal != 0, grid, s, tb, c0, c1);
+  }
+  NOVAK_HIP(h, hipGetLastError());
+  return NOVAK_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// entry points
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor_desc *tensors, int32_t n_tensors,
+                 int32_t device_id) {
+  if (!out) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "out is NULL");
+  *out = nullptr;
+  if (!hp) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "hp is NULL");
+  if (n_tensors < 0) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "n_tensors < 0");
+  if (n_tensors > 0 && !tensors) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "tensors is NULL");
+  if (device_id < 0) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "device_id < 0");
+  novak_hparams eff;
+  uint32_t warn = 0;
+  int rc = novak_validate_hparams(hp, &eff, &warn);
+  if (rc != NOVAK_OK) return fail(nullptr, rc, "hyper-parameters rejected (section 5.8 validation rules)");
+  for (int32_t i = 0; i < n_tensors; ++i) {
+    const novak_tensor_desc &d = tensors[i];
+    if (d.numel < 0) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "tensor " + std::to_string(i) + ": numel < 0");
+    if (d.numel == 0) continue;
+    if (!d.param || !d.exp_avg || !d.exp_avg_sq) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "tensor " + std::to_string(i) + ": param/exp_avg/exp_avg_sq is NULL");
+    if (eff.lookahead_mode != NOVAK_LOOKAHEAD_NONE && !d.la_buf) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "tensor " + std::to_string(i) + ": la_buf is NULL with lookahead on");
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(d.param) | reinterpret_cast<uintptr_t>(d.exp_avg) |
+                           reinterpret_cast<uintptr_t>(d.exp_avg_sq) | reinterpret_cast<uintptr_t>(d.la_buf);
+    if (bits & 3u) return fail(nullptr, NOVAK_ERR_MISALIGNED, "tensor " + std::to_string(i) + ": pointer not 4-byte aligned");
+  }
+
+  novak_handle *h = new (std::nothrow) novak_handle();
+  if (!h) return fail(nullptr, NOVAK_ERR_NO_MEMORY, "host allocation failed");
+  h->hp = eff;
+  h->warnings = warn;
+  h->device_id = device_id;
+  h->tensors.assign(tensors, tensors + n_tensors);
+  h->numels.resize(static_cast<size_t>(n_tensors));
+  for (int32_t i = 0; i < n_tensors; ++i) {
+    h->numels[static_cast<size_t>(i)] = tensors[i].numel;
+    h->total_numel += tensors[i].numel;
+  }
+  h->last_grads.assign(static_cast<size_t>(n_tensors), nullptr);
+
+  auto bail = [&](int status) {
+    g_create_error = h->error;
+    novak_destroy(h);
+    return status;
+  };
+  DeviceScope scope;
+  hipError_t e = scope.enter(device_id);
+  if (e != hipSuccess) return bail(fail_hip(h, e, "hipSetDevice"));
+  if (n_tensors > 0) {
+    const size_t n = static_cast<size_t>(n_tensors);
+    const size_t bytes = 5 * n * sizeof(void *);
+    if ((e = hipMalloc(&h->d_ptrs, bytes)) != hipSuccess) return bail(fail_hip(h, e, "hipMalloc(pointer tables)"));
+    std::vector<void *> host(5 * n, nullptr);
+    for (size_t i = 0; i < n; ++i) {
+      host[0 * n + i] = tensors[i].param;
+      host[1 * n + i] = tensors[i].exp_avg;
+      host[2 * n + i] = tensors[i].exp_avg_sq;
+      host[3 * n + i] = tensors[i].la_buf;
+    }
+    if ((e = hipMemcpy(h->d_ptrs, host.data(), bytes, hipMemcpyHostToDevice)) != hipSuccess) return bail(fail_hip(h, e, "hipMemcpy(pointer tables)"));
+    if ((e = hipHostMalloc(reinterpret_cast<void **>(&h->h_ring), novak_handle::kRing * n * sizeof(void *), hipHostMallocDefault)) != hipSuccess)
+      return bail(fail_hip(h, e, "hipHostMalloc(gradient pointer ring)"));
+    for (int r = 0; r < novak_handle::kRing; ++r)
+      if ((e = hipEventCreateWithFlags(&h->ring_ev[r], hipEventDisableTiming)) != hipSuccess) return bail(fail_hip(h, e, "hipEventCreate"));
+  }
+  rc = build_chunk_table(h);
+  if (rc != NOVAK_OK) return bail(rc);
+  *out = h;
+  return NOVAK_OK;
+}
+
+int novak_destroy(novak_handle *h) {
+  if (!h) return NOVAK_OK;
+  DeviceScope scope;
+  (void)scope.enter(h->device_id);
+  free_device_tables(h);
+  if (h->d_ptrs) (void)hipFree(h->d_ptrs);
+  if (h->h_ring) (void)hipHostFree(h->h_ring);
+  for (int r = 0; r < novak_handle::kRing; ++r)
+    if (h->ring_ev[r]) (void)hipEventDestroy(h->ring_ev[r]);
+  delete h;
+  return NOVAK_OK;
+}
+
+int novak_get_info(const novak_handle *h, novak_info *info) {
+  if (!h || !info) return NOVAK_ERR_NULL_POINTER;
+  if (info->struct_size != sizeof(novak_info)) return NOVAK_ERR_INVALID_ARG;
+  info->nesterov_mode = h->hp.nesterov_mode;
+  info->lookahead_mode = h->hp.lookahead_mode;
+  info->warnings = h->warnings;
+  info->n_tensors = static_cast<int32_t>(h->tensors.size());
+  info->n_chunks = h->n_chunks;
+  info->chunk_elems = h->chunk_elems;
+  info->total_numel = h->total_numel;
+  info->last_step = h->last_step;
+  info->sync_due = h->sync_due;
+  info->device_id = h->device_id;
+  return NOVAK_OK;
+}
+
+const char *novak_last_error(const novak_handle *h) { return h ? h->error.c_str() : g_create_error.c_str(); }
+
+int novak_set_tuning(novak_handle *h, int32_t key, int64_t value) {
+  if (!h) return NOVAK_ERR_NULL_POINTER;
+  if (key == NOVAK_TUNE_NONTEMPORAL) {
+    h->nontemporal = value ? 1 : 0;
+    return NOVAK_OK;
+  }
+  if (key == NOVAK_TUNE_CHUNK_ELEMS) {
+    if (value < NOVAK_CHUNK_MIN || value > NOVAK_CHUNK_MAX || value % NOVAK_CHUNK_MIN) return fail(h, NOVAK_ERR_INVALID_ARG, "chunk_elems must be a multiple of 1024 in [1024, 2^24]");
+    if (value == h->chunk_elems) return NOVAK_OK;
+    DeviceScope scope;
+    NOVAK_HIP(h, scope.enter(h->device_id));
+    // the old table may still be read by kernels in flight
+    NOVAK_HIP(h, hipDeviceSynchronize());
+    const int64_t old = h->chunk_elems;
+    h->chunk_elems = value;
+    const int rc = build_chunk_table(h);
+    if (rc != NOVAK_OK) h->chunk_elems = old;
+    return rc;
+  }
+  return fail(h, NOVAK_ERR_INVALID_ARG, "unknown tuning key");
+}
+
+int novak_lookahead_init(novak_handle *h, void *hip_stream) {
+  if (!h) return NOVAK_ERR_NULL_POINTER;
+  if (h->hp.lookahead_mode == NOVAK_LOOKAHEAD_NONE) return fail(h, NOVAK_ERR_STATE, "lookahead is off");
+  if (h->n_chunks == 0) return NOVAK_OK;
+  DeviceScope scope;
+  NOVAK_HIP(h, scope.enter(h->device_id));
+  launch_la<LA_INIT>(h->nontemporal != 0, dim3(static_cast<unsigned>(h->n_chunks)), static_cast<hipStream_t>(hip_stream), tables_of(h), 0.0f, 0.0f);
+  NOVAK_HIP(h, hipGetLastError());
+  return NOVAK_OK;
+}
+
+int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t step, void *hip_stream) {
+  if (!h) return NOVAK_ERR_NULL_POINTER;
+  const size_t n = h->tensors.size();
+  if (n > 0 && !grads) return fail(h, NOVAK_ERR_NULL_POINTER, "grads is NULL");
+  if (grad_dtype != NOVAK_GRAD_F32 && grad_dtype != NOVAK_GRAD_BF16) return fail(h, NOVAK_ERR_INVALID_ARG, "unknown grad_dtype");
+  if (step < 1) return fail(h, NOVAK_ERR_BAD_STEP, "step must be >= 1 (Eq. 5 is undefined at t = 0)");
+  if (h->last_step != 0 && step != h->last_step + 1) return fail(h, NOVAK_ERR_BAD_STEP, "step must be the previous step + 1");
+  if (h->sync_due) return fail(h, NOVAK_ERR_STATE, "a lookahead sync is due before the next step");
+  const uintptr_t amask = grad_dtype == NOVAK_GRAD_BF16 ? 1u : 3u;
+  for (size_t i = 0; i < n; ++i) {
+    if (h->numels[i] == 0) continue;
+    if (!grads[i]) return fail(h, NOVAK_ERR_NULL_POINTER, "grads[" + std::to_string(i) + "] is NULL");
+    if (reinterpret_cast<uintptr_t>(grads[i]) & amask) return fail(h, NOVAK_ERR_MISALIGNED, "grads[" + std::to_string(i) + "] not aligned to its element size");
+  }
+
+  novak_step_scalars sc;
+  int rc = novak_compute_step_scalars(&h->hp, step, &sc);
+  if (rc != NOVAK_OK) return fail(h, rc, "scalar prologue failed");
+
+  const novak_hparams &hp = h->hp;
+  Consts c;
+  std::memset(&c, 0, sizeof(c));
+  c.omb1 = static_cast<float>(1.0 - hp.beta1);
+  c.omb2 = static_cast<float>(1.0 - hp.beta2);
+  c.beta1 = static_cast<float>(hp.beta1);
+  c.beta_n = static_cast<float>(hp.beta_n);
+  c.inv_bc1 = static_cast<float>(1.0 / sc.bc1);
+  c.inv_bc2 = static_cast<float>(1.0 / sc.bc2);
+  c.eps = static_cast<float>(hp.eps);
+  c.step_size = static_cast<float>(sc.step_size);
+  c.lr_wd = hp.decoupled_decay ? static_cast<float>(hp.lr * hp.weight_decay) : 0.0f;
+  c.wd = hp.decoupled_decay ? 0.0f : static_cast<float>(hp.weight_decay);
+  c.flags = 0;
+  if (hp.nesterov_mode == NOVAK_NESTEROV_APPROX) c.flags |= F_APPROX;
+  if (hp.nesterov_mode == NOVAK_NESTEROV_CLASSICAL) c.flags |= F_CLASSICAL;
+  if (sc.denom_on) c.flags |= F_DENOM;
+  if (!hp.decoupled_decay && hp.weight_decay != 0.0) c.flags |= F_COUPLED;
+
+  // lookahead phase of this step: position in the k-step window (section 4.7; sync when t mod k == 0)
+  int la = LA_OFF;
+  bool window_closes = false, sync_after = false;
+  if (hp.lookahead_mode != NOVAK_LOOKAHEAD_NONE) {
+    const int64_t pos = (step - 1) % hp.la_k + 1;
+    window_closes = pos == hp.la_k;
+    if (hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT) {
+      c.la_c0 = static_cast<float>(1.0 - hp.la_alpha);
+      c.la_c1 = static_cast<float>(hp.la_alpha / hp.la_k);
+      if (pos == 1) {
+        la = LA_FIRST;
+        sync_after = window_closes && hp.auto_sync;   // k == 1: nothing to fuse into
+      } else if (window_closes && hp.auto_sync) {
+        la = LA_LAST_FUSED;
+      } else {
+        la = LA_MID;
+      }
+    } else if (window_closes && hp.auto_sync) {
+      la = LA_BASIC_FUSED;
+      c.la_c0 = static_cast<float>(1.0 - hp.la_alpha);
+      c.la_c1 = static_cast<float>(hp.la_alpha);
+    }
+  }
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (h->n_chunks > 0) {
+    DeviceScope scope;
+    NOVAK_HIP(h, scope.enter(h->device_id));
+    // gradient pointers: upload only when the list changed since the previous step
+    if (!h->grads_uploaded || std::memcmp(h->last_grads.data(), grads, n * sizeof(void *)) != 0) {
+      const int slot = h->ring_next;
+      h->ring_next = (slot + 1) % novak_handle::kRing;
+      if (h->ring_used[slot]) NOVAK_HIP(h, hipEventSynchronize(h->ring_ev[slot]));
+      void **src = h->h_ring + static_cast<size_t>(slot) * n;
+      std::memcpy(src, grads, n * sizeof(void *));
+      void *dst = static_cast<char *>(h->d_ptrs) + 4 * n * sizeof(void *);
+      NOVAK_HIP(h, hipMemcpyAsync(dst, src, n * sizeof(void *), hipMemcpyHostToDevice, stream));
+      NOVAK_HIP(h, hipEventRecord(h->ring_ev[slot], stream));
+      h->ring_used[slot] = true;
+      std::memcpy(h->last_grads.data(), grads, n * sizeof(void *));
+      h->grads_uploaded = true;
+    }
+    launch_step(grad_dtype, h->nontemporal != 0, la, dim3(static_cast<unsigned>(h->n_chunks)), stream, tables_of(h), c);
+    NOVAK_HIP(h, hipGetLastError());
+    if (sync_after) {
+      rc = launch_sync(h, stream);
+      if (rc != NOVAK_OK) return rc;
+    }
+  }
+  h->last_step = step;
+  h->sync_due = (window_closes && !hp.auto_sync) ? 1 : 0;
+  return NOVAK_OK;
+}
+
+int novak_lookahead_sync(novak_handle *h, void *hip_stream) {
+  if (!h) return NOVAK_ERR_NULL_POINTER;
+  if (h->hp.lookahead_mode == NOVAK_LOOKAHEAD_NONE) return fail(h, NOVAK_ERR_STATE, "lookahead is off");
+  if (!h->sync_due) return fail(h, NOVAK_ERR_STATE, "no lookahead sync is due (sync follows the steps with t mod k == 0)");
+  DeviceScope scope;
+  NOVAK_HIP(h, scope.enter(h->device_id));
+  const int rc = launch_sync(h, static_cast<hipStream_t>(hip_stream));
+  if (rc != NOVAK_OK) return rc;
+  h->sync_due = 0;
+  return NOVAK_OK;
+}
+
+}  // extern "C"

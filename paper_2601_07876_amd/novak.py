@@ -1,0 +1,226 @@
+"""Thin ctypes binding over libnovak.so: the C entry points under their own names.
+
+Argument marshalling only; every step of the update runs in the library's HIP kernels.  There is
+no fallback: if the shared library is missing or fails to load, importing the functions raises.
+PyTorch is imported first so that this library binds to the same HIP runtime that owns the
+tensors' memory and streams.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libnovak.so")
+
+# ---- constants of include/novak.h -----------------------------------------------------------------
+NOVAK_OK, NOVAK_ERR_INVALID_ARG, NOVAK_ERR_NULL_POINTER, NOVAK_ERR_MISALIGNED = 0, 1, 2, 3
+NOVAK_ERR_BAD_STEP, NOVAK_ERR_STATE, NOVAK_ERR_HIP, NOVAK_ERR_NOT_IMPLEMENTED, NOVAK_ERR_NO_MEMORY = 4, 5, 6, 7, 8
+NOVAK_NESTEROV_NONE, NOVAK_NESTEROV_APPROX, NOVAK_NESTEROV_CLASSICAL, NOVAK_NESTEROV_TRUE = 0, 1, 2, 3
+NOVAK_LOOKAHEAD_NONE, NOVAK_LOOKAHEAD_MEMORY_EFFICIENT, NOVAK_LOOKAHEAD_BASIC = 0, 1, 2
+NOVAK_UNRECT_ADAM_DENOM, NOVAK_UNRECT_SGDM = 0, 1
+NOVAK_MODE_FAST, NOVAK_MODE_RESEARCH = 0, 1
+NOVAK_GRAD_F32, NOVAK_GRAD_BF16 = 0, 1
+NOVAK_WARN_TRUE_NESTEROV_DOWNGRADED, NOVAK_WARN_LOOKAHEAD_DOWNGRADED = 1, 2
+NOVAK_TUNE_CHUNK_ELEMS, NOVAK_TUNE_NONTEMPORAL = 0, 1
+
+NESTEROV = {"none": 0, "approx": 1, "classical": 2, "true": 3}
+LOOKAHEAD = {"none": 0, "memory_efficient": 1, "basic": 2}
+UNRECT = {"adam_denom": 0, "sgdm": 1}
+MODE = {"fast": 0, "research": 1}
+GRAD_DTYPE = {"f32": 0, "bf16": 1}
+
+
+class novak_hparams(C.Structure):
+    _fields_ = [("struct_size", C.c_size_t),
+                ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
+                ("weight_decay", C.c_double), ("beta_n", C.c_double), ("la_alpha", C.c_double),
+                ("la_k", C.c_int32), ("rectified", C.c_int32), ("decoupled_decay", C.c_int32),
+                ("nesterov_mode", C.c_int32), ("lookahead_mode", C.c_int32), ("unrect_fallback", C.c_int32),
+                ("mode", C.c_int32), ("auto_sync", C.c_int32)]
+
+
+class novak_tensor_desc(C.Structure):
+    _fields_ = [("param", C.c_void_p), ("exp_avg", C.c_void_p), ("exp_avg_sq", C.c_void_p),
+                ("la_buf", C.c_void_p), ("numel", C.c_int64)]
+
+
+class novak_step_scalars(C.Structure):
+    _fields_ = [("bc1", C.c_double), ("bc2", C.c_double), ("rho_inf", C.c_double), ("rho_t", C.c_double),
+                ("r_t", C.c_double), ("step_size", C.c_double), ("decay", C.c_double),
+                ("rectified_now", C.c_int32), ("denom_on", C.c_int32)]
+
+
+class novak_chunk(C.Structure):
+    _fields_ = [("offset", C.c_int64), ("tensor", C.c_int32), ("len", C.c_int32)]
+
+
+class novak_info(C.Structure):
+    _fields_ = [("struct_size", C.c_size_t), ("nesterov_mode", C.c_int32), ("lookahead_mode", C.c_int32),
+                ("warnings", C.c_uint32), ("n_tensors", C.c_int32), ("n_chunks", C.c_int64),
+                ("chunk_elems", C.c_int64), ("total_numel", C.c_int64), ("last_step", C.c_int64),
+                ("sync_due", C.c_int32), ("device_id", C.c_int32)]
+
+
+EXPORTS = ("novak_validate_hparams", "novak_compute_step_scalars", "novak_plan_chunks",
+           "novak_bytes_per_param_step", "novak_bytes_per_param_sync", "novak_status_string",
+           "novak_create", "novak_lookahead_init", "novak_step", "novak_lookahead_sync", "novak_destroy",
+           "novak_get_info", "novak_set_tuning", "novak_last_error")
+
+_lib: Optional[C.CDLL] = None
+
+
+def load_library() -> C.CDLL:
+    """Loads libnovak.so (built in-tree by paper_2601_07876_amd.build).  Raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_07876_amd.build`; "
+                           "there is no fallback path")
+    import torch  # noqa: F401  (loads the HIP runtime this library must share)
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.novak_validate_hparams.argtypes = [C.POINTER(novak_hparams), C.POINTER(novak_hparams), C.POINTER(C.c_uint32)]
+    lib.novak_compute_step_scalars.argtypes = [C.POINTER(novak_hparams), i64, C.POINTER(novak_step_scalars)]
+    lib.novak_plan_chunks.argtypes = [C.POINTER(i64), i32, i64, C.POINTER(novak_chunk), i64, C.POINTER(i64)]
+    lib.novak_bytes_per_param_step.argtypes = [i32, i32, i32, i32, i32]
+    lib.novak_bytes_per_param_step.restype = C.c_double
+    lib.novak_bytes_per_param_sync.argtypes = [i32]
+    lib.novak_bytes_per_param_sync.restype = C.c_double
+    lib.novak_status_string.argtypes = [C.c_int]
+    lib.novak_status_string.restype = C.c_char_p
+    lib.novak_create.argtypes = [C.POINTER(vp), C.POINTER(novak_hparams), C.POINTER(novak_tensor_desc), i32, i32]
+    lib.novak_lookahead_init.argtypes = [vp, vp]
+    lib.novak_step.argtypes = [vp, C.POINTER(vp), i32, i64, vp]
+    lib.novak_lookahead_sync.argtypes = [vp, vp]
+    lib.novak_destroy.argtypes = [vp]
+    lib.novak_get_info.argtypes = [vp, C.POINTER(novak_info)]
+    lib.novak_set_tuning.argtypes = [vp, i32, i64]
+    lib.novak_last_error.argtypes = [vp]
+    lib.novak_last_error.restype = C.c_char_p
+    for name in EXPORTS:
+        fn = getattr(lib, name)
+        if fn.restype is C.c_int:
+            fn.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+class NovakError(RuntimeError):
+    def __init__(self, status: int, where: str, detail: str = ""):
+        self.status = status
+        msg = f"{where}: status {status} ({novak_status_string(status)})"
+        super().__init__(msg + (f": {detail}" if detail else ""))
+
+
+def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, beta_n=0.9, la_alpha=0.5, la_k=5,
+                 rectified=True, decoupled_decay=True, nesterov="approx", lookahead="memory_efficient",
+                 unrect_fallback="adam_denom", mode="fast", auto_sync=False) -> novak_hparams:
+    """Fills a novak_hparams from keyword values (mode names or their integer codes)."""
+    def code(table: Dict[str, int], x):
+        return table[x] if isinstance(x, str) else int(x)
+    return novak_hparams(C.sizeof(novak_hparams), lr, beta1, beta2, eps, weight_decay, beta_n, la_alpha, int(la_k),
+                         int(rectified), int(decoupled_decay), code(NESTEROV, nesterov), code(LOOKAHEAD, lookahead),
+                         code(UNRECT, unrect_fallback), code(MODE, mode), int(auto_sync))
+
+
+# ---- the entry points, same names as the C ABI ------------------------------------------------------
+def novak_status_string(status: int) -> str:
+    return load_library().novak_status_string(int(status)).decode()
+
+
+def novak_validate_hparams(hp: novak_hparams):
+    """-> (status, effective hparams, warning bits)."""
+    eff, warn = novak_hparams(), C.c_uint32(0)
+    rc = load_library().novak_validate_hparams(C.byref(hp), C.byref(eff), C.byref(warn))
+    return rc, eff, warn.value
+
+
+def novak_compute_step_scalars(hp: novak_hparams, step: int):
+    out = novak_step_scalars()
+    rc = load_library().novak_compute_step_scalars(C.byref(hp), int(step), C.byref(out))
+    return rc, out
+
+
+def novak_plan_chunks(numels: Sequence[int], chunk_elems: int):
+    """-> (status, list of (tensor, offset, len))."""
+    lib = load_library()
+    n = len(numels)
+    arr = (C.c_int64 * max(n, 1))(*numels)
+    count = C.c_int64(0)
+    rc = lib.novak_plan_chunks(arr, n, int(chunk_elems), None, 0, C.byref(count))
+    if rc != NOVAK_OK:
+        return rc, []
+    out = (novak_chunk * max(count.value, 1))()
+    rc = lib.novak_plan_chunks(arr, n, int(chunk_elems), out, count.value, C.byref(count))
+    return rc, [(out[i].tensor, out[i].offset, out[i].len) for i in range(count.value)]
+
+
+def novak_bytes_per_param_step(lookahead_mode: int, grad_dtype: int, la_k: int, window_pos: int, fused_sync: int) -> float:
+    return load_library().novak_bytes_per_param_step(lookahead_mode, grad_dtype, la_k, window_pos, fused_sync)
+
+
+def novak_bytes_per_param_sync(lookahead_mode: int) -> float:
+    return load_library().novak_bytes_per_param_sync(lookahead_mode)
+
+
+def novak_create(hp: novak_hparams, descs: Sequence[novak_tensor_desc], device_id: int = 0):
+    """-> (status, handle).  `descs` hold raw device pointers (e.g. tensor.data_ptr())."""
+    lib = load_library()
+    n = len(descs)
+    arr = (novak_tensor_desc * max(n, 1))(*descs)
+    handle = C.c_void_p(None)
+    rc = lib.novak_create(C.byref(handle), C.byref(hp), arr, n, int(device_id))
+    return rc, (handle if rc == NOVAK_OK else None)
+
+
+def novak_lookahead_init(handle, stream: int = 0) -> int:
+    return load_library().novak_lookahead_init(handle, C.c_void_p(stream))
+
+
+def novak_step(handle, grad_ptrs, grad_dtype: int, step: int, stream: int = 0) -> int:
+    """`grad_ptrs`: a ctypes c_void_p array (reused by the caller) or a sequence of device addresses."""
+    if not isinstance(grad_ptrs, C.Array):
+        grad_ptrs = (C.c_void_p * max(len(grad_ptrs), 1))(*grad_ptrs)
+    return load_library().novak_step(handle, grad_ptrs, int(grad_dtype), int(step), C.c_void_p(stream))
+
+
+def novak_lookahead_sync(handle, stream: int = 0) -> int:
+    return load_library().novak_lookahead_sync(handle, C.c_void_p(stream))
+
+
+def novak_destroy(handle) -> int:
+    return load_library().novak_destroy(handle)
+
+
+def novak_get_info(handle):
+    info = novak_info(struct_size=C.sizeof(novak_info))
+    rc = load_library().novak_get_info(handle, C.byref(info))
+    return rc, info
+
+
+def novak_set_tuning(handle, key: int, value: int) -> int:
+    return load_library().novak_set_tuning(handle, int(key), int(value))
+
+
+def novak_last_error(handle=None) -> str:
+    return load_library().novak_last_error(handle).decode()
+
+
+# ---- convenience: marshal torch tensors into descriptors -------------------------------------------
+def tensor_desc(param, exp_avg, exp_avg_sq, la_buf=None) -> novak_tensor_desc:
+    """Descriptor from contiguous fp32 torch tensors that live on the GPU."""
+    for t in (param, exp_avg, exp_avg_sq) + ((la_buf,) if la_buf is not None else ()):
+        if not t.is_contiguous() or str(t.dtype) != "torch.float32" or not t.is_cuda:
+            raise ValueError("state tensors must be contiguous fp32 GPU tensors")
+        if t.numel() != param.numel():
+            raise ValueError("state tensors must have the parameter's element count")
+    return novak_tensor_desc(param.data_ptr(), exp_avg.data_ptr(), exp_avg_sq.data_ptr(),
+                             la_buf.data_ptr() if la_buf is not None else None, param.numel())
+
+
+def check(rc: int, where: str, handle=None) -> None:
+    if rc != NOVAK_OK:
+        raise NovakError(rc, where, novak_last_error(handle))

@@ -1,0 +1,190 @@
+"""GPU parity at the full benchmark sizes (C2..C5), in the launch configuration bench.py times.
+
+Inputs are drawn on the device from a seeded torch generator (input plumbing, not the method); the
+oracle receives copies of the sampled elements' inputs and computes those elements one by one (the
+update is elementwise, so a sample of elements is a valid run).  Samples always include tensor
+heads and tails and elements on both sides of chunk-table boundaries.  Every sampled element of
+theta, m, v (and the lookahead buffer where it is defined) must meet |gpu - ref| <= 1e-7 + 1e-5|ref|.
+On top of that, whole-buffer properties that hold at any size are checked: v >= 0, finiteness,
+and that elements outside every tensor (guard gaps between tensors) are untouched.
+"""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import novak_oracle as O
+from paper_2601_07876_amd import novak as N
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+GAP = 64          # guard elements between consecutive tensors in the flat buffers (keeps 256-B alignment)
+SENTINEL = 777.0
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+class FullRun:
+    """Flat device buffers holding a whole workload, a library handle, and the sampled oracle."""
+
+    def __init__(self, wl: W.Workload, samples_per_tensor: int = 2048, seed: int = 42, device="cuda:0"):
+        self.wl, self.seed = wl, seed
+        self.dev = torch.device(device)
+        self.numels = wl.numels
+        self.offsets = []
+        off = GAP
+        for n in self.numels:
+            self.offsets.append(off)
+            off += ((n + GAP - 1) // GAP) * GAP + GAP
+        self.flat_len = off
+        self.bufs = {r: torch.empty(self.flat_len, dtype=torch.float32, device=self.dev) for r in ("theta", "m", "v", "la")}
+        gdt = torch.bfloat16 if wl.grad_dtype == "bf16" else torch.float32
+        self.g = torch.empty(self.flat_len, dtype=gdt, device=self.dev)
+        self.gen = torch.Generator(device=self.dev)
+        self.chunk_elems = None
+        self.handle = None
+        # sampled global indices
+        idx = []
+        for i, n in enumerate(self.numels):
+            idx.append(W.sample_indices(n, samples_per_tensor, seed, i, block=16384) + self.offsets[i])
+        self.idx_host = np.concatenate(idx)
+        self.idx = torch.from_numpy(self.idx_host).to(self.dev)
+        self._grad_arr = (C.c_void_p * len(self.numels))()
+        for i, (o, n) in enumerate(zip(self.offsets, self.numels)):
+            self._grad_arr[i] = self.g.data_ptr() + o * self.g.element_size()
+
+    def reset(self, hyper, auto_sync=False):
+        if self.handle is not None:
+            torch.cuda.synchronize()
+            N.novak_destroy(self.handle)
+        self.gen.manual_seed(self.seed)
+        for r in ("theta", "m", "v", "la"):
+            self.bufs[r].fill_(SENTINEL)
+        for o, n in zip(self.offsets, self.numels):
+            self.bufs["theta"][o:o + n].normal_(0.0, W.PARAM_STD, generator=self.gen)
+            self.bufs["m"][o:o + n].zero_()
+            self.bufs["v"][o:o + n].zero_()
+        hp = N.make_hparams(auto_sync=auto_sync, **hyper)
+        descs = [N.novak_tensor_desc(*(self.bufs[r].data_ptr() + 4 * o for r in ("theta", "m", "v", "la")), n)
+                 for o, n in zip(self.offsets, self.numels)]
+        rc, self.handle = N.novak_create(hp, descs, 0)
+        N.check(rc, "novak_create")
+        rc, info = N.novak_get_info(self.handle)
+        self.h = H.oracle_hyper(hyper, H.NEST_NAMES[info.nesterov_mode], H.LA_NAMES[info.lookahead_mode])
+        self.auto_sync = auto_sync
+        if self.h.lookahead != "none":
+            N.check(N.novak_lookahead_init(self.handle, 0), "lookahead_init", self.handle)
+        self.state = O.init_state(self.bufs["theta"][self.idx].cpu().numpy(), self.h)
+        self.t = 0
+
+    def step(self):
+        self.t += 1
+        t = self.t
+        if self.g.dtype == torch.bfloat16:
+            tmp = torch.empty(self.flat_len, dtype=torch.float32, device=self.dev)
+            tmp.normal_(0.0, self.wl.grad_std, generator=self.gen)
+            self.g.copy_(tmp)                      # round-to-nearest-even to bf16
+            del tmp
+        else:
+            self.g.normal_(0.0, self.wl.grad_std, generator=self.gen)
+        stream = torch.cuda.current_stream().cuda_stream
+        N.check(N.novak_step(self.handle, self._grad_arr, N.GRAD_DTYPE[self.wl.grad_dtype], t, stream), f"step {t}", self.handle)
+        if (not self.auto_sync) and O.sync_due(t, self.h):
+            N.check(N.novak_lookahead_sync(self.handle, stream), f"sync {t}", self.handle)
+        g_s = self.g[self.idx].float().cpu().numpy()
+        O.step(self.state, g_s, t, self.h)
+        if O.sync_due(t, self.h):
+            O.lookahead_sync(self.state, self.h)
+
+    def check(self, tag):
+        torch.cuda.synchronize()
+        for role, ref in (("theta", self.state.theta), ("m", self.state.m), ("v", self.state.v)):
+            got = self.bufs[role][self.idx].cpu().numpy()
+            H.assert_close(f"{tag} {role}", got, ref)
+            H.assert_close_strict(f"{tag} {role}", got, ref)
+        if self.h.lookahead == "memory_efficient" and not (self.auto_sync and self.t % self.h.la_k == 0):
+            ref = O.blend_buffer(self.state, self.h) if self.state.window else self.state.theta
+            H.assert_close(f"{tag} la", self.bufs["la"][self.idx].cpu().numpy(), ref)
+        if self.h.lookahead == "basic":
+            H.assert_close(f"{tag} slow", self.bufs["la"][self.idx].cpu().numpy(), self.state.slow0)
+        # whole-buffer properties
+        for o, n in zip(self.offsets[:4] + self.offsets[-4:], self.numels[:4] + self.numels[-4:]):
+            for r in ("theta", "m", "v"):
+                b = self.bufs[r]
+                assert bool((b[o - GAP:o] == SENTINEL).all()) and bool((b[o + n:o + n + 1] == SENTINEL).all()), f"{tag}: {r} guard touched"
+        assert bool(torch.isfinite(self.bufs["theta"]).all())
+        assert float(self.bufs["v"].min()) >= 0.0
+
+    def close(self):
+        if self.handle is not None:
+            torch.cuda.synchronize()
+            N.novak_destroy(self.handle)
+            self.handle = None
+
+
+def test_c2_resnet50_fast_path_100_steps():
+    wl = W.get_workload("c2_resnet50")
+    run = FullRun(wl)
+    try:
+        run.reset(wl.hyper)
+        for t in range(1, 101):
+            run.step()
+            if t in (10, 100):
+                run.check(f"c2 t={t}")
+        _say("c2 done")
+    finally:
+        run.close()
+
+
+def test_c3_vgg16_fast_and_research_modes():
+    wl = W.get_workload("c3_vgg16")
+    run = FullRun(wl)
+    try:
+        for name, hyper, auto in (("fast", wl.hyper, False),
+                                  ("fast-auto_sync", wl.hyper, True),
+                                  ("research-basic-classical", dict(wl.hyper, mode="research", lookahead="basic", nesterov="classical"), False)):
+            run.reset(hyper, auto_sync=auto)
+            for t in range(1, 12):
+                run.step()
+                if t in (4, 10, 11):
+                    run.check(f"c3 {name} t={t}")
+            _say(f"c3 {name} done")
+    finally:
+        run.close()
+
+
+def test_c4_vit_b16_bf16_gradients_100_steps():
+    wl = W.get_workload("c4_vit_b16_bf16")
+    run = FullRun(wl)
+    try:
+        run.reset(wl.hyper)
+        for t in range(1, 101):
+            run.step()
+            if t in (7, 100):
+                run.check(f"c4 t={t}")
+        _say("c4 done")
+    finally:
+        run.close()
+
+
+def test_c5_decoder_1p3b_sweep():
+    """1.3B parameters (5.26 GB per buffer, offsets beyond 2^31 bytes): k in {5,10} x Nesterov variants."""
+    wl = W.get_workload("c5_decoder_1p3b")
+    run = FullRun(wl, samples_per_tensor=1024)
+    try:
+        for k in (5, 10):
+            for nest in ("none", "approx", "classical", "true"):
+                hyper = dict(wl.hyper, la_k=k, nesterov=nest, mode="research")
+                run.reset(hyper)
+                for t in range(1, 2 * k + 2):
+                    run.step()
+                    if t in (k - 1, 2 * k, 2 * k + 1):
+                        run.check(f"c5 k={k} {nest} t={t}")
+                _say(f"c5 k={k} nesterov={nest} done")
+    finally:
+        run.close()

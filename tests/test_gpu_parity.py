@@ -1,0 +1,251 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by element.
+
+Bound (per element of theta, m, v and the lookahead buffer): |gpu - ref| <= 1e-7 + 1e-5 |ref|, plus a
+tighter scale-aware check (see harness.assert_close_strict).  Sizes here span many chunks of the
+multi-tensor table and ragged tails; full-size workloads are in test_gpu_fullsize.py.
+"""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import novak_oracle as O
+from paper_2601_07876_amd import novak as N
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("fallback", ["adam_denom", "sgdm"])
+def test_c1_flat_1m_100_steps(fallback):
+    """Configuration 1: one flat 2^20 tensor, 100 steps, research mode, both fallback readings."""
+    wl = W.get_workload("c1_flat_1m")
+    hyper = dict(wl.hyper, unrect_fallback=fallback)
+    _say(f"c1 fallback={fallback}")
+    gpu, states, h = H.run_pair(wl.numels, hyper, wl.steps, wl.grad_std, check_blend_at=(1, 2, 4, 5, 98, 99, 100))
+    try:
+        H.compare_states(gpu, states)
+        # after the sync at t = 100 the buffer equals the new slow weights
+        H.assert_close("la after sync", gpu.host("la")[0], states[0].theta)
+    finally:
+        gpu.close()
+
+
+def test_c1_auto_sync_matches_separate_sync_and_oracle():
+    wl = W.get_workload("c1_flat_1m")
+    n = [1 << 18]
+    a, states, _ = H.run_pair(n, wl.hyper, 23, wl.grad_std, auto_sync=False)
+    b, _, _ = H.run_pair(n, wl.hyper, 23, wl.grad_std, auto_sync=True)
+    try:
+        H.compare_states(b, states)
+        for role in ("theta", "m", "v"):
+            assert np.array_equal(a.host(role)[0], b.host(role)[0]), role
+    finally:
+        a.close()
+        b.close()
+
+
+NEST = ["none", "approx", "classical", "true"]
+LOOK = ["none", "memory_efficient", "basic"]
+
+
+@pytest.mark.parametrize("nesterov,lookahead,grad_dtype,auto_sync",
+                         [c for c in itertools.product(NEST, LOOK, ["f32", "bf16"], [False, True])
+                          if not (c[1] == "none" and c[3])])
+def test_ragged_all_modes(nesterov, lookahead, grad_dtype, auto_sync):
+    """Odd-sized tensor list, every Nesterov x lookahead x gradient dtype, 2k+1 steps, k = 5."""
+    wl = W.get_workload("ragged")
+    hyper = dict(wl.hyper, nesterov=nesterov, lookahead=lookahead)
+    _say(f"ragged {nesterov} {lookahead} {grad_dtype} auto_sync={auto_sync}")
+    gpu, states, h = H.run_pair(wl.numels, hyper, wl.steps, wl.grad_std, grad_dtype, auto_sync=auto_sync,
+                                chunk_elems=4096, guard=16, check_blend_at=(1, 3, 5, 11))
+    try:
+        H.compare_states(gpu, states)
+        assert gpu.guards_intact()
+        if lookahead == "basic":
+            # slow weights: after 11 steps they are the second sync's result
+            la = gpu.host("la")
+            for i, st in enumerate(states):
+                H.assert_close(f"slow[{i}]", la[i], st.slow0)
+    finally:
+        gpu.close()
+
+
+@pytest.mark.parametrize("fallback,rectified,decoupled", [("sgdm", True, True), ("adam_denom", False, True),
+                                                          ("adam_denom", True, False), ("sgdm", True, False)])
+def test_ragged_switches(fallback, rectified, decoupled):
+    wl = W.get_workload("ragged")
+    hyper = dict(wl.hyper, unrect_fallback=fallback, rectified=rectified, decoupled_decay=decoupled, weight_decay=0.05)
+    gpu, states, _ = H.run_pair(wl.numels, hyper, wl.steps, wl.grad_std, chunk_elems=1024)
+    try:
+        H.compare_states(gpu, states)
+    finally:
+        gpu.close()
+
+
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("misalign,grad_misalign", [(1, 0), (0, 1), (3, 3), (2, 5)])
+def test_misaligned_views_take_the_elementwise_path(grad_dtype, misalign, grad_misalign):
+    """Pointers that are only element-aligned: results equal the oracle and nothing outside is touched."""
+    wl = W.get_workload("ragged")
+    _say(f"misaligned {grad_dtype} {misalign} {grad_misalign}")
+    gpu, states, _ = H.run_pair(wl.numels, wl.hyper, 6, wl.grad_std, grad_dtype, misalign=misalign,
+                                grad_misalign=grad_misalign, guard=8, chunk_elems=2048)
+    try:
+        H.compare_states(gpu, states)
+        assert gpu.guards_intact()
+    finally:
+        gpu.close()
+
+
+def test_results_do_not_depend_on_chunking_or_cache_hints():
+    """Elementwise independence on the GPU: any chunk size / hint gives bit-identical results."""
+    wl = W.get_workload("ragged")
+    outs = []
+    for chunk, nt in ((1024, True), (16384, True), (65536, False), (1 << 20, False)):
+        gpu, _, _ = H.run_pair(wl.numels, wl.hyper, 7, wl.grad_std, chunk_elems=chunk, nontemporal=nt)
+        outs.append([gpu.host(r) for r in ("theta", "m", "v", "la")])
+        gpu.close()
+    for other in outs[1:]:
+        for role_a, role_b in zip(outs[0], other):
+            for x, y in zip(role_a, role_b):
+                assert np.array_equal(x, y)
+
+
+def test_aligned_and_elementwise_paths_agree_bitwise():
+    wl = W.get_workload("ragged")
+    a, _, _ = H.run_pair(wl.numels, wl.hyper, 7, wl.grad_std, misalign=0)
+    b, _, _ = H.run_pair(wl.numels, wl.hyper, 7, wl.grad_std, misalign=1)
+    try:
+        for role in ("theta", "m", "v", "la"):
+            for x, y in zip(a.host(role), b.host(role)):
+                assert np.array_equal(x, y)
+    finally:
+        a.close()
+        b.close()
+
+
+def test_resume_is_bitwise():
+    """20 steps straight == 10 steps, destroy, create, 10 more (the handle holds no numerical state)."""
+    wl = W.get_workload("ragged")
+    numels = wl.numels
+    full, _, _ = H.run_pair(numels, wl.hyper, 20, wl.grad_std)
+    part, _, _ = H.run_pair(numels, wl.hyper, 10, wl.grad_std)
+    # new handle over the same device buffers, no lookahead re-initialisation
+    hp = N.make_hparams(**part.hyper)
+    descs = [N.novak_tensor_desc(part.theta[i].data_ptr(), part.m[i].data_ptr(), part.v[i].data_ptr(),
+                                 part.la[i].data_ptr(), n) for i, n in enumerate(numels)]
+    part.close()
+    rc, handle = N.novak_create(hp, descs, 0)
+    N.check(rc, "novak_create")
+    part.handle = handle
+    try:
+        for t in range(11, 21):
+            gd = part.upload_grads(W.host_grads(numels, t, wl.grad_std, 42))
+            N.check(part.step(t, gd), f"step {t}", part.handle)
+        for role in ("theta", "m", "v"):
+            for x, y in zip(full.host(role), part.host(role)):
+                assert np.array_equal(x, y)
+    finally:
+        full.close()
+        part.close()
+
+
+def test_alpha_one_fixed_points_on_gpu():
+    """alpha_LA = 1: basic returns the fast weights bit for bit; memory_efficient does so for k = 1."""
+    wl = W.get_workload("ragged")
+    numels = wl.numels[:10]
+    base = dict(wl.hyper, la_alpha=1.0)
+    fast, _, _ = H.run_pair(numels, dict(base, lookahead="none"), 5, wl.grad_std)
+    basic, _, _ = H.run_pair(numels, dict(base, lookahead="basic", la_k=5), 5, wl.grad_std)
+    me1f, _, _ = H.run_pair(numels, dict(base, lookahead="none"), 1, wl.grad_std)
+    me1, st, _ = H.run_pair(numels, dict(base, lookahead="memory_efficient", la_k=1), 1, wl.grad_std)
+    try:
+        for x, y in zip(fast.host("theta"), basic.host("theta")):
+            assert np.array_equal(x, y)
+        for x, y in zip(me1f.host("theta"), me1.host("theta")):
+            assert np.array_equal(x, y)
+        H.compare_states(me1, st)
+    finally:
+        for g in (fast, basic, me1f, me1):
+            g.close()
+
+
+def test_empty_inputs():
+    """No tensors at all, and tensors of zero elements, are legal no-ops."""
+    hp = N.make_hparams(lookahead="none")
+    rc, h = N.novak_create(hp, [], 0)
+    assert rc == N.NOVAK_OK
+    assert N.novak_step(h, [], N.NOVAK_GRAD_F32, 1, 0) == N.NOVAK_OK
+    assert N.novak_destroy(h) == N.NOVAK_OK
+    numels = [0, 5, 0]
+    gpu, states, _ = H.run_pair(numels, W.BASE_HYPER, 6, 1e-2)
+    try:
+        H.compare_states(gpu, states)
+    finally:
+        gpu.close()
+
+
+def test_state_machine_errors_on_device():
+    wl = W.get_workload("ragged")
+    numels = [4099]
+    hyper = dict(wl.hyper, la_k=2)
+    gpu = H.GpuNovak(numels, hyper, "f32", W.host_params(numels))
+    try:
+        g = gpu.upload_grads(W.host_grads(numels, 1, 1e-2))
+        assert N.novak_lookahead_sync(gpu.handle, gpu.stream) == N.NOVAK_ERR_STATE       # nothing due
+        assert gpu.step(0, g) == N.NOVAK_ERR_BAD_STEP
+        assert gpu.step(1, g) == N.NOVAK_OK
+        assert gpu.step(3, g) == N.NOVAK_ERR_BAD_STEP                                    # skipped a step
+        assert gpu.step(2, g, sync=False) == N.NOVAK_OK
+        rc, info = N.novak_get_info(gpu.handle)
+        assert info.sync_due == 1 and info.last_step == 2
+        assert gpu.step(3, g) == N.NOVAK_ERR_STATE                                       # sync pending
+        assert "sync" in N.novak_last_error(gpu.handle)
+        assert N.novak_lookahead_sync(gpu.handle, gpu.stream) == N.NOVAK_OK
+        assert N.novak_lookahead_sync(gpu.handle, gpu.stream) == N.NOVAK_ERR_STATE
+        assert N.novak_step(gpu.handle, [0], N.NOVAK_GRAD_F32, 3, gpu.stream) == N.NOVAK_ERR_NULL_POINTER
+        assert N.novak_step(gpu.handle, [g[0].data_ptr() + 2], N.NOVAK_GRAD_F32, 3, gpu.stream) == N.NOVAK_ERR_MISALIGNED
+        assert N.novak_step(gpu.handle, [g[0].data_ptr()], 7, 3, gpu.stream) == N.NOVAK_ERR_INVALID_ARG
+        assert gpu.step(3, g) == N.NOVAK_OK                                              # still usable
+    finally:
+        gpu.close()
+
+
+def test_fast_mode_downgrades_run_the_cheap_variants():
+    """FAST + true/basic => approx/memory_efficient (section 7.3): GPU matches the oracle of those."""
+    wl = W.get_workload("ragged")
+    hyper = dict(wl.hyper, mode="fast", nesterov="true", lookahead="basic")
+    gpu, states, h = H.run_pair(wl.numels[:8], hyper, 6, wl.grad_std)
+    try:
+        assert gpu.eff_nesterov == "approx" and gpu.eff_lookahead == "memory_efficient"
+        assert gpu.info.warnings == (N.NOVAK_WARN_TRUE_NESTEROV_DOWNGRADED | N.NOVAK_WARN_LOOKAHEAD_DOWNGRADED)
+        H.compare_states(gpu, states)
+    finally:
+        gpu.close()
+
+
+def test_gradient_pointer_list_changes_between_steps():
+    """Fresh gradient buffers every step and reused ones give the same result (pointer table refresh)."""
+    numels = [5000, 300]
+    a, _, _ = H.run_pair(numels, W.BASE_HYPER, 9, 1e-2)       # new buffers each step
+    theta0 = W.host_params(numels)
+    b = H.GpuNovak(numels, W.BASE_HYPER, "f32", theta0)
+    try:
+        fixed = b.upload_grads(W.host_grads(numels, 1, 1e-2))
+        for t in range(1, 10):
+            for buf, g in zip(fixed, W.host_grads(numels, t, 1e-2)):
+                buf.copy_(torch.from_numpy(g))
+            N.check(b.step(t, fixed), "step", b.handle)
+        for role in ("theta", "m", "v"):
+            for x, y in zip(a.host(role), b.host(role)):
+                assert np.array_equal(x, y)
+    finally:
+        a.close()
+        b.close()
