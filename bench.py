@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the NOVAK update step on one MI355X.
+
+A "step" is one pass of the whole hot path over the workload's parameter list: the scalar prologue,
+the fused update kernel (with the lookahead accumulation) and, every k-th step, the slow-weight
+synchronisation.  All tensors are resident in HBM before the timed region starts.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+Prints ONE JSON line: Gparams/s over the timed region, the roofline of the dominant kernel (HBM
+bound; algorithmic bytes / HIP-event kernel time against 8 TB/s) and the CPU oracle's throughput on
+a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+ALIGN = 64              # elements between tensor starts are rounded to this (256-byte alignment)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c5_decoder_1p3b")
+    ap.add_argument("--lookahead", default=None, help="override: none | memory_efficient | basic")
+    ap.add_argument("--nesterov", default=None, help="override: none | approx | classical | true")
+    ap.add_argument("--la-k", type=int, default=None)
+    ap.add_argument("--separate-sync", action="store_true", help="call novak_lookahead_sync instead of fusing the sync")
+    ap.add_argument("--chunk-elems", type=int, default=None)
+    ap.add_argument("--nontemporal", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 21, help="elements of the oracle's timed sample")
+    return ap.parse_args()
+
+
+def la_variant(lookahead: str, k: int, t: int, fused: bool) -> str:
+    """Name of the step-kernel variant that step t runs (which lookahead stream it touches)."""
+    if lookahead == "none":
+        return "step"
+    pos = (t - 1) % k + 1
+    if lookahead == "memory_efficient":
+        if pos == 1:
+            return "step+la_first"
+        if pos == k and fused:
+            return "step+la_last_fused"
+        return "step+la_mid"
+    return "step+basic_fused" if (pos == k and fused) else "step"
+
+
+def cpu_baseline(wl, hyper, n_sample: int):
+    """The oracle, as it stands, on the first n_sample elements of the workload's largest tensor."""
+    import numpy as np
+    import workloads as W
+    from oracle import novak_oracle as O
+
+    n = min(n_sample, max(wl.numels))
+    h = O.Hyper(**{k: v for k, v in hyper.items() if k not in ("mode", "auto_sync")})
+    theta0 = W.host_params([n], 42)
+    steps = 2 * h.la_k + 1 if h.lookahead != "none" else 11
+    grads = [W.host_grads([n], t, wl.grad_std, 42, bf16=(wl.grad_dtype == "bf16"))[0] for t in range(1, steps + 1)]
+    states = [O.init_state(theta0[0], h)]
+    t0 = time.perf_counter()
+    for t in range(1, steps + 1):
+        O.step(states[0], grads[t - 1], t, h)
+        if O.sync_due(t, h):
+            O.lookahead_sync(states[0], h)
+    dt = time.perf_counter() - t0
+    return {"value": n * steps / dt / 1e9, "unit": "Gparams/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {n} elements of the largest tensor, {steps} steps incl. syncs, numpy fp64 arithmetic / fp32 state, {dt:.1f} s",
+            "host_cpus_visible": os.cpu_count()}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the update is elementwise and would shard "
+              "without communication, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as W
+    from paper_2601_07876_amd import novak as N
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = W.get_workload(args.workload)
+    hyper = dict(wl.hyper)
+    if args.lookahead:
+        hyper["lookahead"] = args.lookahead
+    if args.nesterov:
+        hyper["nesterov"] = args.nesterov
+    if args.la_k:
+        hyper["la_k"] = args.la_k
+    fused = not args.separate_sync
+    numels = wl.numels
+    p = wl.total
+
+    # ---- device buffers: one flat allocation per role, tensors at 256-byte aligned offsets --------
+    offsets, off = [], 0
+    for n in numels:
+        offsets.append(off)
+        off += (n + ALIGN - 1) // ALIGN * ALIGN
+    flat = max(off, 1)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(42)
+    theta = torch.empty(flat, dtype=torch.float32, device=dev).normal_(0.0, W.PARAM_STD, generator=gen)
+    m = torch.zeros(flat, dtype=torch.float32, device=dev)
+    v = torch.zeros(flat, dtype=torch.float32, device=dev)
+    la = torch.zeros(flat, dtype=torch.float32, device=dev)
+    g32 = torch.empty(flat, dtype=torch.float32, device=dev).normal_(0.0, wl.grad_std, generator=gen)
+    grad = g32.to(torch.bfloat16) if wl.grad_dtype == "bf16" else g32
+    del g32
+
+    hp = N.make_hparams(auto_sync=fused, **hyper)
+    descs = [N.novak_tensor_desc(theta.data_ptr() + 4 * o, m.data_ptr() + 4 * o, v.data_ptr() + 4 * o,
+                                 la.data_ptr() + 4 * o, n) for o, n in zip(offsets, numels)]
+    rc, handle = N.novak_create(hp, descs, 0)
+    N.check(rc, "novak_create")
+    if args.chunk_elems:
+        N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_CHUNK_ELEMS, args.chunk_elems), "set_tuning", handle)
+    if args.nontemporal is not None:
+        N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_NONTEMPORAL, args.nontemporal), "set_tuning", handle)
+    rc, info = N.novak_get_info(handle)
+    la_name = {0: "none", 1: "memory_efficient", 2: "basic"}[info.lookahead_mode]
+    nest_name = {0: "none", 1: "approx", 2: "classical", 3: "true"}[info.nesterov_mode]
+    k = int(hyper["la_k"])
+    gdt = N.GRAD_DTYPE[wl.grad_dtype]
+    grad_arr = (C.c_void_p * len(numels))(*[grad.data_ptr() + grad.element_size() * o for o in offsets])
+    stream = torch.cuda.current_stream().cuda_stream
+    if la_name != "none":
+        N.check(N.novak_lookahead_init(handle, stream), "lookahead_init", handle)
+
+    def one_step(t):
+        N.check(N.novak_step(handle, grad_arr, gdt, t, stream), "novak_step", handle)
+        if la_name != "none" and not fused and t % k == 0:
+            N.check(N.novak_lookahead_sync(handle, stream), "novak_lookahead_sync", handle)
+
+    t = 0
+    for _ in range(args.warmup):
+        t += 1
+        one_step(t)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps, per-step HIP events on the launch stream ------------------
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    variants = []
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for i in range(args.steps):
+        t += 1
+        variants.append(la_variant(la_name, k, t, fused))
+        ev[i][0].record()
+        N.check(N.novak_step(handle, grad_arr, gdt, t, stream), "novak_step", handle)
+        ev[i][1].record()
+        if la_name != "none" and not fused and t % k == 0:
+            N.check(N.novak_lookahead_sync(handle, stream), "novak_lookahead_sync", handle)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_begin
+
+    # ---- per-variant kernel time and the roofline of the dominant one -----------------------------
+    per = {}
+    for name, (a, b) in zip(variants, ev):
+        per.setdefault(name, []).append(a.elapsed_time(b))     # ms
+    la_mode = info.lookahead_mode
+
+    def bytes_of(name):
+        pos = {"step": 2 if la_name == "basic" else 1, "step+la_first": 1, "step+la_mid": 2,
+               "step+la_last_fused": k, "step+basic_fused": k}[name]
+        return N.novak_bytes_per_param_step(la_mode, gdt, k, pos, int(fused)) if la_name != "none" else \
+            N.novak_bytes_per_param_step(0, gdt, k, 1, 0)
+
+    kernels = {}
+    for name, ms in per.items():
+        avg = sum(ms) / len(ms)
+        bpp = bytes_of(name)
+        kernels[name] = {"launches": len(ms), "avg_ms": avg, "bytes_per_param": bpp,
+                         "GBps": p * bpp / (avg * 1e-3) / 1e9}
+    dominant = max(kernels, key=lambda n: kernels[n]["launches"] * kernels[n]["avg_ms"])
+    dk = kernels[dominant]
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": dk["GBps"] / HBM_PEAK_GBS, "avg_kernel_ms": dk["avg_ms"],
+                "algorithmic_bytes_per_launch": p * dk["bytes_per_param"], "traffic": measured_traffic(args.workload, dominant)}
+
+    result = {
+        "metric": "Gparams updated/s per NOVAK step",
+        "value": p * args.steps / elapsed / 1e9,
+        "unit": "Gparams/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "params": p, "tensors": len(numels), "grad_dtype": wl.grad_dtype,
+                   "nesterov": nest_name, "lookahead": la_name, "la_k": k, "sync": "fused" if fused else "separate",
+                   "mode": hyper["mode"], "rectified": bool(hyper["rectified"]),
+                   "chunk_elems": int(info.chunk_elems), "chunks": int(info.n_chunks)},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    torch.cuda.synchronize()
+    N.novak_destroy(handle)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, {**hyper, "nesterov": nest_name, "lookahead": la_name}, args.cpu_sample)
+    print(json.dumps(result))
+
+
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch from committed rocprofv3 counter summaries (profiles/traffic_*.txt), or None."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 3 and parts[0] == "hbm_bytes_per_launch" and parts[1] == kernel:
+            return float(parts[2])
+    return None
+
+
+if __name__ == "__main__":
+    main()
