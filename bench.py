@@ -40,6 +40,7 @@ def parse_args():
     ap.add_argument("--separate-sync", action="store_true", help="call novak_lookahead_sync instead of fusing the sync")
     ap.add_argument("--chunk-elems", type=int, default=None)
     ap.add_argument("--nontemporal", type=int, default=None)
+    ap.add_argument("--vec-per-lane", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 21, help="elements of the oracle's timed sample")
     return ap.parse_args()
@@ -136,6 +137,8 @@ def main():
         N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_CHUNK_ELEMS, args.chunk_elems), "set_tuning", handle)
     if args.nontemporal is not None:
         N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_NONTEMPORAL, args.nontemporal), "set_tuning", handle)
+    if args.vec_per_lane is not None:
+        N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_VEC_PER_LANE, args.vec_per_lane), "set_tuning", handle)
     rc, info = N.novak_get_info(handle)
     la_name = {0: "none", 1: "memory_efficient", 2: "basic"}[info.lookahead_mode]
     nest_name = {0: "none", 1: "approx", 2: "classical", 3: "true"}[info.nesterov_mode]

@@ -89,7 +89,8 @@ typedef struct novak_hparams {
  * elements, 4-byte aligned (16-byte alignment of every pointer selects the 128-bit path; any other
  * alignment is handled element-wise).  They must stay valid and fixed until novak_destroy, and no
  * two arrays may overlap.  numel == 0 is allowed.
- *   la_buf: the single lookahead buffer; required unless lookahead is NONE.
+ *   la_buf: the single lookahead buffer; required unless lookahead is NONE.  With auto_sync its
+ *     contents are unspecified between a fused sync and the next step (which overwrites it).
  *     MEMORY_EFFICIENT: running blend (1-alpha_LA)*slow_0 + (alpha_LA/k)*sum of the window's iterates,
  *       which equals Eq. 30's right-hand side when the window is full (one buffer instead of the
  *       Delta + theta_0^slow pair of Table 3).
@@ -136,8 +137,9 @@ typedef struct novak_info {
 
 /* tuning keys for novak_set_tuning */
 enum {
-  NOVAK_TUNE_CHUNK_ELEMS = 0,   /* elements per chunk-table entry; multiple of 1024, 1024..2^24 */
-  NOVAK_TUNE_NONTEMPORAL = 1    /* 0/1: non-temporal hints on the streaming loads and stores */
+  NOVAK_TUNE_CHUNK_ELEMS = 0,   /* elements per chunk-table entry; a power of two in [4096, 2^24] */
+  NOVAK_TUNE_NONTEMPORAL = 1,   /* 0/1: non-temporal hints on the streaming loads and stores */
+  NOVAK_TUNE_VEC_PER_LANE = 2   /* 1, 2 or 4: 128-bit accesses per stream per lane; a workgroup covers 1024x that many elements */
 };
 
 /* ---- host-only helpers (no GPU needed) -------------------------------------------------------- */
@@ -152,7 +154,8 @@ int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, ui
 /* Scalars of step `step` (>= 1) for validated hyper-parameters (Eq. 5-9, 18, 24a).  Host memory. */
 int novak_compute_step_scalars(const novak_hparams *hp, int64_t step, novak_step_scalars *out);
 
-/* Cuts tensors of `numels[i]` elements into chunks of at most `chunk_elems` elements, in tensor
+/* Cuts tensors of `numels[i]` elements into chunks of at most `chunk_elems` elements (a power of two
+ * in [4096, 2^24]), in tensor
  * order; a chunk never spans two tensors and empty tensors produce none.  Writes up to `capacity`
  * entries to `out` (may be NULL with capacity 0 to query) and the total count to `n_chunks`. */
 int novak_plan_chunks(const int64_t *numels, int32_t n_tensors, int64_t chunk_elems,

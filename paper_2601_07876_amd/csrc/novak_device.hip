@@ -4,10 +4,10 @@
 //
 // The step is HBM-bound (section 5.5 of the paper: 4 streams read, 3 written per element, a few
 // dozen flops), so the kernel is built around memory streams, not arithmetic:
-//   * one workgroup (4 wave64) per chunk-table entry; a chunk never spans tensors;
-//   * each lane moves 128 bits per stream per access (4 fp32; 4 bf16 gradients = 64 bits), four
-//     accesses per stream are issued back to back before any arithmetic so that ~16 KB per wave
-//     are in flight;
+//   * a chunk-table entry never spans tensors and is covered by short-lived workgroups (4 wave64)
+//     that each touch 1024..4096 consecutive elements once;
+//   * each lane moves 128 bits per stream per access (4 fp32; 4 bf16 gradients = 64 bits), and all
+//     loads of a workgroup are issued before any arithmetic;
 //   * per-step scalars arrive as kernel arguments (SGPRs); nothing is read from memory except the
 //     chunk entry, five base pointers and the streams themselves;
 //   * streams are touched exactly once per step, so loads and stores may carry non-temporal hints.
@@ -27,7 +27,6 @@
 namespace {
 
 constexpr int kBlock = 256;   // 4 wave64 per workgroup
-constexpr int kUnroll = 4;    // independent 128-bit accesses per stream in flight per lane
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
@@ -134,37 +133,47 @@ __device__ __forceinline__ void update_vec(f32x4 &th, f32x4 g, f32x4 &m, f32x4 &
 constexpr bool la_reads(int la) { return la == LA_MID || la == LA_LAST_FUSED || la == LA_BASIC_FUSED; }
 constexpr bool la_writes(int la) { return la == LA_FIRST || la == LA_MID || la == LA_BASIC_FUSED; }
 
-// GradS: scalar gradient type (float or unsigned short holding bf16 bits); GradV its 4-vector.
-template <typename GradS, typename GradV, int LA, bool NT>
-__global__ __launch_bounds__(kBlock) void novak_step_kernel(Tables tb, Consts c) {
-  const novak_chunk ch = tb.chunks[blockIdx.x];
-  const int len = ch.len;
-  float *__restrict__ th_p = tb.param[ch.tensor] + ch.offset;
-  float *__restrict__ m_p = tb.m[ch.tensor] + ch.offset;
-  float *__restrict__ v_p = tb.v[ch.tensor] + ch.offset;
-  const GradS *__restrict__ g_p = static_cast<const GradS *>(tb.grad[ch.tensor]) + ch.offset;
+// Work decomposition.  A chunk-table entry covers up to chunk_elems (a power of two) elements of one
+// tensor; it is processed by chunk_elems / SUB workgroups ("sub-blocks"), each of which touches
+// SUB = kBlock*4*UN consecutive elements exactly once and exits.  Short-lived workgroups dispatched
+// in address order keep the set of DRAM pages that are open at any moment small, which is what the
+// write path of this memory system rewards; the table stays small because its granularity is
+// decoupled from the workgroup's.  blockIdx.x = (chunk index << sub_shift) | sub-block index.
+//
+// GradS: scalar gradient type (float, or unsigned short holding bf16 bits); GradV its 4-vector.
+template <typename GradS, typename GradV, int LA, bool NT, int UN>
+__global__ __launch_bounds__(kBlock) void novak_step_kernel(Tables tb, Consts c, int sub_shift) {
+  constexpr int SUB = kBlock * 4 * UN;
+  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * SUB;
+  if (start >= ch.len) return;
+  const int n = min(SUB, ch.len - start);
+  const int64_t off = ch.offset + start;
+  float *__restrict__ th_p = tb.param[ch.tensor] + off;
+  float *__restrict__ m_p = tb.m[ch.tensor] + off;
+  float *__restrict__ v_p = tb.v[ch.tensor] + off;
+  const GradS *__restrict__ g_p = static_cast<const GradS *>(tb.grad[ch.tensor]) + off;
   float *__restrict__ la_p = nullptr;
-  if (LA != LA_OFF) la_p = tb.la[ch.tensor] + ch.offset;
+  if (LA != LA_OFF) la_p = tb.la[ch.tensor] + off;
 
   uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) |
                    reinterpret_cast<uintptr_t>(v_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
   mis |= reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1);
 
-  int done = 0;   // elements [0, done) handled by the vector path
+  int done = 0;   // elements [0, done) handled by the 128-bit path
   if (mis == 0) {
-    const int nvec = len >> 2;
-    const f32x4 *th4 = reinterpret_cast<const f32x4 *>(th_p);
-    const f32x4 *m4 = reinterpret_cast<const f32x4 *>(m_p);
-    const f32x4 *v4 = reinterpret_cast<const f32x4 *>(v_p);
-    const f32x4 *la4 = reinterpret_cast<const f32x4 *>(la_p);
+    f32x4 *th4 = reinterpret_cast<f32x4 *>(th_p);
+    f32x4 *m4 = reinterpret_cast<f32x4 *>(m_p);
+    f32x4 *v4 = reinterpret_cast<f32x4 *>(v_p);
+    f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
     const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
-    int i = threadIdx.x;
-    for (; i + (kUnroll - 1) * kBlock < nvec; i += kUnroll * kBlock) {
-      f32x4 th[kUnroll], m[kUnroll], v[kUnroll], la[kUnroll];
-      GradV g[kUnroll];
+    if (n == SUB) {
+      // full sub-block: every load is issued before any arithmetic
+      f32x4 th[UN], m[UN], v[UN], la[UN];
+      GradV g[UN];
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
-        const int j = i + u * kBlock;
+      for (int u = 0; u < UN; ++u) {
+        const int j = threadIdx.x + u * kBlock;
         th[u] = ld<NT>(th4 + j);
         g[u] = ld<NT>(g4 + j);
         m[u] = ld<NT>(m4 + j);
@@ -172,29 +181,31 @@ __global__ __launch_bounds__(kBlock) void novak_step_kernel(Tables tb, Consts c)
         if (la_reads(LA)) la[u] = ld<NT>(la4 + j);
       }
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
-        const int j = i + u * kBlock;
+      for (int u = 0; u < UN; ++u) {
+        const int j = threadIdx.x + u * kBlock;
         update_vec<LA>(th[u], grad_to_f32<GradV>(g[u]), m[u], v[u], la[u], c);
-        st<NT>(const_cast<f32x4 *>(th4) + j, th[u]);
-        st<NT>(const_cast<f32x4 *>(m4) + j, m[u]);
-        st<NT>(const_cast<f32x4 *>(v4) + j, v[u]);
-        if (la_writes(LA)) st<NT>(const_cast<f32x4 *>(la4) + j, la[u]);
+        st<NT>(th4 + j, th[u]);
+        st<NT>(m4 + j, m[u]);
+        st<NT>(v4 + j, v[u]);
+        if (la_writes(LA)) st<NT>(la4 + j, la[u]);
       }
+      return;
     }
-    for (; i < nvec; i += kBlock) {
+    const int nvec = n >> 2;
+    for (int i = threadIdx.x; i < nvec; i += kBlock) {
       f32x4 th = ld<NT>(th4 + i), m = ld<NT>(m4 + i), v = ld<NT>(v4 + i), la;
       GradV g = ld<NT>(g4 + i);
       if (la_reads(LA)) la = ld<NT>(la4 + i);
       update_vec<LA>(th, grad_to_f32<GradV>(g), m, v, la, c);
-      st<NT>(const_cast<f32x4 *>(th4) + i, th);
-      st<NT>(const_cast<f32x4 *>(m4) + i, m);
-      st<NT>(const_cast<f32x4 *>(v4) + i, v);
-      if (la_writes(LA)) st<NT>(const_cast<f32x4 *>(la4) + i, la);
+      st<NT>(th4 + i, th);
+      st<NT>(m4 + i, m);
+      st<NT>(v4 + i, v);
+      if (la_writes(LA)) st<NT>(la4 + i, la);
     }
     done = nvec << 2;
   }
-  // element-wise path: the < 4 element tail of an aligned chunk, or a whole unaligned chunk
-  for (int i = done + threadIdx.x; i < len; i += kBlock) {
+  // element-wise path: the < 4 element tail of an aligned sub-block, or a whole unaligned one
+  for (int i = done + threadIdx.x; i < n; i += kBlock) {
     float th = th_p[i], m = m_p[i], v = v_p[i], la = 0.0f, g;
     if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
     else g = g_p[i];
@@ -207,7 +218,7 @@ __global__ __launch_bounds__(kBlock) void novak_step_kernel(Tables tb, Consts c)
   }
 }
 
-// Lookahead kernels over the same chunk table.
+// Lookahead kernels over the same chunk table and sub-block decomposition (UN = 1).
 //   SYNC_ME:    theta <- A                       (A already holds Eq. 30's right-hand side)
 //   SYNC_BASIC: S <- c1*theta + c0*S; theta <- S (standard Lookahead interpolation)
 //   INIT:       buffer <- theta                  (Eq. 28)
@@ -221,15 +232,19 @@ __device__ __forceinline__ void la_one(float &th, float &la, float c0, float c1)
 }
 
 template <int OP, bool NT>
-__global__ __launch_bounds__(kBlock) void novak_lookahead_kernel(Tables tb, float c0, float c1) {
-  const novak_chunk ch = tb.chunks[blockIdx.x];
-  const int len = ch.len;
-  float *__restrict__ th_p = tb.param[ch.tensor] + ch.offset;
-  float *__restrict__ la_p = tb.la[ch.tensor] + ch.offset;
+__global__ __launch_bounds__(kBlock) void novak_lookahead_kernel(Tables tb, float c0, float c1, int sub_shift) {
+  constexpr int SUB = kBlock * 4;
+  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * SUB;
+  if (start >= ch.len) return;
+  const int n = min(SUB, ch.len - start);
+  const int64_t off = ch.offset + start;
+  float *__restrict__ th_p = tb.param[ch.tensor] + off;
+  float *__restrict__ la_p = tb.la[ch.tensor] + off;
   const uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
   int done = 0;
   if (mis == 0) {
-    const int nvec = len >> 2;
+    const int nvec = n >> 2;
     f32x4 *th4 = reinterpret_cast<f32x4 *>(th_p);
     f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
     for (int i = threadIdx.x; i < nvec; i += kBlock) {
@@ -247,7 +262,7 @@ __global__ __launch_bounds__(kBlock) void novak_lookahead_kernel(Tables tb, floa
     }
     done = nvec << 2;
   }
-  for (int i = done + threadIdx.x; i < len; i += kBlock) {
+  for (int i = done + threadIdx.x; i < n; i += kBlock) {
     float th = 0.0f, la = 0.0f;
     if (OP != SYNC_ME) th = th_p[i];
     if (OP != LA_INIT) la = la_p[i];
@@ -274,6 +289,7 @@ struct novak_handle {
   int64_t chunk_elems = NOVAK_CHUNK_DEFAULT;
   int64_t n_chunks = 0;
   int nontemporal = 1;
+  int vec_per_lane = 1;             // 128-bit accesses per stream per lane (UN): 1, 2 or 4
   int64_t last_step = 0;
   int sync_due = 0;
   // device-side tables (owned)
@@ -350,7 +366,8 @@ int build_chunk_table(novak_handle *h) {
   int64_t n = 0;
   int rc = novak_plan_chunks(h->numels.data(), static_cast<int32_t>(h->numels.size()), h->chunk_elems, nullptr, 0, &n);
   if (rc != NOVAK_OK) return fail(h, rc, "chunk planning failed");
-  if (n > 0x7fffffffLL) return fail(h, NOVAK_ERR_INVALID_ARG, "too many chunks for one launch; raise chunk_elems");
+  // one workgroup per 1024 elements of a chunk at the finest decomposition
+  if (n * (h->chunk_elems / (kBlock * 4)) > 0x7fffffffLL) return fail(h, NOVAK_ERR_INVALID_ARG, "too many workgroups for one launch");
   std::vector<novak_chunk> table(static_cast<size_t>(n));
   rc = novak_plan_chunks(h->numels.data(), static_cast<int32_t>(h->numels.size()), h->chunk_elems, table.data(), n, &n);
   if (rc != NOVAK_OK) return fail(h, rc, "chunk planning failed");
@@ -363,43 +380,72 @@ int build_chunk_table(novak_handle *h) {
   return NOVAK_OK;
 }
 
-template <typename GradS, typename GradV, bool NT>
-void launch_step_la(int la, dim3 grid, hipStream_t s, const Tables &tb, const Consts &c) {
+int log2_exact(int64_t x) {
+  int s = 0;
+  while ((int64_t{1} << s) < x) ++s;
+  return s;
+}
+
+// grid size and sub-block shift for a kernel whose workgroups cover `sub_elems` elements each
+struct Geometry {
+  unsigned grid;
+  int sub_shift;
+};
+Geometry geometry_of(const novak_handle *h, int sub_elems) {
+  Geometry gm;
+  gm.sub_shift = log2_exact(h->chunk_elems / sub_elems);
+  gm.grid = static_cast<unsigned>(h->n_chunks << gm.sub_shift);
+  return gm;
+}
+
+template <typename GradS, typename GradV, bool NT, int UN>
+void launch_step_la(int la, const Geometry &gm, hipStream_t s, const Tables &tb, const Consts &c) {
+  const dim3 grid(gm.grid), block(kBlock);
   switch (la) {
-    case LA_OFF: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_OFF, NT>), grid, dim3(kBlock), 0, s, tb, c); break;
-    case LA_FIRST: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_FIRST, NT>), grid, dim3(kBlock), 0, s, tb, c); break;
-    case LA_MID: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_MID, NT>), grid, dim3(kBlock), 0, s, tb, c); break;
-    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_LAST_FUSED, NT>), grid, dim3(kBlock), 0, s, tb, c); break;
-    default: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_BASIC_FUSED, NT>), grid, dim3(kBlock), 0, s, tb, c); break;
+    case LA_OFF: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_OFF, NT, UN>), grid, block, 0, s, tb, c, gm.sub_shift); break;
+    case LA_FIRST: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_FIRST, NT, UN>), grid, block, 0, s, tb, c, gm.sub_shift); break;
+    case LA_MID: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_MID, NT, UN>), grid, block, 0, s, tb, c, gm.sub_shift); break;
+    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_LAST_FUSED, NT, UN>), grid, block, 0, s, tb, c, gm.sub_shift); break;
+    default: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_BASIC_FUSED, NT, UN>), grid, block, 0, s, tb, c, gm.sub_shift); break;
   }
 }
 
-void launch_step(int grad_dtype, bool nt, int la, dim3 grid, hipStream_t s, const Tables &tb, const Consts &c) {
-  if (grad_dtype == NOVAK_GRAD_BF16) {
-    if (nt) launch_step_la<unsigned short, u16x4, true>(la, grid, s, tb, c);
-    else launch_step_la<unsigned short, u16x4, false>(la, grid, s, tb, c);
-  } else {
-    if (nt) launch_step_la<float, f32x4, true>(la, grid, s, tb, c);
-    else launch_step_la<float, f32x4, false>(la, grid, s, tb, c);
+template <bool NT, int UN>
+void launch_step_dtype(int grad_dtype, int la, const Geometry &gm, hipStream_t s, const Tables &tb, const Consts &c) {
+  if (grad_dtype == NOVAK_GRAD_BF16) launch_step_la<unsigned short, u16x4, NT, UN>(la, gm, s, tb, c);
+  else launch_step_la<float, f32x4, NT, UN>(la, gm, s, tb, c);
+}
+
+template <bool NT>
+void launch_step_un(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+  switch (h->vec_per_lane) {
+    case 1: launch_step_dtype<NT, 1>(grad_dtype, la, geometry_of(h, kBlock * 4 * 1), s, tb, c); break;
+    case 2: launch_step_dtype<NT, 2>(grad_dtype, la, geometry_of(h, kBlock * 4 * 2), s, tb, c); break;
+    default: launch_step_dtype<NT, 4>(grad_dtype, la, geometry_of(h, kBlock * 4 * 4), s, tb, c); break;
   }
+}
+
+void launch_step(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+  if (h->nontemporal) launch_step_un<true>(h, grad_dtype, la, s, tb, c);
+  else launch_step_un<false>(h, grad_dtype, la, s, tb, c);
 }
 
 template <int OP>
-void launch_la(bool nt, dim3 grid, hipStream_t s, const Tables &tb, float c0, float c1) {
-  if (nt) hipLaunchKernelGGL((novak_lookahead_kernel<OP, true>), grid, dim3(kBlock), 0, s, tb, c0, c1);
-  else hipLaunchKernelGGL((novak_lookahead_kernel<OP, false>), grid, dim3(kBlock), 0, s, tb, c0, c1);
+void launch_la(const novak_handle *h, hipStream_t s, const Tables &tb, float c0, float c1) {
+  const Geometry gm = geometry_of(h, kBlock * 4);
+  if (h->nontemporal) hipLaunchKernelGGL((novak_lookahead_kernel<OP, true>), dim3(gm.grid), dim3(kBlock), 0, s, tb, c0, c1, gm.sub_shift);
+  else hipLaunchKernelGGL((novak_lookahead_kernel<OP, false>), dim3(gm.grid), dim3(kBlock), 0, s, tb, c0, c1, gm.sub_shift);
 }
 
 int launch_sync(novak_handle *h, hipStream_t s) {
   if (h->n_chunks == 0) return NOVAK_OK;
   const Tables tb = tables_of(h);
-  const dim3 grid(static_cast<unsigned>(h->n_chunks));
   if (h->hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT) {
-    launch_la<SYNC_ME>(h->nontemporal != 0, grid, s, tb, 0.0f, 0.0f);
+    launch_la<SYNC_ME>(h, s, tb, 0.0f, 0.0f);
   } else {
     const float c1 = static_cast<float>(h->hp.la_alpha);
     const float c0 = static_cast<float>(1.0 - h->hp.la_alpha);
-    launch_la<SYNC_BASIC>(h->nontemporal != 0, grid, s, tb, c0, c1);
+    launch_la<SYNC_BASIC>(h, s, tb, c0, c1);
   }
   NOVAK_HIP(h, hipGetLastError());
   return NOVAK_OK;
@@ -516,8 +562,13 @@ int novak_set_tuning(novak_handle *h, int32_t key, int64_t value) {
     h->nontemporal = value ? 1 : 0;
     return NOVAK_OK;
   }
+  if (key == NOVAK_TUNE_VEC_PER_LANE) {
+    if (value != 1 && value != 2 && value != 4) return fail(h, NOVAK_ERR_INVALID_ARG, "vec_per_lane must be 1, 2 or 4");
+    h->vec_per_lane = static_cast<int>(value);
+    return NOVAK_OK;
+  }
   if (key == NOVAK_TUNE_CHUNK_ELEMS) {
-    if (value < NOVAK_CHUNK_MIN || value > NOVAK_CHUNK_MAX || value % NOVAK_CHUNK_MIN) return fail(h, NOVAK_ERR_INVALID_ARG, "chunk_elems must be a multiple of 1024 in [1024, 2^24]");
+    if (value < NOVAK_CHUNK_MIN || value > NOVAK_CHUNK_MAX || (value & (value - 1))) return fail(h, NOVAK_ERR_INVALID_ARG, "chunk_elems must be a power of two in [4096, 2^24]");
     if (value == h->chunk_elems) return NOVAK_OK;
     DeviceScope scope;
     NOVAK_HIP(h, scope.enter(h->device_id));
@@ -538,7 +589,7 @@ int novak_lookahead_init(novak_handle *h, void *hip_stream) {
   if (h->n_chunks == 0) return NOVAK_OK;
   DeviceScope scope;
   NOVAK_HIP(h, scope.enter(h->device_id));
-  launch_la<LA_INIT>(h->nontemporal != 0, dim3(static_cast<unsigned>(h->n_chunks)), static_cast<hipStream_t>(hip_stream), tables_of(h), 0.0f, 0.0f);
+  launch_la<LA_INIT>(h, static_cast<hipStream_t>(hip_stream), tables_of(h), 0.0f, 0.0f);
   NOVAK_HIP(h, hipGetLastError());
   return NOVAK_OK;
 }
@@ -623,7 +674,7 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
       std::memcpy(h->last_grads.data(), grads, n * sizeof(void *));
       h->grads_uploaded = true;
     }
-    launch_step(grad_dtype, h->nontemporal != 0, la, dim3(static_cast<unsigned>(h->n_chunks)), stream, tables_of(h), c);
+    launch_step(h, grad_dtype, la, stream, tables_of(h), c);
     NOVAK_HIP(h, hipGetLastError());
     if (sync_after) {
       rc = launch_sync(h, stream);

@@ -117,7 +117,7 @@ int novak_plan_chunks(const int64_t *numels, int32_t n_tensors, int64_t chunk_el
                       int64_t capacity, int64_t *n_chunks) {
   if (!n_chunks || (n_tensors > 0 && !numels)) return NOVAK_ERR_NULL_POINTER;
   if (n_tensors < 0 || capacity < 0 || (capacity > 0 && !out)) return NOVAK_ERR_INVALID_ARG;
-  if (chunk_elems < NOVAK_CHUNK_MIN || chunk_elems > NOVAK_CHUNK_MAX || (chunk_elems % NOVAK_CHUNK_MIN) != 0)
+  if (chunk_elems < NOVAK_CHUNK_MIN || chunk_elems > NOVAK_CHUNK_MAX || (chunk_elems & (chunk_elems - 1)) != 0)
     return NOVAK_ERR_INVALID_ARG;
   int64_t n = 0;
   for (int32_t t = 0; t < n_tensors; ++t) {

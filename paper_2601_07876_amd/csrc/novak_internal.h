@@ -4,9 +4,9 @@
 
 #include "novak.h"
 
-// chunk sizes are multiples of NOVAK_CHUNK_MIN so that a chunk start keeps a 16-byte aligned
-// tensor 16-byte aligned for every element type
-#define NOVAK_CHUNK_MIN 1024
+// chunk sizes are powers of two >= NOVAK_CHUNK_MIN: a chunk splits evenly into the workgroups'
+// sub-blocks (1024, 2048 or 4096 elements) and a chunk start keeps a 16-byte aligned tensor aligned
+#define NOVAK_CHUNK_MIN 4096
 #define NOVAK_CHUNK_MAX (1 << 24)
 #define NOVAK_CHUNK_DEFAULT 16384
 

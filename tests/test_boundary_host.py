@@ -89,7 +89,7 @@ def test_prologue_matches_oracle_scalars(beta2, rectified, fallback):
 
 
 @pytest.mark.parametrize("name", W.WORKLOAD_NAMES + ("ragged",))
-@pytest.mark.parametrize("chunk", [1024, 16384, 65536])
+@pytest.mark.parametrize("chunk", [4096, 16384, 65536])
 def test_chunk_table_covers_every_element_exactly_once(name, chunk):
     numels = W.get_workload(name).numels
     rc, table = N.novak_plan_chunks(numels, chunk)
@@ -107,13 +107,15 @@ def test_chunk_table_covers_every_element_exactly_once(name, chunk):
 
 
 def test_chunk_planner_edge_cases():
-    assert N.novak_plan_chunks([], 1024) == (N.NOVAK_OK, [])
-    assert N.novak_plan_chunks([0, 0], 1024) == (N.NOVAK_OK, [])
-    assert N.novak_plan_chunks([1], 1024) == (N.NOVAK_OK, [(0, 0, 1)])
-    assert N.novak_plan_chunks([1024, 1025], 1024)[1] == [(0, 0, 1024), (1, 0, 1024), (1, 1024, 1)]
-    assert N.novak_plan_chunks([5], 1000)[0] == N.NOVAK_ERR_INVALID_ARG        # not a multiple of 1024
+    assert N.novak_plan_chunks([], 4096) == (N.NOVAK_OK, [])
+    assert N.novak_plan_chunks([0, 0], 4096) == (N.NOVAK_OK, [])
+    assert N.novak_plan_chunks([1], 4096) == (N.NOVAK_OK, [(0, 0, 1)])
+    assert N.novak_plan_chunks([4096, 4097], 4096)[1] == [(0, 0, 4096), (1, 0, 4096), (1, 4096, 1)]
+    assert N.novak_plan_chunks([5], 5000)[0] == N.NOVAK_ERR_INVALID_ARG        # not a power of two
+    assert N.novak_plan_chunks([5], 12288)[0] == N.NOVAK_ERR_INVALID_ARG       # multiple of 4096, not a power of two
+    assert N.novak_plan_chunks([5], 2048)[0] == N.NOVAK_ERR_INVALID_ARG        # below the minimum
     assert N.novak_plan_chunks([5], 0)[0] == N.NOVAK_ERR_INVALID_ARG
-    assert N.novak_plan_chunks([-1], 1024)[0] == N.NOVAK_ERR_INVALID_ARG
+    assert N.novak_plan_chunks([-1], 4096)[0] == N.NOVAK_ERR_INVALID_ARG
     # 64-bit offsets: a 3e9-element tensor
     rc, table = N.novak_plan_chunks([3_000_000_000], 1 << 24)
     assert rc == N.NOVAK_OK and table[-1][1] + table[-1][2] == 3_000_000_000 and table[-1][1] > 2 ** 31

@@ -82,7 +82,7 @@ def test_ragged_all_modes(nesterov, lookahead, grad_dtype, auto_sync):
 def test_ragged_switches(fallback, rectified, decoupled):
     wl = W.get_workload("ragged")
     hyper = dict(wl.hyper, unrect_fallback=fallback, rectified=rectified, decoupled_decay=decoupled, weight_decay=0.05)
-    gpu, states, _ = H.run_pair(wl.numels, hyper, wl.steps, wl.grad_std, chunk_elems=1024)
+    gpu, states, _ = H.run_pair(wl.numels, hyper, wl.steps, wl.grad_std, chunk_elems=4096)
     try:
         H.compare_states(gpu, states)
     finally:
@@ -96,7 +96,7 @@ def test_misaligned_views_take_the_elementwise_path(grad_dtype, misalign, grad_m
     wl = W.get_workload("ragged")
     _say(f"misaligned {grad_dtype} {misalign} {grad_misalign}")
     gpu, states, _ = H.run_pair(wl.numels, wl.hyper, 6, wl.grad_std, grad_dtype, misalign=misalign,
-                                grad_misalign=grad_misalign, guard=8, chunk_elems=2048)
+                                grad_misalign=grad_misalign, guard=8, chunk_elems=8192)
     try:
         H.compare_states(gpu, states)
         assert gpu.guards_intact()
@@ -108,8 +108,8 @@ def test_results_do_not_depend_on_chunking_or_cache_hints():
     """Elementwise independence on the GPU: any chunk size / hint gives bit-identical results."""
     wl = W.get_workload("ragged")
     outs = []
-    for chunk, nt in ((1024, True), (16384, True), (65536, False), (1 << 20, False)):
-        gpu, _, _ = H.run_pair(wl.numels, wl.hyper, 7, wl.grad_std, chunk_elems=chunk, nontemporal=nt)
+    for chunk, nt, vpl in ((4096, True, 1), (16384, True, 2), (65536, False, 4), (1 << 20, False, 1), (4096, True, 4)):
+        gpu, _, _ = H.run_pair(wl.numels, wl.hyper, 7, wl.grad_std, chunk_elems=chunk, nontemporal=nt, vec_per_lane=vpl)
         outs.append([gpu.host(r) for r in ("theta", "m", "v", "la")])
         gpu.close()
     for other in outs[1:]:
