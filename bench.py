@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--chunk-elems", type=int, default=None)
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--vec-per-lane", type=int, default=None)
+    ap.add_argument("--threads", type=int, default=None)
+    ap.add_argument("--waves-per-cu", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 21, help="elements of the oracle's timed sample")
     return ap.parse_args()
@@ -139,6 +141,10 @@ def main():
         N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_NONTEMPORAL, args.nontemporal), "set_tuning", handle)
     if args.vec_per_lane is not None:
         N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_VEC_PER_LANE, args.vec_per_lane), "set_tuning", handle)
+    if args.threads is not None:
+        N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_THREADS, args.threads), "set_tuning", handle)
+    if args.waves_per_cu is not None:
+        N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_WAVES_PER_CU, args.waves_per_cu), "set_tuning", handle)
     rc, info = N.novak_get_info(handle)
     la_name = {0: "none", 1: "memory_efficient", 2: "basic"}[info.lookahead_mode]
     nest_name = {0: "none", 1: "approx", 2: "classical", 3: "true"}[info.nesterov_mode]

@@ -139,7 +139,10 @@ typedef struct novak_info {
 enum {
   NOVAK_TUNE_CHUNK_ELEMS = 0,   /* elements per chunk-table entry; a power of two in [4096, 2^24] */
   NOVAK_TUNE_NONTEMPORAL = 1,   /* 0/1: non-temporal hints on the streaming loads and stores */
-  NOVAK_TUNE_VEC_PER_LANE = 2   /* 1, 2 or 4: 128-bit accesses per stream per lane; a workgroup covers 1024x that many elements */
+  NOVAK_TUNE_VEC_PER_LANE = 2,  /* 1, 2 or 4: 128-bit accesses per stream per lane */
+  NOVAK_TUNE_THREADS = 3,       /* 64, 128 or 256 threads per workgroup; a workgroup covers threads*4*vec_per_lane elements */
+  NOVAK_TUNE_WAVES_PER_CU = 4   /* 0..32: cap on waves resident per compute unit (bounds the bytes in flight);
+                                   0 = chosen per kernel variant from its number of streams */
 };
 
 /* ---- host-only helpers (no GPU needed) -------------------------------------------------------- */

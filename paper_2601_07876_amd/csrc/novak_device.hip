@@ -4,8 +4,8 @@
 //
 // The step is HBM-bound (section 5.5 of the paper: 4 streams read, 3 written per element, a few
 // dozen flops), so the kernel is built around memory streams, not arithmetic:
-//   * a chunk-table entry never spans tensors and is covered by short-lived workgroups (4 wave64)
-//     that each touch 1024..4096 consecutive elements once;
+//   * a chunk-table entry never spans tensors and is covered by short-lived workgroups (one wave64
+//     by default) that each touch 256..4096 consecutive elements once;
 //   * each lane moves 128 bits per stream per access (4 fp32; 4 bf16 gradients = 64 bits), and all
 //     loads of a workgroup are issued before any arithmetic;
 //   * per-step scalars arrive as kernel arguments (SGPRs); nothing is read from memory except the
@@ -26,7 +26,7 @@
 
 namespace {
 
-constexpr int kBlock = 256;   // 4 wave64 per workgroup
+constexpr int kMinSub = 64 * 4;   // elements covered by the smallest workgroup (one wave64, one 128-bit access per lane)
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
@@ -40,14 +40,19 @@ enum : int {
   LA_BASIC_FUSED = 4   // k-th step, basic mode:   S = c1*theta_new + c0*S; theta_out=S (S read, written)
 };
 
-enum : uint32_t { F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u };
+enum : uint32_t { F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u, F_FAST = 16u };
+
+// The four state pointers of a tensor sit together so that one 32-byte scalar load fetches them.
+struct TensorPtrs {
+  float *param;
+  float *m;
+  float *v;
+  float *la;
+};
 
 struct Tables {
   const novak_chunk *chunks;
-  float *const *param;
-  float *const *m;
-  float *const *v;
-  float *const *la;
+  const TensorPtrs *tensors;
   const void *const *grad;
 };
 
@@ -79,7 +84,8 @@ __device__ __forceinline__ void update_one(float &th, float g, float &m, float &
   float u = m_hat;
   if (c.flags & F_DENOM) {
     const float v_hat = v * c.inv_bc2;                                  // Eq. 5
-    u = m_hat / (__builtin_sqrtf(v_hat) + c.eps);                       // Eq. 17
+    if (c.flags & F_FAST) u = m_hat * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(v_hat) + c.eps);
+    else u = m_hat / (__builtin_sqrtf(v_hat) + c.eps);                  // Eq. 17
   }
   if (c.flags & F_CLASSICAL) u = __builtin_fmaf(c.beta1, m_hat, c.omb1 * u);   // Eq. 16
   // Eq. 18 + Eq. 24 in additive form: one rounding at theta's magnitude per step
@@ -135,26 +141,29 @@ constexpr bool la_writes(int la) { return la == LA_FIRST || la == LA_MID || la =
 
 // Work decomposition.  A chunk-table entry covers up to chunk_elems (a power of two) elements of one
 // tensor; it is processed by chunk_elems / SUB workgroups ("sub-blocks"), each of which touches
-// SUB = kBlock*4*UN consecutive elements exactly once and exits.  Short-lived workgroups dispatched
+// SUB = BLOCK*4*UN consecutive elements exactly once and exits.  The default is BLOCK = 64, UN = 1:
+// one wave64 per 256 elements, one 128-bit access per lane and stream.  Short-lived workgroups dispatched
 // in address order keep the set of DRAM pages that are open at any moment small, which is what the
 // write path of this memory system rewards; the table stays small because its granularity is
 // decoupled from the workgroup's.  blockIdx.x = (chunk index << sub_shift) | sub-block index.
 //
 // GradS: scalar gradient type (float, or unsigned short holding bf16 bits); GradV its 4-vector.
-template <typename GradS, typename GradV, int LA, bool NT, int UN>
-__global__ __launch_bounds__(kBlock) void novak_step_kernel(Tables tb, Consts c, int sub_shift) {
-  constexpr int SUB = kBlock * 4 * UN;
+template <typename GradS, typename GradV, int LA, bool NT, int UN, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, int sub_shift) {
+  constexpr int SUB = BLOCK * 4 * UN;
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
   const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * SUB;
   if (start >= ch.len) return;
   const int n = min(SUB, ch.len - start);
   const int64_t off = ch.offset + start;
-  float *__restrict__ th_p = tb.param[ch.tensor] + off;
-  float *__restrict__ m_p = tb.m[ch.tensor] + off;
-  float *__restrict__ v_p = tb.v[ch.tensor] + off;
-  const GradS *__restrict__ g_p = static_cast<const GradS *>(tb.grad[ch.tensor]) + off;
+  const TensorPtrs tp = tb.tensors[ch.tensor];          // one scalar load, issued together with the next
+  const void *const g_base = tb.grad[ch.tensor];
+  float *__restrict__ th_p = tp.param + off;
+  float *__restrict__ m_p = tp.m + off;
+  float *__restrict__ v_p = tp.v + off;
+  const GradS *__restrict__ g_p = static_cast<const GradS *>(g_base) + off;
   float *__restrict__ la_p = nullptr;
-  if (LA != LA_OFF) la_p = tb.la[ch.tensor] + off;
+  if (LA != LA_OFF) la_p = tp.la + off;
 
   uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) |
                    reinterpret_cast<uintptr_t>(v_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
@@ -173,7 +182,7 @@ __global__ __launch_bounds__(kBlock) void novak_step_kernel(Tables tb, Consts c,
       GradV g[UN];
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
-        const int j = threadIdx.x + u * kBlock;
+        const int j = threadIdx.x + u * BLOCK;
         th[u] = ld<NT>(th4 + j);
         g[u] = ld<NT>(g4 + j);
         m[u] = ld<NT>(m4 + j);
@@ -182,7 +191,7 @@ __global__ __launch_bounds__(kBlock) void novak_step_kernel(Tables tb, Consts c,
       }
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
-        const int j = threadIdx.x + u * kBlock;
+        const int j = threadIdx.x + u * BLOCK;
         update_vec<LA>(th[u], grad_to_f32<GradV>(g[u]), m[u], v[u], la[u], c);
         st<NT>(th4 + j, th[u]);
         st<NT>(m4 + j, m[u]);
@@ -192,7 +201,7 @@ __global__ __launch_bounds__(kBlock) void novak_step_kernel(Tables tb, Consts c,
       return;
     }
     const int nvec = n >> 2;
-    for (int i = threadIdx.x; i < nvec; i += kBlock) {
+    for (int i = threadIdx.x; i < nvec; i += BLOCK) {
       f32x4 th = ld<NT>(th4 + i), m = ld<NT>(m4 + i), v = ld<NT>(v4 + i), la;
       GradV g = ld<NT>(g4 + i);
       if (la_reads(LA)) la = ld<NT>(la4 + i);
@@ -205,7 +214,7 @@ __global__ __launch_bounds__(kBlock) void novak_step_kernel(Tables tb, Consts c,
     done = nvec << 2;
   }
   // element-wise path: the < 4 element tail of an aligned sub-block, or a whole unaligned one
-  for (int i = done + threadIdx.x; i < n; i += kBlock) {
+  for (int i = done + threadIdx.x; i < n; i += BLOCK) {
     float th = th_p[i], m = m_p[i], v = v_p[i], la = 0.0f, g;
     if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
     else g = g_p[i];
@@ -231,23 +240,24 @@ __device__ __forceinline__ void la_one(float &th, float &la, float c0, float c1)
   else la = th;
 }
 
-template <int OP, bool NT>
-__global__ __launch_bounds__(kBlock) void novak_lookahead_kernel(Tables tb, float c0, float c1, int sub_shift) {
-  constexpr int SUB = kBlock * 4;
+template <int OP, bool NT, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void novak_lookahead_kernel(Tables tb, float c0, float c1, int sub_shift) {
+  constexpr int SUB = BLOCK * 4;
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
   const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * SUB;
   if (start >= ch.len) return;
   const int n = min(SUB, ch.len - start);
   const int64_t off = ch.offset + start;
-  float *__restrict__ th_p = tb.param[ch.tensor] + off;
-  float *__restrict__ la_p = tb.la[ch.tensor] + off;
+  const TensorPtrs tp = tb.tensors[ch.tensor];
+  float *__restrict__ th_p = tp.param + off;
+  float *__restrict__ la_p = tp.la + off;
   const uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
   int done = 0;
   if (mis == 0) {
     const int nvec = n >> 2;
     f32x4 *th4 = reinterpret_cast<f32x4 *>(th_p);
     f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
-    for (int i = threadIdx.x; i < nvec; i += kBlock) {
+    for (int i = threadIdx.x; i < nvec; i += BLOCK) {
       f32x4 th, la;
       if (OP != SYNC_ME) th = ld<NT>(th4 + i);
       if (OP != LA_INIT) la = ld<NT>(la4 + i);
@@ -262,7 +272,7 @@ __global__ __launch_bounds__(kBlock) void novak_lookahead_kernel(Tables tb, floa
     }
     done = nvec << 2;
   }
-  for (int i = done + threadIdx.x; i < n; i += kBlock) {
+  for (int i = done + threadIdx.x; i < n; i += BLOCK) {
     float th = 0.0f, la = 0.0f;
     if (OP != SYNC_ME) th = th_p[i];
     if (OP != LA_INIT) la = la_p[i];
@@ -290,11 +300,14 @@ struct novak_handle {
   int64_t n_chunks = 0;
   int nontemporal = 1;
   int vec_per_lane = 1;             // 128-bit accesses per stream per lane (UN): 1, 2 or 4
+  int threads = 64;                 // workgroup size: 64, 128 or 256 (one to four wave64)
+  int waves_per_cu = 0;             // cap on resident waves per compute unit; 0 = chosen per kernel variant
+  int lds_per_cu = 160 * 1024;      // LDS of one compute unit (queried at create)
   int64_t last_step = 0;
   int sync_due = 0;
   // device-side tables (owned)
   novak_chunk *d_chunks = nullptr;
-  void *d_ptrs = nullptr;           // 5 arrays of n_tensors pointers: param, m, v, la, grad
+  void *d_ptrs = nullptr;           // n_tensors TensorPtrs records, then n_tensors gradient pointers
   // pinned staging ring for the per-step gradient pointer list
   static constexpr int kRing = 4;
   void **h_ring = nullptr;
@@ -348,11 +361,8 @@ Tables tables_of(const novak_handle *h) {
   char *base = static_cast<char *>(h->d_ptrs);
   Tables tb;
   tb.chunks = h->d_chunks;
-  tb.param = reinterpret_cast<float *const *>(base);
-  tb.m = reinterpret_cast<float *const *>(base + 1 * n * sizeof(void *));
-  tb.v = reinterpret_cast<float *const *>(base + 2 * n * sizeof(void *));
-  tb.la = reinterpret_cast<float *const *>(base + 3 * n * sizeof(void *));
-  tb.grad = reinterpret_cast<const void *const *>(base + 4 * n * sizeof(void *));
+  tb.tensors = reinterpret_cast<const TensorPtrs *>(base);
+  tb.grad = reinterpret_cast<const void *const *>(base + n * sizeof(TensorPtrs));
   return tb;
 }
 
@@ -366,8 +376,8 @@ int build_chunk_table(novak_handle *h) {
   int64_t n = 0;
   int rc = novak_plan_chunks(h->numels.data(), static_cast<int32_t>(h->numels.size()), h->chunk_elems, nullptr, 0, &n);
   if (rc != NOVAK_OK) return fail(h, rc, "chunk planning failed");
-  // one workgroup per 1024 elements of a chunk at the finest decomposition
-  if (n * (h->chunk_elems / (kBlock * 4)) > 0x7fffffffLL) return fail(h, NOVAK_ERR_INVALID_ARG, "too many workgroups for one launch");
+  // one workgroup per 256 elements of a chunk at the finest decomposition
+  if (n * (h->chunk_elems / kMinSub) > 0x7fffffffLL) return fail(h, NOVAK_ERR_INVALID_ARG, "too many workgroups for one launch");
   std::vector<novak_chunk> table(static_cast<size_t>(n));
   rc = novak_plan_chunks(h->numels.data(), static_cast<int32_t>(h->numels.size()), h->chunk_elems, table.data(), n, &n);
   if (rc != NOVAK_OK) return fail(h, rc, "chunk planning failed");
@@ -390,51 +400,93 @@ int log2_exact(int64_t x) {
 struct Geometry {
   unsigned grid;
   int sub_shift;
+  unsigned lds;   // dynamic LDS bytes requested per workgroup (never touched; bounds residency)
 };
-Geometry geometry_of(const novak_handle *h, int sub_elems) {
+// `streams16` = 128-bit-per-lane stream equivalents the kernel keeps in flight per wave (reads plus
+// writes; a bf16 gradient stream counts 0.5).  Measured on MI355X, achieved bandwidth peaks when a
+// compute unit has roughly 80 such 1 KB wave-accesses outstanding and falls by 5-10 % at full
+// occupancy, so residency is capped by requesting LDS that the kernel never touches.
+Geometry geometry_of(const novak_handle *h, int sub_elems, int threads, double streams16) {
   Geometry gm;
   gm.sub_shift = log2_exact(h->chunk_elems / sub_elems);
   gm.grid = static_cast<unsigned>(h->n_chunks << gm.sub_shift);
+  int waves = h->waves_per_cu;                       // 0 = automatic
+  if (waves == 0) waves = static_cast<int>(80.0 / (streams16 * h->vec_per_lane) + 0.5);
+  const int waves_per_wg = threads / 64;
+  int wgs = waves / waves_per_wg;
+  if (wgs < 1) wgs = 1;
+  gm.lds = 0;
+  if (wgs * waves_per_wg < 32) {                     // 32 waves per CU is the hardware's own limit
+    unsigned bytes = (static_cast<unsigned>(h->lds_per_cu) / static_cast<unsigned>(wgs)) & ~511u;
+    if (bytes > 65536u) bytes = 65536u;              // larger requests would need an opt-in attribute
+    gm.lds = bytes;
+  }
   return gm;
 }
 
-template <typename GradS, typename GradV, bool NT, int UN>
+double step_streams16(int grad_dtype, int la) {
+  double s = 3.0 + (grad_dtype == NOVAK_GRAD_BF16 ? 0.5 : 1.0) + 3.0;   // theta, m, v, g read; theta, m, v written
+  if (la_reads(la)) s += 1.0;
+  if (la_writes(la)) s += 1.0;
+  return s;
+}
+
+template <typename GradS, typename GradV, bool NT, int UN, int BLOCK>
 void launch_step_la(int la, const Geometry &gm, hipStream_t s, const Tables &tb, const Consts &c) {
-  const dim3 grid(gm.grid), block(kBlock);
+  const dim3 grid(gm.grid), block(BLOCK);
   switch (la) {
-    case LA_OFF: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_OFF, NT, UN>), grid, block, 0, s, tb, c, gm.sub_shift); break;
-    case LA_FIRST: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_FIRST, NT, UN>), grid, block, 0, s, tb, c, gm.sub_shift); break;
-    case LA_MID: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_MID, NT, UN>), grid, block, 0, s, tb, c, gm.sub_shift); break;
-    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_LAST_FUSED, NT, UN>), grid, block, 0, s, tb, c, gm.sub_shift); break;
-    default: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_BASIC_FUSED, NT, UN>), grid, block, 0, s, tb, c, gm.sub_shift); break;
+    case LA_OFF: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_OFF, NT, UN, BLOCK>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_FIRST: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_FIRST, NT, UN, BLOCK>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_MID: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_MID, NT, UN, BLOCK>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_LAST_FUSED, NT, UN, BLOCK>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    default: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_BASIC_FUSED, NT, UN, BLOCK>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
   }
 }
 
-template <bool NT, int UN>
-void launch_step_dtype(int grad_dtype, int la, const Geometry &gm, hipStream_t s, const Tables &tb, const Consts &c) {
-  if (grad_dtype == NOVAK_GRAD_BF16) launch_step_la<unsigned short, u16x4, NT, UN>(la, gm, s, tb, c);
-  else launch_step_la<float, f32x4, NT, UN>(la, gm, s, tb, c);
+template <bool NT, int UN, int BLOCK>
+void launch_step_dtype(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+  const Geometry gm = geometry_of(h, BLOCK * 4 * UN, BLOCK, step_streams16(grad_dtype, la));
+  if (grad_dtype == NOVAK_GRAD_BF16) launch_step_la<unsigned short, u16x4, NT, UN, BLOCK>(la, gm, s, tb, c);
+  else launch_step_la<float, f32x4, NT, UN, BLOCK>(la, gm, s, tb, c);
+}
+
+template <bool NT, int BLOCK>
+void launch_step_un(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+  switch (h->vec_per_lane) {
+    case 1: launch_step_dtype<NT, 1, BLOCK>(h, grad_dtype, la, s, tb, c); break;
+    case 2: launch_step_dtype<NT, 2, BLOCK>(h, grad_dtype, la, s, tb, c); break;
+    default: launch_step_dtype<NT, 4, BLOCK>(h, grad_dtype, la, s, tb, c); break;
+  }
 }
 
 template <bool NT>
-void launch_step_un(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
-  switch (h->vec_per_lane) {
-    case 1: launch_step_dtype<NT, 1>(grad_dtype, la, geometry_of(h, kBlock * 4 * 1), s, tb, c); break;
-    case 2: launch_step_dtype<NT, 2>(grad_dtype, la, geometry_of(h, kBlock * 4 * 2), s, tb, c); break;
-    default: launch_step_dtype<NT, 4>(grad_dtype, la, geometry_of(h, kBlock * 4 * 4), s, tb, c); break;
+void launch_step_block(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+  switch (h->threads) {
+    case 64: launch_step_un<NT, 64>(h, grad_dtype, la, s, tb, c); break;
+    case 128: launch_step_un<NT, 128>(h, grad_dtype, la, s, tb, c); break;
+    default: launch_step_un<NT, 256>(h, grad_dtype, la, s, tb, c); break;
   }
 }
 
 void launch_step(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
-  if (h->nontemporal) launch_step_un<true>(h, grad_dtype, la, s, tb, c);
-  else launch_step_un<false>(h, grad_dtype, la, s, tb, c);
+  if (h->nontemporal) launch_step_block<true>(h, grad_dtype, la, s, tb, c);
+  else launch_step_block<false>(h, grad_dtype, la, s, tb, c);
+}
+
+template <int OP, int BLOCK>
+void launch_la_block(const novak_handle *h, hipStream_t s, const Tables &tb, float c0, float c1) {
+  const Geometry gm = geometry_of(h, BLOCK * 4, BLOCK, OP == SYNC_BASIC ? 4.0 : 2.0);
+  if (h->nontemporal) hipLaunchKernelGGL((novak_lookahead_kernel<OP, true, BLOCK>), dim3(gm.grid), dim3(BLOCK), gm.lds, s, tb, c0, c1, gm.sub_shift);
+  else hipLaunchKernelGGL((novak_lookahead_kernel<OP, false, BLOCK>), dim3(gm.grid), dim3(BLOCK), gm.lds, s, tb, c0, c1, gm.sub_shift);
 }
 
 template <int OP>
 void launch_la(const novak_handle *h, hipStream_t s, const Tables &tb, float c0, float c1) {
-  const Geometry gm = geometry_of(h, kBlock * 4);
-  if (h->nontemporal) hipLaunchKernelGGL((novak_lookahead_kernel<OP, true>), dim3(gm.grid), dim3(kBlock), 0, s, tb, c0, c1, gm.sub_shift);
-  else hipLaunchKernelGGL((novak_lookahead_kernel<OP, false>), dim3(gm.grid), dim3(kBlock), 0, s, tb, c0, c1, gm.sub_shift);
+  switch (h->threads) {
+    case 64: launch_la_block<OP, 64>(h, s, tb, c0, c1); break;
+    case 128: launch_la_block<OP, 128>(h, s, tb, c0, c1); break;
+    default: launch_la_block<OP, 256>(h, s, tb, c0, c1); break;
+  }
 }
 
 int launch_sync(novak_handle *h, hipStream_t s) {
@@ -502,16 +554,19 @@ int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor
   DeviceScope scope;
   hipError_t e = scope.enter(device_id);
   if (e != hipSuccess) return bail(fail_hip(h, e, "hipSetDevice"));
+  int lds_cu = 0;
+  if (hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, device_id) == hipSuccess && lds_cu >= 65536)
+    h->lds_per_cu = lds_cu;
   if (n_tensors > 0) {
     const size_t n = static_cast<size_t>(n_tensors);
     const size_t bytes = 5 * n * sizeof(void *);
     if ((e = hipMalloc(&h->d_ptrs, bytes)) != hipSuccess) return bail(fail_hip(h, e, "hipMalloc(pointer tables)"));
     std::vector<void *> host(5 * n, nullptr);
     for (size_t i = 0; i < n; ++i) {
-      host[0 * n + i] = tensors[i].param;
-      host[1 * n + i] = tensors[i].exp_avg;
-      host[2 * n + i] = tensors[i].exp_avg_sq;
-      host[3 * n + i] = tensors[i].la_buf;
+      host[4 * i + 0] = tensors[i].param;      // TensorPtrs record i
+      host[4 * i + 1] = tensors[i].exp_avg;
+      host[4 * i + 2] = tensors[i].exp_avg_sq;
+      host[4 * i + 3] = tensors[i].la_buf;
     }
     if ((e = hipMemcpy(h->d_ptrs, host.data(), bytes, hipMemcpyHostToDevice)) != hipSuccess) return bail(fail_hip(h, e, "hipMemcpy(pointer tables)"));
     if ((e = hipHostMalloc(reinterpret_cast<void **>(&h->h_ring), novak_handle::kRing * n * sizeof(void *), hipHostMallocDefault)) != hipSuccess)
@@ -560,6 +615,16 @@ int novak_set_tuning(novak_handle *h, int32_t key, int64_t value) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
   if (key == NOVAK_TUNE_NONTEMPORAL) {
     h->nontemporal = value ? 1 : 0;
+    return NOVAK_OK;
+  }
+  if (key == NOVAK_TUNE_WAVES_PER_CU) {
+    if (value < 0 || value > 32) return fail(h, NOVAK_ERR_INVALID_ARG, "waves_per_cu must be in [0, 32]");
+    h->waves_per_cu = static_cast<int>(value);
+    return NOVAK_OK;
+  }
+  if (key == NOVAK_TUNE_THREADS) {
+    if (value != 64 && value != 128 && value != 256) return fail(h, NOVAK_ERR_INVALID_ARG, "threads must be 64, 128 or 256");
+    h->threads = static_cast<int>(value);
     return NOVAK_OK;
   }
   if (key == NOVAK_TUNE_VEC_PER_LANE) {
@@ -631,6 +696,7 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
   if (hp.nesterov_mode == NOVAK_NESTEROV_CLASSICAL) c.flags |= F_CLASSICAL;
   if (sc.denom_on) c.flags |= F_DENOM;
   if (!hp.decoupled_decay && hp.weight_decay != 0.0) c.flags |= F_COUPLED;
+  if (getenv("NOVAK_EXPERIMENT_FAST")) c.flags |= F_FAST;
 
   // lookahead phase of this step: position in the k-step window (section 4.7; sync when t mod k == 0)
   int la = LA_OFF;

@@ -23,7 +23,7 @@ NOVAK_UNRECT_ADAM_DENOM, NOVAK_UNRECT_SGDM = 0, 1
 NOVAK_MODE_FAST, NOVAK_MODE_RESEARCH = 0, 1
 NOVAK_GRAD_F32, NOVAK_GRAD_BF16 = 0, 1
 NOVAK_WARN_TRUE_NESTEROV_DOWNGRADED, NOVAK_WARN_LOOKAHEAD_DOWNGRADED = 1, 2
-NOVAK_TUNE_CHUNK_ELEMS, NOVAK_TUNE_NONTEMPORAL, NOVAK_TUNE_VEC_PER_LANE = 0, 1, 2
+NOVAK_TUNE_CHUNK_ELEMS, NOVAK_TUNE_NONTEMPORAL, NOVAK_TUNE_VEC_PER_LANE, NOVAK_TUNE_THREADS, NOVAK_TUNE_WAVES_PER_CU = 0, 1, 2, 3, 4
 
 NESTEROV = {"none": 0, "approx": 1, "classical": 2, "true": 3}
 LOOKAHEAD = {"none": 0, "memory_efficient": 1, "basic": 2}

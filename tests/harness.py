@@ -44,7 +44,7 @@ class GpuNovak:
                  theta0: Optional[List[np.ndarray]] = None, misalign: int = 0, guard: int = 0,
                  chunk_elems: Optional[int] = None, nontemporal: Optional[bool] = None,
                  auto_sync: bool = False, device: str = "cuda:0", lookahead_init: bool = True,
-                 vec_per_lane: Optional[int] = None):
+                 vec_per_lane: Optional[int] = None, threads: Optional[int] = None):
         self.numels = list(numels)
         self.hyper = dict(hyper)
         self.grad_dtype = grad_dtype
@@ -74,6 +74,8 @@ class GpuNovak:
             N.check(N.novak_set_tuning(self.handle, N.NOVAK_TUNE_NONTEMPORAL, int(nontemporal)), "set_tuning", self.handle)
         if vec_per_lane is not None:
             N.check(N.novak_set_tuning(self.handle, N.NOVAK_TUNE_VEC_PER_LANE, vec_per_lane), "set_tuning", self.handle)
+        if threads is not None:
+            N.check(N.novak_set_tuning(self.handle, N.NOVAK_TUNE_THREADS, threads), "set_tuning", self.handle)
         rc, info = N.novak_get_info(self.handle)
         N.check(rc, "novak_get_info", self.handle)
         self.info = info
@@ -160,11 +162,11 @@ def assert_close_strict(name: str, got: np.ndarray, ref: np.ndarray, rtol: float
 def run_pair(numels: Sequence[int], hyper: Dict[str, object], steps: int, grad_std: float, grad_dtype: str = "f32",
              seed: int = 42, auto_sync: bool = False, chunk_elems: Optional[int] = None,
              nontemporal: Optional[bool] = None, misalign: int = 0, grad_misalign: int = 0, guard: int = 0,
-             check_blend_at: Sequence[int] = (), vec_per_lane: Optional[int] = None):
+             check_blend_at: Sequence[int] = (), vec_per_lane: Optional[int] = None, threads: Optional[int] = None):
     """Runs GPU and oracle over host-generated inputs; returns (gpu, oracle states) after `steps`."""
     theta0 = W.host_params(numels, seed)
     gpu = GpuNovak(numels, hyper, grad_dtype, theta0, misalign=misalign, guard=guard, chunk_elems=chunk_elems,
-                   nontemporal=nontemporal, auto_sync=auto_sync, vec_per_lane=vec_per_lane)
+                   nontemporal=nontemporal, auto_sync=auto_sync, vec_per_lane=vec_per_lane, threads=threads)
     h = oracle_hyper(hyper, gpu.eff_nesterov, gpu.eff_lookahead)
     states = [O.init_state(th, h) for th in theta0]
     for t in range(1, steps + 1):

@@ -108,8 +108,10 @@ def test_results_do_not_depend_on_chunking_or_cache_hints():
     """Elementwise independence on the GPU: any chunk size / hint gives bit-identical results."""
     wl = W.get_workload("ragged")
     outs = []
-    for chunk, nt, vpl in ((4096, True, 1), (16384, True, 2), (65536, False, 4), (1 << 20, False, 1), (4096, True, 4)):
-        gpu, _, _ = H.run_pair(wl.numels, wl.hyper, 7, wl.grad_std, chunk_elems=chunk, nontemporal=nt, vec_per_lane=vpl)
+    for chunk, nt, vpl, thr in ((4096, True, 1, 64), (16384, True, 2, 128), (65536, False, 4, 256), (1 << 20, False, 1, 64),
+                                (4096, True, 4, 256), (4096, False, 4, 64), (8192, True, 1, 256), (16384, True, 2, 64)):
+        gpu, _, _ = H.run_pair(wl.numels, wl.hyper, 7, wl.grad_std, chunk_elems=chunk, nontemporal=nt, vec_per_lane=vpl,
+                               threads=thr)
         outs.append([gpu.host(r) for r in ("theta", "m", "v", "la")])
         gpu.close()
     for other in outs[1:]:
