@@ -44,7 +44,7 @@ def parse_args():
     ap.add_argument("--threads", type=int, default=None)
     ap.add_argument("--waves-per-cu", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 21, help="elements of the oracle's timed sample")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 22, help="elements of the oracle's timed sample")
     return ap.parse_args()
 
 
@@ -62,27 +62,31 @@ def la_variant(lookahead: str, k: int, t: int, fused: bool) -> str:
     return "step+basic_fused" if (pos == k and fused) else "step"
 
 
-def cpu_baseline(wl, hyper, n_sample: int):
-    """The oracle, as it stands, on the first n_sample elements of the workload's largest tensor."""
-    import numpy as np
+def cpu_baseline(wl, hyper, n_sample: int, budget_s: float = 12.0, max_steps: int = 200):
+    """The oracle, as it stands, on the first n_sample elements of the workload's largest tensor.
+
+    Bounded: steps (with their syncs) are run until `budget_s` seconds of oracle time have been spent
+    or `max_steps` steps are done; gradient generation is not timed.
+    """
     import workloads as W
     from oracle import novak_oracle as O
 
     n = min(n_sample, max(wl.numels))
     h = O.Hyper(**{k: v for k, v in hyper.items() if k not in ("mode", "auto_sync")})
     theta0 = W.host_params([n], 42)
-    steps = 2 * h.la_k + 1 if h.lookahead != "none" else 11
-    grads = [W.host_grads([n], t, wl.grad_std, 42, bf16=(wl.grad_dtype == "bf16"))[0] for t in range(1, steps + 1)]
     states = [O.init_state(theta0[0], h)]
-    t0 = time.perf_counter()
-    for t in range(1, steps + 1):
-        O.step(states[0], grads[t - 1], t, h)
-        if O.sync_due(t, h):
+    dt, steps = 0.0, 0
+    while steps < max_steps and (dt < budget_s or (h.lookahead != "none" and steps % h.la_k != 0)):
+        steps += 1
+        g = W.host_grads([n], steps, wl.grad_std, 42, bf16=(wl.grad_dtype == "bf16"))[0]
+        t0 = time.perf_counter()
+        O.step(states[0], g, steps, h)
+        if O.sync_due(steps, h):
             O.lookahead_sync(states[0], h)
-    dt = time.perf_counter() - t0
+        dt += time.perf_counter() - t0
     return {"value": n * steps / dt / 1e9, "unit": "Gparams/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {n} elements of the largest tensor, {steps} steps incl. syncs, numpy fp64 arithmetic / fp32 state, {dt:.1f} s",
-            "host_cpus_visible": os.cpu_count()}
+            "sample": f"first {n} elements of the largest tensor, {steps} steps incl. syncs, numpy fp64 arithmetic / "
+                      f"fp32 state, {dt:.1f} s of oracle time", "host_cpus_visible": os.cpu_count()}
 
 
 def main():
