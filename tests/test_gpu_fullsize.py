@@ -188,3 +188,22 @@ def test_c5_decoder_1p3b_sweep():
                 _say(f"c5 k={k} nesterov={nest} done")
     finally:
         run.close()
+
+
+def test_single_tensor_beyond_2_31_elements():
+    """Maximum-size edge case: one tensor of 2^31 + 4099 elements (element offsets need 64 bits, the
+    element count is odd so the last sub-block has a ragged tail), plus a tiny neighbour."""
+    big = (1 << 31) + 4099
+    wl = W.Workload("huge_single", ((big,), (7,)), 1e-3, "f32", 6, dict(W.BASE_HYPER))
+    run = FullRun(wl, samples_per_tensor=4096)
+    try:
+        # make sure the far end of the tensor is among the samples
+        assert int(run.idx_host.max()) > (1 << 31)
+        run.reset(wl.hyper)
+        for t in range(1, 7):
+            run.step()
+            if t in (1, 5, 6):
+                run.check(f"huge t={t}")
+        _say("huge done")
+    finally:
+        run.close()
