@@ -28,6 +28,16 @@ Readings taken where the paper is silent or inconsistent (each is a named switch
   * nesterov "true": the gradient handed in is already the one evaluated at the extrapolated point
     (Eq. 10-11 need a model); the moment pipeline of Eq. 24 then runs as for "none".
   * nesterov "classical": Eq. 16 literally (blend of un-normalised m_hat with the normalised u).
+  * layer adaptation (Eq. 19 / 25), per tensor: eta = ||theta||_2 / ||u||_2 with theta the parameters
+    BEFORE this step's decay/update and u the base direction of Eq. 17 (Table 2 computes the ratio in
+    Phase 7, before the classical blend of Phase 8); clipped to [0.1, 10]; eta = 1 when either norm is
+    zero (LAMB's convention; the paper is silent).  parity unpinned by the paper for these choices.
+  * auto-LR (Eq. 20-22): EMAs (gamma = 0.1, started at 0) of the GLOBAL norms over all tensors (Table 3
+    stores two scalars), of the gradient as handed in and of the parameters before the step;
+    alpha_auto = clip(g_bar / theta_bar, 0.1, 2), and 1 when theta_bar is 0.  Eq. 23 is a second,
+    different formula for the same symbol that the paper calls an alternative; it is not used.
+    parity unpinned by the paper for scope, initial value and the gradient's processing stage.
+  * alpha_eff = alpha * r_t * eta_clipped * alpha_auto (Eq. 24a); the decay keeps the base alpha.
 """
 from __future__ import annotations
 
@@ -58,6 +68,11 @@ class Hyper:
     nesterov: str = "approx"
     lookahead: str = "memory_efficient"
     unrect_fallback: str = "adam_denom"
+    layer_adaptation: bool = False      # Eq. 19 / 25 (full-features mode)
+    auto_lr: bool = False               # Eq. 20-22 (full-features mode)
+    auto_lr_gamma: float = 0.1
+    trust_clip: tuple = (0.1, 10.0)
+    auto_clip: tuple = (0.1, 2.0)
 
     def __post_init__(self):
         assert self.nesterov in NESTEROV_MODES
@@ -129,11 +144,39 @@ def init_state(theta0: np.ndarray, h: Hyper, state_dtype=np.float32) -> TensorSt
     return st
 
 
-def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper) -> StepScalars:
+def trust_ratio(theta: np.ndarray, u: np.ndarray, h: Hyper) -> float:
+    """Clipped layer-wise trust ratio of one tensor (Eq. 19, Eq. 25)."""
+    n_theta = math.sqrt(float(np.dot(theta, theta)))
+    n_u = math.sqrt(float(np.dot(u, u)))
+    eta = n_theta / n_u if (n_theta > 0.0 and n_u > 0.0) else 1.0
+    return min(max(eta, h.trust_clip[0]), h.trust_clip[1])
+
+
+@dataclass
+class AutoLrState:
+    """The two scalars of Table 3: EMAs of the gradient norm and the parameter norm (Eq. 20-21)."""
+    g_bar: float = 0.0
+    theta_bar: float = 0.0
+
+
+def auto_lr_scale(aux: AutoLrState, thetas, grads, h: Hyper) -> float:
+    """Updates the EMAs from the global norms (Eq. 20-21) and returns alpha_auto (Eq. 22)."""
+    g2 = sum(float(np.dot(x, x)) for x in (np.asarray(g, dtype=np.float64).reshape(-1) for g in grads))
+    t2 = sum(float(np.dot(x, x)) for x in (np.asarray(th, dtype=np.float64).reshape(-1) for th in thetas))
+    gam = h.auto_lr_gamma
+    aux.g_bar = gam * math.sqrt(g2) + (1.0 - gam) * aux.g_bar          # Eq. 20
+    aux.theta_bar = gam * math.sqrt(t2) + (1.0 - gam) * aux.theta_bar  # Eq. 21
+    if aux.theta_bar == 0.0:
+        return 1.0
+    return min(max(aux.g_bar / aux.theta_bar, h.auto_clip[0]), h.auto_clip[1])   # Eq. 22
+
+
+def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float = 1.0) -> StepScalars:
     """One update of one tensor at step t (Phases 2-9), then record the iterate for lookahead.
 
     `grad` holds the gradient values (any float dtype; bf16 gradients arrive as the fp32/fp64
     numbers they exactly represent).  The sync of Phase 10 is a separate call: `lookahead_sync`.
+    `alpha_auto` is the step-wide auto-LR factor (1 unless h.auto_lr; see `auto_lr_scale`).
     """
     s = step_scalars(h, t)
     dt = st.dtype
@@ -154,9 +197,11 @@ def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper) -> StepScalars:
         u = m_hat / (np.sqrt(v_hat) + h.eps)                # Eq. 17
     else:
         u = m_hat                                           # momentum-SGD fallback while rho_t < 5
+    lam_trust = trust_ratio(theta, u, h) if h.layer_adaptation else 1.0   # Eq. 19 / 25 (Phase 7)
     if h.nesterov == "classical":
         u = h.beta1 * m_hat + (1.0 - h.beta1) * u           # Eq. 16
-    theta = theta * s.decay - s.step_size * u               # Eq. 18 then Eq. 24
+    alpha_eff = s.step_size * lam_trust * alpha_auto        # Eq. 24a
+    theta = theta * s.decay - alpha_eff * u                 # Eq. 18 then Eq. 24
 
     st.theta = theta.astype(dt)
     st.m = m.astype(dt)
@@ -201,15 +246,27 @@ def blend_buffer(st: TensorState, h: Hyper) -> np.ndarray:
     return acc
 
 
+def step_all(states: List[TensorState], grads, t: int, h: Hyper, aux: Optional[AutoLrState] = None) -> float:
+    """One step over a tensor list: the step-wide auto-LR factor first (Phase 7), then every tensor."""
+    alpha_auto = 1.0
+    if h.auto_lr:
+        assert aux is not None, "auto_lr needs its two EMA scalars"
+        alpha_auto = auto_lr_scale(aux, [st.theta for st in states], grads, h)
+    for st, g in zip(states, grads):
+        step(st, g, t, h, alpha_auto)
+    return alpha_auto
+
+
 def run(theta0_list, grads_fn, steps: int, h: Hyper, state_dtype=np.float32, t0: int = 0,
-        states: Optional[List[TensorState]] = None) -> List[TensorState]:
+        states: Optional[List[TensorState]] = None, aux: Optional[AutoLrState] = None) -> List[TensorState]:
     """Run `steps` steps over a list of tensors; grads_fn(t) returns the gradient list of step t."""
     if states is None:
         states = [init_state(th, h, state_dtype) for th in theta0_list]
+    if aux is None:
+        aux = AutoLrState()
     for t in range(t0 + 1, t0 + steps + 1):
         grads = grads_fn(t)
-        for st, g in zip(states, grads):
-            step(st, g, t, h)
+        step_all(states, grads, t, h, aux)
         if sync_due(t, h):
             for st in states:
                 lookahead_sync(st, h)

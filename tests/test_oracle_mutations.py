@@ -21,9 +21,9 @@ MUTATIONS = {
     "nesterov_uses_new_m": ("g = g + h.beta_n * (g - m_prev)", "g = g + h.beta_n * (g - (h.beta1 * m_prev + (1.0 - h.beta1) * g))"),
     "eps_inside_root": ("u = m_hat / (np.sqrt(v_hat) + h.eps)", "u = m_hat / np.sqrt(v_hat + h.eps)"),
     "no_v_bias_correction": ("v_hat = v / s.bc2", "v_hat = v"),
-    "double_bias_correction": ("theta = theta * s.decay - s.step_size * u", "theta = theta * s.decay - s.step_size / s.bc1 * u"),
+    "double_bias_correction": ("theta = theta * s.decay - alpha_eff * u", "theta = theta * s.decay - alpha_eff / s.bc1 * u"),
     "decay_with_rectified_lr": ("decay = 1.0 - h.lr * h.weight_decay if", "decay = 1.0 - h.lr * r_t * h.weight_decay if"),
-    "decay_after_update": ("theta = theta * s.decay - s.step_size * u", "theta = (theta - s.step_size * u) * s.decay"),
+    "decay_after_update": ("theta = theta * s.decay - alpha_eff * u", "theta = (theta - alpha_eff * u) * s.decay"),
     "threshold_four": ("if rho_t >= 5.0:", "if rho_t >= 4.0:"),
     "rho_missing_denominator": ("rho_t = rho_inf - 2.0 * t * beta2_t / bc2", "rho_t = rho_inf - 2.0 * t * beta2_t"),
     "r_t_no_sqrt": ("r_t = math.sqrt((rho_t - 4.0)", "r_t = ((rho_t - 4.0)"),
@@ -78,7 +78,7 @@ def _n_disagreements(M) -> int:
 
 def test_unmutated_source_passes():
     text = open(SRC).read()
-    anchor = "theta = theta * s.decay - s.step_size * u"
+    anchor = "theta = theta * s.decay - alpha_eff * u"
     assert _n_disagreements(_load_mutant(anchor, anchor)) == 0
 
 
