@@ -59,14 +59,17 @@ enum { NOVAK_GRAD_F32 = 0, NOVAK_GRAD_BF16 = 1 };
 /* warning bits reported by novak_validate_hparams / novak_get_info (section 7.3: downgrades warn) */
 enum {
   NOVAK_WARN_TRUE_NESTEROV_DOWNGRADED = 1u << 0,  /* FAST + TRUE        -> APPROX           */
-  NOVAK_WARN_LOOKAHEAD_DOWNGRADED = 1u << 1       /* FAST + BASIC       -> MEMORY_EFFICIENT */
+  NOVAK_WARN_LOOKAHEAD_DOWNGRADED = 1u << 1,      /* FAST + BASIC       -> MEMORY_EFFICIENT */
+  NOVAK_WARN_LAYER_ADAPTATION_DISABLED = 1u << 2, /* FAST + layer_adaptation -> off (section 7.1) */
+  NOVAK_WARN_AUTO_LR_DISABLED = 1u << 3           /* FAST + auto_lr          -> off (section 7.1) */
 };
 
 /* ---- hyper-parameters (host memory, plain data) -------------------------------------------------
  * Rules checked (section 5.8 "Hyperparameter validation", section 7.3): lr > 0; beta1, beta2 in
  * [0,1); weight_decay >= 0; beta_n in [0,1); la_k >= 1; eps > 0; beta2 < 1 - 1e-8 when rectified;
  * la_alpha in (0,1] when lookahead is on (the paper's open bound at 1 is relaxed so that the
- * alpha_LA = 1 fixed point can be exercised).  All values must be finite. */
+ * alpha_LA = 1 fixed point can be exercised); auto_lr_gamma in (0,1] and 0 < lo <= hi for both clip
+ * ranges when the respective scaling is on.  All values must be finite. */
 typedef struct novak_hparams {
   size_t struct_size;      /* sizeof(novak_hparams); guards against layout mismatch */
   double lr;               /* alpha   */
@@ -83,6 +86,14 @@ typedef struct novak_hparams {
   int32_t unrect_fallback; /* NOVAK_UNRECT_* */
   int32_t mode;            /* NOVAK_MODE_* */
   int32_t auto_sync;       /* 1: novak_step performs the sync itself, fused into the k-th step's pass */
+  /* Full-features scalings of alpha_eff = alpha * r_t * lambda_trust * alpha_auto (Eq. 24a); RESEARCH mode only.
+   * Either one turns the step into two passes over the state (norms first, then the update). */
+  int32_t layer_adaptation; /* 1: per-tensor trust ratio ||theta||/||u||, u of Eq. 17, clipped (Eq. 19, 25); 1 when a norm is 0 */
+  int32_t auto_lr;          /* 1: alpha_auto = clip(g_bar/theta_bar) from EMAs of the global gradient and parameter
+                               norms (Eq. 20-22); needs novak_set_auto_lr_state */
+  double auto_lr_gamma;     /* gamma of Eq. 20-21, in (0,1]; the paper uses 0.1 */
+  double trust_clip_lo, trust_clip_hi;   /* clip range of Eq. 19; the paper uses [0.1, 10]; 0 < lo <= hi */
+  double auto_clip_lo, auto_clip_hi;     /* clip range of Eq. 22; the paper uses [0.1, 2];  0 < lo <= hi */
 } novak_hparams;
 
 /* One parameter tensor.  All pointers are DEVICE pointers to contiguous fp32 arrays of `numel`
@@ -133,6 +144,8 @@ typedef struct novak_info {
   int64_t last_step;         /* 0 before the first step on this handle */
   int32_t sync_due;          /* 1 between a k-th step and its novak_lookahead_sync (auto_sync off) */
   int32_t device_id;
+  int32_t layer_adaptation;  /* effective */
+  int32_t auto_lr;           /* effective */
 } novak_info;
 
 /* tuning keys for novak_set_tuning */
@@ -170,6 +183,11 @@ int novak_plan_chunks(const int64_t *numels, int32_t n_tensors, int64_t chunk_el
  * `fused_sync` says whether the k-th step also performs the sync. */
 double novak_bytes_per_param_step(int32_t lookahead_mode, int32_t grad_dtype, int32_t la_k,
                                   int32_t window_pos, int32_t fused_sync);
+/* The same for a two-pass step (layer_adaptation or auto_lr on): pass 1 reads theta, g, m, v and writes
+ * m, v; pass 2 reads theta, m, v and writes theta, plus the lookahead traffic; the per-wave norm
+ * partials (16 bytes per 256 elements, written and read once) are not counted. */
+double novak_bytes_per_param_scaled_step(int32_t lookahead_mode, int32_t grad_dtype, int32_t la_k,
+                                         int32_t window_pos, int32_t fused_sync);
 /* Algorithmic bytes per parameter of the separate sync kernel. */
 double novak_bytes_per_param_sync(int32_t lookahead_mode);
 
@@ -196,6 +214,16 @@ int novak_lookahead_init(novak_handle *h, void *hip_stream);
  * t mod k == 0 leaves the handle in "sync due" state and the next call must be
  * novak_lookahead_sync; with auto_sync on, that step applies Eq. 30-31 itself. */
 int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t step, void *hip_stream);
+
+/* Auto-LR state (Table 3: two scalars): `ema` is a DEVICE pointer to two doubles owned by the caller,
+ * g_bar then theta_bar (Eq. 20-21), zero before the first step; the library updates them every step.
+ * Required before the first novak_step when auto_lr is on (else NOVAK_ERR_STATE there).  Keeping the
+ * two values is what resuming needs. */
+int novak_set_auto_lr_state(novak_handle *h, void *ema);
+
+/* Monitoring: copies lambda_trust * alpha_auto of the last two-pass step, one float per tensor, to HOST
+ * memory `out` (n_tensors floats).  Waits for `hip_stream` first.  NOVAK_ERR_STATE on a single-pass handle. */
+int novak_copy_tensor_scales(novak_handle *h, float *out, void *hip_stream);
 
 /* Eq. 30-31 over all tensors in one launch: theta <- slow_new, and the buffer is left equal to the
  * new slow weights.  Legal only when a sync is due. */

@@ -71,25 +71,36 @@ struct Consts {
 
 __device__ __forceinline__ float bf16_to_f32(unsigned short b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 
-// One element of the update.  `la` is the lookahead buffer value (read when the phase reads it,
-// returned updated when the phase writes it).
-template <int LA>
-__device__ __forceinline__ void update_one(float &th, float g, float &m, float &v, float &la, const Consts &c) {
-  const float th_in = th;
+// The update of one element, in three parts so that the two-pass (per-tensor scaled) path can reuse
+// the exact arithmetic of the fused one.
+//   moments():   Phases 2 and 4 - gradient processing and the two EMAs (Eq. 13, 1, 2)
+//   direction(): Phases 5 and 8a - bias correction and the base direction u (Eq. 5, 17)
+//   apply():     Phases 8b, 9, 10 - classical blend, decay + update, lookahead (Eq. 16, 18, 24, 28-31)
+__device__ __forceinline__ void moments(float th_in, float g, float &m, float &v, const Consts &c) {
   if (c.flags & F_COUPLED) g = __builtin_fmaf(c.wd, th_in, g);          // classic L2 reading
   if (c.flags & F_APPROX) g = __builtin_fmaf(c.beta_n, g - m, g);       // Eq. 13
   m = __builtin_fmaf(c.omb1, g - m, m);                                 // Eq. 1:  m + (1-b1)(g - m)
   v = __builtin_fmaf(c.omb2, __builtin_fmaf(g, g, -v), v);              // Eq. 2:  v + (1-b2)(g^2 - v)
-  const float m_hat = m * c.inv_bc1;                                    // Eq. 5
+}
+
+__device__ __forceinline__ float direction(float m, float v, const Consts &c, float &m_hat) {
+  m_hat = m * c.inv_bc1;                                                // Eq. 5
   float u = m_hat;
   if (c.flags & F_DENOM) {
     const float v_hat = v * c.inv_bc2;                                  // Eq. 5
-    if (c.flags & F_FAST) u = m_hat * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(v_hat) + c.eps);
-    else u = m_hat / (__builtin_sqrtf(v_hat) + c.eps);                  // Eq. 17
+    u = m_hat / (__builtin_sqrtf(v_hat) + c.eps);                       // Eq. 17
   }
+  return u;
+}
+
+// `step` is alpha*r_t, times the tensor's trust ratio and the auto-LR factor on the scaled path (Eq. 24a).
+// `la` is the lookahead buffer value (read when the phase reads it, returned updated when it writes it).
+template <int LA>
+__device__ __forceinline__ void apply(float &th, float u, float m_hat, float &la, const Consts &c, float step) {
+  const float th_in = th;
   if (c.flags & F_CLASSICAL) u = __builtin_fmaf(c.beta1, m_hat, c.omb1 * u);   // Eq. 16
   // Eq. 18 + Eq. 24 in additive form: one rounding at theta's magnitude per step
-  const float th_new = th_in - __builtin_fmaf(c.step_size, u, c.lr_wd * th_in);
+  const float th_new = th_in - __builtin_fmaf(step, u, c.lr_wd * th_in);
   th = th_new;
   if (LA == LA_FIRST) {
     la = __builtin_fmaf(c.la_c1, th_new, c.la_c0 * th_in);
@@ -101,6 +112,14 @@ __device__ __forceinline__ void update_one(float &th, float g, float &m, float &
     la = __builtin_fmaf(c.la_c1, th_new, c.la_c0 * la);
     th = la;
   }
+}
+
+template <int LA>
+__device__ __forceinline__ void update_one(float &th, float g, float &m, float &v, float &la, const Consts &c) {
+  moments(th, g, m, v, c);
+  float m_hat;
+  const float u = direction(m, v, c, m_hat);
+  apply<LA>(th, u, m_hat, la, c, c.step_size);
 }
 
 template <bool NT, typename T>
@@ -282,6 +301,236 @@ __global__ __launch_bounds__(BLOCK) void novak_lookahead_kernel(Tables tb, float
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Two-pass path for the full-features scalings (layer-wise trust ratio, Eq. 19 / 25; auto-LR, Eq.
+// 20-22).  Both need norms over whole tensors before any parameter may move, so the step splits:
+//   pass 1  novak_moments_kernel   reads theta, g, m, v; writes m, v; one partial (sum theta^2,
+//                                  sum u^2, sum g^2) per wave, u being Eq. 17's base direction
+//   reduce  chunks -> tensors -> (global)   fixed-order sums in double: results do not depend on timing
+//   pass 2  novak_apply_kernel     reads theta, m, v; recomputes u with the same arithmetic; applies
+//                                  alpha*r_t*scale[tensor] and the lookahead phase; writes theta
+// One wave64 per 256 elements in both passes, as in the fused kernel.
+// ------------------------------------------------------------------------------------------------
+constexpr int kScaledBlock = 64;
+constexpr int kScaledSub = kScaledBlock * 4;
+
+struct NormPartial {   // one per wave of pass 1
+  float theta2, u2, g2, pad;
+};
+struct NormSums {      // per chunk / per tensor, in double
+  double theta2, u2, g2;
+};
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+
+template <typename GradS, typename GradV, bool NT>
+__global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, Consts c, int sub_shift, NormPartial *partials) {
+  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kScaledSub;
+  if (start >= ch.len) return;
+  const int n = min(kScaledSub, ch.len - start);
+  const int64_t off = ch.offset + start;
+  const TensorPtrs tp = tb.tensors[ch.tensor];
+  const void *const g_base = tb.grad[ch.tensor];
+  const float *__restrict__ th_p = tp.param + off;
+  float *__restrict__ m_p = tp.m + off;
+  float *__restrict__ v_p = tp.v + off;
+  const GradS *__restrict__ g_p = static_cast<const GradS *>(g_base) + off;
+
+  uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) | reinterpret_cast<uintptr_t>(v_p)) & 15u;
+  mis |= reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1);
+
+  float s_th = 0.0f, s_u = 0.0f, s_g = 0.0f;
+  int done = 0;
+  if (mis == 0) {
+    const int nvec = n >> 2;
+    const f32x4 *th4 = reinterpret_cast<const f32x4 *>(th_p);
+    f32x4 *m4 = reinterpret_cast<f32x4 *>(m_p);
+    f32x4 *v4 = reinterpret_cast<f32x4 *>(v_p);
+    const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
+    const int i = threadIdx.x;
+    if (i < nvec) {
+      const f32x4 th = ld<NT>(th4 + i);
+      const f32x4 g = grad_to_f32<GradV>(ld<NT>(g4 + i));
+      f32x4 m = ld<NT>(m4 + i), v = ld<NT>(v4 + i);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        float m_k = m[k], v_k = v[k], m_hat;
+        moments(th[k], g[k], m_k, v_k, c);
+        const float u = direction(m_k, v_k, c, m_hat);
+        s_th = __builtin_fmaf(th[k], th[k], s_th);
+        s_u = __builtin_fmaf(u, u, s_u);
+        s_g = __builtin_fmaf(g[k], g[k], s_g);
+        m[k] = m_k; v[k] = v_k;
+      }
+      st<NT>(m4 + i, m);
+      st<NT>(v4 + i, v);
+    }
+    done = nvec << 2;
+  }
+  for (int i = done + threadIdx.x; i < n; i += kScaledBlock) {
+    const float th = th_p[i];
+    float m = m_p[i], v = v_p[i], g, m_hat;
+    if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
+    else g = g_p[i];
+    moments(th, g, m, v, c);
+    const float u = direction(m, v, c, m_hat);
+    s_th = __builtin_fmaf(th, th, s_th);
+    s_u = __builtin_fmaf(u, u, s_u);
+    s_g = __builtin_fmaf(g, g, s_g);
+    m_p[i] = m;
+    v_p[i] = v;
+  }
+  s_th = wave_sum(s_th);
+  s_u = wave_sum(s_u);
+  s_g = wave_sum(s_g);
+  if (threadIdx.x == 0) {
+    NormPartial p;
+    p.theta2 = s_th; p.u2 = s_u; p.g2 = s_g; p.pad = 0.0f;
+    partials[blockIdx.x] = p;
+  }
+}
+
+// one wave per chunk: sums the chunk's per-wave partials in a fixed order
+__global__ __launch_bounds__(64) void novak_reduce_chunks_kernel(const novak_chunk *chunks, int sub_shift,
+                                                                 const NormPartial *partials, NormSums *chunk_sums) {
+  const novak_chunk ch = chunks[blockIdx.x];
+  const int nsub = (ch.len + kScaledSub - 1) / kScaledSub;
+  const NormPartial *p = partials + (static_cast<size_t>(blockIdx.x) << sub_shift);
+  double a = 0.0, b = 0.0, g = 0.0;
+  for (int j = threadIdx.x; j < nsub; j += 64) {
+    const NormPartial x = p[j];
+    a += static_cast<double>(x.theta2);
+    b += static_cast<double>(x.u2);
+    g += static_cast<double>(x.g2);
+  }
+  a = wave_sum(a); b = wave_sum(b); g = wave_sum(g);
+  if (threadIdx.x == 0) {
+    NormSums s; s.theta2 = a; s.u2 = b; s.g2 = g;
+    chunk_sums[blockIdx.x] = s;
+  }
+}
+
+struct ScaleParams {
+  float trust_lo, trust_hi;    // clip range of Eq. 19
+  float auto_lo, auto_hi;      // clip range of Eq. 22
+  double gamma;                // EMA weight of Eq. 20-21
+  int layer_adaptation, auto_lr;
+};
+
+// one wave per tensor: per-tensor sums; the clipped trust ratio (Eq. 19 / 25) goes to scale[t]
+__global__ __launch_bounds__(64) void novak_reduce_tensors_kernel(const int *first_chunk, const NormSums *chunk_sums,
+                                                                  NormSums *tensor_sums, float *scale, ScaleParams sp) {
+  const int t = blockIdx.x;
+  const int c0 = first_chunk[t], c1 = first_chunk[t + 1];
+  double a = 0.0, b = 0.0, g = 0.0;
+  for (int j = c0 + threadIdx.x; j < c1; j += 64) {
+    const NormSums x = chunk_sums[j];
+    a += x.theta2; b += x.u2; g += x.g2;
+  }
+  a = wave_sum(a); b = wave_sum(b); g = wave_sum(g);
+  if (threadIdx.x == 0) {
+    NormSums s; s.theta2 = a; s.u2 = b; s.g2 = g;
+    tensor_sums[t] = s;
+    float eta = 1.0f;
+    if (sp.layer_adaptation) {
+      // eta = ||theta|| / ||u||, 1 when either norm is zero; clipped
+      double r = (a > 0.0 && b > 0.0) ? sqrt(a / b) : 1.0;
+      r = r < static_cast<double>(sp.trust_lo) ? static_cast<double>(sp.trust_lo) : r;
+      r = r > static_cast<double>(sp.trust_hi) ? static_cast<double>(sp.trust_hi) : r;
+      eta = static_cast<float>(r);
+    }
+    scale[t] = eta;
+  }
+}
+
+// one wave: global norms -> EMAs (Eq. 20-21, state in `ema`: g_bar, theta_bar) -> alpha_auto (Eq. 22),
+// folded into every tensor's scale
+__global__ __launch_bounds__(64) void novak_auto_lr_kernel(int n_tensors, const NormSums *tensor_sums, float *scale,
+                                                           double *ema, ScaleParams sp) {
+  double a = 0.0, g = 0.0;
+  for (int j = threadIdx.x; j < n_tensors; j += 64) {
+    a += tensor_sums[j].theta2;
+    g += tensor_sums[j].g2;
+  }
+  a = wave_sum(a); g = wave_sum(g);
+  // every lane holds the same sums; every lane computes the same factor
+  const double g_bar = sp.gamma * sqrt(g) + (1.0 - sp.gamma) * ema[0];
+  const double th_bar = sp.gamma * sqrt(a) + (1.0 - sp.gamma) * ema[1];
+  double f = 1.0;
+  if (th_bar != 0.0) {
+    f = g_bar / th_bar;
+    f = f < static_cast<double>(sp.auto_lo) ? static_cast<double>(sp.auto_lo) : f;
+    f = f > static_cast<double>(sp.auto_hi) ? static_cast<double>(sp.auto_hi) : f;
+  }
+  const float ff = static_cast<float>(f);
+  for (int j = threadIdx.x; j < n_tensors; j += 64) scale[j] *= ff;
+  __syncthreads();   // all lanes have read ema before lane 0 replaces it
+  if (threadIdx.x == 0) {
+    ema[0] = g_bar;
+    ema[1] = th_bar;
+  }
+}
+
+template <int LA, bool NT>
+__global__ __launch_bounds__(kScaledBlock) void novak_apply_kernel(Tables tb, Consts c, int sub_shift, const float *scale) {
+  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kScaledSub;
+  if (start >= ch.len) return;
+  const int n = min(kScaledSub, ch.len - start);
+  const int64_t off = ch.offset + start;
+  const TensorPtrs tp = tb.tensors[ch.tensor];
+  const float step = c.step_size * scale[ch.tensor];                    // Eq. 24a
+  float *__restrict__ th_p = tp.param + off;
+  const float *__restrict__ m_p = tp.m + off;
+  const float *__restrict__ v_p = tp.v + off;
+  float *__restrict__ la_p = nullptr;
+  if (LA != LA_OFF) la_p = tp.la + off;
+  const uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) |
+                         reinterpret_cast<uintptr_t>(v_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
+  int done = 0;
+  if (mis == 0) {
+    const int nvec = n >> 2;
+    f32x4 *th4 = reinterpret_cast<f32x4 *>(th_p);
+    const f32x4 *m4 = reinterpret_cast<const f32x4 *>(m_p);
+    const f32x4 *v4 = reinterpret_cast<const f32x4 *>(v_p);
+    f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
+    const int i = threadIdx.x;
+    if (i < nvec) {
+      f32x4 th = ld<NT>(th4 + i), la;
+      const f32x4 m = ld<NT>(m4 + i), v = ld<NT>(v4 + i);
+      if (la_reads(LA)) la = ld<NT>(la4 + i);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        float th_k = th[k], la_k = la[k], m_hat;
+        const float u = direction(m[k], v[k], c, m_hat);
+        apply<LA>(th_k, u, m_hat, la_k, c, step);
+        th[k] = th_k; la[k] = la_k;
+      }
+      st<NT>(th4 + i, th);
+      if (la_writes(LA)) st<NT>(la4 + i, la);
+    }
+    done = nvec << 2;
+  }
+  for (int i = done + threadIdx.x; i < n; i += kScaledBlock) {
+    float th = th_p[i], la = 0.0f, m_hat;
+    if (la_reads(LA)) la = la_p[i];
+    const float u = direction(m_p[i], v_p[i], c, m_hat);
+    apply<LA>(th, u, m_hat, la, c, step);
+    th_p[i] = th;
+    if (la_writes(LA)) la_p[i] = la;
+  }
+}
+
 thread_local std::string g_create_error = "";
 
 }  // namespace
@@ -305,6 +554,13 @@ struct novak_handle {
   int lds_per_cu = 160 * 1024;      // LDS of one compute unit (queried at create)
   int64_t last_step = 0;
   int sync_due = 0;
+  // two-pass path (layer adaptation / auto-LR): library-owned reduction scratch, rebuilt with the table
+  NormPartial *d_partials = nullptr;   // one per wave of pass 1
+  NormSums *d_chunk_sums = nullptr;    // one per chunk
+  NormSums *d_tensor_sums = nullptr;   // one per tensor
+  int *d_first_chunk = nullptr;        // n_tensors + 1: chunk range of each tensor
+  float *d_scale = nullptr;            // n_tensors: lambda_trust * alpha_auto
+  double *d_ema = nullptr;             // caller-owned: g_bar, theta_bar
   // device-side tables (owned)
   novak_chunk *d_chunks = nullptr;
   void *d_ptrs = nullptr;           // n_tensors TensorPtrs records, then n_tensors gradient pointers
@@ -366,9 +622,21 @@ Tables tables_of(const novak_handle *h) {
   return tb;
 }
 
+bool two_pass(const novak_handle *h) { return h->hp.layer_adaptation || h->hp.auto_lr; }
+
 void free_device_tables(novak_handle *h) {
   if (h->d_chunks) (void)hipFree(h->d_chunks);
+  if (h->d_partials) (void)hipFree(h->d_partials);
+  if (h->d_chunk_sums) (void)hipFree(h->d_chunk_sums);
+  if (h->d_tensor_sums) (void)hipFree(h->d_tensor_sums);
+  if (h->d_first_chunk) (void)hipFree(h->d_first_chunk);
+  if (h->d_scale) (void)hipFree(h->d_scale);
   h->d_chunks = nullptr;
+  h->d_partials = nullptr;
+  h->d_chunk_sums = nullptr;
+  h->d_tensor_sums = nullptr;
+  h->d_first_chunk = nullptr;
+  h->d_scale = nullptr;
 }
 
 // (Re)build and upload the chunk table for the current chunk_elems.  Synchronous.
@@ -386,6 +654,23 @@ int build_chunk_table(novak_handle *h) {
   if (n > 0) {
     NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_chunks), static_cast<size_t>(n) * sizeof(novak_chunk)));
     NOVAK_HIP(h, hipMemcpy(h->d_chunks, table.data(), static_cast<size_t>(n) * sizeof(novak_chunk), hipMemcpyHostToDevice));
+  }
+  if (two_pass(h) && !h->tensors.empty()) {
+    const size_t nt = h->tensors.size();
+    std::vector<int> first(nt + 1, 0);
+    for (const novak_chunk &c : table) first[static_cast<size_t>(c.tensor) + 1] += 1;
+    for (size_t t = 0; t < nt; ++t) first[t + 1] += first[t];
+    NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_first_chunk), (nt + 1) * sizeof(int)));
+    NOVAK_HIP(h, hipMemcpy(h->d_first_chunk, first.data(), (nt + 1) * sizeof(int), hipMemcpyHostToDevice));
+    NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_tensor_sums), nt * sizeof(NormSums)));
+    NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_scale), nt * sizeof(float)));
+    std::vector<float> ones(nt, 1.0f);
+    NOVAK_HIP(h, hipMemcpy(h->d_scale, ones.data(), nt * sizeof(float), hipMemcpyHostToDevice));
+    if (n > 0) {
+      const size_t waves = static_cast<size_t>(n) * static_cast<size_t>(h->chunk_elems / kScaledSub);
+      NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_partials), waves * sizeof(NormPartial)));
+      NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_chunk_sums), static_cast<size_t>(n) * sizeof(NormSums)));
+    }
   }
   return NOVAK_OK;
 }
@@ -487,6 +772,59 @@ void launch_la(const novak_handle *h, hipStream_t s, const Tables &tb, float c0,
     case 128: launch_la_block<OP, 128>(h, s, tb, c0, c1); break;
     default: launch_la_block<OP, 256>(h, s, tb, c0, c1); break;
   }
+}
+
+template <bool NT>
+void launch_apply(int la, const Geometry &gm, hipStream_t s, const Tables &tb, const Consts &c, const float *scale) {
+  const dim3 grid(gm.grid), block(kScaledBlock);
+  switch (la) {
+    case LA_OFF: hipLaunchKernelGGL((novak_apply_kernel<LA_OFF, NT>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
+    case LA_FIRST: hipLaunchKernelGGL((novak_apply_kernel<LA_FIRST, NT>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
+    case LA_MID: hipLaunchKernelGGL((novak_apply_kernel<LA_MID, NT>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
+    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_apply_kernel<LA_LAST_FUSED, NT>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
+    default: hipLaunchKernelGGL((novak_apply_kernel<LA_BASIC_FUSED, NT>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
+  }
+}
+
+// The two-pass step: moments + norm partials, fixed-order reductions, scaled apply.
+int launch_scaled_step(novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+  const novak_hparams &hp = h->hp;
+  const double g16 = grad_dtype == NOVAK_GRAD_BF16 ? 0.5 : 1.0;
+  const Geometry g1 = geometry_of(h, kScaledSub, kScaledBlock, 3.0 + g16 + 2.0);
+  const dim3 grid1(g1.grid), block(kScaledBlock);
+  const bool nt = h->nontemporal != 0;
+  if (grad_dtype == NOVAK_GRAD_BF16) {
+    if (nt) hipLaunchKernelGGL((novak_moments_kernel<unsigned short, u16x4, true>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
+    else hipLaunchKernelGGL((novak_moments_kernel<unsigned short, u16x4, false>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
+  } else {
+    if (nt) hipLaunchKernelGGL((novak_moments_kernel<float, f32x4, true>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
+    else hipLaunchKernelGGL((novak_moments_kernel<float, f32x4, false>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
+  }
+  NOVAK_HIP(h, hipGetLastError());
+  ScaleParams sp;
+  sp.trust_lo = static_cast<float>(hp.trust_clip_lo);
+  sp.trust_hi = static_cast<float>(hp.trust_clip_hi);
+  sp.auto_lo = static_cast<float>(hp.auto_clip_lo);
+  sp.auto_hi = static_cast<float>(hp.auto_clip_hi);
+  sp.gamma = hp.auto_lr_gamma;
+  sp.layer_adaptation = hp.layer_adaptation;
+  sp.auto_lr = hp.auto_lr;
+  const int nt_count = static_cast<int>(h->tensors.size());
+  hipLaunchKernelGGL(novak_reduce_chunks_kernel, dim3(static_cast<unsigned>(h->n_chunks)), dim3(64), 0, s, h->d_chunks, g1.sub_shift,
+                     h->d_partials, h->d_chunk_sums);
+  hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(64), 0, s, h->d_first_chunk, h->d_chunk_sums,
+                     h->d_tensor_sums, h->d_scale, sp);
+  if (hp.auto_lr)
+    hipLaunchKernelGGL(novak_auto_lr_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, h->d_scale, h->d_ema, sp);
+  NOVAK_HIP(h, hipGetLastError());
+  double s2 = 3.0 + 1.0;   // theta, m, v read; theta written
+  if (la_reads(la)) s2 += 1.0;
+  if (la_writes(la)) s2 += 1.0;
+  const Geometry g2 = geometry_of(h, kScaledSub, kScaledBlock, s2);
+  if (nt) launch_apply<true>(la, g2, s, tb, c, h->d_scale);
+  else launch_apply<false>(la, g2, s, tb, c, h->d_scale);
+  NOVAK_HIP(h, hipGetLastError());
+  return NOVAK_OK;
 }
 
 int launch_sync(novak_handle *h, hipStream_t s) {
@@ -606,6 +944,29 @@ int novak_get_info(const novak_handle *h, novak_info *info) {
   info->last_step = h->last_step;
   info->sync_due = h->sync_due;
   info->device_id = h->device_id;
+  info->layer_adaptation = h->hp.layer_adaptation;
+  info->auto_lr = h->hp.auto_lr;
+  return NOVAK_OK;
+}
+
+int novak_set_auto_lr_state(novak_handle *h, void *ema) {
+  if (!h) return NOVAK_ERR_NULL_POINTER;
+  if (!h->hp.auto_lr) return fail(h, NOVAK_ERR_STATE, "auto_lr is off (or was disabled by the fast path)");
+  if (!ema) return fail(h, NOVAK_ERR_NULL_POINTER, "ema is NULL");
+  if (reinterpret_cast<uintptr_t>(ema) & 7u) return fail(h, NOVAK_ERR_MISALIGNED, "ema must be 8-byte aligned");
+  h->d_ema = static_cast<double *>(ema);
+  return NOVAK_OK;
+}
+
+int novak_copy_tensor_scales(novak_handle *h, float *out, void *hip_stream) {
+  if (!h) return NOVAK_ERR_NULL_POINTER;
+  if (!two_pass(h)) return fail(h, NOVAK_ERR_STATE, "the handle runs the single-pass step: there are no per-tensor scales");
+  if (h->tensors.empty()) return NOVAK_OK;
+  if (!out) return fail(h, NOVAK_ERR_NULL_POINTER, "out is NULL");
+  DeviceScope scope;
+  NOVAK_HIP(h, scope.enter(h->device_id));
+  NOVAK_HIP(h, hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
+  NOVAK_HIP(h, hipMemcpy(out, h->d_scale, h->tensors.size() * sizeof(float), hipMemcpyDeviceToHost));
   return NOVAK_OK;
 }
 
@@ -667,6 +1028,7 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
   if (step < 1) return fail(h, NOVAK_ERR_BAD_STEP, "step must be >= 1 (Eq. 5 is undefined at t = 0)");
   if (h->last_step != 0 && step != h->last_step + 1) return fail(h, NOVAK_ERR_BAD_STEP, "step must be the previous step + 1");
   if (h->sync_due) return fail(h, NOVAK_ERR_STATE, "a lookahead sync is due before the next step");
+  if (h->hp.auto_lr && !h->d_ema) return fail(h, NOVAK_ERR_STATE, "auto_lr is on but novak_set_auto_lr_state was not called");
   const uintptr_t amask = grad_dtype == NOVAK_GRAD_BF16 ? 1u : 3u;
   for (size_t i = 0; i < n; ++i) {
     if (h->numels[i] == 0) continue;
@@ -740,8 +1102,13 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
       std::memcpy(h->last_grads.data(), grads, n * sizeof(void *));
       h->grads_uploaded = true;
     }
-    launch_step(h, grad_dtype, la, stream, tables_of(h), c);
-    NOVAK_HIP(h, hipGetLastError());
+    if (two_pass(h)) {
+      rc = launch_scaled_step(h, grad_dtype, la, stream, tables_of(h), c);
+      if (rc != NOVAK_OK) return rc;
+    } else {
+      launch_step(h, grad_dtype, la, stream, tables_of(h), c);
+      NOVAK_HIP(h, hipGetLastError());
+    }
     if (sync_after) {
       rc = launch_sync(h, stream);
       if (rc != NOVAK_OK) return rc;

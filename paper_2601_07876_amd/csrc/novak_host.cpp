@@ -10,7 +10,8 @@
 namespace {
 
 bool finite_all(const novak_hparams &hp) {
-  const double vals[] = {hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, hp.beta_n, hp.la_alpha};
+  const double vals[] = {hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, hp.beta_n, hp.la_alpha,
+                         hp.auto_lr_gamma, hp.trust_clip_lo, hp.trust_clip_hi, hp.auto_clip_lo, hp.auto_clip_hi};
   for (double x : vals)
     if (!std::isfinite(x)) return false;
   return true;
@@ -62,6 +63,12 @@ int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, ui
   if (hp->mode != NOVAK_MODE_FAST && hp->mode != NOVAK_MODE_RESEARCH) return NOVAK_ERR_INVALID_ARG;
   if (hp->lookahead_mode != NOVAK_LOOKAHEAD_NONE && !(hp->la_alpha > 0.0 && hp->la_alpha <= 1.0)) return NOVAK_ERR_INVALID_ARG;
 
+  if (hp->layer_adaptation && !(hp->trust_clip_lo > 0.0 && hp->trust_clip_lo <= hp->trust_clip_hi)) return NOVAK_ERR_INVALID_ARG;
+  if (hp->auto_lr) {
+    if (!(hp->auto_lr_gamma > 0.0 && hp->auto_lr_gamma <= 1.0)) return NOVAK_ERR_INVALID_ARG;
+    if (!(hp->auto_clip_lo > 0.0 && hp->auto_clip_lo <= hp->auto_clip_hi)) return NOVAK_ERR_INVALID_ARG;
+  }
+
   novak_hparams eff = *hp;
   uint32_t warn = 0;
   // section 7.3: the fast path substitutes cheap variants for expensive ones and warns
@@ -73,6 +80,19 @@ int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, ui
     if (eff.lookahead_mode == NOVAK_LOOKAHEAD_BASIC) {
       eff.lookahead_mode = NOVAK_LOOKAHEAD_MEMORY_EFFICIENT;
       warn |= NOVAK_WARN_LOOKAHEAD_DOWNGRADED;
+    }
+  }
+  eff.layer_adaptation = eff.layer_adaptation ? 1 : 0;
+  eff.auto_lr = eff.auto_lr ? 1 : 0;
+  // section 7.1: layer adaptation and auto-LR exist only in full-features mode
+  if (eff.mode == NOVAK_MODE_FAST) {
+    if (eff.layer_adaptation) {
+      eff.layer_adaptation = 0;
+      warn |= NOVAK_WARN_LAYER_ADAPTATION_DISABLED;
+    }
+    if (eff.auto_lr) {
+      eff.auto_lr = 0;
+      warn |= NOVAK_WARN_AUTO_LR_DISABLED;
     }
   }
   eff.rectified = eff.rectified ? 1 : 0;
@@ -149,6 +169,12 @@ double novak_bytes_per_param_step(int32_t lookahead_mode, int32_t grad_dtype, in
     if (window_pos == la_k && fused_sync) bytes += 8;   // slow weights read and written
   }
   return bytes;
+}
+
+double novak_bytes_per_param_scaled_step(int32_t lookahead_mode, int32_t grad_dtype, int32_t la_k, int32_t window_pos,
+                                         int32_t fused_sync) {
+  // the single-pass figure plus pass 2 reading theta, m, v again
+  return novak_bytes_per_param_step(lookahead_mode, grad_dtype, la_k, window_pos, fused_sync) + 12;
 }
 
 double novak_bytes_per_param_sync(int32_t lookahead_mode) {

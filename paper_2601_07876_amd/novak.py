@@ -23,6 +23,7 @@ NOVAK_UNRECT_ADAM_DENOM, NOVAK_UNRECT_SGDM = 0, 1
 NOVAK_MODE_FAST, NOVAK_MODE_RESEARCH = 0, 1
 NOVAK_GRAD_F32, NOVAK_GRAD_BF16 = 0, 1
 NOVAK_WARN_TRUE_NESTEROV_DOWNGRADED, NOVAK_WARN_LOOKAHEAD_DOWNGRADED = 1, 2
+NOVAK_WARN_LAYER_ADAPTATION_DISABLED, NOVAK_WARN_AUTO_LR_DISABLED = 4, 8
 NOVAK_TUNE_CHUNK_ELEMS, NOVAK_TUNE_NONTEMPORAL, NOVAK_TUNE_VEC_PER_LANE, NOVAK_TUNE_THREADS, NOVAK_TUNE_WAVES_PER_CU = 0, 1, 2, 3, 4
 
 NESTEROV = {"none": 0, "approx": 1, "classical": 2, "true": 3}
@@ -38,7 +39,10 @@ class novak_hparams(C.Structure):
                 ("weight_decay", C.c_double), ("beta_n", C.c_double), ("la_alpha", C.c_double),
                 ("la_k", C.c_int32), ("rectified", C.c_int32), ("decoupled_decay", C.c_int32),
                 ("nesterov_mode", C.c_int32), ("lookahead_mode", C.c_int32), ("unrect_fallback", C.c_int32),
-                ("mode", C.c_int32), ("auto_sync", C.c_int32)]
+                ("mode", C.c_int32), ("auto_sync", C.c_int32),
+                ("layer_adaptation", C.c_int32), ("auto_lr", C.c_int32), ("auto_lr_gamma", C.c_double),
+                ("trust_clip_lo", C.c_double), ("trust_clip_hi", C.c_double),
+                ("auto_clip_lo", C.c_double), ("auto_clip_hi", C.c_double)]
 
 
 class novak_tensor_desc(C.Structure):
@@ -60,13 +64,15 @@ class novak_info(C.Structure):
     _fields_ = [("struct_size", C.c_size_t), ("nesterov_mode", C.c_int32), ("lookahead_mode", C.c_int32),
                 ("warnings", C.c_uint32), ("n_tensors", C.c_int32), ("n_chunks", C.c_int64),
                 ("chunk_elems", C.c_int64), ("total_numel", C.c_int64), ("last_step", C.c_int64),
-                ("sync_due", C.c_int32), ("device_id", C.c_int32)]
+                ("sync_due", C.c_int32), ("device_id", C.c_int32),
+                ("layer_adaptation", C.c_int32), ("auto_lr", C.c_int32)]
 
 
 EXPORTS = ("novak_validate_hparams", "novak_compute_step_scalars", "novak_plan_chunks",
-           "novak_bytes_per_param_step", "novak_bytes_per_param_sync", "novak_status_string",
-           "novak_create", "novak_lookahead_init", "novak_step", "novak_lookahead_sync", "novak_destroy",
-           "novak_get_info", "novak_set_tuning", "novak_last_error")
+           "novak_bytes_per_param_step", "novak_bytes_per_param_scaled_step", "novak_bytes_per_param_sync",
+           "novak_status_string", "novak_create", "novak_lookahead_init", "novak_step", "novak_lookahead_sync",
+           "novak_destroy", "novak_get_info", "novak_set_tuning", "novak_last_error", "novak_set_auto_lr_state",
+           "novak_copy_tensor_scales")
 
 _lib: Optional[C.CDLL] = None
 
@@ -87,6 +93,10 @@ def load_library() -> C.CDLL:
     lib.novak_plan_chunks.argtypes = [C.POINTER(i64), i32, i64, C.POINTER(novak_chunk), i64, C.POINTER(i64)]
     lib.novak_bytes_per_param_step.argtypes = [i32, i32, i32, i32, i32]
     lib.novak_bytes_per_param_step.restype = C.c_double
+    lib.novak_bytes_per_param_scaled_step.argtypes = [i32, i32, i32, i32, i32]
+    lib.novak_bytes_per_param_scaled_step.restype = C.c_double
+    lib.novak_set_auto_lr_state.argtypes = [vp, vp]
+    lib.novak_copy_tensor_scales.argtypes = [vp, C.POINTER(C.c_float), vp]
     lib.novak_bytes_per_param_sync.argtypes = [i32]
     lib.novak_bytes_per_param_sync.restype = C.c_double
     lib.novak_status_string.argtypes = [C.c_int]
@@ -117,13 +127,16 @@ class NovakError(RuntimeError):
 
 def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, beta_n=0.9, la_alpha=0.5, la_k=5,
                  rectified=True, decoupled_decay=True, nesterov="approx", lookahead="memory_efficient",
-                 unrect_fallback="adam_denom", mode="fast", auto_sync=False) -> novak_hparams:
+                 unrect_fallback="adam_denom", mode="fast", auto_sync=False, layer_adaptation=False, auto_lr=False,
+                 auto_lr_gamma=0.1, trust_clip=(0.1, 10.0), auto_clip=(0.1, 2.0)) -> novak_hparams:
     """Fills a novak_hparams from keyword values (mode names or their integer codes)."""
     def code(table: Dict[str, int], x):
         return table[x] if isinstance(x, str) else int(x)
     return novak_hparams(C.sizeof(novak_hparams), lr, beta1, beta2, eps, weight_decay, beta_n, la_alpha, int(la_k),
                          int(rectified), int(decoupled_decay), code(NESTEROV, nesterov), code(LOOKAHEAD, lookahead),
-                         code(UNRECT, unrect_fallback), code(MODE, mode), int(auto_sync))
+                         code(UNRECT, unrect_fallback), code(MODE, mode), int(auto_sync), int(layer_adaptation),
+                         int(auto_lr), float(auto_lr_gamma), float(trust_clip[0]), float(trust_clip[1]),
+                         float(auto_clip[0]), float(auto_clip[1]))
 
 
 # ---- the entry points, same names as the C ABI ------------------------------------------------------
@@ -160,6 +173,21 @@ def novak_plan_chunks(numels: Sequence[int], chunk_elems: int):
 
 def novak_bytes_per_param_step(lookahead_mode: int, grad_dtype: int, la_k: int, window_pos: int, fused_sync: int) -> float:
     return load_library().novak_bytes_per_param_step(lookahead_mode, grad_dtype, la_k, window_pos, fused_sync)
+
+
+def novak_bytes_per_param_scaled_step(lookahead_mode: int, grad_dtype: int, la_k: int, window_pos: int, fused_sync: int) -> float:
+    return load_library().novak_bytes_per_param_scaled_step(lookahead_mode, grad_dtype, la_k, window_pos, fused_sync)
+
+
+def novak_set_auto_lr_state(handle, ema_ptr: int) -> int:
+    return load_library().novak_set_auto_lr_state(handle, C.c_void_p(ema_ptr))
+
+
+def novak_copy_tensor_scales(handle, n_tensors: int, stream: int = 0):
+    """-> (status, list of n_tensors floats)."""
+    buf = (C.c_float * max(n_tensors, 1))()
+    rc = load_library().novak_copy_tensor_scales(handle, buf, C.c_void_p(stream))
+    return rc, [buf[i] for i in range(n_tensors)]
 
 
 def novak_bytes_per_param_sync(lookahead_mode: int) -> float:

@@ -23,12 +23,16 @@ ATOL, RTOL = 1e-7, 1e-5
 
 
 def oracle_hyper(hyper: Dict[str, object], effective_nesterov: Optional[str] = None,
-                 effective_lookahead: Optional[str] = None) -> O.Hyper:
+                 effective_lookahead: Optional[str] = None, info=None) -> O.Hyper:
+    """Oracle hyper-parameters for what the library says it effectively runs (after fast-path downgrades)."""
     h = {k: v for k, v in hyper.items() if k not in ("mode", "auto_sync")}
     if effective_nesterov is not None:
         h["nesterov"] = effective_nesterov
     if effective_lookahead is not None:
         h["lookahead"] = effective_lookahead
+    if info is not None:
+        h["layer_adaptation"] = bool(info.layer_adaptation)
+        h["auto_lr"] = bool(info.auto_lr)
     return O.Hyper(**h)
 
 
@@ -84,6 +88,10 @@ class GpuNovak:
         self.auto_sync = auto_sync
         self.la_k = int(self.hyper.get("la_k", 5))
         self._grad_arr = (C.c_void_p * max(len(self.numels), 1))()
+        self.ema = None
+        if info.auto_lr:
+            self.ema = torch.zeros(2, dtype=torch.float64, device=self.device)
+            N.check(N.novak_set_auto_lr_state(self.handle, self.ema.data_ptr()), "novak_set_auto_lr_state", self.handle)
         if lookahead_init and self.eff_lookahead != "none":
             N.check(N.novak_lookahead_init(self.handle, self.stream), "novak_lookahead_init", self.handle)
 
@@ -117,6 +125,12 @@ class GpuNovak:
     def host(self, role: str) -> List[np.ndarray]:
         torch.cuda.synchronize(self.device)
         return [x.detach().cpu().numpy().copy() for x in getattr(self, role)]
+
+    def tensor_scales(self) -> np.ndarray:
+        """lambda_trust * alpha_auto per tensor of the last two-pass step."""
+        rc, vals = N.novak_copy_tensor_scales(self.handle, len(self.numels), self.stream)
+        N.check(rc, "novak_copy_tensor_scales", self.handle)
+        return np.array(vals, dtype=np.float64)
 
     def guards_intact(self) -> bool:
         torch.cuda.synchronize(self.device)
@@ -167,14 +181,14 @@ def run_pair(numels: Sequence[int], hyper: Dict[str, object], steps: int, grad_s
     theta0 = W.host_params(numels, seed)
     gpu = GpuNovak(numels, hyper, grad_dtype, theta0, misalign=misalign, guard=guard, chunk_elems=chunk_elems,
                    nontemporal=nontemporal, auto_sync=auto_sync, vec_per_lane=vec_per_lane, threads=threads)
-    h = oracle_hyper(hyper, gpu.eff_nesterov, gpu.eff_lookahead)
+    h = oracle_hyper(hyper, gpu.eff_nesterov, gpu.eff_lookahead, gpu.info)
     states = [O.init_state(th, h) for th in theta0]
+    aux = O.AutoLrState()
     for t in range(1, steps + 1):
         gh = W.host_grads(numels, t, grad_std, seed, bf16=(grad_dtype == "bf16"))
         gd = gpu.upload_grads(gh, misalign=grad_misalign)
         N.check(gpu.step(t, gd), f"novak_step t={t}", gpu.handle)
-        for st, g in zip(states, gh):
-            O.step(st, g, t, h)
+        O.step_all(states, gh, t, h, aux)
         if t in check_blend_at and h.lookahead == "memory_efficient" and not (auto_sync and t % h.la_k == 0):
             la = gpu.host("la")
             for i, st in enumerate(states):

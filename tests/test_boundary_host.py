@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert C.sizeof(N.novak_hparams) == 8 + 7 * 8 + 8 * 4
+    assert C.sizeof(N.novak_hparams) == 8 + 7 * 8 + 10 * 4 + 5 * 8
     assert C.sizeof(N.novak_tensor_desc) == 40
     assert C.sizeof(N.novak_chunk) == 16
     hp = N.make_hparams()
@@ -60,6 +60,22 @@ def test_validation_accepts_edges():
     for bad in (dict(nesterov=4), dict(lookahead=3), dict(unrect_fallback=2), dict(mode=2), dict(nesterov=-1)):
         assert N.novak_validate_hparams(N.make_hparams(**dict(GOOD, **bad)))[0] == N.NOVAK_ERR_INVALID_ARG
     assert N.load_library().novak_validate_hparams(None, None, None) == N.NOVAK_ERR_NULL_POINTER
+
+
+def test_scaling_features_validation_and_fast_mode_switch_off():
+    ok = dict(GOOD, mode="research", layer_adaptation=True, auto_lr=True)
+    rc, eff, warn = N.novak_validate_hparams(N.make_hparams(**ok))
+    assert (rc, eff.layer_adaptation, eff.auto_lr, warn) == (0, 1, 1, 0)
+    for bad in (dict(trust_clip=(0.0, 10.0)), dict(trust_clip=(2.0, 1.0)), dict(auto_clip=(-1.0, 2.0)), dict(auto_clip=(3.0, 2.0)),
+                dict(auto_lr_gamma=0.0), dict(auto_lr_gamma=1.5), dict(auto_lr_gamma=float("nan"))):
+        assert N.novak_validate_hparams(N.make_hparams(**dict(ok, **bad)))[0] == N.NOVAK_ERR_INVALID_ARG, bad
+    # the ranges are not checked when the feature is off
+    assert N.novak_validate_hparams(N.make_hparams(**dict(GOOD, trust_clip=(0.0, 0.0), auto_lr_gamma=0.0)))[0] == N.NOVAK_OK
+    rc, eff, warn = N.novak_validate_hparams(N.make_hparams(**dict(ok, mode="fast")))
+    assert (rc, eff.layer_adaptation, eff.auto_lr) == (0, 0, 0)
+    assert warn == N.NOVAK_WARN_LAYER_ADAPTATION_DISABLED | N.NOVAK_WARN_AUTO_LR_DISABLED
+    assert N.novak_bytes_per_param_scaled_step(0, N.NOVAK_GRAD_F32, 5, 1, 0) == 40
+    assert N.novak_bytes_per_param_scaled_step(N.NOVAK_LOOKAHEAD_MEMORY_EFFICIENT, N.NOVAK_GRAD_BF16, 5, 2, 0) == 46
 
 
 def test_fast_path_downgrades_warn_and_research_mode_does_not():
