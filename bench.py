@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--nesterov", default=None, help="override: none | approx | classical | true")
     ap.add_argument("--la-k", type=int, default=None)
     ap.add_argument("--separate-sync", action="store_true", help="call novak_lookahead_sync instead of fusing the sync")
+    ap.add_argument("--layer-adaptation", action="store_true", help="research mode: per-tensor trust ratio (two-pass step)")
+    ap.add_argument("--auto-lr", action="store_true", help="research mode: auto-LR factor (two-pass step)")
     ap.add_argument("--chunk-elems", type=int, default=None)
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--vec-per-lane", type=int, default=None)
@@ -114,6 +116,9 @@ def main():
         hyper["nesterov"] = args.nesterov
     if args.la_k:
         hyper["la_k"] = args.la_k
+    scaled = args.layer_adaptation or args.auto_lr
+    if scaled:
+        hyper.update(mode="research", layer_adaptation=args.layer_adaptation, auto_lr=args.auto_lr)
     fused = not args.separate_sync
     numels = wl.numels
     p = wl.total
@@ -158,6 +163,10 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     if la_name != "none":
         N.check(N.novak_lookahead_init(handle, stream), "lookahead_init", handle)
+    ema = torch.zeros(2, dtype=torch.float64, device=dev)
+    if info.auto_lr:
+        N.check(N.novak_set_auto_lr_state(handle, ema.data_ptr()), "set_auto_lr_state", handle)
+    scaled = bool(info.layer_adaptation or info.auto_lr)
 
     def one_step(t):
         N.check(N.novak_step(handle, grad_arr, gdt, t, stream), "novak_step", handle)
@@ -177,7 +186,7 @@ def main():
     t_begin = time.perf_counter()
     for i in range(args.steps):
         t += 1
-        variants.append(la_variant(la_name, k, t, fused))
+        variants.append(("scaled_" if scaled else "") + la_variant(la_name, k, t, fused))
         ev[i][0].record()
         N.check(N.novak_step(handle, grad_arr, gdt, t, stream), "novak_step", handle)
         ev[i][1].record()
@@ -193,10 +202,12 @@ def main():
     la_mode = info.lookahead_mode
 
     def bytes_of(name):
+        # a two-pass ("scaled_") step is timed as a whole: both passes and the small reductions between them
+        fn = N.novak_bytes_per_param_scaled_step if name.startswith("scaled_") else N.novak_bytes_per_param_step
+        base = name[len("scaled_"):] if name.startswith("scaled_") else name
         pos = {"step": 2 if la_name == "basic" else 1, "step+la_first": 1, "step+la_mid": 2,
-               "step+la_last_fused": k, "step+basic_fused": k}[name]
-        return N.novak_bytes_per_param_step(la_mode, gdt, k, pos, int(fused)) if la_name != "none" else \
-            N.novak_bytes_per_param_step(0, gdt, k, 1, 0)
+               "step+la_last_fused": k, "step+basic_fused": k}[base]
+        return fn(la_mode, gdt, k, pos, int(fused)) if la_name != "none" else fn(0, gdt, k, 1, 0)
 
     kernels = {}
     for name, ms in per.items():
@@ -221,6 +232,7 @@ def main():
         "config": {"workload": wl.name, "params": p, "tensors": len(numels), "grad_dtype": wl.grad_dtype,
                    "nesterov": nest_name, "lookahead": la_name, "la_k": k, "sync": "fused" if fused else "separate",
                    "mode": hyper["mode"], "rectified": bool(hyper["rectified"]),
+                   "layer_adaptation": bool(info.layer_adaptation), "auto_lr": bool(info.auto_lr),
                    "chunk_elems": int(info.chunk_elems), "chunks": int(info.n_chunks)},
         "roofline": roofline,
         "kernels": kernels,

@@ -162,3 +162,73 @@ def test_scaled_results_are_reproducible_and_independent_of_chunking_within_tole
     finally:
         for g in (a, b, c):
             g.close()
+
+
+# ---- full benchmark sizes: the norms need whole tensors, so the oracle runs on every element --------
+def _full_size_scaled(workload, steps, layer, auto, auto_sync=True, nesterov=None):
+    wl = W.get_workload(workload)
+    hyper = dict(wl.hyper, mode="research", layer_adaptation=layer, auto_lr=auto)
+    if nesterov:
+        hyper["nesterov"] = nesterov
+    dev = torch.device("cuda:0")
+    numels = wl.numels
+    offs, off = [], 0
+    for n in numels:
+        offs.append(off)
+        off += (n + 63) // 64 * 64
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(2025)
+    bufs = {r: torch.zeros(off, dtype=torch.float32, device=dev) for r in ("theta", "m", "v", "la")}
+    bufs["theta"].normal_(0.0, W.PARAM_STD, generator=gen)
+    gdt = torch.bfloat16 if wl.grad_dtype == "bf16" else torch.float32
+    g = torch.empty(off, dtype=gdt, device=dev)
+    hp = N.make_hparams(auto_sync=auto_sync, **hyper)
+    descs = [N.novak_tensor_desc(*(bufs[r].data_ptr() + 4 * o for r in ("theta", "m", "v", "la")), n) for o, n in zip(offs, numels)]
+    rc, handle = N.novak_create(hp, descs, 0)
+    N.check(rc, "create")
+    ema = torch.zeros(2, dtype=torch.float64, device=dev)
+    try:
+        if auto:
+            N.check(N.novak_set_auto_lr_state(handle, ema.data_ptr()), "ema", handle)
+        N.check(N.novak_lookahead_init(handle, 0), "init", handle)
+        h = H.oracle_hyper(hyper)
+        theta_host = bufs["theta"].cpu().numpy()
+        states = [O.init_state(theta_host[o:o + n], h) for o, n in zip(offs, numels)]
+        aux = O.AutoLrState()
+        garr = (H.C.c_void_p * len(numels))(*[g.data_ptr() + g.element_size() * o for o in offs])
+        for t in range(1, steps + 1):
+            tmp = torch.empty(off, dtype=torch.float32, device=dev).normal_(0.0, wl.grad_std, generator=gen)
+            g.copy_(tmp)
+            del tmp
+            N.check(N.novak_step(handle, garr, N.GRAD_DTYPE[wl.grad_dtype], t, 0), f"step {t}", handle)
+            g_host = g.float().cpu().numpy()
+            O.step_all(states, [g_host[o:o + n] for o, n in zip(offs, numels)], t, h, aux)
+            if O.sync_due(t, h):
+                for st in states:
+                    O.lookahead_sync(st, h)
+            print(f"{workload} scaled step {t} done", flush=True)
+        torch.cuda.synchronize()
+        for role in ("theta", "m", "v"):
+            got = bufs[role].cpu().numpy()
+            for i, (o, n) in enumerate(zip(offs, numels)):
+                ref = getattr(states[i], role)
+                H.assert_close(f"{workload} {role}[{i}]", got[o:o + n], ref)
+                H.assert_close_strict(f"{workload} {role}[{i}]", got[o:o + n], ref)
+        if auto:
+            e = ema.cpu().numpy()
+            assert e[0] == pytest.approx(aux.g_bar, rel=1e-6) and e[1] == pytest.approx(aux.theta_bar, rel=1e-6)
+    finally:
+        torch.cuda.synchronize()
+        N.novak_destroy(handle)
+
+
+def test_c2_resnet50_research_mode_scaled_full_oracle():
+    _full_size_scaled("c2_resnet50", 6, layer=True, auto=True)
+
+
+def test_c4_vit_b16_bf16_research_mode_layer_adaptation_full_oracle():
+    _full_size_scaled("c4_vit_b16_bf16", 3, layer=True, auto=False, auto_sync=False)
+
+
+def test_c3_vgg16_research_mode_scaled_full_oracle():
+    _full_size_scaled("c3_vgg16", 3, layer=True, auto=True, nesterov="classical")
