@@ -38,6 +38,12 @@ Readings taken where the paper is silent or inconsistent (each is a named switch
     different formula for the same symbol that the paper calls an alternative; it is not used.
     parity unpinned by the paper for scope, initial value and the gradient's processing stage.
   * alpha_eff = alpha * r_t * eta_clipped * alpha_auto (Eq. 24a); the decay keeps the base alpha.
+  * gradient clipping (sections 5.8, 7.3; Table 2 Phase 2): if the GLOBAL norm over all tensors of the
+    gradient as handed in exceeds c_clip, every gradient is scaled by c_clip/norm, before any other
+    processing (coupled decay, Nesterov approximation).  The auto-LR norm of Eq. 20 keeps using the
+    gradient as handed in.  parity unpinned by the paper for that last choice.
+  * sparse threshold (Eq. 27): the base direction u is zeroed where |u| <= tau, after the trust ratio is
+    taken (Phase 7 precedes Phase 8) and before the classical blend (Table 2's order within Phase 8).
 """
 from __future__ import annotations
 
@@ -73,6 +79,8 @@ class Hyper:
     auto_lr_gamma: float = 0.1
     trust_clip: tuple = (0.1, 10.0)
     auto_clip: tuple = (0.1, 2.0)
+    clip_threshold: float = 0.0         # c_clip on the global gradient norm; 0 = off (section 5.8)
+    sparse_threshold: float = 0.0       # tau of Eq. 27; 0 = off
 
     def __post_init__(self):
         assert self.nesterov in NESTEROV_MODES
@@ -171,19 +179,30 @@ def auto_lr_scale(aux: AutoLrState, thetas, grads, h: Hyper) -> float:
     return min(max(aux.g_bar / aux.theta_bar, h.auto_clip[0]), h.auto_clip[1])   # Eq. 22
 
 
-def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float = 1.0) -> StepScalars:
+def clip_scale(grads, h: Hyper) -> float:
+    """Factor applied to every gradient: c_clip/||g|| when the global norm exceeds c_clip, else 1."""
+    if h.clip_threshold <= 0.0:
+        return 1.0
+    g2 = sum(float(np.dot(x, x)) for x in (np.asarray(g, dtype=np.float64).reshape(-1) for g in grads))
+    norm = math.sqrt(g2)
+    return h.clip_threshold / norm if norm > h.clip_threshold else 1.0
+
+
+def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float = 1.0,
+         g_scale: float = 1.0) -> StepScalars:
     """One update of one tensor at step t (Phases 2-9), then record the iterate for lookahead.
 
     `grad` holds the gradient values (any float dtype; bf16 gradients arrive as the fp32/fp64
     numbers they exactly represent).  The sync of Phase 10 is a separate call: `lookahead_sync`.
-    `alpha_auto` is the step-wide auto-LR factor (1 unless h.auto_lr; see `auto_lr_scale`).
+    `alpha_auto` is the step-wide auto-LR factor (1 unless h.auto_lr; see `auto_lr_scale`);
+    `g_scale` the step-wide clipping factor (see `clip_scale`).
     """
     s = step_scalars(h, t)
     dt = st.dtype
     theta = st.theta.astype(np.float64)
     m_prev = st.m.astype(np.float64)
     v_prev = st.v.astype(np.float64)
-    g = np.asarray(grad).reshape(-1).astype(np.float64)
+    g = np.asarray(grad).reshape(-1).astype(np.float64) * g_scale   # clipping comes first (section 7.3)
 
     if (not h.decoupled_decay) and h.weight_decay != 0.0:
         g = g + h.weight_decay * theta                      # coupled L2 (reading; see header)
@@ -198,6 +217,8 @@ def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float 
     else:
         u = m_hat                                           # momentum-SGD fallback while rho_t < 5
     lam_trust = trust_ratio(theta, u, h) if h.layer_adaptation else 1.0   # Eq. 19 / 25 (Phase 7)
+    if h.sparse_threshold > 0.0:
+        u = np.where(np.abs(u) > h.sparse_threshold, u, 0.0)   # Eq. 27
     if h.nesterov == "classical":
         u = h.beta1 * m_hat + (1.0 - h.beta1) * u           # Eq. 16
     alpha_eff = s.step_size * lam_trust * alpha_auto        # Eq. 24a
@@ -252,8 +273,9 @@ def step_all(states: List[TensorState], grads, t: int, h: Hyper, aux: Optional[A
     if h.auto_lr:
         assert aux is not None, "auto_lr needs its two EMA scalars"
         alpha_auto = auto_lr_scale(aux, [st.theta for st in states], grads, h)
+    g_scale = clip_scale(grads, h)
     for st, g in zip(states, grads):
-        step(st, g, t, h, alpha_auto)
+        step(st, g, t, h, alpha_auto, g_scale)
     return alpha_auto
 
 
