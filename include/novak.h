@@ -69,7 +69,8 @@ enum {
  * [0,1); weight_decay >= 0; beta_n in [0,1); la_k >= 1; eps > 0; beta2 < 1 - 1e-8 when rectified;
  * la_alpha in (0,1] when lookahead is on (the paper's open bound at 1 is relaxed so that the
  * alpha_LA = 1 fixed point can be exercised); auto_lr_gamma in (0,1] and 0 < lo <= hi for both clip
- * ranges when the respective scaling is on.  All values must be finite. */
+ * ranges when the respective scaling is on; clip_threshold >= 0; sparse_threshold >= 0.  All values
+ * must be finite. */
 typedef struct novak_hparams {
   size_t struct_size;      /* sizeof(novak_hparams); guards against layout mismatch */
   double lr;               /* alpha   */
@@ -94,6 +95,10 @@ typedef struct novak_hparams {
   double auto_lr_gamma;     /* gamma of Eq. 20-21, in (0,1]; the paper uses 0.1 */
   double trust_clip_lo, trust_clip_hi;   /* clip range of Eq. 19; the paper uses [0.1, 10]; 0 < lo <= hi */
   double auto_clip_lo, auto_clip_hi;     /* clip range of Eq. 22; the paper uses [0.1, 2];  0 < lo <= hi */
+  /* Phase 2 / Phase 8 options, legal in both modes. */
+  double clip_threshold;    /* c_clip >= 0 on the GLOBAL gradient norm (sections 5.8, 7.3), applied before any other
+                               processing; 0 = off.  Costs one extra read of the gradients per step. */
+  double sparse_threshold;  /* tau >= 0 of Eq. 27: the base direction u is zeroed where |u| <= tau; 0 = off */
 } novak_hparams;
 
 /* One parameter tensor.  All pointers are DEVICE pointers to contiguous fp32 arrays of `numel`
@@ -188,6 +193,8 @@ double novak_bytes_per_param_step(int32_t lookahead_mode, int32_t grad_dtype, in
  * partials (16 bytes per 256 elements, written and read once) are not counted. */
 double novak_bytes_per_param_scaled_step(int32_t lookahead_mode, int32_t grad_dtype, int32_t la_k,
                                          int32_t window_pos, int32_t fused_sync);
+/* Algorithmic bytes per parameter of the clipping pre-pass (one read of the gradients). */
+double novak_bytes_per_param_clip(int32_t grad_dtype);
 /* Algorithmic bytes per parameter of the separate sync kernel. */
 double novak_bytes_per_param_sync(int32_t lookahead_mode);
 

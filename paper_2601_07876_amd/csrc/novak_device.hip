@@ -40,7 +40,7 @@ enum : int {
   LA_BASIC_FUSED = 4   // k-th step, basic mode:   S = c1*theta_new + c0*S; theta_out=S (S read, written)
 };
 
-enum : uint32_t { F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u, F_FAST = 16u };
+enum : uint32_t { F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u, F_CLIP = 16u, F_SPARSE = 32u };
 
 // The four state pointers of a tensor sit together so that one 32-byte scalar load fetches them.
 struct TensorPtrs {
@@ -54,6 +54,7 @@ struct Tables {
   const novak_chunk *chunks;
   const TensorPtrs *tensors;
   const void *const *grad;
+  const float *gscale;   // one float: the step's gradient-clipping factor (read only when F_CLIP is set)
 };
 
 // Per-step scalars, rounded once from the host's double values.
@@ -66,6 +67,7 @@ struct Consts {
   float lr_wd;           // alpha * lambda (decoupled) or 0
   float wd;              // lambda (coupled) or 0
   float la_c0, la_c1;    // lookahead blend coefficients (meaning depends on the LA phase)
+  float sparse_tau;      // tau of Eq. 27 (used when F_SPARSE is set)
   uint32_t flags;
 };
 
@@ -76,7 +78,8 @@ __device__ __forceinline__ float bf16_to_f32(unsigned short b) { return __uint_a
 //   moments():   Phases 2 and 4 - gradient processing and the two EMAs (Eq. 13, 1, 2)
 //   direction(): Phases 5 and 8a - bias correction and the base direction u (Eq. 5, 17)
 //   apply():     Phases 8b, 9, 10 - classical blend, decay + update, lookahead (Eq. 16, 18, 24, 28-31)
-__device__ __forceinline__ void moments(float th_in, float g, float &m, float &v, const Consts &c) {
+__device__ __forceinline__ void moments(float th_in, float g, float &m, float &v, const Consts &c, float gs) {
+  if (c.flags & F_CLIP) g *= gs;                                        // global-norm clipping comes first
   if (c.flags & F_COUPLED) g = __builtin_fmaf(c.wd, th_in, g);          // classic L2 reading
   if (c.flags & F_APPROX) g = __builtin_fmaf(c.beta_n, g - m, g);       // Eq. 13
   m = __builtin_fmaf(c.omb1, g - m, m);                                 // Eq. 1:  m + (1-b1)(g - m)
@@ -98,6 +101,7 @@ __device__ __forceinline__ float direction(float m, float v, const Consts &c, fl
 template <int LA>
 __device__ __forceinline__ void apply(float &th, float u, float m_hat, float &la, const Consts &c, float step) {
   const float th_in = th;
+  if ((c.flags & F_SPARSE) && !(__builtin_fabsf(u) > c.sparse_tau)) u = 0.0f;  // Eq. 27
   if (c.flags & F_CLASSICAL) u = __builtin_fmaf(c.beta1, m_hat, c.omb1 * u);   // Eq. 16
   // Eq. 18 + Eq. 24 in additive form: one rounding at theta's magnitude per step
   const float th_new = th_in - __builtin_fmaf(step, u, c.lr_wd * th_in);
@@ -115,8 +119,8 @@ __device__ __forceinline__ void apply(float &th, float u, float m_hat, float &la
 }
 
 template <int LA>
-__device__ __forceinline__ void update_one(float &th, float g, float &m, float &v, float &la, const Consts &c) {
-  moments(th, g, m, v, c);
+__device__ __forceinline__ void update_one(float &th, float g, float &m, float &v, float &la, const Consts &c, float gs) {
+  moments(th, g, m, v, c, gs);
   float m_hat;
   const float u = direction(m, v, c, m_hat);
   apply<LA>(th, u, m_hat, la, c, c.step_size);
@@ -146,11 +150,11 @@ __device__ __forceinline__ f32x4 grad_to_f32<u16x4>(u16x4 g) {
 }
 
 template <int LA>
-__device__ __forceinline__ void update_vec(f32x4 &th, f32x4 g, f32x4 &m, f32x4 &v, f32x4 &la, const Consts &c) {
+__device__ __forceinline__ void update_vec(f32x4 &th, f32x4 g, f32x4 &m, f32x4 &v, f32x4 &la, const Consts &c, float gs) {
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     float th_k = th[k], m_k = m[k], v_k = v[k], la_k = la[k];
-    update_one<LA>(th_k, g[k], m_k, v_k, la_k, c);
+    update_one<LA>(th_k, g[k], m_k, v_k, la_k, c, gs);
     th[k] = th_k; m[k] = m_k; v[k] = v_k; la[k] = la_k;
   }
 }
@@ -177,6 +181,7 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
   const int64_t off = ch.offset + start;
   const TensorPtrs tp = tb.tensors[ch.tensor];          // one scalar load, issued together with the next
   const void *const g_base = tb.grad[ch.tensor];
+  const float gs = (c.flags & F_CLIP) ? *tb.gscale : 1.0f;
   float *__restrict__ th_p = tp.param + off;
   float *__restrict__ m_p = tp.m + off;
   float *__restrict__ v_p = tp.v + off;
@@ -211,7 +216,7 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
         const int j = threadIdx.x + u * BLOCK;
-        update_vec<LA>(th[u], grad_to_f32<GradV>(g[u]), m[u], v[u], la[u], c);
+        update_vec<LA>(th[u], grad_to_f32<GradV>(g[u]), m[u], v[u], la[u], c, gs);
         st<NT>(th4 + j, th[u]);
         st<NT>(m4 + j, m[u]);
         st<NT>(v4 + j, v[u]);
@@ -224,7 +229,7 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
       f32x4 th = ld<NT>(th4 + i), m = ld<NT>(m4 + i), v = ld<NT>(v4 + i), la;
       GradV g = ld<NT>(g4 + i);
       if (la_reads(LA)) la = ld<NT>(la4 + i);
-      update_vec<LA>(th, grad_to_f32<GradV>(g), m, v, la, c);
+      update_vec<LA>(th, grad_to_f32<GradV>(g), m, v, la, c, gs);
       st<NT>(th4 + i, th);
       st<NT>(m4 + i, m);
       st<NT>(v4 + i, v);
@@ -238,7 +243,7 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
     if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
     else g = g_p[i];
     if (la_reads(LA)) la = la_p[i];
-    update_one<LA>(th, g, m, v, la, c);
+    update_one<LA>(th, g, m, v, la, c, gs);
     th_p[i] = th;
     m_p[i] = m;
     v_p[i] = v;
@@ -341,6 +346,7 @@ __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, 
   const int64_t off = ch.offset + start;
   const TensorPtrs tp = tb.tensors[ch.tensor];
   const void *const g_base = tb.grad[ch.tensor];
+  const float gs = (c.flags & F_CLIP) ? *tb.gscale : 1.0f;
   const float *__restrict__ th_p = tp.param + off;
   float *__restrict__ m_p = tp.m + off;
   float *__restrict__ v_p = tp.v + off;
@@ -365,7 +371,7 @@ __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, 
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         float m_k = m[k], v_k = v[k], m_hat;
-        moments(th[k], g[k], m_k, v_k, c);
+        moments(th[k], g[k], m_k, v_k, c, gs);
         const float u = direction(m_k, v_k, c, m_hat);
         s_th = __builtin_fmaf(th[k], th[k], s_th);
         s_u = __builtin_fmaf(u, u, s_u);
@@ -382,7 +388,7 @@ __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, 
     float m = m_p[i], v = v_p[i], g, m_hat;
     if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
     else g = g_p[i];
-    moments(th, g, m, v, c);
+    moments(th, g, m, v, c, gs);
     const float u = direction(m, v, c, m_hat);
     s_th = __builtin_fmaf(th, th, s_th);
     s_u = __builtin_fmaf(u, u, s_u);
@@ -417,6 +423,52 @@ __global__ __launch_bounds__(64) void novak_reduce_chunks_kernel(const novak_chu
   if (threadIdx.x == 0) {
     NormSums s; s.theta2 = a; s.u2 = b; s.g2 = g;
     chunk_sums[blockIdx.x] = s;
+  }
+}
+
+// Clipping pre-pass (sections 5.8, 7.3): one read of the gradients, one partial (sum g^2) per wave; the
+// chunk and tensor reductions above are reused, then novak_clip_kernel turns the global norm into the
+// factor min(1, c_clip/||g||) that every later kernel of the step multiplies the gradients by.
+template <typename GradS, typename GradV, bool NT>
+__global__ __launch_bounds__(kScaledBlock) void novak_gradnorm_kernel(Tables tb, int sub_shift, NormPartial *partials) {
+  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kScaledSub;
+  if (start >= ch.len) return;
+  const int n = min(kScaledSub, ch.len - start);
+  const GradS *__restrict__ g_p = static_cast<const GradS *>(tb.grad[ch.tensor]) + (ch.offset + start);
+  float s_g = 0.0f;
+  int done = 0;
+  if ((reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1)) == 0) {
+    const int nvec = n >> 2;
+    const int i = threadIdx.x;
+    if (i < nvec) {
+      const f32x4 g = grad_to_f32<GradV>(ld<NT>(reinterpret_cast<const GradV *>(g_p) + i));
+#pragma unroll
+      for (int k = 0; k < 4; ++k) s_g = __builtin_fmaf(g[k], g[k], s_g);
+    }
+    done = nvec << 2;
+  }
+  for (int i = done + threadIdx.x; i < n; i += kScaledBlock) {
+    float g;
+    if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
+    else g = g_p[i];
+    s_g = __builtin_fmaf(g, g, s_g);
+  }
+  s_g = wave_sum(s_g);
+  if (threadIdx.x == 0) {
+    NormPartial p;
+    p.theta2 = 0.0f; p.u2 = 0.0f; p.g2 = s_g; p.pad = 0.0f;
+    partials[blockIdx.x] = p;
+  }
+}
+
+__global__ __launch_bounds__(64) void novak_clip_kernel(int n_tensors, const NormSums *tensor_sums, float c_clip, float *gscale) {
+  double g = 0.0;
+  for (int j = threadIdx.x; j < n_tensors; j += 64) g += tensor_sums[j].g2;
+  g = wave_sum(g);
+  if (threadIdx.x == 0) {
+    const double norm = sqrt(g);
+    gscale[0] = norm > static_cast<double>(c_clip) ? static_cast<float>(static_cast<double>(c_clip) / norm) : 1.0f;
   }
 }
 
@@ -560,6 +612,7 @@ struct novak_handle {
   NormSums *d_tensor_sums = nullptr;   // one per tensor
   int *d_first_chunk = nullptr;        // n_tensors + 1: chunk range of each tensor
   float *d_scale = nullptr;            // n_tensors: lambda_trust * alpha_auto
+  float *d_gscale = nullptr;           // one float: gradient-clipping factor of the current step
   double *d_ema = nullptr;             // caller-owned: g_bar, theta_bar
   // device-side tables (owned)
   novak_chunk *d_chunks = nullptr;
@@ -619,10 +672,13 @@ Tables tables_of(const novak_handle *h) {
   tb.chunks = h->d_chunks;
   tb.tensors = reinterpret_cast<const TensorPtrs *>(base);
   tb.grad = reinterpret_cast<const void *const *>(base + n * sizeof(TensorPtrs));
+  tb.gscale = h->d_gscale;
   return tb;
 }
 
 bool two_pass(const novak_handle *h) { return h->hp.layer_adaptation || h->hp.auto_lr; }
+bool clipping(const novak_handle *h) { return h->hp.clip_threshold > 0.0; }
+bool needs_reductions(const novak_handle *h) { return two_pass(h) || clipping(h); }
 
 void free_device_tables(novak_handle *h) {
   if (h->d_chunks) (void)hipFree(h->d_chunks);
@@ -631,6 +687,8 @@ void free_device_tables(novak_handle *h) {
   if (h->d_tensor_sums) (void)hipFree(h->d_tensor_sums);
   if (h->d_first_chunk) (void)hipFree(h->d_first_chunk);
   if (h->d_scale) (void)hipFree(h->d_scale);
+  if (h->d_gscale) (void)hipFree(h->d_gscale);
+  h->d_gscale = nullptr;
   h->d_chunks = nullptr;
   h->d_partials = nullptr;
   h->d_chunk_sums = nullptr;
@@ -655,8 +713,11 @@ int build_chunk_table(novak_handle *h) {
     NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_chunks), static_cast<size_t>(n) * sizeof(novak_chunk)));
     NOVAK_HIP(h, hipMemcpy(h->d_chunks, table.data(), static_cast<size_t>(n) * sizeof(novak_chunk), hipMemcpyHostToDevice));
   }
-  if (two_pass(h) && !h->tensors.empty()) {
+  if (needs_reductions(h) && !h->tensors.empty()) {
     const size_t nt = h->tensors.size();
+    const float one = 1.0f;
+    NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_gscale), sizeof(float)));
+    NOVAK_HIP(h, hipMemcpy(h->d_gscale, &one, sizeof(float), hipMemcpyHostToDevice));
     std::vector<int> first(nt + 1, 0);
     for (const novak_chunk &c : table) first[static_cast<size_t>(c.tensor) + 1] += 1;
     for (size_t t = 0; t < nt; ++t) first[t + 1] += first[t];
@@ -784,6 +845,30 @@ void launch_apply(int la, const Geometry &gm, hipStream_t s, const Tables &tb, c
     case LA_LAST_FUSED: hipLaunchKernelGGL((novak_apply_kernel<LA_LAST_FUSED, NT>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
     default: hipLaunchKernelGGL((novak_apply_kernel<LA_BASIC_FUSED, NT>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
   }
+}
+
+// Clipping pre-pass: gradient norm partials -> chunk sums -> tensor sums -> global factor in d_gscale.
+int launch_clip_prepass(novak_handle *h, int grad_dtype, hipStream_t s, const Tables &tb) {
+  const Geometry g0 = geometry_of(h, kScaledSub, kScaledBlock, 1.0);    // a single read stream: full residency
+  const dim3 grid(g0.grid), block(kScaledBlock);
+  const bool nt = h->nontemporal != 0;
+  if (grad_dtype == NOVAK_GRAD_BF16) {
+    if (nt) hipLaunchKernelGGL((novak_gradnorm_kernel<unsigned short, u16x4, true>), grid, block, g0.lds, s, tb, g0.sub_shift, h->d_partials);
+    else hipLaunchKernelGGL((novak_gradnorm_kernel<unsigned short, u16x4, false>), grid, block, g0.lds, s, tb, g0.sub_shift, h->d_partials);
+  } else {
+    if (nt) hipLaunchKernelGGL((novak_gradnorm_kernel<float, f32x4, true>), grid, block, g0.lds, s, tb, g0.sub_shift, h->d_partials);
+    else hipLaunchKernelGGL((novak_gradnorm_kernel<float, f32x4, false>), grid, block, g0.lds, s, tb, g0.sub_shift, h->d_partials);
+  }
+  ScaleParams sp;
+  std::memset(&sp, 0, sizeof(sp));
+  const int nt_count = static_cast<int>(h->tensors.size());
+  hipLaunchKernelGGL(novak_reduce_chunks_kernel, dim3(static_cast<unsigned>(h->n_chunks)), dim3(64), 0, s, h->d_chunks, g0.sub_shift,
+                     h->d_partials, h->d_chunk_sums);
+  hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(64), 0, s, h->d_first_chunk, h->d_chunk_sums,
+                     h->d_tensor_sums, h->d_scale, sp);
+  hipLaunchKernelGGL(novak_clip_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, static_cast<float>(h->hp.clip_threshold), h->d_gscale);
+  NOVAK_HIP(h, hipGetLastError());
+  return NOVAK_OK;
 }
 
 // The two-pass step: moments + norm partials, fixed-order reductions, scaled apply.
@@ -1058,7 +1143,11 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
   if (hp.nesterov_mode == NOVAK_NESTEROV_CLASSICAL) c.flags |= F_CLASSICAL;
   if (sc.denom_on) c.flags |= F_DENOM;
   if (!hp.decoupled_decay && hp.weight_decay != 0.0) c.flags |= F_COUPLED;
-  if (getenv("NOVAK_EXPERIMENT_FAST")) c.flags |= F_FAST;
+  if (hp.clip_threshold > 0.0) c.flags |= F_CLIP;
+  if (hp.sparse_threshold > 0.0) {
+    c.flags |= F_SPARSE;
+    c.sparse_tau = static_cast<float>(hp.sparse_threshold);
+  }
 
   // lookahead phase of this step: position in the k-step window (section 4.7; sync when t mod k == 0)
   int la = LA_OFF;
@@ -1101,6 +1190,10 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
       h->ring_used[slot] = true;
       std::memcpy(h->last_grads.data(), grads, n * sizeof(void *));
       h->grads_uploaded = true;
+    }
+    if (clipping(h)) {
+      rc = launch_clip_prepass(h, grad_dtype, stream, tables_of(h));
+      if (rc != NOVAK_OK) return rc;
     }
     if (two_pass(h)) {
       rc = launch_scaled_step(h, grad_dtype, la, stream, tables_of(h), c);

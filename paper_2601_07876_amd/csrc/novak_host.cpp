@@ -11,7 +11,8 @@ namespace {
 
 bool finite_all(const novak_hparams &hp) {
   const double vals[] = {hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, hp.beta_n, hp.la_alpha,
-                         hp.auto_lr_gamma, hp.trust_clip_lo, hp.trust_clip_hi, hp.auto_clip_lo, hp.auto_clip_hi};
+                         hp.auto_lr_gamma, hp.trust_clip_lo, hp.trust_clip_hi, hp.auto_clip_lo, hp.auto_clip_hi,
+                         hp.clip_threshold, hp.sparse_threshold};
   for (double x : vals)
     if (!std::isfinite(x)) return false;
   return true;
@@ -63,6 +64,7 @@ int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, ui
   if (hp->mode != NOVAK_MODE_FAST && hp->mode != NOVAK_MODE_RESEARCH) return NOVAK_ERR_INVALID_ARG;
   if (hp->lookahead_mode != NOVAK_LOOKAHEAD_NONE && !(hp->la_alpha > 0.0 && hp->la_alpha <= 1.0)) return NOVAK_ERR_INVALID_ARG;
 
+  if (!(hp->clip_threshold >= 0.0) || !(hp->sparse_threshold >= 0.0)) return NOVAK_ERR_INVALID_ARG;
   if (hp->layer_adaptation && !(hp->trust_clip_lo > 0.0 && hp->trust_clip_lo <= hp->trust_clip_hi)) return NOVAK_ERR_INVALID_ARG;
   if (hp->auto_lr) {
     if (!(hp->auto_lr_gamma > 0.0 && hp->auto_lr_gamma <= 1.0)) return NOVAK_ERR_INVALID_ARG;
@@ -176,6 +178,8 @@ double novak_bytes_per_param_scaled_step(int32_t lookahead_mode, int32_t grad_dt
   // the single-pass figure plus pass 2 reading theta, m, v again
   return novak_bytes_per_param_step(lookahead_mode, grad_dtype, la_k, window_pos, fused_sync) + 12;
 }
+
+double novak_bytes_per_param_clip(int32_t grad_dtype) { return grad_dtype == NOVAK_GRAD_BF16 ? 2 : 4; }
 
 double novak_bytes_per_param_sync(int32_t lookahead_mode) {
   if (lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT) return 8;   // buffer read, theta written

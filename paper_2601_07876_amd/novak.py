@@ -42,7 +42,8 @@ class novak_hparams(C.Structure):
                 ("mode", C.c_int32), ("auto_sync", C.c_int32),
                 ("layer_adaptation", C.c_int32), ("auto_lr", C.c_int32), ("auto_lr_gamma", C.c_double),
                 ("trust_clip_lo", C.c_double), ("trust_clip_hi", C.c_double),
-                ("auto_clip_lo", C.c_double), ("auto_clip_hi", C.c_double)]
+                ("auto_clip_lo", C.c_double), ("auto_clip_hi", C.c_double),
+                ("clip_threshold", C.c_double), ("sparse_threshold", C.c_double)]
 
 
 class novak_tensor_desc(C.Structure):
@@ -69,7 +70,8 @@ class novak_info(C.Structure):
 
 
 EXPORTS = ("novak_validate_hparams", "novak_compute_step_scalars", "novak_plan_chunks",
-           "novak_bytes_per_param_step", "novak_bytes_per_param_scaled_step", "novak_bytes_per_param_sync",
+           "novak_bytes_per_param_step", "novak_bytes_per_param_scaled_step", "novak_bytes_per_param_clip",
+           "novak_bytes_per_param_sync",
            "novak_status_string", "novak_create", "novak_lookahead_init", "novak_step", "novak_lookahead_sync",
            "novak_destroy", "novak_get_info", "novak_set_tuning", "novak_last_error", "novak_set_auto_lr_state",
            "novak_copy_tensor_scales")
@@ -97,6 +99,8 @@ def load_library() -> C.CDLL:
     lib.novak_bytes_per_param_scaled_step.restype = C.c_double
     lib.novak_set_auto_lr_state.argtypes = [vp, vp]
     lib.novak_copy_tensor_scales.argtypes = [vp, C.POINTER(C.c_float), vp]
+    lib.novak_bytes_per_param_clip.argtypes = [i32]
+    lib.novak_bytes_per_param_clip.restype = C.c_double
     lib.novak_bytes_per_param_sync.argtypes = [i32]
     lib.novak_bytes_per_param_sync.restype = C.c_double
     lib.novak_status_string.argtypes = [C.c_int]
@@ -128,7 +132,8 @@ class NovakError(RuntimeError):
 def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, beta_n=0.9, la_alpha=0.5, la_k=5,
                  rectified=True, decoupled_decay=True, nesterov="approx", lookahead="memory_efficient",
                  unrect_fallback="adam_denom", mode="fast", auto_sync=False, layer_adaptation=False, auto_lr=False,
-                 auto_lr_gamma=0.1, trust_clip=(0.1, 10.0), auto_clip=(0.1, 2.0)) -> novak_hparams:
+                 auto_lr_gamma=0.1, trust_clip=(0.1, 10.0), auto_clip=(0.1, 2.0), clip_threshold=0.0,
+                 sparse_threshold=0.0) -> novak_hparams:
     """Fills a novak_hparams from keyword values (mode names or their integer codes)."""
     def code(table: Dict[str, int], x):
         return table[x] if isinstance(x, str) else int(x)
@@ -136,7 +141,7 @@ def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, be
                          int(rectified), int(decoupled_decay), code(NESTEROV, nesterov), code(LOOKAHEAD, lookahead),
                          code(UNRECT, unrect_fallback), code(MODE, mode), int(auto_sync), int(layer_adaptation),
                          int(auto_lr), float(auto_lr_gamma), float(trust_clip[0]), float(trust_clip[1]),
-                         float(auto_clip[0]), float(auto_clip[1]))
+                         float(auto_clip[0]), float(auto_clip[1]), float(clip_threshold), float(sparse_threshold))
 
 
 # ---- the entry points, same names as the C ABI ------------------------------------------------------
@@ -188,6 +193,10 @@ def novak_copy_tensor_scales(handle, n_tensors: int, stream: int = 0):
     buf = (C.c_float * max(n_tensors, 1))()
     rc = load_library().novak_copy_tensor_scales(handle, buf, C.c_void_p(stream))
     return rc, [buf[i] for i in range(n_tensors)]
+
+
+def novak_bytes_per_param_clip(grad_dtype: int) -> float:
+    return load_library().novak_bytes_per_param_clip(grad_dtype)
 
 
 def novak_bytes_per_param_sync(lookahead_mode: int) -> float:

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert C.sizeof(N.novak_hparams) == 8 + 7 * 8 + 10 * 4 + 5 * 8
+    assert C.sizeof(N.novak_hparams) == 8 + 7 * 8 + 10 * 4 + 7 * 8
     assert C.sizeof(N.novak_tensor_desc) == 40
     assert C.sizeof(N.novak_chunk) == 16
     hp = N.make_hparams()
@@ -43,6 +43,7 @@ GOOD = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=1e-2, beta_n
     ("eps", 0.0), ("eps", -1e-8), ("la_k", 0), ("la_k", -3),
     ("la_alpha", 0.0), ("la_alpha", 1.0000001), ("la_alpha", -0.5),
     ("beta2", 1.0 - 1e-9),                      # rho_inf ill-defined when rectified
+    ("clip_threshold", -1.0), ("sparse_threshold", -1e-9), ("clip_threshold", float("nan")),
 ])
 def test_validation_rejects(field, value):
     kw = dict(GOOD)

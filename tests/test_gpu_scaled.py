@@ -165,9 +165,9 @@ def test_scaled_results_are_reproducible_and_independent_of_chunking_within_tole
 
 
 # ---- full benchmark sizes: the norms need whole tensors, so the oracle runs on every element --------
-def _full_size_scaled(workload, steps, layer, auto, auto_sync=True, nesterov=None):
+def _full_size_scaled(workload, steps, layer, auto, auto_sync=True, nesterov=None, **over):
     wl = W.get_workload(workload)
-    hyper = dict(wl.hyper, mode="research", layer_adaptation=layer, auto_lr=auto)
+    hyper = dict(wl.hyper, mode="research", layer_adaptation=layer, auto_lr=auto, **over)
     if nesterov:
         hyper["nesterov"] = nesterov
     dev = torch.device("cuda:0")
@@ -232,3 +232,9 @@ def test_c4_vit_b16_bf16_research_mode_layer_adaptation_full_oracle():
 
 def test_c3_vgg16_research_mode_scaled_full_oracle():
     _full_size_scaled("c3_vgg16", 3, layer=True, auto=True, nesterov="classical")
+
+
+def test_c2_resnet50_clipping_and_sparse_threshold_full_oracle():
+    """Global-norm clipping (active: ||g|| ~ 5 for this workload) and Eq. 27, single-pass and two-pass."""
+    _full_size_scaled("c2_resnet50", 6, layer=False, auto=False, clip_threshold=1.0, sparse_threshold=0.05)
+    _full_size_scaled("c2_resnet50", 3, layer=True, auto=True, clip_threshold=1.0, sparse_threshold=0.05)
