@@ -44,6 +44,10 @@ Readings taken where the paper is silent or inconsistent (each is a named switch
     gradient as handed in.  parity unpinned by the paper for that last choice.
   * sparse threshold (Eq. 27): the base direction u is zeroed where |u| <= tau, after the trust ratio is
     taken (Phase 7 precedes Phase 8) and before the classical blend (Table 2's order within Phase 8).
+    The mask is a discontinuous decision on a floating-point value: an implementation in another
+    precision may decide differently where |u| is within rounding of tau.  For comparisons, the
+    oracle records in TensorState.ambiguous the elements whose |u| ever came within a relative
+    AMBIGUITY_BAND of tau; it does not change any result.
 """
 from __future__ import annotations
 
@@ -56,6 +60,7 @@ import numpy as np
 NESTEROV_MODES = ("none", "approx", "classical", "true")
 LOOKAHEAD_MODES = ("none", "memory_efficient", "basic")
 UNRECT_FALLBACKS = ("adam_denom", "sgdm")
+AMBIGUITY_BAND = 5e-5      # relative half-width around tau in which the Eq. 27 decision is called ambiguous
 
 
 @dataclass
@@ -137,6 +142,7 @@ class TensorState:
     v: np.ndarray
     slow0: Optional[np.ndarray] = None                 # theta_0^slow of the open window (Eq. 28)
     window: List[np.ndarray] = field(default_factory=list)   # the fast iterates of the open window
+    ambiguous: Optional[np.ndarray] = None             # bookkeeping for comparisons only (see header, Eq. 27)
 
     @property
     def dtype(self):
@@ -218,6 +224,8 @@ def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float 
         u = m_hat                                           # momentum-SGD fallback while rho_t < 5
     lam_trust = trust_ratio(theta, u, h) if h.layer_adaptation else 1.0   # Eq. 19 / 25 (Phase 7)
     if h.sparse_threshold > 0.0:
+        near = np.abs(np.abs(u) - h.sparse_threshold) <= AMBIGUITY_BAND * h.sparse_threshold
+        st.ambiguous = near if st.ambiguous is None else (st.ambiguous | near)
         u = np.where(np.abs(u) > h.sparse_threshold, u, 0.0)   # Eq. 27
     if h.nesterov == "classical":
         u = h.beta1 * m_hat + (1.0 - h.beta1) * u           # Eq. 16

@@ -199,13 +199,32 @@ def run_pair(numels: Sequence[int], hyper: Dict[str, object], steps: int, grad_s
     return gpu, states, h
 
 
-def compare_states(gpu: GpuNovak, states: List[O.TensorState], strict: bool = True, tag: str = ""):
+def split_ambiguous(name: str, got: np.ndarray, ref: np.ndarray, ambiguous: Optional[np.ndarray], max_move: float):
+    """Elements whose Eq. 27 mask decision was within rounding of the threshold at some step may
+    legitimately differ by up to the steps they took or skipped: they are checked against that weaker
+    bound and removed from the element-wise comparison.  Their fraction must stay tiny."""
+    if ambiguous is None or not ambiguous.any():
+        return got, ref
+    count = int(ambiguous.sum())
+    assert count <= max(2, 2e-3 * ambiguous.size), \
+        f"{name}: {count}/{ambiguous.size} elements are ambiguous - the band is too wide to mean anything"
+    d = np.abs(got[ambiguous].astype(np.float64) - ref[ambiguous].astype(np.float64))
+    assert np.all(d <= max_move), f"{name}: an ambiguous element moved by {d.max():.3e} > {max_move:.3e}"
+    keep = ~ambiguous
+    return got[keep], ref[keep]
+
+
+def compare_states(gpu: GpuNovak, states: List[O.TensorState], strict: bool = True, tag: str = "", max_move: float = 2e-2):
+    """`max_move` bounds how far an element with an ambiguous sparse-mask decision may sit from the oracle."""
     th, m, v = gpu.host("theta"), gpu.host("m"), gpu.host("v")
     for i, st in enumerate(states):
-        assert_close(f"{tag}theta[{i}]", th[i], st.theta)
+        th_i, ref_i = split_ambiguous(f"{tag}theta[{i}]", th[i], st.theta, st.ambiguous, max_move)
+        assert_close(f"{tag}theta[{i}]", th_i, ref_i)
+        if strict and ref_i.size:
+            assert_close_strict(f"{tag}theta[{i}]", th_i, ref_i)
         assert_close(f"{tag}m[{i}]", m[i], st.m)
         assert_close(f"{tag}v[{i}]", v[i], st.v)
         if strict and st.theta.size:
-            assert_close_strict(f"{tag}theta[{i}]", th[i], st.theta)
             assert_close_strict(f"{tag}m[{i}]", m[i], st.m)
             assert_close_strict(f"{tag}v[{i}]", v[i], st.v)
+
