@@ -61,7 +61,8 @@ enum {
   NOVAK_WARN_TRUE_NESTEROV_DOWNGRADED = 1u << 0,  /* FAST + TRUE        -> APPROX           */
   NOVAK_WARN_LOOKAHEAD_DOWNGRADED = 1u << 1,      /* FAST + BASIC       -> MEMORY_EFFICIENT */
   NOVAK_WARN_LAYER_ADAPTATION_DISABLED = 1u << 2, /* FAST + layer_adaptation -> off (section 7.1) */
-  NOVAK_WARN_AUTO_LR_DISABLED = 1u << 3           /* FAST + auto_lr          -> off (section 7.1) */
+  NOVAK_WARN_AUTO_LR_DISABLED = 1u << 3,          /* FAST + auto_lr          -> off (section 7.1) */
+  NOVAK_WARN_GC_DISABLED = 1u << 4                /* FAST + use_gc           -> off (section 7.1) */
 };
 
 /* ---- hyper-parameters (host memory, plain data) -------------------------------------------------
@@ -99,6 +100,10 @@ typedef struct novak_hparams {
   double clip_threshold;    /* c_clip >= 0 on the GLOBAL gradient norm (sections 5.8, 7.3), applied before any other
                                processing; 0 = off.  Costs one extra read of the gradients per step. */
   double sparse_threshold;  /* tau >= 0 of Eq. 27: the base direction u is zeroed where |u| <= tau; 0 = off */
+  int32_t use_gc;           /* 1: gradient centralization (Eq. 26) on tensors whose descriptor gives rows >= 1; RESEARCH
+                               mode only; runs after clipping, before the Nesterov approximation; costs one extra
+                               read of those tensors' gradients per step */
+  int32_t reserved0;        /* must be 0 */
 } novak_hparams;
 
 /* One parameter tensor.  All pointers are DEVICE pointers to contiguous fp32 arrays of `numel`
@@ -117,6 +122,8 @@ typedef struct novak_tensor_desc {
   void *exp_avg_sq;  /* v, updated in place       */
   void *la_buf;      /* see above; may be NULL when lookahead is NONE */
   int64_t numel;
+  int64_t rows;      /* Eq. 26: size of the first dimension if the tensor has more than one dimension, else 0
+                        (not centralized); must divide numel.  Ignored unless use_gc is on. */
 } novak_tensor_desc;
 
 /* Per-step scalars (Phases 5-6), as the host prologue computes them in double. */
@@ -151,6 +158,8 @@ typedef struct novak_info {
   int32_t device_id;
   int32_t layer_adaptation;  /* effective */
   int32_t auto_lr;           /* effective */
+  int32_t use_gc;            /* effective */
+  int32_t n_centralized;     /* tensors that are centralized (use_gc on and rows >= 1) */
 } novak_info;
 
 /* tuning keys for novak_set_tuning */

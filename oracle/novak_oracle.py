@@ -42,6 +42,11 @@ Readings taken where the paper is silent or inconsistent (each is a named switch
     gradient as handed in exceeds c_clip, every gradient is scaled by c_clip/norm, before any other
     processing (coupled decay, Nesterov approximation).  The auto-LR norm of Eq. 20 keeps using the
     gradient as handed in.  parity unpinned by the paper for that last choice.
+  * gradient centralization (Eq. 26; full-features mode, tensors with more than one dimension): the
+    mean over all dimensions but the first is subtracted from each dim-0 slice.  It runs after the
+    clipping and before the Nesterov approximation (section 7.3 puts clipping before any other
+    processing; Table 2 lists the approximation last in Phase 2).  A tensor opts in through
+    TensorState.rows = size of its first dimension (0 = not centralized).
   * sparse threshold (Eq. 27): the base direction u is zeroed where |u| <= tau, after the trust ratio is
     taken (Phase 7 precedes Phase 8) and before the classical blend (Table 2's order within Phase 8).
     The mask is a discontinuous decision on a floating-point value: an implementation in another
@@ -86,6 +91,7 @@ class Hyper:
     auto_clip: tuple = (0.1, 2.0)
     clip_threshold: float = 0.0         # c_clip on the global gradient norm; 0 = off (section 5.8)
     sparse_threshold: float = 0.0       # tau of Eq. 27; 0 = off
+    use_gc: bool = False                # Eq. 26 on tensors that declare rows >= 1
 
     def __post_init__(self):
         assert self.nesterov in NESTEROV_MODES
@@ -143,16 +149,17 @@ class TensorState:
     slow0: Optional[np.ndarray] = None                 # theta_0^slow of the open window (Eq. 28)
     window: List[np.ndarray] = field(default_factory=list)   # the fast iterates of the open window
     ambiguous: Optional[np.ndarray] = None             # bookkeeping for comparisons only (see header, Eq. 27)
+    rows: int = 0                                      # size of dim 0 if the tensor has more than one dim, else 0 (Eq. 26)
 
     @property
     def dtype(self):
         return self.theta.dtype
 
 
-def init_state(theta0: np.ndarray, h: Hyper, state_dtype=np.float32) -> TensorState:
+def init_state(theta0: np.ndarray, h: Hyper, state_dtype=np.float32, rows: int = 0) -> TensorState:
     """m_0 = v_0 = 0; with lookahead on, slow weights start at theta_0 (Eq. 28, section 5.8)."""
     theta = np.array(theta0, dtype=state_dtype).reshape(-1).copy()
-    st = TensorState(theta, np.zeros_like(theta), np.zeros_like(theta))
+    st = TensorState(theta, np.zeros_like(theta), np.zeros_like(theta), rows=rows)
     if h.lookahead != "none":
         st.slow0 = theta.copy()
     return st
@@ -210,6 +217,9 @@ def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float 
     v_prev = st.v.astype(np.float64)
     g = np.asarray(grad).reshape(-1).astype(np.float64) * g_scale   # clipping comes first (section 7.3)
 
+    if h.use_gc and st.rows >= 1:
+        g2d = g.reshape(st.rows, -1)
+        g = (g2d - g2d.mean(axis=1, keepdims=True)).reshape(-1)    # Eq. 26
     if (not h.decoupled_decay) and h.weight_decay != 0.0:
         g = g + h.weight_decay * theta                      # coupled L2 (reading; see header)
     if h.nesterov == "approx":
@@ -288,10 +298,11 @@ def step_all(states: List[TensorState], grads, t: int, h: Hyper, aux: Optional[A
 
 
 def run(theta0_list, grads_fn, steps: int, h: Hyper, state_dtype=np.float32, t0: int = 0,
-        states: Optional[List[TensorState]] = None, aux: Optional[AutoLrState] = None) -> List[TensorState]:
+        states: Optional[List[TensorState]] = None, aux: Optional[AutoLrState] = None,
+        rows: Optional[List[int]] = None) -> List[TensorState]:
     """Run `steps` steps over a list of tensors; grads_fn(t) returns the gradient list of step t."""
     if states is None:
-        states = [init_state(th, h, state_dtype) for th in theta0_list]
+        states = [init_state(th, h, state_dtype, rows[i] if rows else 0) for i, th in enumerate(theta0_list)]
     if aux is None:
         aux = AutoLrState()
     for t in range(t0 + 1, t0 + steps + 1):

@@ -40,7 +40,7 @@ enum : int {
   LA_BASIC_FUSED = 4   // k-th step, basic mode:   S = c1*theta_new + c0*S; theta_out=S (S read, written)
 };
 
-enum : uint32_t { F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u, F_CLIP = 16u, F_SPARSE = 32u };
+enum : uint32_t { F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u, F_CLIP = 16u, F_SPARSE = 32u, F_GC = 64u };
 
 // The four state pointers of a tensor sit together so that one 32-byte scalar load fetches them.
 struct TensorPtrs {
@@ -50,12 +50,49 @@ struct TensorPtrs {
   float *la;
 };
 
+// Gradient centralization (Eq. 26) of one tensor: rows of `cols` contiguous elements; cols == 0 means
+// the tensor is not centralized.  `means` holds this step's mean of every row of the raw gradient.
+struct GcInfo {
+  int64_t cols;
+  double inv_cols;
+  const float *means;
+};
+
 struct Tables {
   const novak_chunk *chunks;
   const TensorPtrs *tensors;
   const void *const *grad;
   const float *gscale;   // one float: the step's gradient-clipping factor (read only when F_CLIP is set)
+  const GcInfo *gc;      // per tensor (read only when F_GC is set)
 };
+
+// idx / cols for 0 <= idx < 2^52 without an integer divide: double estimate, then one correction step
+__device__ __forceinline__ int64_t row_of(int64_t idx, int64_t cols, double inv_cols) {
+  int64_t q = static_cast<int64_t>(static_cast<double>(idx) * inv_cols);
+  if (q * cols > idx) --q;
+  else if ((q + 1) * cols <= idx) ++q;
+  return q;
+}
+
+// Subtracts the row means from `n` (<= 4) consecutive gradient values that start at element `e0` of a
+// centralized tensor.  Centralizing the raw gradient and scaling by the clipping factor afterwards
+// equals clipping first (the factor is one scalar for all tensors).
+template <typename V>
+__device__ __forceinline__ void centralize(V &g, int n, int64_t e0, const GcInfo &gc) {
+  int64_t row = row_of(e0, gc.cols, gc.inv_cols);
+  int64_t rem = e0 - row * gc.cols;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    if (k < n) {
+      while (rem >= gc.cols) { rem -= gc.cols; ++row; }
+      g[k] -= gc.means[row];
+      ++rem;
+    }
+  }
+}
+__device__ __forceinline__ float centralize_one(float g, int64_t e, const GcInfo &gc) {
+  return g - gc.means[row_of(e, gc.cols, gc.inv_cols)];
+}
 
 // Per-step scalars, rounded once from the host's double values.
 struct Consts {
@@ -171,7 +208,9 @@ constexpr bool la_writes(int la) { return la == LA_FIRST || la == LA_MID || la =
 // decoupled from the workgroup's.  blockIdx.x = (chunk index << sub_shift) | sub-block index.
 //
 // GradS: scalar gradient type (float, or unsigned short holding bf16 bits); GradV its 4-vector.
-template <typename GradS, typename GradV, int LA, bool NT, int UN, int BLOCK>
+// GC: compiled-in gradient centralization (Eq. 26) for tensors that ask for it (only instantiated for
+// the default shape UN = 1, BLOCK = 64).
+template <typename GradS, typename GradV, int LA, bool NT, int UN, int BLOCK, bool GC = false>
 __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, int sub_shift) {
   constexpr int SUB = BLOCK * 4 * UN;
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
@@ -182,6 +221,9 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
   const TensorPtrs tp = tb.tensors[ch.tensor];          // one scalar load, issued together with the next
   const void *const g_base = tb.grad[ch.tensor];
   const float gs = (c.flags & F_CLIP) ? *tb.gscale : 1.0f;
+  GcInfo gi;
+  gi.cols = 0;
+  if (GC) gi = tb.gc[ch.tensor];
   float *__restrict__ th_p = tp.param + off;
   float *__restrict__ m_p = tp.m + off;
   float *__restrict__ v_p = tp.v + off;
@@ -216,7 +258,9 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
         const int j = threadIdx.x + u * BLOCK;
-        update_vec<LA>(th[u], grad_to_f32<GradV>(g[u]), m[u], v[u], la[u], c, gs);
+        f32x4 gf = grad_to_f32<GradV>(g[u]);
+        if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(j), gi);
+        update_vec<LA>(th[u], gf, m[u], v[u], la[u], c, gs);
         st<NT>(th4 + j, th[u]);
         st<NT>(m4 + j, m[u]);
         st<NT>(v4 + j, v[u]);
@@ -229,7 +273,9 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
       f32x4 th = ld<NT>(th4 + i), m = ld<NT>(m4 + i), v = ld<NT>(v4 + i), la;
       GradV g = ld<NT>(g4 + i);
       if (la_reads(LA)) la = ld<NT>(la4 + i);
-      update_vec<LA>(th, grad_to_f32<GradV>(g), m, v, la, c, gs);
+      f32x4 gf = grad_to_f32<GradV>(g);
+      if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(i), gi);
+      update_vec<LA>(th, gf, m, v, la, c, gs);
       st<NT>(th4 + i, th);
       st<NT>(m4 + i, m);
       st<NT>(v4 + i, v);
@@ -243,6 +289,7 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
     if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
     else g = g_p[i];
     if (la_reads(LA)) la = la_p[i];
+    if (GC && gi.cols) g = centralize_one(g, off + i, gi);
     update_one<LA>(th, g, m, v, la, c, gs);
     th_p[i] = th;
     m_p[i] = m;
@@ -347,6 +394,9 @@ __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, 
   const TensorPtrs tp = tb.tensors[ch.tensor];
   const void *const g_base = tb.grad[ch.tensor];
   const float gs = (c.flags & F_CLIP) ? *tb.gscale : 1.0f;
+  GcInfo gi;
+  gi.cols = 0;
+  if (c.flags & F_GC) gi = tb.gc[ch.tensor];
   const float *__restrict__ th_p = tp.param + off;
   float *__restrict__ m_p = tp.m + off;
   float *__restrict__ v_p = tp.v + off;
@@ -366,8 +416,11 @@ __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, 
     const int i = threadIdx.x;
     if (i < nvec) {
       const f32x4 th = ld<NT>(th4 + i);
-      const f32x4 g = grad_to_f32<GradV>(ld<NT>(g4 + i));
+      f32x4 g = grad_to_f32<GradV>(ld<NT>(g4 + i));
       f32x4 m = ld<NT>(m4 + i), v = ld<NT>(v4 + i);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) s_g = __builtin_fmaf(g[k], g[k], s_g);     // norm of the gradient as handed in
+      if (gi.cols) centralize(g, 4, off + 4 * static_cast<int64_t>(i), gi);
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         float m_k = m[k], v_k = v[k], m_hat;
@@ -375,7 +428,6 @@ __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, 
         const float u = direction(m_k, v_k, c, m_hat);
         s_th = __builtin_fmaf(th[k], th[k], s_th);
         s_u = __builtin_fmaf(u, u, s_u);
-        s_g = __builtin_fmaf(g[k], g[k], s_g);
         m[k] = m_k; v[k] = v_k;
       }
       st<NT>(m4 + i, m);
@@ -388,11 +440,12 @@ __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, 
     float m = m_p[i], v = v_p[i], g, m_hat;
     if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
     else g = g_p[i];
+    s_g = __builtin_fmaf(g, g, s_g);
+    if (gi.cols) g = centralize_one(g, off + i, gi);
     moments(th, g, m, v, c, gs);
     const float u = direction(m, v, c, m_hat);
     s_th = __builtin_fmaf(th, th, s_th);
     s_u = __builtin_fmaf(u, u, s_u);
-    s_g = __builtin_fmaf(g, g, s_g);
     m_p[i] = m;
     v_p[i] = v;
   }
@@ -470,6 +523,32 @@ __global__ __launch_bounds__(64) void novak_clip_kernel(int n_tensors, const Nor
     const double norm = sqrt(g);
     gscale[0] = norm > static_cast<double>(c_clip) ? static_cast<float>(static_cast<double>(c_clip) / norm) : 1.0f;
   }
+}
+
+// Row means for gradient centralization (Eq. 26): one wave per row of a centralized tensor.
+// `gc_tensor[j]` lists the centralized tensors, `row_first[j]` the index of tensor j's first row in
+// the launch (prefix sums, n_gc + 1 entries).
+template <typename GradS>
+__global__ __launch_bounds__(64) void novak_rowmean_kernel(const void *const *grad, const int *gc_tensor, const int64_t *row_first,
+                                                          int n_gc, const GcInfo *gc, float *means) {
+  const int64_t row = blockIdx.x;
+  int lo = 0, hi = n_gc - 1;                     // largest j with row_first[j] <= row
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (row_first[mid] <= row) lo = mid;
+    else hi = mid - 1;
+  }
+  const int t = gc_tensor[lo];
+  const int64_t local = row - row_first[lo];
+  const int64_t cols = gc[t].cols;
+  const GradS *__restrict__ p = static_cast<const GradS *>(grad[t]) + local * cols;
+  float acc = 0.0f;
+  for (int64_t i = threadIdx.x; i < cols; i += 64) {
+    if constexpr (sizeof(GradS) == 2) acc += bf16_to_f32(p[i]);
+    else acc += p[i];
+  }
+  const double sum = wave_sum(static_cast<double>(acc));
+  if (threadIdx.x == 0) means[row] = static_cast<float>(sum / static_cast<double>(cols));
 }
 
 struct ScaleParams {
@@ -613,6 +692,13 @@ struct novak_handle {
   int *d_first_chunk = nullptr;        // n_tensors + 1: chunk range of each tensor
   float *d_scale = nullptr;            // n_tensors: lambda_trust * alpha_auto
   float *d_gscale = nullptr;           // one float: gradient-clipping factor of the current step
+  // gradient centralization (built once in novak_create)
+  GcInfo *d_gc = nullptr;              // per tensor
+  int *d_gc_tensor = nullptr;          // centralized tensors
+  int64_t *d_row_first = nullptr;      // their first rows (prefix sums, n_gc + 1)
+  float *d_row_means = nullptr;        // one float per row
+  int n_gc = 0;
+  int64_t total_rows = 0;
   double *d_ema = nullptr;             // caller-owned: g_bar, theta_bar
   // device-side tables (owned)
   novak_chunk *d_chunks = nullptr;
@@ -673,6 +759,7 @@ Tables tables_of(const novak_handle *h) {
   tb.tensors = reinterpret_cast<const TensorPtrs *>(base);
   tb.grad = reinterpret_cast<const void *const *>(base + n * sizeof(TensorPtrs));
   tb.gscale = h->d_gscale;
+  tb.gc = h->d_gc;
   return tb;
 }
 
@@ -814,9 +901,42 @@ void launch_step_block(const novak_handle *h, int grad_dtype, int la, hipStream_
   }
 }
 
+template <typename GradS, typename GradV, bool NT>
+void launch_step_gc(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+  const Geometry gm = geometry_of(h, 256, 64, step_streams16(grad_dtype, la));
+  const dim3 grid(gm.grid), block(64);
+  switch (la) {
+    case LA_OFF: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_OFF, NT, 1, 64, true>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_FIRST: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_FIRST, NT, 1, 64, true>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_MID: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_MID, NT, 1, 64, true>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_LAST_FUSED, NT, 1, 64, true>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    default: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_BASIC_FUSED, NT, 1, 64, true>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+  }
+}
+
 void launch_step(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+  if (c.flags & F_GC) {   // centralization is compiled into the default launch shape only
+    if (grad_dtype == NOVAK_GRAD_BF16) {
+      if (h->nontemporal) launch_step_gc<unsigned short, u16x4, true>(h, grad_dtype, la, s, tb, c);
+      else launch_step_gc<unsigned short, u16x4, false>(h, grad_dtype, la, s, tb, c);
+    } else {
+      if (h->nontemporal) launch_step_gc<float, f32x4, true>(h, grad_dtype, la, s, tb, c);
+      else launch_step_gc<float, f32x4, false>(h, grad_dtype, la, s, tb, c);
+    }
+    return;
+  }
   if (h->nontemporal) launch_step_block<true>(h, grad_dtype, la, s, tb, c);
   else launch_step_block<false>(h, grad_dtype, la, s, tb, c);
+}
+
+int launch_rowmeans(novak_handle *h, int grad_dtype, hipStream_t s, const Tables &tb) {
+  const dim3 grid(static_cast<unsigned>(h->total_rows)), block(64);
+  if (grad_dtype == NOVAK_GRAD_BF16)
+    hipLaunchKernelGGL((novak_rowmean_kernel<unsigned short>), grid, block, 0, s, tb.grad, h->d_gc_tensor, h->d_row_first, h->n_gc, h->d_gc, h->d_row_means);
+  else
+    hipLaunchKernelGGL((novak_rowmean_kernel<float>), grid, block, 0, s, tb.grad, h->d_gc_tensor, h->d_row_first, h->n_gc, h->d_gc, h->d_row_means);
+  NOVAK_HIP(h, hipGetLastError());
+  return NOVAK_OK;
 }
 
 template <int OP, int BLOCK>
@@ -954,6 +1074,8 @@ int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor
     const uintptr_t bits = reinterpret_cast<uintptr_t>(d.param) | reinterpret_cast<uintptr_t>(d.exp_avg) |
                            reinterpret_cast<uintptr_t>(d.exp_avg_sq) | reinterpret_cast<uintptr_t>(d.la_buf);
     if (bits & 3u) return fail(nullptr, NOVAK_ERR_MISALIGNED, "tensor " + std::to_string(i) + ": pointer not 4-byte aligned");
+    if (eff.use_gc && (d.rows < 0 || (d.rows > 0 && d.numel % d.rows != 0)))
+      return fail(nullptr, NOVAK_ERR_INVALID_ARG, "tensor " + std::to_string(i) + ": rows must be >= 0 and divide numel");
   }
 
   novak_handle *h = new (std::nothrow) novak_handle();
@@ -997,6 +1119,39 @@ int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor
     for (int r = 0; r < novak_handle::kRing; ++r)
       if ((e = hipEventCreateWithFlags(&h->ring_ev[r], hipEventDisableTiming)) != hipSuccess) return bail(fail_hip(h, e, "hipEventCreate"));
   }
+  if (eff.use_gc && n_tensors > 0) {
+    const size_t n = static_cast<size_t>(n_tensors);
+    std::vector<GcInfo> info(n);
+    std::vector<int> list;
+    std::vector<int64_t> first(1, 0);
+    for (size_t i = 0; i < n; ++i) {
+      info[i].cols = 0; info[i].inv_cols = 0.0; info[i].means = nullptr;
+      if (tensors[i].rows >= 1 && tensors[i].numel > 0) {
+        list.push_back(static_cast<int>(i));
+        first.push_back(first.back() + tensors[i].rows);
+      }
+    }
+    h->n_gc = static_cast<int>(list.size());
+    h->total_rows = first.back();
+    if (h->total_rows > 0x7fffffffLL) return bail(fail(h, NOVAK_ERR_INVALID_ARG, "too many rows to centralize in one launch"));
+    if (h->n_gc > 0) {
+      if ((e = hipMalloc(reinterpret_cast<void **>(&h->d_row_means), static_cast<size_t>(h->total_rows) * sizeof(float))) != hipSuccess)
+        return bail(fail_hip(h, e, "hipMalloc(row means)"));
+      for (size_t j = 0; j < list.size(); ++j) {
+        const size_t i = static_cast<size_t>(list[j]);
+        info[i].cols = tensors[i].numel / tensors[i].rows;
+        info[i].inv_cols = 1.0 / static_cast<double>(info[i].cols);
+        info[i].means = h->d_row_means + first[j];
+      }
+      if ((e = hipMalloc(reinterpret_cast<void **>(&h->d_gc), n * sizeof(GcInfo))) != hipSuccess ||
+          (e = hipMemcpy(h->d_gc, info.data(), n * sizeof(GcInfo), hipMemcpyHostToDevice)) != hipSuccess ||
+          (e = hipMalloc(reinterpret_cast<void **>(&h->d_gc_tensor), list.size() * sizeof(int))) != hipSuccess ||
+          (e = hipMemcpy(h->d_gc_tensor, list.data(), list.size() * sizeof(int), hipMemcpyHostToDevice)) != hipSuccess ||
+          (e = hipMalloc(reinterpret_cast<void **>(&h->d_row_first), first.size() * sizeof(int64_t))) != hipSuccess ||
+          (e = hipMemcpy(h->d_row_first, first.data(), first.size() * sizeof(int64_t), hipMemcpyHostToDevice)) != hipSuccess)
+        return bail(fail_hip(h, e, "gradient-centralization tables"));
+    }
+  }
   rc = build_chunk_table(h);
   if (rc != NOVAK_OK) return bail(rc);
   *out = h;
@@ -1009,6 +1164,10 @@ int novak_destroy(novak_handle *h) {
   (void)scope.enter(h->device_id);
   free_device_tables(h);
   if (h->d_ptrs) (void)hipFree(h->d_ptrs);
+  if (h->d_gc) (void)hipFree(h->d_gc);
+  if (h->d_gc_tensor) (void)hipFree(h->d_gc_tensor);
+  if (h->d_row_first) (void)hipFree(h->d_row_first);
+  if (h->d_row_means) (void)hipFree(h->d_row_means);
   if (h->h_ring) (void)hipHostFree(h->h_ring);
   for (int r = 0; r < novak_handle::kRing; ++r)
     if (h->ring_ev[r]) (void)hipEventDestroy(h->ring_ev[r]);
@@ -1031,6 +1190,8 @@ int novak_get_info(const novak_handle *h, novak_info *info) {
   info->device_id = h->device_id;
   info->layer_adaptation = h->hp.layer_adaptation;
   info->auto_lr = h->hp.auto_lr;
+  info->use_gc = h->hp.use_gc;
+  info->n_centralized = h->n_gc;
   return NOVAK_OK;
 }
 
@@ -1193,6 +1354,11 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
     }
     if (clipping(h)) {
       rc = launch_clip_prepass(h, grad_dtype, stream, tables_of(h));
+      if (rc != NOVAK_OK) return rc;
+    }
+    if (h->n_gc > 0) {
+      c.flags |= F_GC;
+      rc = launch_rowmeans(h, grad_dtype, stream, tables_of(h));
       if (rc != NOVAK_OK) return rc;
     }
     if (two_pass(h)) {

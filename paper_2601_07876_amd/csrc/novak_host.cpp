@@ -65,6 +65,7 @@ int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, ui
   if (hp->lookahead_mode != NOVAK_LOOKAHEAD_NONE && !(hp->la_alpha > 0.0 && hp->la_alpha <= 1.0)) return NOVAK_ERR_INVALID_ARG;
 
   if (!(hp->clip_threshold >= 0.0) || !(hp->sparse_threshold >= 0.0)) return NOVAK_ERR_INVALID_ARG;
+  if (hp->reserved0 != 0) return NOVAK_ERR_INVALID_ARG;
   if (hp->layer_adaptation && !(hp->trust_clip_lo > 0.0 && hp->trust_clip_lo <= hp->trust_clip_hi)) return NOVAK_ERR_INVALID_ARG;
   if (hp->auto_lr) {
     if (!(hp->auto_lr_gamma > 0.0 && hp->auto_lr_gamma <= 1.0)) return NOVAK_ERR_INVALID_ARG;
@@ -86,6 +87,7 @@ int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, ui
   }
   eff.layer_adaptation = eff.layer_adaptation ? 1 : 0;
   eff.auto_lr = eff.auto_lr ? 1 : 0;
+  eff.use_gc = eff.use_gc ? 1 : 0;
   // section 7.1: layer adaptation and auto-LR exist only in full-features mode
   if (eff.mode == NOVAK_MODE_FAST) {
     if (eff.layer_adaptation) {
@@ -95,6 +97,10 @@ int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, ui
     if (eff.auto_lr) {
       eff.auto_lr = 0;
       warn |= NOVAK_WARN_AUTO_LR_DISABLED;
+    }
+    if (eff.use_gc) {
+      eff.use_gc = 0;
+      warn |= NOVAK_WARN_GC_DISABLED;
     }
   }
   eff.rectified = eff.rectified ? 1 : 0;

@@ -23,7 +23,7 @@ NOVAK_UNRECT_ADAM_DENOM, NOVAK_UNRECT_SGDM = 0, 1
 NOVAK_MODE_FAST, NOVAK_MODE_RESEARCH = 0, 1
 NOVAK_GRAD_F32, NOVAK_GRAD_BF16 = 0, 1
 NOVAK_WARN_TRUE_NESTEROV_DOWNGRADED, NOVAK_WARN_LOOKAHEAD_DOWNGRADED = 1, 2
-NOVAK_WARN_LAYER_ADAPTATION_DISABLED, NOVAK_WARN_AUTO_LR_DISABLED = 4, 8
+NOVAK_WARN_LAYER_ADAPTATION_DISABLED, NOVAK_WARN_AUTO_LR_DISABLED, NOVAK_WARN_GC_DISABLED = 4, 8, 16
 NOVAK_TUNE_CHUNK_ELEMS, NOVAK_TUNE_NONTEMPORAL, NOVAK_TUNE_VEC_PER_LANE, NOVAK_TUNE_THREADS, NOVAK_TUNE_WAVES_PER_CU = 0, 1, 2, 3, 4
 
 NESTEROV = {"none": 0, "approx": 1, "classical": 2, "true": 3}
@@ -43,12 +43,13 @@ class novak_hparams(C.Structure):
                 ("layer_adaptation", C.c_int32), ("auto_lr", C.c_int32), ("auto_lr_gamma", C.c_double),
                 ("trust_clip_lo", C.c_double), ("trust_clip_hi", C.c_double),
                 ("auto_clip_lo", C.c_double), ("auto_clip_hi", C.c_double),
-                ("clip_threshold", C.c_double), ("sparse_threshold", C.c_double)]
+                ("clip_threshold", C.c_double), ("sparse_threshold", C.c_double),
+                ("use_gc", C.c_int32), ("reserved0", C.c_int32)]
 
 
 class novak_tensor_desc(C.Structure):
     _fields_ = [("param", C.c_void_p), ("exp_avg", C.c_void_p), ("exp_avg_sq", C.c_void_p),
-                ("la_buf", C.c_void_p), ("numel", C.c_int64)]
+                ("la_buf", C.c_void_p), ("numel", C.c_int64), ("rows", C.c_int64)]
 
 
 class novak_step_scalars(C.Structure):
@@ -66,7 +67,8 @@ class novak_info(C.Structure):
                 ("warnings", C.c_uint32), ("n_tensors", C.c_int32), ("n_chunks", C.c_int64),
                 ("chunk_elems", C.c_int64), ("total_numel", C.c_int64), ("last_step", C.c_int64),
                 ("sync_due", C.c_int32), ("device_id", C.c_int32),
-                ("layer_adaptation", C.c_int32), ("auto_lr", C.c_int32)]
+                ("layer_adaptation", C.c_int32), ("auto_lr", C.c_int32), ("use_gc", C.c_int32),
+                ("n_centralized", C.c_int32)]
 
 
 EXPORTS = ("novak_validate_hparams", "novak_compute_step_scalars", "novak_plan_chunks",
@@ -133,7 +135,7 @@ def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, be
                  rectified=True, decoupled_decay=True, nesterov="approx", lookahead="memory_efficient",
                  unrect_fallback="adam_denom", mode="fast", auto_sync=False, layer_adaptation=False, auto_lr=False,
                  auto_lr_gamma=0.1, trust_clip=(0.1, 10.0), auto_clip=(0.1, 2.0), clip_threshold=0.0,
-                 sparse_threshold=0.0) -> novak_hparams:
+                 sparse_threshold=0.0, use_gc=False) -> novak_hparams:
     """Fills a novak_hparams from keyword values (mode names or their integer codes)."""
     def code(table: Dict[str, int], x):
         return table[x] if isinstance(x, str) else int(x)
@@ -141,7 +143,8 @@ def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, be
                          int(rectified), int(decoupled_decay), code(NESTEROV, nesterov), code(LOOKAHEAD, lookahead),
                          code(UNRECT, unrect_fallback), code(MODE, mode), int(auto_sync), int(layer_adaptation),
                          int(auto_lr), float(auto_lr_gamma), float(trust_clip[0]), float(trust_clip[1]),
-                         float(auto_clip[0]), float(auto_clip[1]), float(clip_threshold), float(sparse_threshold))
+                         float(auto_clip[0]), float(auto_clip[1]), float(clip_threshold), float(sparse_threshold),
+                         int(use_gc), 0)
 
 
 # ---- the entry points, same names as the C ABI ------------------------------------------------------
@@ -248,14 +251,16 @@ def novak_last_error(handle=None) -> str:
 
 # ---- convenience: marshal torch tensors into descriptors -------------------------------------------
 def tensor_desc(param, exp_avg, exp_avg_sq, la_buf=None) -> novak_tensor_desc:
-    """Descriptor from contiguous fp32 torch tensors that live on the GPU."""
+    """Descriptor from contiguous fp32 torch tensors that live on the GPU; `rows` (Eq. 26) is the size of
+    the parameter's first dimension when it has more than one."""
     for t in (param, exp_avg, exp_avg_sq) + ((la_buf,) if la_buf is not None else ()):
         if not t.is_contiguous() or str(t.dtype) != "torch.float32" or not t.is_cuda:
             raise ValueError("state tensors must be contiguous fp32 GPU tensors")
         if t.numel() != param.numel():
             raise ValueError("state tensors must have the parameter's element count")
     return novak_tensor_desc(param.data_ptr(), exp_avg.data_ptr(), exp_avg_sq.data_ptr(),
-                             la_buf.data_ptr() if la_buf is not None else None, param.numel())
+                             la_buf.data_ptr() if la_buf is not None else None, param.numel(),
+                             param.shape[0] if param.dim() > 1 else 0)
 
 
 def check(rc: int, where: str, handle=None) -> None:

@@ -33,6 +33,7 @@ def oracle_hyper(hyper: Dict[str, object], effective_nesterov: Optional[str] = N
     if info is not None:
         h["layer_adaptation"] = bool(info.layer_adaptation)
         h["auto_lr"] = bool(info.auto_lr)
+        h["use_gc"] = bool(info.use_gc)
     return O.Hyper(**h)
 
 
@@ -48,8 +49,9 @@ class GpuNovak:
                  theta0: Optional[List[np.ndarray]] = None, misalign: int = 0, guard: int = 0,
                  chunk_elems: Optional[int] = None, nontemporal: Optional[bool] = None,
                  auto_sync: bool = False, device: str = "cuda:0", lookahead_init: bool = True,
-                 vec_per_lane: Optional[int] = None, threads: Optional[int] = None):
+                 vec_per_lane: Optional[int] = None, threads: Optional[int] = None, rows: Optional[Sequence[int]] = None):
         self.numels = list(numels)
+        self.rows = list(rows) if rows is not None else [0] * len(self.numels)
         self.hyper = dict(hyper)
         self.grad_dtype = grad_dtype
         self.device = torch.device(device)
@@ -69,7 +71,7 @@ class GpuNovak:
                 self.theta[i].copy_(torch.from_numpy(np.ascontiguousarray(theta0[i], dtype=np.float32)))
         hp = N.make_hparams(auto_sync=auto_sync, **self.hyper)
         descs = [N.novak_tensor_desc(self.theta[i].data_ptr(), self.m[i].data_ptr(), self.v[i].data_ptr(),
-                                     self.la[i].data_ptr(), n) for i, n in enumerate(self.numels)]
+                                     self.la[i].data_ptr(), n, self.rows[i]) for i, n in enumerate(self.numels)]
         rc, self.handle = N.novak_create(hp, descs, self.device.index or 0)
         N.check(rc, "novak_create")
         if chunk_elems is not None:
@@ -176,13 +178,14 @@ def assert_close_strict(name: str, got: np.ndarray, ref: np.ndarray, rtol: float
 def run_pair(numels: Sequence[int], hyper: Dict[str, object], steps: int, grad_std: float, grad_dtype: str = "f32",
              seed: int = 42, auto_sync: bool = False, chunk_elems: Optional[int] = None,
              nontemporal: Optional[bool] = None, misalign: int = 0, grad_misalign: int = 0, guard: int = 0,
-             check_blend_at: Sequence[int] = (), vec_per_lane: Optional[int] = None, threads: Optional[int] = None):
+             check_blend_at: Sequence[int] = (), vec_per_lane: Optional[int] = None, threads: Optional[int] = None,
+             rows: Optional[Sequence[int]] = None):
     """Runs GPU and oracle over host-generated inputs; returns (gpu, oracle states) after `steps`."""
     theta0 = W.host_params(numels, seed)
     gpu = GpuNovak(numels, hyper, grad_dtype, theta0, misalign=misalign, guard=guard, chunk_elems=chunk_elems,
-                   nontemporal=nontemporal, auto_sync=auto_sync, vec_per_lane=vec_per_lane, threads=threads)
+                   nontemporal=nontemporal, auto_sync=auto_sync, vec_per_lane=vec_per_lane, threads=threads, rows=rows)
     h = oracle_hyper(hyper, gpu.eff_nesterov, gpu.eff_lookahead, gpu.info)
-    states = [O.init_state(th, h) for th in theta0]
+    states = [O.init_state(th, h, rows=gpu.rows[i]) for i, th in enumerate(theta0)]
     aux = O.AutoLrState()
     for t in range(1, steps + 1):
         gh = W.host_grads(numels, t, grad_std, seed, bf16=(grad_dtype == "bf16"))

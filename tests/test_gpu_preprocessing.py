@@ -57,3 +57,48 @@ def test_sparse_mask_zeroes_small_directions_exactly():
         assert np.all(th[1::2] != theta0[0][1::2])
     finally:
         gpu.close()
+
+
+GC_SHAPES = [(64, 3, 7, 7), (64,), (256, 64, 1, 1), (5, 1021), (1000, 2048), (1000,), (3, 5, 7), (4099, 1), (1, 4097), (2, 65536 + 3)]
+
+
+@pytest.mark.parametrize("grad_dtype,two_pass,clip,misalign", [("f32", False, 0.0, 0), ("bf16", False, 1.0, 0), ("f32", True, 1.0, 0),
+                                                               ("f32", False, 0.0, 1), ("bf16", True, 0.0, 3)])
+def test_gradient_centralization(grad_dtype, two_pass, clip, misalign):
+    """Eq. 26 on conv / linear shaped tensors: rows of 147, 64, 1021, 2048 elements, one-element rows
+    (the centralized gradient is zero), one single long row, and vectors that are left alone."""
+    numels = [int(np.prod(s)) for s in GC_SHAPES]
+    rows = [s[0] if len(s) > 1 else 0 for s in GC_SHAPES]
+    hyper = dict(W.BASE_HYPER, mode="research", use_gc=True, clip_threshold=clip, layer_adaptation=two_pass, auto_lr=two_pass)
+    print(f"gc {grad_dtype} {two_pass} {clip} {misalign}", flush=True)
+    gpu, states, h = H.run_pair(numels, hyper, 7, 1e-2, grad_dtype, auto_sync=True, rows=rows, guard=8,
+                                misalign=misalign, grad_misalign=misalign)
+    try:
+        assert gpu.info.use_gc == 1 and gpu.info.n_centralized == sum(1 for r in rows if r >= 1)
+        H.compare_states(gpu, states)
+        assert gpu.guards_intact()
+        # rows of one element: the centralized gradient is exactly zero, so m stays zero
+        assert not gpu.host("m")[7].any()
+    finally:
+        gpu.close()
+
+
+def test_centralization_changes_results_and_fast_mode_switches_it_off():
+    numels = [int(np.prod(s)) for s in GC_SHAPES[:4]]
+    rows = [s[0] if len(s) > 1 else 0 for s in GC_SHAPES[:4]]
+    on, st_on, _ = H.run_pair(numels, dict(W.BASE_HYPER, mode="research", use_gc=True), 3, 1e-2, rows=rows)
+    off, st_off, _ = H.run_pair(numels, dict(W.BASE_HYPER, mode="fast", use_gc=True), 3, 1e-2, rows=rows)
+    try:
+        assert off.info.use_gc == 0 and off.info.warnings & N.NOVAK_WARN_GC_DISABLED
+        H.compare_states(on, st_on)
+        H.compare_states(off, st_off)
+        assert np.max(np.abs(on.host("theta")[0] - off.host("theta")[0])) > 1e-6
+    finally:
+        on.close()
+        off.close()
+
+
+def test_rows_must_divide_numel():
+    hp = N.make_hparams(mode="research", use_gc=True, lookahead="none")
+    assert N.novak_create(hp, [N.novak_tensor_desc(256, 512, 768, None, 10, 3)])[0] == N.NOVAK_ERR_INVALID_ARG
+    assert N.novak_create(hp, [N.novak_tensor_desc(256, 512, 768, None, 10, -1)])[0] == N.NOVAK_ERR_INVALID_ARG

@@ -77,3 +77,50 @@ def test_sparse_mask_comes_before_the_classical_blend_and_after_the_trust_ratio(
     eta = np.linalg.norm(theta) / np.linalg.norm(u)
     st = O.run([theta], lambda t: [g], 1, _h(sparse_threshold=0.5, layer_adaptation=True), state_dtype=np.float64)[0]
     np.testing.assert_allclose(st.theta, theta - 1e-3 * eta * masked, rtol=1e-13)
+
+
+def test_gradient_centralization_matches_library_definition():
+    """Eq. 26 on a 4-D conv gradient: g - mean over dims 1..3, against torch's mean reduction."""
+    rng = np.random.default_rng(3)
+    shape = (6, 3, 5, 5)
+    g = rng.normal(0.3, 1.0, shape)
+    want = torch.tensor(g) - torch.tensor(g).mean(dim=(1, 2, 3), keepdim=True)
+    h = _h(use_gc=True, lr=1.0, beta1=0.0, beta2=0.0, eps=1e-300)      # m = g_c after one step
+    st = O.run([np.zeros(g.size)], lambda t: [g.reshape(-1)], 1, h, state_dtype=np.float64, rows=[6])[0]
+    np.testing.assert_allclose(st.m, want.numpy().reshape(-1), rtol=1e-12, atol=1e-15)
+    # each dim-0 slice of the centralized gradient sums to zero
+    assert np.max(np.abs(st.m.reshape(6, -1).sum(axis=1))) < 1e-12
+    # vectors (rows = 0) are left alone, and so is everything when use_gc is off
+    st1 = O.run([np.zeros(g.size)], lambda t: [g.reshape(-1)], 1, h, state_dtype=np.float64, rows=[0])[0]
+    np.testing.assert_allclose(st1.m, g.reshape(-1), rtol=1e-15)
+    st2 = O.run([np.zeros(g.size)], lambda t: [g.reshape(-1)], 1, _h(lr=1.0, beta1=0.0, beta2=0.0), state_dtype=np.float64, rows=[6])[0]
+    np.testing.assert_allclose(st2.m, g.reshape(-1), rtol=1e-15)
+
+
+def test_centralization_order_after_clip_before_nesterov():
+    """clip -> centralize -> approximation: equals feeding the pre-processed gradient to a plain run."""
+    rng = np.random.default_rng(4)
+    rows, cols = 5, 12
+    th = [rng.normal(0, 0.02, rows * cols), rng.normal(0, 0.02, 9)]
+    gs = [[rng.normal(0.5, 2.0, rows * cols), rng.normal(0, 2.0, 9)] for _ in range(5)]
+    kw = dict(nesterov="approx", rectified=True, weight_decay=0.01)
+    a = O.run(th, lambda t: gs[t - 1], 5, _h(clip_threshold=1.0, use_gc=True, **kw), state_dtype=np.float64, rows=[rows, 0])
+    pre = []
+    for g in gs:
+        s = 1.0 / np.sqrt(sum(float(np.dot(x, x)) for x in g))       # all norms exceed 1
+        g0 = (g[0] * s).reshape(rows, cols)
+        pre.append([(g0 - g0.mean(axis=1, keepdims=True)).reshape(-1), g[1] * s])
+    b = O.run(th, lambda t: pre[t - 1], 5, _h(**kw), state_dtype=np.float64)
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(x.theta, y.theta, rtol=1e-12)
+        np.testing.assert_allclose(x.m, y.m, rtol=1e-11, atol=1e-18)
+
+
+def test_centralization_degenerate_rows():
+    """rows = numel: every slice is one element, the centralized gradient is zero; rows = 1: global mean."""
+    g = np.array([1.0, 2.0, 4.0, 9.0])
+    h = _h(use_gc=True, lr=1.0, beta1=0.0, beta2=0.0)
+    st = O.run([np.zeros(4)], lambda t: [g], 1, h, state_dtype=np.float64, rows=[4])[0]
+    assert not st.m.any()
+    st = O.run([np.zeros(4)], lambda t: [g], 1, h, state_dtype=np.float64, rows=[1])[0]
+    np.testing.assert_allclose(st.m, g - 4.0, rtol=1e-15)

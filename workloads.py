@@ -131,6 +131,11 @@ class Workload:
     def total(self) -> int:
         return sum(self.numels)
 
+    @property
+    def rows(self) -> List[int]:
+        """Size of the first dimension of tensors with more than one dimension, else 0."""
+        return [int(s[0]) if len(s) > 1 else 0 for s in self.shapes]
+
 
 # Hyper-parameters shared by every configuration unless a workload overrides them.
 BASE_HYPER: Dict[str, object] = dict(
