@@ -51,11 +51,14 @@ struct TensorPtrs {
 };
 
 // Gradient centralization (Eq. 26) of one tensor: rows of `cols` contiguous elements; cols == 0 means
-// the tensor is not centralized.  `means` holds this step's mean of every row of the raw gradient.
+// the tensor is not centralized.  `means` holds this step's mean of every row of the raw gradient, in
+// double: g - mean is formed in double and rounded once, so an element whose centralized gradient
+// nearly cancels keeps a relative (not absolute) error - at t = 1 the direction g/(|g|+eps) is
+// sign-like and would amplify an absolute error of half an ulp of g.
 struct GcInfo {
   int64_t cols;
   double inv_cols;
-  const float *means;
+  const double *means;
 };
 
 struct Tables {
@@ -85,13 +88,13 @@ __device__ __forceinline__ void centralize(V &g, int n, int64_t e0, const GcInfo
   for (int k = 0; k < 4; ++k) {
     if (k < n) {
       while (rem >= gc.cols) { rem -= gc.cols; ++row; }
-      g[k] -= gc.means[row];
+      g[k] = static_cast<float>(static_cast<double>(g[k]) - gc.means[row]);
       ++rem;
     }
   }
 }
 __device__ __forceinline__ float centralize_one(float g, int64_t e, const GcInfo &gc) {
-  return g - gc.means[row_of(e, gc.cols, gc.inv_cols)];
+  return static_cast<float>(static_cast<double>(g) - gc.means[row_of(e, gc.cols, gc.inv_cols)]);
 }
 
 // Per-step scalars, rounded once from the host's double values.
@@ -530,7 +533,7 @@ __global__ __launch_bounds__(64) void novak_clip_kernel(int n_tensors, const Nor
 // the launch (prefix sums, n_gc + 1 entries).
 template <typename GradS>
 __global__ __launch_bounds__(64) void novak_rowmean_kernel(const void *const *grad, const int *gc_tensor, const int64_t *row_first,
-                                                          int n_gc, const GcInfo *gc, float *means) {
+                                                          int n_gc, const GcInfo *gc, double *means) {
   const int64_t row = blockIdx.x;
   int lo = 0, hi = n_gc - 1;                     // largest j with row_first[j] <= row
   while (lo < hi) {
@@ -542,13 +545,13 @@ __global__ __launch_bounds__(64) void novak_rowmean_kernel(const void *const *gr
   const int64_t local = row - row_first[lo];
   const int64_t cols = gc[t].cols;
   const GradS *__restrict__ p = static_cast<const GradS *>(grad[t]) + local * cols;
-  float acc = 0.0f;
+  double acc = 0.0;
   for (int64_t i = threadIdx.x; i < cols; i += 64) {
-    if constexpr (sizeof(GradS) == 2) acc += bf16_to_f32(p[i]);
-    else acc += p[i];
+    if constexpr (sizeof(GradS) == 2) acc += static_cast<double>(bf16_to_f32(p[i]));
+    else acc += static_cast<double>(p[i]);
   }
-  const double sum = wave_sum(static_cast<double>(acc));
-  if (threadIdx.x == 0) means[row] = static_cast<float>(sum / static_cast<double>(cols));
+  const double sum = wave_sum(acc);
+  if (threadIdx.x == 0) means[row] = sum / static_cast<double>(cols);
 }
 
 struct ScaleParams {
@@ -696,7 +699,7 @@ struct novak_handle {
   GcInfo *d_gc = nullptr;              // per tensor
   int *d_gc_tensor = nullptr;          // centralized tensors
   int64_t *d_row_first = nullptr;      // their first rows (prefix sums, n_gc + 1)
-  float *d_row_means = nullptr;        // one float per row
+  double *d_row_means = nullptr;       // one double per row
   int n_gc = 0;
   int64_t total_rows = 0;
   double *d_ema = nullptr;             // caller-owned: g_bar, theta_bar
@@ -1135,7 +1138,7 @@ int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor
     h->total_rows = first.back();
     if (h->total_rows > 0x7fffffffLL) return bail(fail(h, NOVAK_ERR_INVALID_ARG, "too many rows to centralize in one launch"));
     if (h->n_gc > 0) {
-      if ((e = hipMalloc(reinterpret_cast<void **>(&h->d_row_means), static_cast<size_t>(h->total_rows) * sizeof(float))) != hipSuccess)
+      if ((e = hipMalloc(reinterpret_cast<void **>(&h->d_row_means), static_cast<size_t>(h->total_rows) * sizeof(double))) != hipSuccess)
         return bail(fail_hip(h, e, "hipMalloc(row means)"));
       for (size_t j = 0; j < list.size(); ++j) {
         const size_t i = static_cast<size_t>(list[j]);
