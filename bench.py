@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--separate-sync", action="store_true", help="call novak_lookahead_sync instead of fusing the sync")
     ap.add_argument("--layer-adaptation", action="store_true", help="research mode: per-tensor trust ratio (two-pass step)")
     ap.add_argument("--auto-lr", action="store_true", help="research mode: auto-LR factor (two-pass step)")
+    ap.add_argument("--use-gc", action="store_true", help="research mode: gradient centralization of the multi-dimensional tensors")
+    ap.add_argument("--clip", type=float, default=0.0, help="global-norm gradient clipping threshold (0 = off)")
+    ap.add_argument("--sparse", type=float, default=0.0, help="sparse threshold tau of Eq. 27 (0 = off)")
     ap.add_argument("--chunk-elems", type=int, default=None)
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--vec-per-lane", type=int, default=None)
@@ -117,8 +120,9 @@ def main():
     if args.la_k:
         hyper["la_k"] = args.la_k
     scaled = args.layer_adaptation or args.auto_lr
-    if scaled:
-        hyper.update(mode="research", layer_adaptation=args.layer_adaptation, auto_lr=args.auto_lr)
+    if scaled or args.use_gc:
+        hyper.update(mode="research", layer_adaptation=args.layer_adaptation, auto_lr=args.auto_lr, use_gc=args.use_gc)
+    hyper.update(clip_threshold=args.clip, sparse_threshold=args.sparse)
     fused = not args.separate_sync
     numels = wl.numels
     p = wl.total
@@ -141,7 +145,7 @@ def main():
 
     hp = N.make_hparams(auto_sync=fused, **hyper)
     descs = [N.novak_tensor_desc(theta.data_ptr() + 4 * o, m.data_ptr() + 4 * o, v.data_ptr() + 4 * o,
-                                 la.data_ptr() + 4 * o, n) for o, n in zip(offsets, numels)]
+                                 la.data_ptr() + 4 * o, n, r) for o, n, r in zip(offsets, numels, wl.rows)]
     rc, handle = N.novak_create(hp, descs, 0)
     N.check(rc, "novak_create")
     if args.chunk_elems:
@@ -201,13 +205,18 @@ def main():
         per.setdefault(name, []).append(a.elapsed_time(b))     # ms
     la_mode = info.lookahead_mode
 
+    # extra gradient reads of the pre-passes (clipping: all tensors; centralization: the centralized ones)
+    extra_bpp = (N.novak_bytes_per_param_clip(gdt) if args.clip > 0 else 0.0)
+    if info.use_gc:
+        extra_bpp += N.novak_bytes_per_param_clip(gdt) * sum(n for n, r in zip(numels, wl.rows) if r >= 1) / max(p, 1)
+
     def bytes_of(name):
         # a two-pass ("scaled_") step is timed as a whole: both passes and the small reductions between them
         fn = N.novak_bytes_per_param_scaled_step if name.startswith("scaled_") else N.novak_bytes_per_param_step
         base = name[len("scaled_"):] if name.startswith("scaled_") else name
         pos = {"step": 2 if la_name == "basic" else 1, "step+la_first": 1, "step+la_mid": 2,
                "step+la_last_fused": k, "step+basic_fused": k}[base]
-        return fn(la_mode, gdt, k, pos, int(fused)) if la_name != "none" else fn(0, gdt, k, 1, 0)
+        return extra_bpp + (fn(la_mode, gdt, k, pos, int(fused)) if la_name != "none" else fn(0, gdt, k, 1, 0))
 
     kernels = {}
     for name, ms in per.items():
@@ -233,6 +242,7 @@ def main():
                    "nesterov": nest_name, "lookahead": la_name, "la_k": k, "sync": "fused" if fused else "separate",
                    "mode": hyper["mode"], "rectified": bool(hyper["rectified"]),
                    "layer_adaptation": bool(info.layer_adaptation), "auto_lr": bool(info.auto_lr),
+                   "use_gc": bool(info.use_gc), "clip_threshold": args.clip, "sparse_threshold": args.sparse,
                    "chunk_elems": int(info.chunk_elems), "chunks": int(info.n_chunks)},
         "roofline": roofline,
         "kernels": kernels,

@@ -463,10 +463,10 @@ __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, 
 }
 
 // one wave per chunk: sums the chunk's per-wave partials in a fixed order
-__global__ __launch_bounds__(64) void novak_reduce_chunks_kernel(const novak_chunk *chunks, int sub_shift,
+__global__ __launch_bounds__(64) void novak_reduce_chunks_kernel(const novak_chunk *chunks, int sub_shift, int sub_elems,
                                                                  const NormPartial *partials, NormSums *chunk_sums) {
   const novak_chunk ch = chunks[blockIdx.x];
-  const int nsub = (ch.len + kScaledSub - 1) / kScaledSub;
+  const int nsub = (ch.len + sub_elems - 1) / sub_elems;
   const NormPartial *p = partials + (static_cast<size_t>(blockIdx.x) << sub_shift);
   double a = 0.0, b = 0.0, g = 0.0;
   for (int j = threadIdx.x; j < nsub; j += 64) {
@@ -485,22 +485,37 @@ __global__ __launch_bounds__(64) void novak_reduce_chunks_kernel(const novak_chu
 // Clipping pre-pass (sections 5.8, 7.3): one read of the gradients, one partial (sum g^2) per wave; the
 // chunk and tensor reductions above are reused, then novak_clip_kernel turns the global norm into the
 // factor min(1, c_clip/||g||) that every later kernel of the step multiplies the gradients by.
+constexpr int kNormUnroll = 4;                          // 128-bit loads in flight per lane in the read-only pre-pass
+constexpr int kNormSub = kScaledSub * kNormUnroll;      // elements per wave there
+
 template <typename GradS, typename GradV, bool NT>
 __global__ __launch_bounds__(kScaledBlock) void novak_gradnorm_kernel(Tables tb, int sub_shift, NormPartial *partials) {
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
-  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kScaledSub;
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kNormSub;
   if (start >= ch.len) return;
-  const int n = min(kScaledSub, ch.len - start);
+  const int n = min(kNormSub, ch.len - start);
   const GradS *__restrict__ g_p = static_cast<const GradS *>(tb.grad[ch.tensor]) + (ch.offset + start);
   float s_g = 0.0f;
   int done = 0;
   if ((reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1)) == 0) {
     const int nvec = n >> 2;
-    const int i = threadIdx.x;
-    if (i < nvec) {
-      const f32x4 g = grad_to_f32<GradV>(ld<NT>(reinterpret_cast<const GradV *>(g_p) + i));
+    const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
+    if (n == kNormSub) {
+      GradV g[kNormUnroll];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) s_g = __builtin_fmaf(g[k], g[k], s_g);
+      for (int u = 0; u < kNormUnroll; ++u) g[u] = ld<NT>(g4 + threadIdx.x + u * kScaledBlock);
+#pragma unroll
+      for (int u = 0; u < kNormUnroll; ++u) {
+        const f32x4 gf = grad_to_f32<GradV>(g[u]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s_g = __builtin_fmaf(gf[k], gf[k], s_g);
+      }
+    } else {
+      for (int i = threadIdx.x; i < nvec; i += kScaledBlock) {
+        const f32x4 gf = grad_to_f32<GradV>(ld<NT>(g4 + i));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s_g = __builtin_fmaf(gf[k], gf[k], s_g);
+      }
     }
     done = nvec << 2;
   }
@@ -546,7 +561,29 @@ __global__ __launch_bounds__(64) void novak_rowmean_kernel(const void *const *gr
   const int64_t cols = gc[t].cols;
   const GradS *__restrict__ p = static_cast<const GradS *>(grad[t]) + local * cols;
   double acc = 0.0;
-  for (int64_t i = threadIdx.x; i < cols; i += 64) {
+  int64_t done = 0;
+  if constexpr (sizeof(GradS) == 4) {
+    // 128-bit path for rows that start 16-byte aligned; four loads in flight per lane
+    if ((reinterpret_cast<uintptr_t>(p) & 15u) == 0) {
+      const f32x4 *p4 = reinterpret_cast<const f32x4 *>(p);
+      const int64_t nvec = cols >> 2;
+      int64_t i = threadIdx.x;
+      for (; i + 3 * 64 < nvec; i += 4 * 64) {
+        const f32x4 a = __builtin_nontemporal_load(p4 + i), b = __builtin_nontemporal_load(p4 + i + 64),
+                    c4 = __builtin_nontemporal_load(p4 + i + 128), d = __builtin_nontemporal_load(p4 + i + 192);
+        acc += (static_cast<double>(a[0]) + a[1]) + (static_cast<double>(a[2]) + a[3]);
+        acc += (static_cast<double>(b[0]) + b[1]) + (static_cast<double>(b[2]) + b[3]);
+        acc += (static_cast<double>(c4[0]) + c4[1]) + (static_cast<double>(c4[2]) + c4[3]);
+        acc += (static_cast<double>(d[0]) + d[1]) + (static_cast<double>(d[2]) + d[3]);
+      }
+      for (; i < nvec; i += 64) {
+        const f32x4 a = __builtin_nontemporal_load(p4 + i);
+        acc += (static_cast<double>(a[0]) + a[1]) + (static_cast<double>(a[2]) + a[3]);
+      }
+      done = nvec << 2;
+    }
+  }
+  for (int64_t i = done + threadIdx.x; i < cols; i += 64) {
     if constexpr (sizeof(GradS) == 2) acc += static_cast<double>(bf16_to_f32(p[i]));
     else acc += static_cast<double>(p[i]);
   }
@@ -972,7 +1009,7 @@ void launch_apply(int la, const Geometry &gm, hipStream_t s, const Tables &tb, c
 
 // Clipping pre-pass: gradient norm partials -> chunk sums -> tensor sums -> global factor in d_gscale.
 int launch_clip_prepass(novak_handle *h, int grad_dtype, hipStream_t s, const Tables &tb) {
-  const Geometry g0 = geometry_of(h, kScaledSub, kScaledBlock, 1.0);    // a single read stream: full residency
+  const Geometry g0 = geometry_of(h, kNormSub, kScaledBlock, 1.0);      // a single read stream: full residency
   const dim3 grid(g0.grid), block(kScaledBlock);
   const bool nt = h->nontemporal != 0;
   if (grad_dtype == NOVAK_GRAD_BF16) {
@@ -986,7 +1023,7 @@ int launch_clip_prepass(novak_handle *h, int grad_dtype, hipStream_t s, const Ta
   std::memset(&sp, 0, sizeof(sp));
   const int nt_count = static_cast<int>(h->tensors.size());
   hipLaunchKernelGGL(novak_reduce_chunks_kernel, dim3(static_cast<unsigned>(h->n_chunks)), dim3(64), 0, s, h->d_chunks, g0.sub_shift,
-                     h->d_partials, h->d_chunk_sums);
+                     kNormSub, h->d_partials, h->d_chunk_sums);
   hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(64), 0, s, h->d_first_chunk, h->d_chunk_sums,
                      h->d_tensor_sums, h->d_scale, sp);
   hipLaunchKernelGGL(novak_clip_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, static_cast<float>(h->hp.clip_threshold), h->d_gscale);
@@ -1019,7 +1056,7 @@ int launch_scaled_step(novak_handle *h, int grad_dtype, int la, hipStream_t s, c
   sp.auto_lr = hp.auto_lr;
   const int nt_count = static_cast<int>(h->tensors.size());
   hipLaunchKernelGGL(novak_reduce_chunks_kernel, dim3(static_cast<unsigned>(h->n_chunks)), dim3(64), 0, s, h->d_chunks, g1.sub_shift,
-                     h->d_partials, h->d_chunk_sums);
+                     kScaledSub, h->d_partials, h->d_chunk_sums);
   hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(64), 0, s, h->d_first_chunk, h->d_chunk_sums,
                      h->d_tensor_sums, h->d_scale, sp);
   if (hp.auto_lr)
