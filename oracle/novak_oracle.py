@@ -47,6 +47,14 @@ Readings taken where the paper is silent or inconsistent (each is a named switch
     clipping and before the Nesterov approximation (section 7.3 puts clipping before any other
     processing; Table 2 lists the approximation last in Phase 2).  A tensor opts in through
     TensorState.rows = size of its first dimension (0 = not centralized).
+  * adaptive beta (Eq. 3-4): beta_i(t) = beta_i * (1 - exp(-t/tau_i)) replaces beta_i in the moment
+    updates (Eq. 1-2) at every t (the schedule is smooth and asymptotic; the text's "t < tau_1" is read
+    as describing where it matters, not a cut-off).  Bias correction (Eq. 5), the rectification
+    schedule (Eq. 6-9) and the classical blend (Eq. 16) keep the base betas, as printed.
+    parity unpinned by the paper for this interplay.
+  * true Nesterov (Eq. 10): the extrapolated point is theta + beta_n * m with the sign as printed;
+    `extrapolate` returns it.  With n_taylor > 0 the mode "true" behaves as "approx" for t > n_taylor
+    (automatic fallback, sections 4.4 and 5.8).
   * sparse threshold (Eq. 27): the base direction u is zeroed where |u| <= tau, after the trust ratio is
     taken (Phase 7 precedes Phase 8) and before the classical blend (Table 2's order within Phase 8).
     The mask is a discontinuous decision on a floating-point value: an implementation in another
@@ -92,6 +100,10 @@ class Hyper:
     clip_threshold: float = 0.0         # c_clip on the global gradient norm; 0 = off (section 5.8)
     sparse_threshold: float = 0.0       # tau of Eq. 27; 0 = off
     use_gc: bool = False                # Eq. 26 on tensors that declare rows >= 1
+    adaptive_beta: bool = False         # Eq. 3-4
+    beta_tau1: float = 1000.0
+    beta_tau2: float = 5000.0
+    n_taylor: int = 0                   # "true" Nesterov falls back to "approx" after this many steps; 0 = never
 
     def __post_init__(self):
         assert self.nesterov in NESTEROV_MODES
@@ -118,6 +130,26 @@ def one_minus_pow(beta: float, t: int) -> float:
     if beta == 0.0:
         return 1.0
     return -math.expm1(t * math.log(beta))
+
+
+def scheduled_betas(h: Hyper, t: int):
+    """(beta1, beta2) used by the moment updates at step t (Eq. 3-4 when adaptive_beta, else the base values)."""
+    if not h.adaptive_beta:
+        return h.beta1, h.beta2
+    return (h.beta1 * (1.0 - math.exp(-t / h.beta_tau1)),      # Eq. 3
+            h.beta2 * (1.0 - math.exp(-t / h.beta_tau2)))      # Eq. 4
+
+
+def effective_nesterov(h: Hyper, t: int) -> str:
+    """Nesterov variant in force at step t: "true" hands over to "approx" after n_taylor steps."""
+    if h.nesterov == "true" and h.n_taylor > 0 and t > h.n_taylor:
+        return "approx"
+    return h.nesterov
+
+
+def extrapolate(st: "TensorState", h: Hyper) -> np.ndarray:
+    """Eq. 10: the point at which true Nesterov evaluates the gradient (double)."""
+    return st.theta.astype(np.float64) + h.beta_n * st.m.astype(np.float64)
 
 
 def step_scalars(h: Hyper, t: int) -> StepScalars:
@@ -222,10 +254,11 @@ def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float 
         g = (g2d - g2d.mean(axis=1, keepdims=True)).reshape(-1)    # Eq. 26
     if (not h.decoupled_decay) and h.weight_decay != 0.0:
         g = g + h.weight_decay * theta                      # coupled L2 (reading; see header)
-    if h.nesterov == "approx":
+    if effective_nesterov(h, t) == "approx":
         g = g + h.beta_n * (g - m_prev)                     # Eq. 13; replaces g for both moments
-    m = h.beta1 * m_prev + (1.0 - h.beta1) * g              # Eq. 1
-    v = h.beta2 * v_prev + (1.0 - h.beta2) * g * g          # Eq. 2
+    b1_t, b2_t = scheduled_betas(h, t)                      # Eq. 3-4 (Phase 3)
+    m = b1_t * m_prev + (1.0 - b1_t) * g                    # Eq. 1
+    v = b2_t * v_prev + (1.0 - b2_t) * g * g                # Eq. 2
     m_hat = m / s.bc1                                       # Eq. 5
     if s.denom_on:
         v_hat = v / s.bc2                                   # Eq. 5

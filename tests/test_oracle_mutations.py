@@ -27,14 +27,14 @@ MUTATIONS = {
     "threshold_four": ("if rho_t >= 5.0:", "if rho_t >= 4.0:"),
     "rho_missing_denominator": ("rho_t = rho_inf - 2.0 * t * beta2_t / bc2", "rho_t = rho_inf - 2.0 * t * beta2_t"),
     "r_t_no_sqrt": ("r_t = math.sqrt((rho_t - 4.0)", "r_t = ((rho_t - 4.0)"),
-    "second_moment_not_squared": ("(1.0 - h.beta2) * g * g", "(1.0 - h.beta2) * np.abs(g)"),
+    "second_moment_not_squared": ("(1.0 - b2_t) * g * g", "(1.0 - b2_t) * np.abs(g)"),
     "classical_swapped_weights": ("u = h.beta1 * m_hat + (1.0 - h.beta1) * u", "u = (1.0 - h.beta1) * m_hat + h.beta1 * u"),
     "lookahead_k_minus_1": ("slow_new = slow0 + h.la_alpha * delta / h.la_k", "slow_new = slow0 + h.la_alpha * delta / (h.la_k - 1)"),
     "lookahead_sum_of_updates": ("delta += th.astype(np.float64) - slow0", "delta += (th.astype(np.float64) - slow0) / len(st.window)"),
     "sync_one_step_early": ("return h.lookahead != \"none\" and t % h.la_k == 0", "return h.lookahead != \"none\" and (t + 1) % h.la_k == 0"),
     "coupled_decay_sign": ("g = g + h.weight_decay * theta", "g = g - h.weight_decay * theta"),
     "fallback_keeps_denominator": ("denom_on = (h.unrect_fallback == \"adam_denom\")", "denom_on = True"),
-    "m_and_v_betas_swapped": ("m = h.beta1 * m_prev + (1.0 - h.beta1) * g", "m = h.beta2 * m_prev + (1.0 - h.beta2) * g"),
+    "m_and_v_betas_swapped": ("m = b1_t * m_prev + (1.0 - b1_t) * g", "m = b2_t * m_prev + (1.0 - b2_t) * g"),
 }
 
 
