@@ -103,7 +103,11 @@ typedef struct novak_hparams {
   int32_t use_gc;           /* 1: gradient centralization (Eq. 26) on tensors whose descriptor gives rows >= 1; RESEARCH
                                mode only; runs after clipping, before the Nesterov approximation; costs one extra
                                read of those tensors' gradients per step */
-  int32_t reserved0;        /* must be 0 */
+  int32_t adaptive_beta;    /* 1: beta_i(t) = beta_i (1 - exp(-t/tau_i)) in the moment updates (Eq. 3-4); bias correction,
+                               rectification and the classical blend keep the base betas, as printed */
+  double beta_tau1, beta_tau2; /* tau_1, tau_2 of Eq. 3-4 (> 0 when adaptive_beta); the paper uses 1000 and 5000 */
+  int64_t n_taylor;         /* TRUE Nesterov behaves as APPROX for steps t > n_taylor (sections 4.4, 5.8: 100-200);
+                               0 = never; ignored for the other modes */
 } novak_hparams;
 
 /* One parameter tensor.  All pointers are DEVICE pointers to contiguous fp32 arrays of `numel`
@@ -135,6 +139,9 @@ typedef struct novak_step_scalars {
   double decay;            /* 1 - alpha*lambda (Eq. 18), or 1 with coupled decay */
   int32_t rectified_now;   /* rectified && rho_t >= 5 */
   int32_t denom_on;        /* 0 only in the SGDM fallback while rho_t < 5 */
+  double beta1_t, beta2_t; /* betas used by the moment updates at this step (Eq. 3-4, or the base values) */
+  int32_t nesterov_mode;   /* variant in force at this step (TRUE -> APPROX after n_taylor steps) */
+  int32_t reserved0;
 } novak_step_scalars;
 
 /* One entry of the multi-tensor chunk table: `len` elements of tensor `tensor` starting at `offset`. */
@@ -240,6 +247,13 @@ int novak_set_auto_lr_state(novak_handle *h, void *ema);
 /* Monitoring: copies lambda_trust * alpha_auto of the last two-pass step, one float per tensor, to HOST
  * memory `out` (n_tensors floats).  Waits for `hip_stream` first.  NOVAK_ERR_STATE on a single-pass handle. */
 int novak_copy_tensor_scales(novak_handle *h, float *out, void *hip_stream);
+
+/* True Nesterov, Eq. 10: writes the extrapolated parameters theta + beta_n * m of every tensor to the
+ * caller's buffers (`out` is a HOST array of n_tensors DEVICE pointers to fp32 arrays of numel elements,
+ * 4-byte aligned, not overlapping the state).  The caller evaluates the gradient there (Eq. 11) and
+ * passes it to novak_step; theta itself is left untouched, so there is nothing to restore.  One launch;
+ * 12 bytes per parameter.  Legal in any Nesterov mode. */
+int novak_nesterov_extrapolate(novak_handle *h, void *const *out, void *hip_stream);
 
 /* Eq. 30-31 over all tensors in one launch: theta <- slow_new, and the buffer is left equal to the
  * new slow weights.  Legal only when a sync is due. */

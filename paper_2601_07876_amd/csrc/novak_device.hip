@@ -108,6 +108,7 @@ struct Consts {
   float wd;              // lambda (coupled) or 0
   float la_c0, la_c1;    // lookahead blend coefficients (meaning depends on the LA phase)
   float sparse_tau;      // tau of Eq. 27 (used when F_SPARSE is set)
+  float blend_w;         // 1-beta1 of Eq. 16 (base beta1; omb1 follows the schedule of Eq. 3)
   uint32_t flags;
 };
 
@@ -142,7 +143,7 @@ template <int LA>
 __device__ __forceinline__ void apply(float &th, float u, float m_hat, float &la, const Consts &c, float step) {
   const float th_in = th;
   if ((c.flags & F_SPARSE) && !(__builtin_fabsf(u) > c.sparse_tau)) u = 0.0f;  // Eq. 27
-  if (c.flags & F_CLASSICAL) u = __builtin_fmaf(c.beta1, m_hat, c.omb1 * u);   // Eq. 16
+  if (c.flags & F_CLASSICAL) u = __builtin_fmaf(c.beta1, m_hat, c.blend_w * u);  // Eq. 16
   // Eq. 18 + Eq. 24 in additive form: one rounding at theta's magnitude per step
   const float th_new = th_in - __builtin_fmaf(step, u, c.lr_wd * th_in);
   th = th_new;
@@ -354,6 +355,36 @@ __global__ __launch_bounds__(BLOCK) void novak_lookahead_kernel(Tables tb, float
     if (OP != LA_INIT) th_p[i] = th;
     if (OP != SYNC_ME) la_p[i] = la;
   }
+}
+
+// True Nesterov, Eq. 10: out <- theta + beta_n * m over the chunk table (one wave per 256 elements).
+template <bool NT>
+__global__ __launch_bounds__(64) void novak_extrapolate_kernel(Tables tb, float *const *out, float beta_n, int sub_shift) {
+  constexpr int SUB = 64 * 4;
+  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * SUB;
+  if (start >= ch.len) return;
+  const int n = min(SUB, ch.len - start);
+  const int64_t off = ch.offset + start;
+  const TensorPtrs tp = tb.tensors[ch.tensor];
+  const float *__restrict__ th_p = tp.param + off;
+  const float *__restrict__ m_p = tp.m + off;
+  float *__restrict__ o_p = out[ch.tensor] + off;
+  const uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) | reinterpret_cast<uintptr_t>(o_p)) & 15u;
+  int done = 0;
+  if (mis == 0) {
+    const int nvec = n >> 2;
+    const int i = threadIdx.x;
+    if (i < nvec) {
+      const f32x4 th = ld<NT>(reinterpret_cast<const f32x4 *>(th_p) + i), m = ld<NT>(reinterpret_cast<const f32x4 *>(m_p) + i);
+      f32x4 o;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] = __builtin_fmaf(beta_n, m[k], th[k]);
+      st<NT>(reinterpret_cast<f32x4 *>(o_p) + i, o);
+    }
+    done = nvec << 2;
+  }
+  for (int i = done + threadIdx.x; i < n; i += 64) o_p[i] = __builtin_fmaf(beta_n, m_p[i], th_p[i]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -732,6 +763,7 @@ struct novak_handle {
   int *d_first_chunk = nullptr;        // n_tensors + 1: chunk range of each tensor
   float *d_scale = nullptr;            // n_tensors: lambda_trust * alpha_auto
   float *d_gscale = nullptr;           // one float: gradient-clipping factor of the current step
+  float **d_out_ptrs = nullptr;        // n_tensors output pointers of novak_nesterov_extrapolate (allocated in create)
   // gradient centralization (built once in novak_create)
   GcInfo *d_gc = nullptr;              // per tensor
   int *d_gc_tensor = nullptr;          // centralized tensors
@@ -750,6 +782,7 @@ struct novak_handle {
   bool ring_used[kRing] = {};
   int ring_next = 0;
   std::vector<void *> last_grads;
+  std::vector<void *> out_host;        // host copy of the last novak_nesterov_extrapolate pointer list
   bool grads_uploaded = false;
   std::string error;
 };
@@ -1154,6 +1187,7 @@ int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor
       host[4 * i + 3] = tensors[i].la_buf;
     }
     if ((e = hipMemcpy(h->d_ptrs, host.data(), bytes, hipMemcpyHostToDevice)) != hipSuccess) return bail(fail_hip(h, e, "hipMemcpy(pointer tables)"));
+    if ((e = hipMalloc(reinterpret_cast<void **>(&h->d_out_ptrs), n * sizeof(float *))) != hipSuccess) return bail(fail_hip(h, e, "hipMalloc(output pointers)"));
     if ((e = hipHostMalloc(reinterpret_cast<void **>(&h->h_ring), novak_handle::kRing * n * sizeof(void *), hipHostMallocDefault)) != hipSuccess)
       return bail(fail_hip(h, e, "hipHostMalloc(gradient pointer ring)"));
     for (int r = 0; r < novak_handle::kRing; ++r)
@@ -1204,6 +1238,7 @@ int novak_destroy(novak_handle *h) {
   (void)scope.enter(h->device_id);
   free_device_tables(h);
   if (h->d_ptrs) (void)hipFree(h->d_ptrs);
+  if (h->d_out_ptrs) (void)hipFree(h->d_out_ptrs);
   if (h->d_gc) (void)hipFree(h->d_gc);
   if (h->d_gc_tensor) (void)hipFree(h->d_gc_tensor);
   if (h->d_row_first) (void)hipFree(h->d_row_first);
@@ -1232,6 +1267,29 @@ int novak_get_info(const novak_handle *h, novak_info *info) {
   info->auto_lr = h->hp.auto_lr;
   info->use_gc = h->hp.use_gc;
   info->n_centralized = h->n_gc;
+  return NOVAK_OK;
+}
+
+int novak_nesterov_extrapolate(novak_handle *h, void *const *out, void *hip_stream) {
+  if (!h) return NOVAK_ERR_NULL_POINTER;
+  const size_t n = h->tensors.size();
+  if (n > 0 && !out) return fail(h, NOVAK_ERR_NULL_POINTER, "out is NULL");
+  for (size_t i = 0; i < n; ++i) {
+    if (h->numels[i] == 0) continue;
+    if (!out[i]) return fail(h, NOVAK_ERR_NULL_POINTER, "out[" + std::to_string(i) + "] is NULL");
+    if (reinterpret_cast<uintptr_t>(out[i]) & 3u) return fail(h, NOVAK_ERR_MISALIGNED, "out[" + std::to_string(i) + "] not 4-byte aligned");
+  }
+  if (h->n_chunks == 0) return NOVAK_OK;
+  DeviceScope scope;
+  NOVAK_HIP(h, scope.enter(h->device_id));
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  // the list is copied into the handle first, so the caller's array may be reused as soon as this returns
+  h->out_host.assign(out, out + n);
+  NOVAK_HIP(h, hipMemcpyAsync(h->d_out_ptrs, h->out_host.data(), n * sizeof(float *), hipMemcpyHostToDevice, stream));
+  const Geometry gm = geometry_of(h, 256, 64, 3.0);
+  if (h->nontemporal) hipLaunchKernelGGL((novak_extrapolate_kernel<true>), dim3(gm.grid), dim3(64), gm.lds, stream, tables_of(h), h->d_out_ptrs, static_cast<float>(h->hp.beta_n), gm.sub_shift);
+  else hipLaunchKernelGGL((novak_extrapolate_kernel<false>), dim3(gm.grid), dim3(64), gm.lds, stream, tables_of(h), h->d_out_ptrs, static_cast<float>(h->hp.beta_n), gm.sub_shift);
+  NOVAK_HIP(h, hipGetLastError());
   return NOVAK_OK;
 }
 
@@ -1329,8 +1387,9 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
   const novak_hparams &hp = h->hp;
   Consts c;
   std::memset(&c, 0, sizeof(c));
-  c.omb1 = static_cast<float>(1.0 - hp.beta1);
-  c.omb2 = static_cast<float>(1.0 - hp.beta2);
+  c.omb1 = static_cast<float>(1.0 - sc.beta1_t);      // the moment updates follow Eq. 3-4 when scheduled
+  c.omb2 = static_cast<float>(1.0 - sc.beta2_t);
+  c.blend_w = static_cast<float>(1.0 - hp.beta1);
   c.beta1 = static_cast<float>(hp.beta1);
   c.beta_n = static_cast<float>(hp.beta_n);
   c.inv_bc1 = static_cast<float>(1.0 / sc.bc1);
@@ -1340,7 +1399,7 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
   c.lr_wd = hp.decoupled_decay ? static_cast<float>(hp.lr * hp.weight_decay) : 0.0f;
   c.wd = hp.decoupled_decay ? 0.0f : static_cast<float>(hp.weight_decay);
   c.flags = 0;
-  if (hp.nesterov_mode == NOVAK_NESTEROV_APPROX) c.flags |= F_APPROX;
+  if (sc.nesterov_mode == NOVAK_NESTEROV_APPROX) c.flags |= F_APPROX;
   if (hp.nesterov_mode == NOVAK_NESTEROV_CLASSICAL) c.flags |= F_CLASSICAL;
   if (sc.denom_on) c.flags |= F_DENOM;
   if (!hp.decoupled_decay && hp.weight_decay != 0.0) c.flags |= F_COUPLED;

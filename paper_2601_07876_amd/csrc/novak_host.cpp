@@ -12,7 +12,7 @@ namespace {
 bool finite_all(const novak_hparams &hp) {
   const double vals[] = {hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, hp.beta_n, hp.la_alpha,
                          hp.auto_lr_gamma, hp.trust_clip_lo, hp.trust_clip_hi, hp.auto_clip_lo, hp.auto_clip_hi,
-                         hp.clip_threshold, hp.sparse_threshold};
+                         hp.clip_threshold, hp.sparse_threshold, hp.beta_tau1, hp.beta_tau2};
   for (double x : vals)
     if (!std::isfinite(x)) return false;
   return true;
@@ -65,7 +65,8 @@ int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, ui
   if (hp->lookahead_mode != NOVAK_LOOKAHEAD_NONE && !(hp->la_alpha > 0.0 && hp->la_alpha <= 1.0)) return NOVAK_ERR_INVALID_ARG;
 
   if (!(hp->clip_threshold >= 0.0) || !(hp->sparse_threshold >= 0.0)) return NOVAK_ERR_INVALID_ARG;
-  if (hp->reserved0 != 0) return NOVAK_ERR_INVALID_ARG;
+  if (hp->adaptive_beta && !(hp->beta_tau1 > 0.0 && hp->beta_tau2 > 0.0)) return NOVAK_ERR_INVALID_ARG;
+  if (hp->n_taylor < 0) return NOVAK_ERR_INVALID_ARG;
   if (hp->layer_adaptation && !(hp->trust_clip_lo > 0.0 && hp->trust_clip_lo <= hp->trust_clip_hi)) return NOVAK_ERR_INVALID_ARG;
   if (hp->auto_lr) {
     if (!(hp->auto_lr_gamma > 0.0 && hp->auto_lr_gamma <= 1.0)) return NOVAK_ERR_INVALID_ARG;
@@ -88,6 +89,7 @@ int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, ui
   eff.layer_adaptation = eff.layer_adaptation ? 1 : 0;
   eff.auto_lr = eff.auto_lr ? 1 : 0;
   eff.use_gc = eff.use_gc ? 1 : 0;
+  eff.adaptive_beta = eff.adaptive_beta ? 1 : 0;
   // section 7.1: layer adaptation and auto-LR exist only in full-features mode
   if (eff.mode == NOVAK_MODE_FAST) {
     if (eff.layer_adaptation) {
@@ -135,6 +137,14 @@ int novak_compute_step_scalars(const novak_hparams *hp, int64_t step, novak_step
       s.denom_on = 0;
     }
   }
+  s.beta1_t = hp->beta1;
+  s.beta2_t = hp->beta2;
+  if (hp->adaptive_beta) {                                           // Eq. 3-4
+    s.beta1_t = hp->beta1 * (1.0 - std::exp(-static_cast<double>(step) / hp->beta_tau1));
+    s.beta2_t = hp->beta2 * (1.0 - std::exp(-static_cast<double>(step) / hp->beta_tau2));
+  }
+  s.nesterov_mode = hp->nesterov_mode;                               // automatic fallback of the true variant
+  if (hp->nesterov_mode == NOVAK_NESTEROV_TRUE && hp->n_taylor > 0 && step > hp->n_taylor) s.nesterov_mode = NOVAK_NESTEROV_APPROX;
   s.step_size = hp->lr * s.r_t;                                      // Eq. 24a
   s.decay = hp->decoupled_decay ? 1.0 - hp->lr * hp->weight_decay : 1.0;  // Eq. 18
   *out = s;

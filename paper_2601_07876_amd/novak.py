@@ -44,7 +44,8 @@ class novak_hparams(C.Structure):
                 ("trust_clip_lo", C.c_double), ("trust_clip_hi", C.c_double),
                 ("auto_clip_lo", C.c_double), ("auto_clip_hi", C.c_double),
                 ("clip_threshold", C.c_double), ("sparse_threshold", C.c_double),
-                ("use_gc", C.c_int32), ("reserved0", C.c_int32)]
+                ("use_gc", C.c_int32), ("adaptive_beta", C.c_int32),
+                ("beta_tau1", C.c_double), ("beta_tau2", C.c_double), ("n_taylor", C.c_int64)]
 
 
 class novak_tensor_desc(C.Structure):
@@ -55,7 +56,8 @@ class novak_tensor_desc(C.Structure):
 class novak_step_scalars(C.Structure):
     _fields_ = [("bc1", C.c_double), ("bc2", C.c_double), ("rho_inf", C.c_double), ("rho_t", C.c_double),
                 ("r_t", C.c_double), ("step_size", C.c_double), ("decay", C.c_double),
-                ("rectified_now", C.c_int32), ("denom_on", C.c_int32)]
+                ("rectified_now", C.c_int32), ("denom_on", C.c_int32),
+                ("beta1_t", C.c_double), ("beta2_t", C.c_double), ("nesterov_mode", C.c_int32), ("reserved0", C.c_int32)]
 
 
 class novak_chunk(C.Structure):
@@ -76,7 +78,7 @@ EXPORTS = ("novak_validate_hparams", "novak_compute_step_scalars", "novak_plan_c
            "novak_bytes_per_param_sync",
            "novak_status_string", "novak_create", "novak_lookahead_init", "novak_step", "novak_lookahead_sync",
            "novak_destroy", "novak_get_info", "novak_set_tuning", "novak_last_error", "novak_set_auto_lr_state",
-           "novak_copy_tensor_scales")
+           "novak_copy_tensor_scales", "novak_nesterov_extrapolate")
 
 _lib: Optional[C.CDLL] = None
 
@@ -101,6 +103,7 @@ def load_library() -> C.CDLL:
     lib.novak_bytes_per_param_scaled_step.restype = C.c_double
     lib.novak_set_auto_lr_state.argtypes = [vp, vp]
     lib.novak_copy_tensor_scales.argtypes = [vp, C.POINTER(C.c_float), vp]
+    lib.novak_nesterov_extrapolate.argtypes = [vp, C.POINTER(vp), vp]
     lib.novak_bytes_per_param_clip.argtypes = [i32]
     lib.novak_bytes_per_param_clip.restype = C.c_double
     lib.novak_bytes_per_param_sync.argtypes = [i32]
@@ -135,7 +138,8 @@ def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, be
                  rectified=True, decoupled_decay=True, nesterov="approx", lookahead="memory_efficient",
                  unrect_fallback="adam_denom", mode="fast", auto_sync=False, layer_adaptation=False, auto_lr=False,
                  auto_lr_gamma=0.1, trust_clip=(0.1, 10.0), auto_clip=(0.1, 2.0), clip_threshold=0.0,
-                 sparse_threshold=0.0, use_gc=False) -> novak_hparams:
+                 sparse_threshold=0.0, use_gc=False, adaptive_beta=False, beta_tau1=1000.0, beta_tau2=5000.0,
+                 n_taylor=0) -> novak_hparams:
     """Fills a novak_hparams from keyword values (mode names or their integer codes)."""
     def code(table: Dict[str, int], x):
         return table[x] if isinstance(x, str) else int(x)
@@ -144,7 +148,7 @@ def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, be
                          code(UNRECT, unrect_fallback), code(MODE, mode), int(auto_sync), int(layer_adaptation),
                          int(auto_lr), float(auto_lr_gamma), float(trust_clip[0]), float(trust_clip[1]),
                          float(auto_clip[0]), float(auto_clip[1]), float(clip_threshold), float(sparse_threshold),
-                         int(use_gc), 0)
+                         int(use_gc), int(adaptive_beta), float(beta_tau1), float(beta_tau2), int(n_taylor))
 
 
 # ---- the entry points, same names as the C ABI ------------------------------------------------------
@@ -196,6 +200,13 @@ def novak_copy_tensor_scales(handle, n_tensors: int, stream: int = 0):
     buf = (C.c_float * max(n_tensors, 1))()
     rc = load_library().novak_copy_tensor_scales(handle, buf, C.c_void_p(stream))
     return rc, [buf[i] for i in range(n_tensors)]
+
+
+def novak_nesterov_extrapolate(handle, out_ptrs, stream: int = 0) -> int:
+    """`out_ptrs`: a ctypes c_void_p array or a sequence of device addresses, one per tensor."""
+    if not isinstance(out_ptrs, C.Array):
+        out_ptrs = (C.c_void_p * max(len(out_ptrs), 1))(*out_ptrs)
+    return load_library().novak_nesterov_extrapolate(handle, out_ptrs, C.c_void_p(stream))
 
 
 def novak_bytes_per_param_clip(grad_dtype: int) -> float:

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert C.sizeof(N.novak_hparams) == 8 + 7 * 8 + 10 * 4 + 7 * 8 + 2 * 4
+    assert C.sizeof(N.novak_hparams) == 8 + 7 * 8 + 10 * 4 + 7 * 8 + 2 * 4 + 3 * 8
     assert C.sizeof(N.novak_tensor_desc) == 48
     assert C.sizeof(N.novak_chunk) == 16
     hp = N.make_hparams()
@@ -79,6 +79,19 @@ def test_scaling_features_validation_and_fast_mode_switch_off():
     assert N.novak_bytes_per_param_scaled_step(N.NOVAK_LOOKAHEAD_MEMORY_EFFICIENT, N.NOVAK_GRAD_BF16, 5, 2, 0) == 46
 
 
+def test_schedules_in_the_prologue_match_the_oracle():
+    kw = dict(GOOD, adaptive_beta=True, beta_tau1=300.0, beta_tau2=700.0, nesterov="true", mode="research", n_taylor=150)
+    hp = N.make_hparams(**kw)
+    h = O.Hyper(**{k: v for k, v in kw.items() if k != "mode"})
+    for t in (1, 2, 50, 150, 151, 1000, 10 ** 5):
+        rc, s = N.novak_compute_step_scalars(hp, t)
+        b1, b2 = O.scheduled_betas(h, t)
+        assert rc == 0 and s.beta1_t == pytest.approx(b1, rel=1e-15) and s.beta2_t == pytest.approx(b2, rel=1e-15)
+        assert {1: "approx", 3: "true"}[s.nesterov_mode] == O.effective_nesterov(h, t)
+    assert N.novak_validate_hparams(N.make_hparams(**dict(kw, beta_tau1=0.0)))[0] == N.NOVAK_ERR_INVALID_ARG
+    assert N.novak_validate_hparams(N.make_hparams(**dict(kw, n_taylor=-1)))[0] == N.NOVAK_ERR_INVALID_ARG
+
+
 def test_fast_path_downgrades_warn_and_research_mode_does_not():
     rc, eff, warn = N.novak_validate_hparams(N.make_hparams(mode="fast", nesterov="true", lookahead="basic"))
     assert rc == N.NOVAK_OK
@@ -101,6 +114,7 @@ def test_prologue_matches_oracle_scalars(beta2, rectified, fallback):
         o = O.step_scalars(h, t)
         for name in ("bc1", "bc2", "rho_inf", "rho_t", "r_t", "step_size", "decay"):
             assert getattr(s, name) == pytest.approx(getattr(o, name), rel=4e-16, abs=0), (name, t)
+        assert (s.beta1_t, s.beta2_t) == (0.9, beta2)
         assert bool(s.rectified_now) == o.rectified_now and bool(s.denom_on) == o.denom_on
     assert N.novak_compute_step_scalars(hp, 0)[0] == N.NOVAK_ERR_BAD_STEP
 
