@@ -229,6 +229,8 @@ def main():
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": dk["GBps"] / HBM_PEAK_GBS, "avg_kernel_ms": dk["avg_ms"],
                 "algorithmic_bytes_per_launch": p * dk["bytes_per_param"], "traffic": measured_traffic(args.workload, dominant)}
+    if roofline["traffic"]:
+        roofline["traffic_GBps"] = roofline["traffic"] / (dk["avg_ms"] * 1e-3) / 1e9   # counter-derived bandwidth
 
     result = {
         "metric": "Gparams updated/s per NOVAK step",
