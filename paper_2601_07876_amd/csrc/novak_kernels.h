@@ -1,0 +1,737 @@
+// HIP kernels of the NOVAK update-step library for gfx950 (MI355X): the fused single-pass update over
+// a multi-tensor chunk table, the lookahead sync / init kernels, the Eq. 10 extrapolation, and the
+// two-pass path with its norm reductions, clipping and centralization pre-passes.
+// Included once, by novak_device.hip, which holds the handle and the C entry points.
+//
+// The step is HBM-bound (section 5.5 of the paper: 4 streams read, 3 written per element, a few
+// dozen flops), so the kernels are built around memory streams, not arithmetic:
+//   * a chunk-table entry never spans tensors and is covered by short-lived workgroups (one wave64
+//     by default) that each touch 256..4096 consecutive elements once;
+//   * each lane moves 128 bits per stream per access (4 fp32; 4 bf16 gradients = 64 bits), and all
+//     loads of a workgroup are issued before any arithmetic;
+//   * per-step scalars arrive as kernel arguments (SGPRs); nothing is read from memory except the
+//     chunk entry, the tensor's pointer record and the streams themselves;
+//   * streams are touched exactly once per step, so loads and stores may carry non-temporal hints.
+// Arithmetic is IEEE fp32 with explicit FMAs (compiled with -ffp-contract=off, no fast-math);
+// square root and division are the correctly rounded ones.
+#ifndef NOVAK_KERNELS_H_
+#define NOVAK_KERNELS_H_
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "novak_internal.h"
+
+namespace {
+
+constexpr int kMinSub = 64 * 4;   // elements covered by the smallest workgroup (one wave64, one 128-bit access per lane)
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+
+// lookahead work done inside the step kernel (which extra stream is read / written)
+enum : int {
+  LA_OFF = 0,          // no lookahead traffic in this step
+  LA_FIRST = 1,        // first step of a window:  A  = c0*theta_in + c1*theta_new      (A written)
+  LA_MID = 2,          // later steps:             A += c1*theta_new                    (A read, written)
+  LA_LAST_FUSED = 3,   // k-th step, sync fused:   theta_out = A + c1*theta_new         (A read)
+  LA_BASIC_FUSED = 4   // k-th step, basic mode:   S = c1*theta_new + c0*S; theta_out=S (S read, written)
+};
+
+enum : uint32_t { F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u, F_CLIP = 16u, F_SPARSE = 32u, F_GC = 64u };
+
+// The four state pointers of a tensor sit together so that one 32-byte scalar load fetches them.
+struct TensorPtrs {
+  float *param;
+  float *m;
+  float *v;
+  float *la;
+};
+
+// Gradient centralization (Eq. 26) of one tensor: rows of `cols` contiguous elements; cols == 0 means
+// the tensor is not centralized.  `means` holds this step's mean of every row of the raw gradient, in
+// double: g - mean is formed in double and rounded once, so an element whose centralized gradient
+// nearly cancels keeps a relative (not absolute) error - at t = 1 the direction g/(|g|+eps) is
+// sign-like and would amplify an absolute error of half an ulp of g.
+struct GcInfo {
+  int64_t cols;
+  double inv_cols;
+  const double *means;
+};
+
+struct Tables {
+  const novak_chunk *chunks;
+  const TensorPtrs *tensors;
+  const void *const *grad;
+  const float *gscale;   // one float: the step's gradient-clipping factor (read only when F_CLIP is set)
+  const GcInfo *gc;      // per tensor (read only when F_GC is set)
+};
+
+// idx / cols for 0 <= idx < 2^52 without an integer divide: double estimate, then one correction step
+__device__ __forceinline__ int64_t row_of(int64_t idx, int64_t cols, double inv_cols) {
+  int64_t q = static_cast<int64_t>(static_cast<double>(idx) * inv_cols);
+  if (q * cols > idx) --q;
+  else if ((q + 1) * cols <= idx) ++q;
+  return q;
+}
+
+// Subtracts the row means from `n` (<= 4) consecutive gradient values that start at element `e0` of a
+// centralized tensor.  Centralizing the raw gradient and scaling by the clipping factor afterwards
+// equals clipping first (the factor is one scalar for all tensors).
+template <typename V>
+__device__ __forceinline__ void centralize(V &g, int n, int64_t e0, const GcInfo &gc) {
+  int64_t row = row_of(e0, gc.cols, gc.inv_cols);
+  int64_t rem = e0 - row * gc.cols;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    if (k < n) {
+      while (rem >= gc.cols) { rem -= gc.cols; ++row; }
+      g[k] = static_cast<float>(static_cast<double>(g[k]) - gc.means[row]);
+      ++rem;
+    }
+  }
+}
+__device__ __forceinline__ float centralize_one(float g, int64_t e, const GcInfo &gc) {
+  return static_cast<float>(static_cast<double>(g) - gc.means[row_of(e, gc.cols, gc.inv_cols)]);
+}
+
+// Per-step scalars, rounded once from the host's double values.
+struct Consts {
+  float omb1, omb2;      // 1-beta1, 1-beta2
+  float beta1, beta_n;
+  float inv_bc1, inv_bc2;
+  float eps;
+  float step_size;       // alpha * r_t
+  float lr_wd;           // alpha * lambda (decoupled) or 0
+  float wd;              // lambda (coupled) or 0
+  float la_c0, la_c1;    // lookahead blend coefficients (meaning depends on the LA phase)
+  float sparse_tau;      // tau of Eq. 27 (used when F_SPARSE is set)
+  float blend_w;         // 1-beta1 of Eq. 16 (base beta1; omb1 follows the schedule of Eq. 3)
+  uint32_t flags;
+};
+
+__device__ __forceinline__ float bf16_to_f32(unsigned short b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+
+// The update of one element, in three parts so that the two-pass (per-tensor scaled) path can reuse
+// the exact arithmetic of the fused one.
+//   moments():   Phases 2 and 4 - gradient processing and the two EMAs (Eq. 13, 1, 2)
+//   direction(): Phases 5 and 8a - bias correction and the base direction u (Eq. 5, 17)
+//   apply():     Phases 8b, 9, 10 - classical blend, decay + update, lookahead (Eq. 16, 18, 24, 28-31)
+__device__ __forceinline__ void moments(float th_in, float g, float &m, float &v, const Consts &c, float gs) {
+  if (c.flags & F_CLIP) g *= gs;                                        // global-norm clipping comes first
+  if (c.flags & F_COUPLED) g = __builtin_fmaf(c.wd, th_in, g);          // classic L2 reading
+  if (c.flags & F_APPROX) g = __builtin_fmaf(c.beta_n, g - m, g);       // Eq. 13
+  m = __builtin_fmaf(c.omb1, g - m, m);                                 // Eq. 1:  m + (1-b1)(g - m)
+  v = __builtin_fmaf(c.omb2, __builtin_fmaf(g, g, -v), v);              // Eq. 2:  v + (1-b2)(g^2 - v)
+}
+
+__device__ __forceinline__ float direction(float m, float v, const Consts &c, float &m_hat) {
+  m_hat = m * c.inv_bc1;                                                // Eq. 5
+  float u = m_hat;
+  if (c.flags & F_DENOM) {
+    const float v_hat = v * c.inv_bc2;                                  // Eq. 5
+    u = m_hat / (__builtin_sqrtf(v_hat) + c.eps);                       // Eq. 17
+  }
+  return u;
+}
+
+// `step` is alpha*r_t, times the tensor's trust ratio and the auto-LR factor on the scaled path (Eq. 24a).
+// `la` is the lookahead buffer value (read when the phase reads it, returned updated when it writes it).
+template <int LA>
+__device__ __forceinline__ void apply(float &th, float u, float m_hat, float &la, const Consts &c, float step) {
+  const float th_in = th;
+  if ((c.flags & F_SPARSE) && !(__builtin_fabsf(u) > c.sparse_tau)) u = 0.0f;  // Eq. 27
+  if (c.flags & F_CLASSICAL) u = __builtin_fmaf(c.beta1, m_hat, c.blend_w * u);  // Eq. 16
+  // Eq. 18 + Eq. 24 in additive form: one rounding at theta's magnitude per step
+  const float th_new = th_in - __builtin_fmaf(step, u, c.lr_wd * th_in);
+  th = th_new;
+  if (LA == LA_FIRST) {
+    la = __builtin_fmaf(c.la_c1, th_new, c.la_c0 * th_in);
+  } else if (LA == LA_MID) {
+    la = __builtin_fmaf(c.la_c1, th_new, la);
+  } else if (LA == LA_LAST_FUSED) {
+    th = __builtin_fmaf(c.la_c1, th_new, la);                           // Eq. 30-31
+  } else if (LA == LA_BASIC_FUSED) {
+    la = __builtin_fmaf(c.la_c1, th_new, c.la_c0 * la);
+    th = la;
+  }
+}
+
+template <int LA>
+__device__ __forceinline__ void update_one(float &th, float g, float &m, float &v, float &la, const Consts &c, float gs) {
+  moments(th, g, m, v, c, gs);
+  float m_hat;
+  const float u = direction(m, v, c, m_hat);
+  apply<LA>(th, u, m_hat, la, c, c.step_size);
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ T ld(const T *p) {
+  if (NT) return __builtin_nontemporal_load(p);
+  return *p;
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void st(T *p, T x) {
+  if (NT) __builtin_nontemporal_store(x, p);
+  else *p = x;
+}
+
+template <typename GradV>
+__device__ __forceinline__ f32x4 grad_to_f32(GradV g);
+template <>
+__device__ __forceinline__ f32x4 grad_to_f32<f32x4>(f32x4 g) { return g; }
+template <>
+__device__ __forceinline__ f32x4 grad_to_f32<u16x4>(u16x4 g) {
+  f32x4 r;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) r[k] = bf16_to_f32(g[k]);
+  return r;
+}
+
+template <int LA>
+__device__ __forceinline__ void update_vec(f32x4 &th, f32x4 g, f32x4 &m, f32x4 &v, f32x4 &la, const Consts &c, float gs) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    float th_k = th[k], m_k = m[k], v_k = v[k], la_k = la[k];
+    update_one<LA>(th_k, g[k], m_k, v_k, la_k, c, gs);
+    th[k] = th_k; m[k] = m_k; v[k] = v_k; la[k] = la_k;
+  }
+}
+
+constexpr bool la_reads(int la) { return la == LA_MID || la == LA_LAST_FUSED || la == LA_BASIC_FUSED; }
+constexpr bool la_writes(int la) { return la == LA_FIRST || la == LA_MID || la == LA_BASIC_FUSED; }
+
+// Work decomposition.  A chunk-table entry covers up to chunk_elems (a power of two) elements of one
+// tensor; it is processed by chunk_elems / SUB workgroups ("sub-blocks"), each of which touches
+// SUB = BLOCK*4*UN consecutive elements exactly once and exits.  The default is BLOCK = 64, UN = 1:
+// one wave64 per 256 elements, one 128-bit access per lane and stream.  Short-lived workgroups dispatched
+// in address order keep the set of DRAM pages that are open at any moment small, which is what the
+// write path of this memory system rewards; the table stays small because its granularity is
+// decoupled from the workgroup's.  blockIdx.x = (chunk index << sub_shift) | sub-block index.
+//
+// GradS: scalar gradient type (float, or unsigned short holding bf16 bits); GradV its 4-vector.
+// GC: compiled-in gradient centralization (Eq. 26) for tensors that ask for it (only instantiated for
+// the default shape UN = 1, BLOCK = 64).
+template <typename GradS, typename GradV, int LA, bool NT, int UN, int BLOCK, bool GC = false>
+__global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, int sub_shift) {
+  constexpr int SUB = BLOCK * 4 * UN;
+  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * SUB;
+  if (start >= ch.len) return;
+  const int n = min(SUB, ch.len - start);
+  const int64_t off = ch.offset + start;
+  const TensorPtrs tp = tb.tensors[ch.tensor];          // one scalar load, issued together with the next
+  const void *const g_base = tb.grad[ch.tensor];
+  const float gs = (c.flags & F_CLIP) ? *tb.gscale : 1.0f;
+  GcInfo gi;
+  gi.cols = 0;
+  if (GC) gi = tb.gc[ch.tensor];
+  float *__restrict__ th_p = tp.param + off;
+  float *__restrict__ m_p = tp.m + off;
+  float *__restrict__ v_p = tp.v + off;
+  const GradS *__restrict__ g_p = static_cast<const GradS *>(g_base) + off;
+  float *__restrict__ la_p = nullptr;
+  if (LA != LA_OFF) la_p = tp.la + off;
+
+  uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) |
+                   reinterpret_cast<uintptr_t>(v_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
+  mis |= reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1);
+
+  int done = 0;   // elements [0, done) handled by the 128-bit path
+  if (mis == 0) {
+    f32x4 *th4 = reinterpret_cast<f32x4 *>(th_p);
+    f32x4 *m4 = reinterpret_cast<f32x4 *>(m_p);
+    f32x4 *v4 = reinterpret_cast<f32x4 *>(v_p);
+    f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
+    const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
+    if (n == SUB) {
+      // full sub-block: every load is issued before any arithmetic
+      f32x4 th[UN], m[UN], v[UN], la[UN];
+      GradV g[UN];
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        const int j = threadIdx.x + u * BLOCK;
+        th[u] = ld<NT>(th4 + j);
+        g[u] = ld<NT>(g4 + j);
+        m[u] = ld<NT>(m4 + j);
+        v[u] = ld<NT>(v4 + j);
+        if (la_reads(LA)) la[u] = ld<NT>(la4 + j);
+      }
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        const int j = threadIdx.x + u * BLOCK;
+        f32x4 gf = grad_to_f32<GradV>(g[u]);
+        if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(j), gi);
+        update_vec<LA>(th[u], gf, m[u], v[u], la[u], c, gs);
+        st<NT>(th4 + j, th[u]);
+        st<NT>(m4 + j, m[u]);
+        st<NT>(v4 + j, v[u]);
+        if (la_writes(LA)) st<NT>(la4 + j, la[u]);
+      }
+      return;
+    }
+    const int nvec = n >> 2;
+    for (int i = threadIdx.x; i < nvec; i += BLOCK) {
+      f32x4 th = ld<NT>(th4 + i), m = ld<NT>(m4 + i), v = ld<NT>(v4 + i), la;
+      GradV g = ld<NT>(g4 + i);
+      if (la_reads(LA)) la = ld<NT>(la4 + i);
+      f32x4 gf = grad_to_f32<GradV>(g);
+      if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(i), gi);
+      update_vec<LA>(th, gf, m, v, la, c, gs);
+      st<NT>(th4 + i, th);
+      st<NT>(m4 + i, m);
+      st<NT>(v4 + i, v);
+      if (la_writes(LA)) st<NT>(la4 + i, la);
+    }
+    done = nvec << 2;
+  }
+  // element-wise path: the < 4 element tail of an aligned sub-block, or a whole unaligned one
+  for (int i = done + threadIdx.x; i < n; i += BLOCK) {
+    float th = th_p[i], m = m_p[i], v = v_p[i], la = 0.0f, g;
+    if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
+    else g = g_p[i];
+    if (la_reads(LA)) la = la_p[i];
+    if (GC && gi.cols) g = centralize_one(g, off + i, gi);
+    update_one<LA>(th, g, m, v, la, c, gs);
+    th_p[i] = th;
+    m_p[i] = m;
+    v_p[i] = v;
+    if (la_writes(LA)) la_p[i] = la;
+  }
+}
+
+// Lookahead kernels over the same chunk table and sub-block decomposition (UN = 1).
+//   SYNC_ME:    theta <- A                       (A already holds Eq. 30's right-hand side)
+//   SYNC_BASIC: S <- c1*theta + c0*S; theta <- S (standard Lookahead interpolation)
+//   INIT:       buffer <- theta                  (Eq. 28)
+enum : int { SYNC_ME = 0, SYNC_BASIC = 1, LA_INIT = 2 };
+
+template <int OP>
+__device__ __forceinline__ void la_one(float &th, float &la, float c0, float c1) {
+  if (OP == SYNC_ME) th = la;
+  else if (OP == SYNC_BASIC) { la = __builtin_fmaf(c1, th, c0 * la); th = la; }
+  else la = th;
+}
+
+template <int OP, bool NT, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void novak_lookahead_kernel(Tables tb, float c0, float c1, int sub_shift) {
+  constexpr int SUB = BLOCK * 4;
+  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * SUB;
+  if (start >= ch.len) return;
+  const int n = min(SUB, ch.len - start);
+  const int64_t off = ch.offset + start;
+  const TensorPtrs tp = tb.tensors[ch.tensor];
+  float *__restrict__ th_p = tp.param + off;
+  float *__restrict__ la_p = tp.la + off;
+  const uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
+  int done = 0;
+  if (mis == 0) {
+    const int nvec = n >> 2;
+    f32x4 *th4 = reinterpret_cast<f32x4 *>(th_p);
+    f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
+    for (int i = threadIdx.x; i < nvec; i += BLOCK) {
+      f32x4 th, la;
+      if (OP != SYNC_ME) th = ld<NT>(th4 + i);
+      if (OP != LA_INIT) la = ld<NT>(la4 + i);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        float th_k = th[k], la_k = la[k];
+        la_one<OP>(th_k, la_k, c0, c1);
+        th[k] = th_k; la[k] = la_k;
+      }
+      if (OP != LA_INIT) st<NT>(th4 + i, th);
+      if (OP != SYNC_ME) st<NT>(la4 + i, la);
+    }
+    done = nvec << 2;
+  }
+  for (int i = done + threadIdx.x; i < n; i += BLOCK) {
+    float th = 0.0f, la = 0.0f;
+    if (OP != SYNC_ME) th = th_p[i];
+    if (OP != LA_INIT) la = la_p[i];
+    la_one<OP>(th, la, c0, c1);
+    if (OP != LA_INIT) th_p[i] = th;
+    if (OP != SYNC_ME) la_p[i] = la;
+  }
+}
+
+// True Nesterov, Eq. 10: out <- theta + beta_n * m over the chunk table (one wave per 256 elements).
+template <bool NT>
+__global__ __launch_bounds__(64) void novak_extrapolate_kernel(Tables tb, float *const *out, float beta_n, int sub_shift) {
+  constexpr int SUB = 64 * 4;
+  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * SUB;
+  if (start >= ch.len) return;
+  const int n = min(SUB, ch.len - start);
+  const int64_t off = ch.offset + start;
+  const TensorPtrs tp = tb.tensors[ch.tensor];
+  const float *__restrict__ th_p = tp.param + off;
+  const float *__restrict__ m_p = tp.m + off;
+  float *__restrict__ o_p = out[ch.tensor] + off;
+  const uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) | reinterpret_cast<uintptr_t>(o_p)) & 15u;
+  int done = 0;
+  if (mis == 0) {
+    const int nvec = n >> 2;
+    const int i = threadIdx.x;
+    if (i < nvec) {
+      const f32x4 th = ld<NT>(reinterpret_cast<const f32x4 *>(th_p) + i), m = ld<NT>(reinterpret_cast<const f32x4 *>(m_p) + i);
+      f32x4 o;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] = __builtin_fmaf(beta_n, m[k], th[k]);
+      st<NT>(reinterpret_cast<f32x4 *>(o_p) + i, o);
+    }
+    done = nvec << 2;
+  }
+  for (int i = done + threadIdx.x; i < n; i += 64) o_p[i] = __builtin_fmaf(beta_n, m_p[i], th_p[i]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Two-pass path for the full-features scalings (layer-wise trust ratio, Eq. 19 / 25; auto-LR, Eq.
+// 20-22).  Both need norms over whole tensors before any parameter may move, so the step splits:
+//   pass 1  novak_moments_kernel   reads theta, g, m, v; writes m, v; one partial (sum theta^2,
+//                                  sum u^2, sum g^2) per wave, u being Eq. 17's base direction
+//   reduce  chunks -> tensors -> (global)   fixed-order sums in double: results do not depend on timing
+//   pass 2  novak_apply_kernel     reads theta, m, v; recomputes u with the same arithmetic; applies
+//                                  alpha*r_t*scale[tensor] and the lookahead phase; writes theta
+// One wave64 per 256 elements in both passes, as in the fused kernel.
+// ------------------------------------------------------------------------------------------------
+constexpr int kScaledBlock = 64;
+constexpr int kScaledSub = kScaledBlock * 4;
+
+struct NormPartial {   // one per wave of pass 1
+  float theta2, u2, g2, pad;
+};
+struct NormSums {      // per chunk / per tensor, in double
+  double theta2, u2, g2;
+};
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+
+template <typename GradS, typename GradV, bool NT>
+__global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, Consts c, int sub_shift, NormPartial *partials) {
+  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kScaledSub;
+  if (start >= ch.len) return;
+  const int n = min(kScaledSub, ch.len - start);
+  const int64_t off = ch.offset + start;
+  const TensorPtrs tp = tb.tensors[ch.tensor];
+  const void *const g_base = tb.grad[ch.tensor];
+  const float gs = (c.flags & F_CLIP) ? *tb.gscale : 1.0f;
+  GcInfo gi;
+  gi.cols = 0;
+  if (c.flags & F_GC) gi = tb.gc[ch.tensor];
+  const float *__restrict__ th_p = tp.param + off;
+  float *__restrict__ m_p = tp.m + off;
+  float *__restrict__ v_p = tp.v + off;
+  const GradS *__restrict__ g_p = static_cast<const GradS *>(g_base) + off;
+
+  uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) | reinterpret_cast<uintptr_t>(v_p)) & 15u;
+  mis |= reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1);
+
+  float s_th = 0.0f, s_u = 0.0f, s_g = 0.0f;
+  int done = 0;
+  if (mis == 0) {
+    const int nvec = n >> 2;
+    const f32x4 *th4 = reinterpret_cast<const f32x4 *>(th_p);
+    f32x4 *m4 = reinterpret_cast<f32x4 *>(m_p);
+    f32x4 *v4 = reinterpret_cast<f32x4 *>(v_p);
+    const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
+    const int i = threadIdx.x;
+    if (i < nvec) {
+      const f32x4 th = ld<NT>(th4 + i);
+      f32x4 g = grad_to_f32<GradV>(ld<NT>(g4 + i));
+      f32x4 m = ld<NT>(m4 + i), v = ld<NT>(v4 + i);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) s_g = __builtin_fmaf(g[k], g[k], s_g);     // norm of the gradient as handed in
+      if (gi.cols) centralize(g, 4, off + 4 * static_cast<int64_t>(i), gi);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        float m_k = m[k], v_k = v[k], m_hat;
+        moments(th[k], g[k], m_k, v_k, c, gs);
+        const float u = direction(m_k, v_k, c, m_hat);
+        s_th = __builtin_fmaf(th[k], th[k], s_th);
+        s_u = __builtin_fmaf(u, u, s_u);
+        m[k] = m_k; v[k] = v_k;
+      }
+      st<NT>(m4 + i, m);
+      st<NT>(v4 + i, v);
+    }
+    done = nvec << 2;
+  }
+  for (int i = done + threadIdx.x; i < n; i += kScaledBlock) {
+    const float th = th_p[i];
+    float m = m_p[i], v = v_p[i], g, m_hat;
+    if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
+    else g = g_p[i];
+    s_g = __builtin_fmaf(g, g, s_g);
+    if (gi.cols) g = centralize_one(g, off + i, gi);
+    moments(th, g, m, v, c, gs);
+    const float u = direction(m, v, c, m_hat);
+    s_th = __builtin_fmaf(th, th, s_th);
+    s_u = __builtin_fmaf(u, u, s_u);
+    m_p[i] = m;
+    v_p[i] = v;
+  }
+  s_th = wave_sum(s_th);
+  s_u = wave_sum(s_u);
+  s_g = wave_sum(s_g);
+  if (threadIdx.x == 0) {
+    NormPartial p;
+    p.theta2 = s_th; p.u2 = s_u; p.g2 = s_g; p.pad = 0.0f;
+    partials[blockIdx.x] = p;
+  }
+}
+
+// one wave per chunk: sums the chunk's per-wave partials in a fixed order
+__global__ __launch_bounds__(64) void novak_reduce_chunks_kernel(const novak_chunk *chunks, int sub_shift, int sub_elems,
+                                                                 const NormPartial *partials, NormSums *chunk_sums) {
+  const novak_chunk ch = chunks[blockIdx.x];
+  const int nsub = (ch.len + sub_elems - 1) / sub_elems;
+  const NormPartial *p = partials + (static_cast<size_t>(blockIdx.x) << sub_shift);
+  double a = 0.0, b = 0.0, g = 0.0;
+  for (int j = threadIdx.x; j < nsub; j += 64) {
+    const NormPartial x = p[j];
+    a += static_cast<double>(x.theta2);
+    b += static_cast<double>(x.u2);
+    g += static_cast<double>(x.g2);
+  }
+  a = wave_sum(a); b = wave_sum(b); g = wave_sum(g);
+  if (threadIdx.x == 0) {
+    NormSums s; s.theta2 = a; s.u2 = b; s.g2 = g;
+    chunk_sums[blockIdx.x] = s;
+  }
+}
+
+// Clipping pre-pass (sections 5.8, 7.3): one read of the gradients, one partial (sum g^2) per wave; the
+// chunk and tensor reductions above are reused, then novak_clip_kernel turns the global norm into the
+// factor min(1, c_clip/||g||) that every later kernel of the step multiplies the gradients by.
+constexpr int kNormUnroll = 4;                          // 128-bit loads in flight per lane in the read-only pre-pass
+constexpr int kNormSub = kScaledSub * kNormUnroll;      // elements per wave there
+
+template <typename GradS, typename GradV, bool NT>
+__global__ __launch_bounds__(kScaledBlock) void novak_gradnorm_kernel(Tables tb, int sub_shift, NormPartial *partials) {
+  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kNormSub;
+  if (start >= ch.len) return;
+  const int n = min(kNormSub, ch.len - start);
+  const GradS *__restrict__ g_p = static_cast<const GradS *>(tb.grad[ch.tensor]) + (ch.offset + start);
+  float s_g = 0.0f;
+  int done = 0;
+  if ((reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1)) == 0) {
+    const int nvec = n >> 2;
+    const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
+    if (n == kNormSub) {
+      GradV g[kNormUnroll];
+#pragma unroll
+      for (int u = 0; u < kNormUnroll; ++u) g[u] = ld<NT>(g4 + threadIdx.x + u * kScaledBlock);
+#pragma unroll
+      for (int u = 0; u < kNormUnroll; ++u) {
+        const f32x4 gf = grad_to_f32<GradV>(g[u]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s_g = __builtin_fmaf(gf[k], gf[k], s_g);
+      }
+    } else {
+      for (int i = threadIdx.x; i < nvec; i += kScaledBlock) {
+        const f32x4 gf = grad_to_f32<GradV>(ld<NT>(g4 + i));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s_g = __builtin_fmaf(gf[k], gf[k], s_g);
+      }
+    }
+    done = nvec << 2;
+  }
+  for (int i = done + threadIdx.x; i < n; i += kScaledBlock) {
+    float g;
+    if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
+    else g = g_p[i];
+    s_g = __builtin_fmaf(g, g, s_g);
+  }
+  s_g = wave_sum(s_g);
+  if (threadIdx.x == 0) {
+    NormPartial p;
+    p.theta2 = 0.0f; p.u2 = 0.0f; p.g2 = s_g; p.pad = 0.0f;
+    partials[blockIdx.x] = p;
+  }
+}
+
+__global__ __launch_bounds__(64) void novak_clip_kernel(int n_tensors, const NormSums *tensor_sums, float c_clip, float *gscale) {
+  double g = 0.0;
+  for (int j = threadIdx.x; j < n_tensors; j += 64) g += tensor_sums[j].g2;
+  g = wave_sum(g);
+  if (threadIdx.x == 0) {
+    const double norm = sqrt(g);
+    gscale[0] = norm > static_cast<double>(c_clip) ? static_cast<float>(static_cast<double>(c_clip) / norm) : 1.0f;
+  }
+}
+
+// Row means for gradient centralization (Eq. 26): one wave per row of a centralized tensor.
+// `gc_tensor[j]` lists the centralized tensors, `row_first[j]` the index of tensor j's first row in
+// the launch (prefix sums, n_gc + 1 entries).
+template <typename GradS>
+__global__ __launch_bounds__(64) void novak_rowmean_kernel(const void *const *grad, const int *gc_tensor, const int64_t *row_first,
+                                                          int n_gc, const GcInfo *gc, double *means) {
+  const int64_t row = blockIdx.x;
+  int lo = 0, hi = n_gc - 1;                     // largest j with row_first[j] <= row
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (row_first[mid] <= row) lo = mid;
+    else hi = mid - 1;
+  }
+  const int t = gc_tensor[lo];
+  const int64_t local = row - row_first[lo];
+  const int64_t cols = gc[t].cols;
+  const GradS *__restrict__ p = static_cast<const GradS *>(grad[t]) + local * cols;
+  double acc = 0.0;
+  int64_t done = 0;
+  if constexpr (sizeof(GradS) == 4) {
+    // 128-bit path for rows that start 16-byte aligned; four loads in flight per lane
+    if ((reinterpret_cast<uintptr_t>(p) & 15u) == 0) {
+      const f32x4 *p4 = reinterpret_cast<const f32x4 *>(p);
+      const int64_t nvec = cols >> 2;
+      int64_t i = threadIdx.x;
+      for (; i + 3 * 64 < nvec; i += 4 * 64) {
+        const f32x4 a = __builtin_nontemporal_load(p4 + i), b = __builtin_nontemporal_load(p4 + i + 64),
+                    c4 = __builtin_nontemporal_load(p4 + i + 128), d = __builtin_nontemporal_load(p4 + i + 192);
+        acc += (static_cast<double>(a[0]) + a[1]) + (static_cast<double>(a[2]) + a[3]);
+        acc += (static_cast<double>(b[0]) + b[1]) + (static_cast<double>(b[2]) + b[3]);
+        acc += (static_cast<double>(c4[0]) + c4[1]) + (static_cast<double>(c4[2]) + c4[3]);
+        acc += (static_cast<double>(d[0]) + d[1]) + (static_cast<double>(d[2]) + d[3]);
+      }
+      for (; i < nvec; i += 64) {
+        const f32x4 a = __builtin_nontemporal_load(p4 + i);
+        acc += (static_cast<double>(a[0]) + a[1]) + (static_cast<double>(a[2]) + a[3]);
+      }
+      done = nvec << 2;
+    }
+  }
+  for (int64_t i = done + threadIdx.x; i < cols; i += 64) {
+    if constexpr (sizeof(GradS) == 2) acc += static_cast<double>(bf16_to_f32(p[i]));
+    else acc += static_cast<double>(p[i]);
+  }
+  const double sum = wave_sum(acc);
+  if (threadIdx.x == 0) means[row] = sum / static_cast<double>(cols);
+}
+
+struct ScaleParams {
+  float trust_lo, trust_hi;    // clip range of Eq. 19
+  float auto_lo, auto_hi;      // clip range of Eq. 22
+  double gamma;                // EMA weight of Eq. 20-21
+  int layer_adaptation, auto_lr;
+};
+
+// one wave per tensor: per-tensor sums; the clipped trust ratio (Eq. 19 / 25) goes to scale[t]
+__global__ __launch_bounds__(64) void novak_reduce_tensors_kernel(const int *first_chunk, const NormSums *chunk_sums,
+                                                                  NormSums *tensor_sums, float *scale, ScaleParams sp) {
+  const int t = blockIdx.x;
+  const int c0 = first_chunk[t], c1 = first_chunk[t + 1];
+  double a = 0.0, b = 0.0, g = 0.0;
+  for (int j = c0 + threadIdx.x; j < c1; j += 64) {
+    const NormSums x = chunk_sums[j];
+    a += x.theta2; b += x.u2; g += x.g2;
+  }
+  a = wave_sum(a); b = wave_sum(b); g = wave_sum(g);
+  if (threadIdx.x == 0) {
+    NormSums s; s.theta2 = a; s.u2 = b; s.g2 = g;
+    tensor_sums[t] = s;
+    float eta = 1.0f;
+    if (sp.layer_adaptation) {
+      // eta = ||theta|| / ||u||, 1 when either norm is zero; clipped
+      double r = (a > 0.0 && b > 0.0) ? sqrt(a / b) : 1.0;
+      r = r < static_cast<double>(sp.trust_lo) ? static_cast<double>(sp.trust_lo) : r;
+      r = r > static_cast<double>(sp.trust_hi) ? static_cast<double>(sp.trust_hi) : r;
+      eta = static_cast<float>(r);
+    }
+    scale[t] = eta;
+  }
+}
+
+// one wave: global norms -> EMAs (Eq. 20-21, state in `ema`: g_bar, theta_bar) -> alpha_auto (Eq. 22),
+// folded into every tensor's scale
+__global__ __launch_bounds__(64) void novak_auto_lr_kernel(int n_tensors, const NormSums *tensor_sums, float *scale,
+                                                           double *ema, ScaleParams sp) {
+  double a = 0.0, g = 0.0;
+  for (int j = threadIdx.x; j < n_tensors; j += 64) {
+    a += tensor_sums[j].theta2;
+    g += tensor_sums[j].g2;
+  }
+  a = wave_sum(a); g = wave_sum(g);
+  // every lane holds the same sums; every lane computes the same factor
+  const double g_bar = sp.gamma * sqrt(g) + (1.0 - sp.gamma) * ema[0];
+  const double th_bar = sp.gamma * sqrt(a) + (1.0 - sp.gamma) * ema[1];
+  double f = 1.0;
+  if (th_bar != 0.0) {
+    f = g_bar / th_bar;
+    f = f < static_cast<double>(sp.auto_lo) ? static_cast<double>(sp.auto_lo) : f;
+    f = f > static_cast<double>(sp.auto_hi) ? static_cast<double>(sp.auto_hi) : f;
+  }
+  const float ff = static_cast<float>(f);
+  for (int j = threadIdx.x; j < n_tensors; j += 64) scale[j] *= ff;
+  __syncthreads();   // all lanes have read ema before lane 0 replaces it
+  if (threadIdx.x == 0) {
+    ema[0] = g_bar;
+    ema[1] = th_bar;
+  }
+}
+
+template <int LA, bool NT>
+__global__ __launch_bounds__(kScaledBlock) void novak_apply_kernel(Tables tb, Consts c, int sub_shift, const float *scale) {
+  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kScaledSub;
+  if (start >= ch.len) return;
+  const int n = min(kScaledSub, ch.len - start);
+  const int64_t off = ch.offset + start;
+  const TensorPtrs tp = tb.tensors[ch.tensor];
+  const float step = c.step_size * scale[ch.tensor];                    // Eq. 24a
+  float *__restrict__ th_p = tp.param + off;
+  const float *__restrict__ m_p = tp.m + off;
+  const float *__restrict__ v_p = tp.v + off;
+  float *__restrict__ la_p = nullptr;
+  if (LA != LA_OFF) la_p = tp.la + off;
+  const uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) |
+                         reinterpret_cast<uintptr_t>(v_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
+  int done = 0;
+  if (mis == 0) {
+    const int nvec = n >> 2;
+    f32x4 *th4 = reinterpret_cast<f32x4 *>(th_p);
+    const f32x4 *m4 = reinterpret_cast<const f32x4 *>(m_p);
+    const f32x4 *v4 = reinterpret_cast<const f32x4 *>(v_p);
+    f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
+    const int i = threadIdx.x;
+    if (i < nvec) {
+      f32x4 th = ld<NT>(th4 + i), la;
+      const f32x4 m = ld<NT>(m4 + i), v = ld<NT>(v4 + i);
+      if (la_reads(LA)) la = ld<NT>(la4 + i);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        float th_k = th[k], la_k = la[k], m_hat;
+        const float u = direction(m[k], v[k], c, m_hat);
+        apply<LA>(th_k, u, m_hat, la_k, c, step);
+        th[k] = th_k; la[k] = la_k;
+      }
+      st<NT>(th4 + i, th);
+      if (la_writes(LA)) st<NT>(la4 + i, la);
+    }
+    done = nvec << 2;
+  }
+  for (int i = done + threadIdx.x; i < n; i += kScaledBlock) {
+    float th = th_p[i], la = 0.0f, m_hat;
+    if (la_reads(LA)) la = la_p[i];
+    const float u = direction(m_p[i], v_p[i], c, m_hat);
+    apply<LA>(th, u, m_hat, la, c, step);
+    th_p[i] = th;
+    if (la_writes(LA)) la_p[i] = la;
+  }
+}
+
+}  // namespace
+
+#endif  // NOVAK_KERNELS_H_
