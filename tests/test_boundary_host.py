@@ -195,3 +195,27 @@ def test_create_rejects_bad_arguments_before_touching_the_gpu():
     assert N.novak_lookahead_sync(None, 0) == N.NOVAK_ERR_NULL_POINTER
     assert N.novak_lookahead_init(None, 0) == N.NOVAK_ERR_NULL_POINTER
     assert N.novak_status_string(N.NOVAK_ERR_STATE) != N.novak_status_string(12345)
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No fallback path: without the built shared library the binding raises instead of computing elsewhere."""
+    monkeypatch.setattr(N, "_lib", None)
+    monkeypatch.setattr(N, "LIB_PATH", str(tmp_path / "libnovak.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        N.load_library()
+    with pytest.raises(RuntimeError):
+        N.novak_validate_hparams(N.make_hparams())
+
+
+def test_product_never_imports_the_oracle():
+    """The package, the bench's GPU leg and the build step contain no reference to oracle/ (only the
+    cpu_baseline function of bench.py and the smoke check do)."""
+    pkg = os.path.join(ROOT, "paper_2601_07876_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    body = bench.split("def cpu_baseline(")[0] + bench.split("def main():")[1]
+    assert "from oracle" not in body and "import oracle" not in body

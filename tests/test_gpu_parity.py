@@ -251,3 +251,21 @@ def test_gradient_pointer_list_changes_between_steps():
     finally:
         a.close()
         b.close()
+
+
+def test_tensor_desc_helper_from_torch_tensors():
+    """The binding's marshalling helper: shapes, dtypes and contiguity are checked, rows follow dim 0."""
+    dev = "cuda:0"
+    p = torch.zeros(6, 3, 5, 5, device=dev)
+    m, v, la = torch.zeros_like(p), torch.zeros_like(p), torch.zeros_like(p)
+    d = N.tensor_desc(p, m, v, la)
+    assert (d.numel, d.rows, d.param, d.la_buf) == (450, 6, p.data_ptr(), la.data_ptr())
+    assert N.tensor_desc(torch.zeros(7, device=dev), torch.zeros(7, device=dev), torch.zeros(7, device=dev)).rows == 0
+    with pytest.raises(ValueError):
+        N.tensor_desc(p.double(), m, v)
+    with pytest.raises(ValueError):
+        N.tensor_desc(p.transpose(0, 1), m, v)
+    with pytest.raises(ValueError):
+        N.tensor_desc(p, m[:3], v)
+    with pytest.raises(ValueError):
+        N.tensor_desc(p.cpu(), m, v)
