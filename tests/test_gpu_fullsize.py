@@ -186,6 +186,13 @@ def test_c5_decoder_1p3b_sweep():
                     if t in (k - 1, 2 * k, 2 * k + 1):
                         run.check(f"c5 k={k} {nest} t={t}")
                 _say(f"c5 k={k} nesterov={nest} done")
+        # the exact configuration bench.py times: fast mode, approximation, k = 5, sync fused into the k-th step
+        run.reset(wl.hyper, auto_sync=True)
+        for t in range(1, 12):
+            run.step()
+            if t in (4, 5, 6, 10, 11):
+                run.check(f"c5 bench-config t={t}")
+        _say("c5 bench configuration done")
     finally:
         run.close()
 

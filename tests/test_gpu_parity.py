@@ -269,3 +269,17 @@ def test_tensor_desc_helper_from_torch_tensors():
         N.tensor_desc(p, m[:3], v)
     with pytest.raises(ValueError):
         N.tensor_desc(p.cpu(), m, v)
+
+
+@pytest.mark.parametrize("lookahead", ["memory_efficient", "basic"])
+@pytest.mark.parametrize("auto_sync", [False, True])
+@pytest.mark.parametrize("k", [1, 2])
+def test_short_lookahead_windows(lookahead, auto_sync, k):
+    """k = 1 (every step is first and last step of its window) and k = 2 (no middle step)."""
+    wl = W.get_workload("ragged")
+    hyper = dict(wl.hyper, lookahead=lookahead, la_k=k, la_alpha=0.3)
+    gpu, states, _ = H.run_pair(wl.numels[:11], hyper, 5, wl.grad_std, auto_sync=auto_sync, check_blend_at=(1, 2, 3))
+    try:
+        H.compare_states(gpu, states)
+    finally:
+        gpu.close()
