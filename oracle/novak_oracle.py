@@ -55,6 +55,14 @@ Readings taken where the paper is silent or inconsistent (each is a named switch
   * true Nesterov (Eq. 10): the extrapolated point is theta + beta_n * m with the sign as printed;
     `extrapolate` returns it.  With n_taylor > 0 the mode "true" behaves as "approx" for t > n_taylor
     (automatic fallback, sections 4.4 and 5.8).
+  * reduced-precision first moment (the paper's "multi-precision" outlook, sections 3 and 10.3; not part
+    of its method): moment_dtype = "bf16_m" stores m as bfloat16, rounded to nearest-even from the
+    exactly computed value at the end of every step; all arithmetic stays in double here (fp32 in an
+    implementation).  v stays fp32: with beta2 = 0.999 its per-step change (0.1 % of v) is below half
+    a bfloat16 ulp (0.2-0.4 %), so a round-to-nearest bf16 v would stop moving.  An implementation that
+    forms m in fp32 before rounding can land on the other side of a rounding boundary; the oracle
+    records in TensorState.ambiguous the elements whose exact m ever came within BF16_BAND ulps of a
+    midpoint.  parity unpinned by the paper (it defines no such mode).
   * sparse threshold (Eq. 27): the base direction u is zeroed where |u| <= tau, after the trust ratio is
     taken (Phase 7 precedes Phase 8) and before the classical blend (Table 2's order within Phase 8).
     The mask is a discontinuous decision on a floating-point value: an implementation in another
@@ -74,6 +82,8 @@ NESTEROV_MODES = ("none", "approx", "classical", "true")
 LOOKAHEAD_MODES = ("none", "memory_efficient", "basic")
 UNRECT_FALLBACKS = ("adam_denom", "sgdm")
 AMBIGUITY_BAND = 5e-5      # relative half-width around tau in which the Eq. 27 decision is called ambiguous
+BF16_BAND = 2e-4           # distance from a bfloat16 rounding midpoint, in bf16 ulps, that is called ambiguous
+MOMENT_DTYPES = ("f32", "bf16_m")
 
 
 @dataclass
@@ -104,11 +114,13 @@ class Hyper:
     beta_tau1: float = 1000.0
     beta_tau2: float = 5000.0
     n_taylor: int = 0                   # "true" Nesterov falls back to "approx" after this many steps; 0 = never
+    moment_dtype: str = "f32"           # "bf16_m": m is stored as bfloat16 (see header)
 
     def __post_init__(self):
         assert self.nesterov in NESTEROV_MODES
         assert self.lookahead in LOOKAHEAD_MODES
         assert self.unrect_fallback in UNRECT_FALLBACKS
+        assert self.moment_dtype in MOMENT_DTYPES
 
 
 @dataclass
@@ -130,6 +142,20 @@ def one_minus_pow(beta: float, t: int) -> float:
     if beta == 0.0:
         return 1.0
     return -math.expm1(t * math.log(beta))
+
+
+def round_to_bf16(x: np.ndarray):
+    """Round double values to the nearest bfloat16 (8 significant bits, ties to even) in ONE rounding.
+
+    Returns (rounded values as float64, distance of x from the nearest rounding midpoint in bf16 ulps).
+    Subnormal bfloat16 results are not handled (the moments here never get below 1e-38).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    mant, exp = np.frexp(x)                      # x = mant * 2^exp, 0.5 <= |mant| < 1
+    scaled = mant * 256.0                        # 128 <= |scaled| < 256: one unit = one bf16 ulp
+    q = np.rint(scaled)                          # ties to even
+    frac = np.abs(scaled) - np.floor(np.abs(scaled))
+    return np.ldexp(q, exp - 8), np.abs(frac - 0.5)
 
 
 def scheduled_betas(h: Hyper, t: int):
@@ -275,6 +301,10 @@ def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float 
     alpha_eff = s.step_size * lam_trust * alpha_auto        # Eq. 24a
     theta = theta * s.decay - alpha_eff * u                 # Eq. 18 then Eq. 24
 
+    if h.moment_dtype == "bf16_m":
+        m, dist = round_to_bf16(m)
+        near = (dist < BF16_BAND) & (m != 0.0)
+        st.ambiguous = near if st.ambiguous is None else (st.ambiguous | near)
     st.theta = theta.astype(dt)
     st.m = m.astype(dt)
     st.v = v.astype(dt)
