@@ -57,11 +57,13 @@ Readings taken where the paper is silent or inconsistent (each is a named switch
     (automatic fallback, sections 4.4 and 5.8).
   * reduced-precision first moment (the paper's "multi-precision" outlook, sections 3 and 10.3; not part
     of its method): moment_dtype = "bf16_m" stores m as bfloat16, rounded to nearest-even from the
-    exactly computed value at the end of every step; all arithmetic stays in double here (fp32 in an
-    implementation).  v stays fp32: with beta2 = 0.999 its per-step change (0.1 % of v) is below half
+    exactly computed value of Eq. 1; that stored m_t is what bias correction and the direction of the
+    same step use.  All arithmetic stays in double here (fp32 in an implementation).  v stays fp32: with beta2 = 0.999 its per-step change (0.1 % of v) is below half
     a bfloat16 ulp (0.2-0.4 %), so a round-to-nearest bf16 v would stop moving.  An implementation that
-    forms m in fp32 before rounding can land on the other side of a rounding boundary; the oracle
-    records in TensorState.ambiguous the elements whose exact m ever came within BF16_BAND ulps of a
+    forms m in fp32 before rounding can land on the other side of a rounding boundary.  To first order
+    an fp32 evaluation of Eq. 13 and Eq. 1 (each operation and each constant rounded once) is within
+    2^-24 [(1-beta1)(2|g| + 3|g~| + 4|m_prev|) + |m|] of the exact m; the oracle records in
+    TensorState.ambiguous the elements whose exact m ever came within FP32_SLACK times that of a
     midpoint.  parity unpinned by the paper (it defines no such mode).
   * sparse threshold (Eq. 27): the base direction u is zeroed where |u| <= tau, after the trust ratio is
     taken (Phase 7 precedes Phase 8) and before the classical blend (Table 2's order within Phase 8).
@@ -82,7 +84,8 @@ NESTEROV_MODES = ("none", "approx", "classical", "true")
 LOOKAHEAD_MODES = ("none", "memory_efficient", "basic")
 UNRECT_FALLBACKS = ("adam_denom", "sgdm")
 AMBIGUITY_BAND = 5e-5      # relative half-width around tau in which the Eq. 27 decision is called ambiguous
-BF16_BAND = 2e-4           # distance from a bfloat16 rounding midpoint, in bf16 ulps, that is called ambiguous
+FP32_UNIT = 2.0 ** -24     # unit roundoff of fp32
+FP32_SLACK = 2.0           # safety factor on the first-order fp32 error bound used to call a bf16 rounding ambiguous
 MOMENT_DTYPES = ("f32", "bf16_m")
 
 
@@ -156,6 +159,11 @@ def round_to_bf16(x: np.ndarray):
     q = np.rint(scaled)                          # ties to even
     frac = np.abs(scaled) - np.floor(np.abs(scaled))
     return np.ldexp(q, exp - 8), np.abs(frac - 0.5)
+
+
+def bf16_ulp(x: np.ndarray) -> np.ndarray:
+    """Spacing of bfloat16 numbers in the binade of x (x != 0)."""
+    return np.ldexp(1.0, np.frexp(np.asarray(x, dtype=np.float64))[1] - 8)
 
 
 def scheduled_betas(h: Hyper, t: int):
@@ -280,11 +288,20 @@ def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float 
         g = (g2d - g2d.mean(axis=1, keepdims=True)).reshape(-1)    # Eq. 26
     if (not h.decoupled_decay) and h.weight_decay != 0.0:
         g = g + h.weight_decay * theta                      # coupled L2 (reading; see header)
+    g_in = g
     if effective_nesterov(h, t) == "approx":
         g = g + h.beta_n * (g - m_prev)                     # Eq. 13; replaces g for both moments
     b1_t, b2_t = scheduled_betas(h, t)                      # Eq. 3-4 (Phase 3)
     m = b1_t * m_prev + (1.0 - b1_t) * g                    # Eq. 1
     v = b2_t * v_prev + (1.0 - b2_t) * g * g                # Eq. 2
+    if h.moment_dtype == "bf16_m":                          # m_t is what is stored: the rest of the step uses it
+        m_exact = m
+        m, dist = round_to_bf16(m_exact)
+        # bookkeeping only: could an fp32 evaluation of Eq. 13 and Eq. 1 have crossed the midpoint?
+        fp32_error = FP32_SLACK * FP32_UNIT * ((1.0 - b1_t) * (2.0 * np.abs(g_in) + 3.0 * np.abs(g) + 4.0 * np.abs(m_prev))
+                                               + np.abs(m_exact))
+        near = (dist * bf16_ulp(m_exact) <= fp32_error) & (m_exact != 0.0)
+        st.ambiguous = near if st.ambiguous is None else (st.ambiguous | near)
     m_hat = m / s.bc1                                       # Eq. 5
     if s.denom_on:
         v_hat = v / s.bc2                                   # Eq. 5
@@ -301,10 +318,6 @@ def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float 
     alpha_eff = s.step_size * lam_trust * alpha_auto        # Eq. 24a
     theta = theta * s.decay - alpha_eff * u                 # Eq. 18 then Eq. 24
 
-    if h.moment_dtype == "bf16_m":
-        m, dist = round_to_bf16(m)
-        near = (dist < BF16_BAND) & (m != 0.0)
-        st.ambiguous = near if st.ambiguous is None else (st.ambiguous | near)
     st.theta = theta.astype(dt)
     st.m = m.astype(dt)
     st.v = v.astype(dt)

@@ -82,3 +82,30 @@ def test_bf16_moment_changes_only_m_storage_and_flags_near_midpoints():
     assert np.max(np.abs(a.theta - b.theta)) < 1e-4 and np.max(np.abs(a.theta - b.theta)) > 0
     assert a.ambiguous is not None and a.ambiguous.mean() < 0.02
     assert b.ambiguous is None
+
+
+def test_flags_cover_every_disagreement_with_an_fp32_evaluation():
+    """The oracle's flag is a claim about fp32 arithmetic: wherever Eq. 13 and Eq. 1 evaluated in fp32
+    (fused multiply-adds emulated through double) round to another bfloat16 than the exact value, the
+    element must have been flagged; and the flags must stay rare."""
+    import workloads as W
+    f32 = np.float32
+    n, steps = 1 << 15, 30
+
+    def fma(a, b, c):
+        return (a.astype(np.float64) * np.float64(b) + c.astype(np.float64)).astype(f32)
+
+    h = O.Hyper(lookahead="none", weight_decay=1e-2, moment_dtype="bf16_m")
+    st = O.init_state(W.host_params([n], 42)[0], h)
+    m = np.zeros(n, f32)
+    differing = 0
+    for t in range(1, steps + 1):
+        g = W.host_grads([n], t, 1e-2, 42)[0]
+        O.step(st, g, t, h)
+        gt = fma((g - m).astype(f32), f32(0.9), g)                 # Eq. 13
+        m = W.round_to_bf16(fma((gt - m).astype(f32), f32(1.0 - 0.9), m))   # Eq. 1, then the storage rounding
+        diff = m != st.m
+        differing = max(differing, int(diff.sum()))
+        assert not np.any(diff & ~st.ambiguous), t
+    assert differing > 0                       # the situation the flags exist for does occur
+    assert st.ambiguous.mean() < 1.5 * steps * 8e-4
