@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--use-gc", action="store_true", help="research mode: gradient centralization of the multi-dimensional tensors")
     ap.add_argument("--clip", type=float, default=0.0, help="global-norm gradient clipping threshold (0 = off)")
     ap.add_argument("--sparse", type=float, default=0.0, help="sparse threshold tau of Eq. 27 (0 = off)")
+    ap.add_argument("--moment-dtype", default="f32", choices=("f32", "bf16_m"),
+                    help="storage of the first moment: fp32, or bfloat16 (reduced-precision state; not the headline configuration)")
     ap.add_argument("--chunk-elems", type=int, default=None)
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--vec-per-lane", type=int, default=None)
@@ -122,7 +124,7 @@ def main():
     scaled = args.layer_adaptation or args.auto_lr
     if scaled or args.use_gc:
         hyper.update(mode="research", layer_adaptation=args.layer_adaptation, auto_lr=args.auto_lr, use_gc=args.use_gc)
-    hyper.update(clip_threshold=args.clip, sparse_threshold=args.sparse)
+    hyper.update(clip_threshold=args.clip, sparse_threshold=args.sparse, moment_dtype=args.moment_dtype)
     fused = not args.separate_sync
     numels = wl.numels
     p = wl.total
@@ -136,7 +138,7 @@ def main():
     gen = torch.Generator(device=dev)
     gen.manual_seed(42)
     theta = torch.empty(flat, dtype=torch.float32, device=dev).normal_(0.0, W.PARAM_STD, generator=gen)
-    m = torch.zeros(flat, dtype=torch.float32, device=dev)
+    m = torch.zeros(flat, dtype=torch.bfloat16 if args.moment_dtype == "bf16_m" else torch.float32, device=dev)
     v = torch.zeros(flat, dtype=torch.float32, device=dev)
     la = torch.zeros(flat, dtype=torch.float32, device=dev)
     g32 = torch.empty(flat, dtype=torch.float32, device=dev).normal_(0.0, wl.grad_std, generator=gen)
@@ -144,7 +146,7 @@ def main():
     del g32
 
     hp = N.make_hparams(auto_sync=fused, **hyper)
-    descs = [N.novak_tensor_desc(theta.data_ptr() + 4 * o, m.data_ptr() + 4 * o, v.data_ptr() + 4 * o,
+    descs = [N.novak_tensor_desc(theta.data_ptr() + 4 * o, m.data_ptr() + m.element_size() * o, v.data_ptr() + 4 * o,
                                  la.data_ptr() + 4 * o, n, r) for o, n, r in zip(offsets, numels, wl.rows)]
     rc, handle = N.novak_create(hp, descs, 0)
     N.check(rc, "novak_create")
@@ -171,6 +173,7 @@ def main():
     if info.auto_lr:
         N.check(N.novak_set_auto_lr_state(handle, ema.data_ptr()), "set_auto_lr_state", handle)
     scaled = bool(info.layer_adaptation or info.auto_lr)
+    m_tag = "+bf16_m" if info.moment_dtype == N.NOVAK_MOMENT_BF16_M else ""
 
     def one_step(t):
         N.check(N.novak_step(handle, grad_arr, gdt, t, stream), "novak_step", handle)
@@ -190,7 +193,7 @@ def main():
     t_begin = time.perf_counter()
     for i in range(args.steps):
         t += 1
-        variants.append(("scaled_" if scaled else "") + la_variant(la_name, k, t, fused))
+        variants.append(("scaled_" if scaled else "") + la_variant(la_name, k, t, fused) + m_tag)
         ev[i][0].record()
         N.check(N.novak_step(handle, grad_arr, gdt, t, stream), "novak_step", handle)
         ev[i][1].record()
@@ -214,9 +217,11 @@ def main():
         # a two-pass ("scaled_") step is timed as a whole: both passes and the small reductions between them
         fn = N.novak_bytes_per_param_scaled_step if name.startswith("scaled_") else N.novak_bytes_per_param_step
         base = name[len("scaled_"):] if name.startswith("scaled_") else name
+        base = base[:len(base) - len(m_tag)] if m_tag else base
         pos = {"step": 2 if la_name == "basic" else 1, "step+la_first": 1, "step+la_mid": 2,
                "step+la_last_fused": k, "step+basic_fused": k}[base]
-        return extra_bpp + (fn(la_mode, gdt, k, pos, int(fused)) if la_name != "none" else fn(0, gdt, k, 1, 0))
+        saved = N.novak_bytes_per_param_moment_saving(info.moment_dtype, int(name.startswith("scaled_")))
+        return extra_bpp - saved + (fn(la_mode, gdt, k, pos, int(fused)) if la_name != "none" else fn(0, gdt, k, 1, 0))
 
     kernels = {}
     for name, ms in per.items():
@@ -244,7 +249,7 @@ def main():
                    "nesterov": nest_name, "lookahead": la_name, "la_k": k, "sync": "fused" if fused else "separate",
                    "mode": hyper["mode"], "rectified": bool(hyper["rectified"]),
                    "layer_adaptation": bool(info.layer_adaptation), "auto_lr": bool(info.auto_lr),
-                   "use_gc": bool(info.use_gc), "clip_threshold": args.clip, "sparse_threshold": args.sparse,
+                   "use_gc": bool(info.use_gc), "moment_dtype": args.moment_dtype, "clip_threshold": args.clip, "sparse_threshold": args.sparse,
                    "chunk_elems": int(info.chunk_elems), "chunks": int(info.n_chunks)},
         "roofline": roofline,
         "kernels": kernels,

@@ -55,6 +55,11 @@ enum { NOVAK_UNRECT_ADAM_DENOM = 0, NOVAK_UNRECT_SGDM = 1 };
 /* Dual-mode control of section 7.1: FAST is the paper's fast path, RESEARCH its full-features mode. */
 enum { NOVAK_MODE_FAST = 0, NOVAK_MODE_RESEARCH = 1 };
 enum { NOVAK_GRAD_F32 = 0, NOVAK_GRAD_BF16 = 1 };
+/* Storage of the first moment.  BF16_M (the paper's "multi-precision" outlook, not part of its method):
+ * exp_avg is an array of bfloat16, rounded to nearest-even once per step from the fp32 value of Eq. 1;
+ * the rounded value is the m_t the rest of the step uses.  exp_avg_sq stays fp32 (with beta2 = 0.999 its
+ * per-step change is below half a bfloat16 ulp and a rounded v would stop moving). */
+enum { NOVAK_MOMENT_F32 = 0, NOVAK_MOMENT_BF16_M = 1 };
 
 /* warning bits reported by novak_validate_hparams / novak_get_info (section 7.3: downgrades warn) */
 enum {
@@ -108,6 +113,8 @@ typedef struct novak_hparams {
   double beta_tau1, beta_tau2; /* tau_1, tau_2 of Eq. 3-4 (> 0 when adaptive_beta); the paper uses 1000 and 5000 */
   int64_t n_taylor;         /* TRUE Nesterov behaves as APPROX for steps t > n_taylor (sections 4.4, 5.8: 100-200);
                                0 = never; ignored for the other modes */
+  int32_t moment_dtype;     /* NOVAK_MOMENT_*: element type of every tensor's exp_avg array */
+  int32_t reserved0;        /* must be 0 */
 } novak_hparams;
 
 /* One parameter tensor.  All pointers are DEVICE pointers to contiguous fp32 arrays of `numel`
@@ -122,7 +129,7 @@ typedef struct novak_hparams {
  *     BASIC: the slow weights theta^slow. */
 typedef struct novak_tensor_desc {
   void *param;       /* theta, updated in place   */
-  void *exp_avg;     /* m, updated in place       */
+  void *exp_avg;     /* m, updated in place (fp32; bfloat16, 2-byte aligned, with NOVAK_MOMENT_BF16_M) */
   void *exp_avg_sq;  /* v, updated in place       */
   void *la_buf;      /* see above; may be NULL when lookahead is NONE */
   int64_t numel;
@@ -167,6 +174,8 @@ typedef struct novak_info {
   int32_t auto_lr;           /* effective */
   int32_t use_gc;            /* effective */
   int32_t n_centralized;     /* tensors that are centralized (use_gc on and rows >= 1) */
+  int32_t moment_dtype;      /* NOVAK_MOMENT_* */
+  int32_t reserved0;
 } novak_info;
 
 /* tuning keys for novak_set_tuning */
@@ -209,6 +218,9 @@ double novak_bytes_per_param_step(int32_t lookahead_mode, int32_t grad_dtype, in
  * partials (16 bytes per 256 elements, written and read once) are not counted. */
 double novak_bytes_per_param_scaled_step(int32_t lookahead_mode, int32_t grad_dtype, int32_t la_k,
                                          int32_t window_pos, int32_t fused_sync);
+/* Bytes per parameter that NOVAK_MOMENT_BF16_M removes from a step: 4 single-pass (m read and written
+ * at 2 bytes instead of 4), 6 two-pass (m is read twice). */
+double novak_bytes_per_param_moment_saving(int32_t moment_dtype, int32_t two_pass);
 /* Algorithmic bytes per parameter of the clipping pre-pass (one read of the gradients). */
 double novak_bytes_per_param_clip(int32_t grad_dtype);
 /* Algorithmic bytes per parameter of the separate sync kernel. */

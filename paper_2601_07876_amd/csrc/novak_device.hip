@@ -253,30 +253,38 @@ void launch_step_block(const novak_handle *h, int grad_dtype, int la, hipStream_
   }
 }
 
-template <typename GradS, typename GradV, bool NT>
-void launch_step_gc(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
-  const Geometry gm = geometry_of(h, 256, 64, step_streams16(grad_dtype, la));
+// Centralization and the bfloat16 first moment are compiled into the default launch shape only
+// (one wave64 per 256 elements).
+template <typename GradS, typename GradV, bool NT, bool GC, typename MomS, typename MomV>
+void launch_step_special(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+  const Geometry gm = geometry_of(h, 256, 64, step_streams16(grad_dtype, la) - (sizeof(MomS) == 2 ? 1.0 : 0.0));
   const dim3 grid(gm.grid), block(64);
   switch (la) {
-    case LA_OFF: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_OFF, NT, 1, 64, true>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
-    case LA_FIRST: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_FIRST, NT, 1, 64, true>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
-    case LA_MID: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_MID, NT, 1, 64, true>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
-    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_LAST_FUSED, NT, 1, 64, true>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
-    default: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_BASIC_FUSED, NT, 1, 64, true>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_OFF: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_OFF, NT, 1, 64, GC, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_FIRST: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_FIRST, NT, 1, 64, GC, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_MID: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_MID, NT, 1, 64, GC, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_LAST_FUSED, NT, 1, 64, GC, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    default: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_BASIC_FUSED, NT, 1, 64, GC, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+  }
+}
+
+template <bool GC, typename MomS, typename MomV>
+void launch_step_special_dtype(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+  if (grad_dtype == NOVAK_GRAD_BF16) {
+    if (h->nontemporal) launch_step_special<unsigned short, u16x4, true, GC, MomS, MomV>(h, grad_dtype, la, s, tb, c);
+    else launch_step_special<unsigned short, u16x4, false, GC, MomS, MomV>(h, grad_dtype, la, s, tb, c);
+  } else {
+    if (h->nontemporal) launch_step_special<float, f32x4, true, GC, MomS, MomV>(h, grad_dtype, la, s, tb, c);
+    else launch_step_special<float, f32x4, false, GC, MomS, MomV>(h, grad_dtype, la, s, tb, c);
   }
 }
 
 void launch_step(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
-  if (c.flags & F_GC) {   // centralization is compiled into the default launch shape only
-    if (grad_dtype == NOVAK_GRAD_BF16) {
-      if (h->nontemporal) launch_step_gc<unsigned short, u16x4, true>(h, grad_dtype, la, s, tb, c);
-      else launch_step_gc<unsigned short, u16x4, false>(h, grad_dtype, la, s, tb, c);
-    } else {
-      if (h->nontemporal) launch_step_gc<float, f32x4, true>(h, grad_dtype, la, s, tb, c);
-      else launch_step_gc<float, f32x4, false>(h, grad_dtype, la, s, tb, c);
-    }
-    return;
-  }
+  const bool gc = (c.flags & F_GC) != 0;
+  const bool bf16_m = h->hp.moment_dtype == NOVAK_MOMENT_BF16_M;
+  if (gc && bf16_m) return launch_step_special_dtype<true, unsigned short, u16x4>(h, grad_dtype, la, s, tb, c);
+  if (bf16_m) return launch_step_special_dtype<false, unsigned short, u16x4>(h, grad_dtype, la, s, tb, c);
+  if (gc) return launch_step_special_dtype<true, float, f32x4>(h, grad_dtype, la, s, tb, c);
   if (h->nontemporal) launch_step_block<true>(h, grad_dtype, la, s, tb, c);
   else launch_step_block<false>(h, grad_dtype, la, s, tb, c);
 }
@@ -307,15 +315,28 @@ void launch_la(const novak_handle *h, hipStream_t s, const Tables &tb, float c0,
   }
 }
 
-template <bool NT>
+template <bool NT, typename MomS, typename MomV>
 void launch_apply(int la, const Geometry &gm, hipStream_t s, const Tables &tb, const Consts &c, const float *scale) {
   const dim3 grid(gm.grid), block(kScaledBlock);
   switch (la) {
-    case LA_OFF: hipLaunchKernelGGL((novak_apply_kernel<LA_OFF, NT>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
-    case LA_FIRST: hipLaunchKernelGGL((novak_apply_kernel<LA_FIRST, NT>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
-    case LA_MID: hipLaunchKernelGGL((novak_apply_kernel<LA_MID, NT>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
-    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_apply_kernel<LA_LAST_FUSED, NT>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
-    default: hipLaunchKernelGGL((novak_apply_kernel<LA_BASIC_FUSED, NT>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
+    case LA_OFF: hipLaunchKernelGGL((novak_apply_kernel<LA_OFF, NT, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
+    case LA_FIRST: hipLaunchKernelGGL((novak_apply_kernel<LA_FIRST, NT, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
+    case LA_MID: hipLaunchKernelGGL((novak_apply_kernel<LA_MID, NT, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
+    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_apply_kernel<LA_LAST_FUSED, NT, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
+    default: hipLaunchKernelGGL((novak_apply_kernel<LA_BASIC_FUSED, NT, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift, scale); break;
+  }
+}
+
+template <typename MomS, typename MomV>
+void launch_moments(const novak_handle *h, int grad_dtype, const Geometry &g1, hipStream_t s, const Tables &tb, const Consts &c) {
+  const dim3 grid1(g1.grid), block(kScaledBlock);
+  const bool nt = h->nontemporal != 0;
+  if (grad_dtype == NOVAK_GRAD_BF16) {
+    if (nt) hipLaunchKernelGGL((novak_moments_kernel<unsigned short, u16x4, true, MomS, MomV>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
+    else hipLaunchKernelGGL((novak_moments_kernel<unsigned short, u16x4, false, MomS, MomV>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
+  } else {
+    if (nt) hipLaunchKernelGGL((novak_moments_kernel<float, f32x4, true, MomS, MomV>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
+    else hipLaunchKernelGGL((novak_moments_kernel<float, f32x4, false, MomS, MomV>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
   }
 }
 
@@ -347,16 +368,11 @@ int launch_clip_prepass(novak_handle *h, int grad_dtype, hipStream_t s, const Ta
 int launch_scaled_step(novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
   const novak_hparams &hp = h->hp;
   const double g16 = grad_dtype == NOVAK_GRAD_BF16 ? 0.5 : 1.0;
-  const Geometry g1 = geometry_of(h, kScaledSub, kScaledBlock, 3.0 + g16 + 2.0);
-  const dim3 grid1(g1.grid), block(kScaledBlock);
+  const bool bf16_m = hp.moment_dtype == NOVAK_MOMENT_BF16_M;
+  const Geometry g1 = geometry_of(h, kScaledSub, kScaledBlock, 3.0 + g16 + 2.0 - (bf16_m ? 1.0 : 0.0));
   const bool nt = h->nontemporal != 0;
-  if (grad_dtype == NOVAK_GRAD_BF16) {
-    if (nt) hipLaunchKernelGGL((novak_moments_kernel<unsigned short, u16x4, true>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
-    else hipLaunchKernelGGL((novak_moments_kernel<unsigned short, u16x4, false>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
-  } else {
-    if (nt) hipLaunchKernelGGL((novak_moments_kernel<float, f32x4, true>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
-    else hipLaunchKernelGGL((novak_moments_kernel<float, f32x4, false>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
-  }
+  if (bf16_m) launch_moments<unsigned short, u16x4>(h, grad_dtype, g1, s, tb, c);
+  else launch_moments<float, f32x4>(h, grad_dtype, g1, s, tb, c);
   NOVAK_HIP(h, hipGetLastError());
   ScaleParams sp;
   sp.trust_lo = static_cast<float>(hp.trust_clip_lo);
@@ -374,12 +390,17 @@ int launch_scaled_step(novak_handle *h, int grad_dtype, int la, hipStream_t s, c
   if (hp.auto_lr)
     hipLaunchKernelGGL(novak_auto_lr_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, h->d_scale, h->d_ema, sp);
   NOVAK_HIP(h, hipGetLastError());
-  double s2 = 3.0 + 1.0;   // theta, m, v read; theta written
+  double s2 = 3.0 + 1.0 - (bf16_m ? 0.5 : 0.0);   // theta, m, v read; theta written
   if (la_reads(la)) s2 += 1.0;
   if (la_writes(la)) s2 += 1.0;
   const Geometry g2 = geometry_of(h, kScaledSub, kScaledBlock, s2);
-  if (nt) launch_apply<true>(la, g2, s, tb, c, h->d_scale);
-  else launch_apply<false>(la, g2, s, tb, c, h->d_scale);
+  if (bf16_m) {
+    if (nt) launch_apply<true, unsigned short, u16x4>(la, g2, s, tb, c, h->d_scale);
+    else launch_apply<false, unsigned short, u16x4>(la, g2, s, tb, c, h->d_scale);
+  } else {
+    if (nt) launch_apply<true, float, f32x4>(la, g2, s, tb, c, h->d_scale);
+    else launch_apply<false, float, f32x4>(la, g2, s, tb, c, h->d_scale);
+  }
   NOVAK_HIP(h, hipGetLastError());
   return NOVAK_OK;
 }
@@ -423,9 +444,10 @@ int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor
     if (d.numel == 0) continue;
     if (!d.param || !d.exp_avg || !d.exp_avg_sq) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "tensor " + std::to_string(i) + ": param/exp_avg/exp_avg_sq is NULL");
     if (eff.lookahead_mode != NOVAK_LOOKAHEAD_NONE && !d.la_buf) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "tensor " + std::to_string(i) + ": la_buf is NULL with lookahead on");
-    const uintptr_t bits = reinterpret_cast<uintptr_t>(d.param) | reinterpret_cast<uintptr_t>(d.exp_avg) |
-                           reinterpret_cast<uintptr_t>(d.exp_avg_sq) | reinterpret_cast<uintptr_t>(d.la_buf);
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(d.param) | reinterpret_cast<uintptr_t>(d.exp_avg_sq) | reinterpret_cast<uintptr_t>(d.la_buf);
     if (bits & 3u) return fail(nullptr, NOVAK_ERR_MISALIGNED, "tensor " + std::to_string(i) + ": pointer not 4-byte aligned");
+    if (reinterpret_cast<uintptr_t>(d.exp_avg) & (eff.moment_dtype == NOVAK_MOMENT_BF16_M ? 1u : 3u))
+      return fail(nullptr, NOVAK_ERR_MISALIGNED, "tensor " + std::to_string(i) + ": exp_avg not aligned to its element size");
     if (eff.use_gc && (d.rows < 0 || (d.rows > 0 && d.numel % d.rows != 0)))
       return fail(nullptr, NOVAK_ERR_INVALID_ARG, "tensor " + std::to_string(i) + ": rows must be >= 0 and divide numel");
   }
@@ -545,6 +567,7 @@ int novak_get_info(const novak_handle *h, novak_info *info) {
   info->layer_adaptation = h->hp.layer_adaptation;
   info->auto_lr = h->hp.auto_lr;
   info->use_gc = h->hp.use_gc;
+  info->moment_dtype = h->hp.moment_dtype;
   info->n_centralized = h->n_gc;
   return NOVAK_OK;
 }
@@ -566,8 +589,15 @@ int novak_nesterov_extrapolate(novak_handle *h, void *const *out, void *hip_stre
   h->out_host.assign(out, out + n);
   NOVAK_HIP(h, hipMemcpyAsync(h->d_out_ptrs, h->out_host.data(), n * sizeof(float *), hipMemcpyHostToDevice, stream));
   const Geometry gm = geometry_of(h, 256, 64, 3.0);
-  if (h->nontemporal) hipLaunchKernelGGL((novak_extrapolate_kernel<true>), dim3(gm.grid), dim3(64), gm.lds, stream, tables_of(h), h->d_out_ptrs, static_cast<float>(h->hp.beta_n), gm.sub_shift);
-  else hipLaunchKernelGGL((novak_extrapolate_kernel<false>), dim3(gm.grid), dim3(64), gm.lds, stream, tables_of(h), h->d_out_ptrs, static_cast<float>(h->hp.beta_n), gm.sub_shift);
+  const float bn = static_cast<float>(h->hp.beta_n);
+  const dim3 grid(gm.grid), block(64);
+  if (h->hp.moment_dtype == NOVAK_MOMENT_BF16_M) {
+    if (h->nontemporal) hipLaunchKernelGGL((novak_extrapolate_kernel<true, unsigned short, u16x4>), grid, block, gm.lds, stream, tables_of(h), h->d_out_ptrs, bn, gm.sub_shift);
+    else hipLaunchKernelGGL((novak_extrapolate_kernel<false, unsigned short, u16x4>), grid, block, gm.lds, stream, tables_of(h), h->d_out_ptrs, bn, gm.sub_shift);
+  } else {
+    if (h->nontemporal) hipLaunchKernelGGL((novak_extrapolate_kernel<true, float, f32x4>), grid, block, gm.lds, stream, tables_of(h), h->d_out_ptrs, bn, gm.sub_shift);
+    else hipLaunchKernelGGL((novak_extrapolate_kernel<false, float, f32x4>), grid, block, gm.lds, stream, tables_of(h), h->d_out_ptrs, bn, gm.sub_shift);
+  }
   NOVAK_HIP(h, hipGetLastError());
   return NOVAK_OK;
 }

@@ -67,6 +67,8 @@ int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, ui
   if (!(hp->clip_threshold >= 0.0) || !(hp->sparse_threshold >= 0.0)) return NOVAK_ERR_INVALID_ARG;
   if (hp->adaptive_beta && !(hp->beta_tau1 > 0.0 && hp->beta_tau2 > 0.0)) return NOVAK_ERR_INVALID_ARG;
   if (hp->n_taylor < 0) return NOVAK_ERR_INVALID_ARG;
+  if (hp->moment_dtype != NOVAK_MOMENT_F32 && hp->moment_dtype != NOVAK_MOMENT_BF16_M) return NOVAK_ERR_INVALID_ARG;
+  if (hp->reserved0 != 0) return NOVAK_ERR_INVALID_ARG;
   if (hp->layer_adaptation && !(hp->trust_clip_lo > 0.0 && hp->trust_clip_lo <= hp->trust_clip_hi)) return NOVAK_ERR_INVALID_ARG;
   if (hp->auto_lr) {
     if (!(hp->auto_lr_gamma > 0.0 && hp->auto_lr_gamma <= 1.0)) return NOVAK_ERR_INVALID_ARG;
@@ -193,6 +195,11 @@ double novak_bytes_per_param_scaled_step(int32_t lookahead_mode, int32_t grad_dt
                                          int32_t fused_sync) {
   // the single-pass figure plus pass 2 reading theta, m, v again
   return novak_bytes_per_param_step(lookahead_mode, grad_dtype, la_k, window_pos, fused_sync) + 12;
+}
+
+double novak_bytes_per_param_moment_saving(int32_t moment_dtype, int32_t two_pass) {
+  if (moment_dtype != NOVAK_MOMENT_BF16_M) return 0;
+  return two_pass ? 6 : 4;
 }
 
 double novak_bytes_per_param_clip(int32_t grad_dtype) { return grad_dtype == NOVAK_GRAD_BF16 ? 2 : 4; }

@@ -113,6 +113,54 @@ struct Consts {
 
 __device__ __forceinline__ float bf16_to_f32(unsigned short b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 
+// fp32 -> bfloat16, round to nearest even; NaN stays NaN (quiet), infinities stay
+__device__ __forceinline__ unsigned short f32_to_bf16(float x) {
+  uint32_t b = __float_as_uint(x);
+  if ((b & 0x7fffffffu) > 0x7f800000u) return static_cast<unsigned short>((b >> 16) | 0x40u);
+  b += 0x7fffu + ((b >> 16) & 1u);
+  return static_cast<unsigned short>(b >> 16);
+}
+
+// The first moment as stored: fp32, or bfloat16 (rounded once per step from the fp32 value of Eq. 1).
+// store_m returns what was stored, which is the m_t the rest of the step uses.
+template <typename MomV>
+__device__ __forceinline__ f32x4 mom_to_f32(MomV m);
+template <>
+__device__ __forceinline__ f32x4 mom_to_f32<f32x4>(f32x4 m) { return m; }
+template <>
+__device__ __forceinline__ f32x4 mom_to_f32<u16x4>(u16x4 m) {
+  f32x4 r;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) r[k] = bf16_to_f32(m[k]);
+  return r;
+}
+template <typename MomS>
+__device__ __forceinline__ float round_mom(float m) {
+  if constexpr (sizeof(MomS) == 2) return bf16_to_f32(f32_to_bf16(m));
+  else return m;
+}
+template <typename MomV>
+__device__ __forceinline__ MomV f32_to_mom(f32x4 m);
+template <>
+__device__ __forceinline__ f32x4 f32_to_mom<f32x4>(f32x4 m) { return m; }
+template <>
+__device__ __forceinline__ u16x4 f32_to_mom<u16x4>(f32x4 m) {
+  u16x4 r;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) r[k] = f32_to_bf16(m[k]);
+  return r;
+}
+template <typename MomS>
+__device__ __forceinline__ float load_mom(const MomS *p) {
+  if constexpr (sizeof(MomS) == 2) return bf16_to_f32(*p);
+  else return *p;
+}
+template <typename MomS>
+__device__ __forceinline__ void store_mom(MomS *p, float m) {
+  if constexpr (sizeof(MomS) == 2) *p = f32_to_bf16(m);
+  else *p = m;
+}
+
 // The update of one element, in three parts so that the two-pass (per-tensor scaled) path can reuse
 // the exact arithmetic of the fused one.
 //   moments():   Phases 2 and 4 - gradient processing and the two EMAs (Eq. 13, 1, 2)
@@ -158,9 +206,10 @@ __device__ __forceinline__ void apply(float &th, float u, float m_hat, float &la
   }
 }
 
-template <int LA>
+template <int LA, typename MomS = float>
 __device__ __forceinline__ void update_one(float &th, float g, float &m, float &v, float &la, const Consts &c, float gs) {
   moments(th, g, m, v, c, gs);
+  m = round_mom<MomS>(m);          // the stored m_t is what the rest of the step uses
   float m_hat;
   const float u = direction(m, v, c, m_hat);
   apply<LA>(th, u, m_hat, la, c, c.step_size);
@@ -189,12 +238,12 @@ __device__ __forceinline__ f32x4 grad_to_f32<u16x4>(u16x4 g) {
   return r;
 }
 
-template <int LA>
+template <int LA, typename MomS = float>
 __device__ __forceinline__ void update_vec(f32x4 &th, f32x4 g, f32x4 &m, f32x4 &v, f32x4 &la, const Consts &c, float gs) {
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     float th_k = th[k], m_k = m[k], v_k = v[k], la_k = la[k];
-    update_one<LA>(th_k, g[k], m_k, v_k, la_k, c, gs);
+    update_one<LA, MomS>(th_k, g[k], m_k, v_k, la_k, c, gs);
     th[k] = th_k; m[k] = m_k; v[k] = v_k; la[k] = la_k;
   }
 }
@@ -213,7 +262,10 @@ constexpr bool la_writes(int la) { return la == LA_FIRST || la == LA_MID || la =
 // GradS: scalar gradient type (float, or unsigned short holding bf16 bits); GradV its 4-vector.
 // GC: compiled-in gradient centralization (Eq. 26) for tensors that ask for it (only instantiated for
 // the default shape UN = 1, BLOCK = 64).
-template <typename GradS, typename GradV, int LA, bool NT, int UN, int BLOCK, bool GC = false>
+// MomS / MomV: storage type of the first moment and its 4-vector (float / f32x4, or unsigned short /
+// u16x4 for bfloat16; the latter also only for UN = 1, BLOCK = 64).
+template <typename GradS, typename GradV, int LA, bool NT, int UN, int BLOCK, bool GC = false, typename MomS = float,
+          typename MomV = f32x4>
 __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, int sub_shift) {
   constexpr int SUB = BLOCK * 4 * UN;
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
@@ -228,26 +280,27 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
   gi.cols = 0;
   if (GC) gi = tb.gc[ch.tensor];
   float *__restrict__ th_p = tp.param + off;
-  float *__restrict__ m_p = tp.m + off;
+  MomS *__restrict__ m_p = reinterpret_cast<MomS *>(tp.m) + off;
   float *__restrict__ v_p = tp.v + off;
   const GradS *__restrict__ g_p = static_cast<const GradS *>(g_base) + off;
   float *__restrict__ la_p = nullptr;
   if (LA != LA_OFF) la_p = tp.la + off;
 
-  uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) |
-                   reinterpret_cast<uintptr_t>(v_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
+  uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(v_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
   mis |= reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1);
+  mis |= reinterpret_cast<uintptr_t>(m_p) & (sizeof(MomV) - 1);
 
   int done = 0;   // elements [0, done) handled by the 128-bit path
   if (mis == 0) {
     f32x4 *th4 = reinterpret_cast<f32x4 *>(th_p);
-    f32x4 *m4 = reinterpret_cast<f32x4 *>(m_p);
+    MomV *m4 = reinterpret_cast<MomV *>(m_p);
     f32x4 *v4 = reinterpret_cast<f32x4 *>(v_p);
     f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
     const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
     if (n == SUB) {
       // full sub-block: every load is issued before any arithmetic
-      f32x4 th[UN], m[UN], v[UN], la[UN];
+      f32x4 th[UN], v[UN], la[UN];
+      MomV m[UN];
       GradV g[UN];
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
@@ -263,9 +316,10 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
         const int j = threadIdx.x + u * BLOCK;
         f32x4 gf = grad_to_f32<GradV>(g[u]);
         if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(j), gi);
-        update_vec<LA>(th[u], gf, m[u], v[u], la[u], c, gs);
+        f32x4 mf = mom_to_f32<MomV>(m[u]);
+        update_vec<LA, MomS>(th[u], gf, mf, v[u], la[u], c, gs);
         st<NT>(th4 + j, th[u]);
-        st<NT>(m4 + j, m[u]);
+        st<NT>(m4 + j, f32_to_mom<MomV>(mf));
         st<NT>(v4 + j, v[u]);
         if (la_writes(LA)) st<NT>(la4 + j, la[u]);
       }
@@ -273,14 +327,14 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
     }
     const int nvec = n >> 2;
     for (int i = threadIdx.x; i < nvec; i += BLOCK) {
-      f32x4 th = ld<NT>(th4 + i), m = ld<NT>(m4 + i), v = ld<NT>(v4 + i), la;
+      f32x4 th = ld<NT>(th4 + i), m = mom_to_f32<MomV>(ld<NT>(m4 + i)), v = ld<NT>(v4 + i), la;
       GradV g = ld<NT>(g4 + i);
       if (la_reads(LA)) la = ld<NT>(la4 + i);
       f32x4 gf = grad_to_f32<GradV>(g);
       if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(i), gi);
-      update_vec<LA>(th, gf, m, v, la, c, gs);
+      update_vec<LA, MomS>(th, gf, m, v, la, c, gs);
       st<NT>(th4 + i, th);
-      st<NT>(m4 + i, m);
+      st<NT>(m4 + i, f32_to_mom<MomV>(m));
       st<NT>(v4 + i, v);
       if (la_writes(LA)) st<NT>(la4 + i, la);
     }
@@ -288,14 +342,14 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
   }
   // element-wise path: the < 4 element tail of an aligned sub-block, or a whole unaligned one
   for (int i = done + threadIdx.x; i < n; i += BLOCK) {
-    float th = th_p[i], m = m_p[i], v = v_p[i], la = 0.0f, g;
+    float th = th_p[i], m = load_mom<MomS>(m_p + i), v = v_p[i], la = 0.0f, g;
     if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
     else g = g_p[i];
     if (la_reads(LA)) la = la_p[i];
     if (GC && gi.cols) g = centralize_one(g, off + i, gi);
-    update_one<LA>(th, g, m, v, la, c, gs);
+    update_one<LA, MomS>(th, g, m, v, la, c, gs);
     th_p[i] = th;
-    m_p[i] = m;
+    store_mom<MomS>(m_p + i, m);
     v_p[i] = v;
     if (la_writes(LA)) la_p[i] = la;
   }
@@ -357,7 +411,7 @@ __global__ __launch_bounds__(BLOCK) void novak_lookahead_kernel(Tables tb, float
 }
 
 // True Nesterov, Eq. 10: out <- theta + beta_n * m over the chunk table (one wave per 256 elements).
-template <bool NT>
+template <bool NT, typename MomS = float, typename MomV = f32x4>
 __global__ __launch_bounds__(64) void novak_extrapolate_kernel(Tables tb, float *const *out, float beta_n, int sub_shift) {
   constexpr int SUB = 64 * 4;
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
@@ -367,15 +421,17 @@ __global__ __launch_bounds__(64) void novak_extrapolate_kernel(Tables tb, float 
   const int64_t off = ch.offset + start;
   const TensorPtrs tp = tb.tensors[ch.tensor];
   const float *__restrict__ th_p = tp.param + off;
-  const float *__restrict__ m_p = tp.m + off;
+  const MomS *__restrict__ m_p = reinterpret_cast<const MomS *>(tp.m) + off;
   float *__restrict__ o_p = out[ch.tensor] + off;
-  const uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) | reinterpret_cast<uintptr_t>(o_p)) & 15u;
+  const uintptr_t mis = ((reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(o_p)) & 15u) |
+                        (reinterpret_cast<uintptr_t>(m_p) & (sizeof(MomV) - 1));
   int done = 0;
   if (mis == 0) {
     const int nvec = n >> 2;
     const int i = threadIdx.x;
     if (i < nvec) {
-      const f32x4 th = ld<NT>(reinterpret_cast<const f32x4 *>(th_p) + i), m = ld<NT>(reinterpret_cast<const f32x4 *>(m_p) + i);
+      const f32x4 th = ld<NT>(reinterpret_cast<const f32x4 *>(th_p) + i),
+                  m = mom_to_f32<MomV>(ld<NT>(reinterpret_cast<const MomV *>(m_p) + i));
       f32x4 o;
 #pragma unroll
       for (int k = 0; k < 4; ++k) o[k] = __builtin_fmaf(beta_n, m[k], th[k]);
@@ -383,7 +439,7 @@ __global__ __launch_bounds__(64) void novak_extrapolate_kernel(Tables tb, float 
     }
     done = nvec << 2;
   }
-  for (int i = done + threadIdx.x; i < n; i += 64) o_p[i] = __builtin_fmaf(beta_n, m_p[i], th_p[i]);
+  for (int i = done + threadIdx.x; i < n; i += 64) o_p[i] = __builtin_fmaf(beta_n, load_mom<MomS>(m_p + i), th_p[i]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -417,7 +473,7 @@ __device__ __forceinline__ double wave_sum(double x) {
   return x;
 }
 
-template <typename GradS, typename GradV, bool NT>
+template <typename GradS, typename GradV, bool NT, typename MomS = float, typename MomV = f32x4>
 __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, Consts c, int sub_shift, NormPartial *partials) {
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
   const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kScaledSub;
@@ -431,26 +487,27 @@ __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, 
   gi.cols = 0;
   if (c.flags & F_GC) gi = tb.gc[ch.tensor];
   const float *__restrict__ th_p = tp.param + off;
-  float *__restrict__ m_p = tp.m + off;
+  MomS *__restrict__ m_p = reinterpret_cast<MomS *>(tp.m) + off;
   float *__restrict__ v_p = tp.v + off;
   const GradS *__restrict__ g_p = static_cast<const GradS *>(g_base) + off;
 
-  uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) | reinterpret_cast<uintptr_t>(v_p)) & 15u;
+  uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(v_p)) & 15u;
   mis |= reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1);
+  mis |= reinterpret_cast<uintptr_t>(m_p) & (sizeof(MomV) - 1);
 
   float s_th = 0.0f, s_u = 0.0f, s_g = 0.0f;
   int done = 0;
   if (mis == 0) {
     const int nvec = n >> 2;
     const f32x4 *th4 = reinterpret_cast<const f32x4 *>(th_p);
-    f32x4 *m4 = reinterpret_cast<f32x4 *>(m_p);
+    MomV *m4 = reinterpret_cast<MomV *>(m_p);
     f32x4 *v4 = reinterpret_cast<f32x4 *>(v_p);
     const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
     const int i = threadIdx.x;
     if (i < nvec) {
       const f32x4 th = ld<NT>(th4 + i);
       f32x4 g = grad_to_f32<GradV>(ld<NT>(g4 + i));
-      f32x4 m = ld<NT>(m4 + i), v = ld<NT>(v4 + i);
+      f32x4 m = mom_to_f32<MomV>(ld<NT>(m4 + i)), v = ld<NT>(v4 + i);
 #pragma unroll
       for (int k = 0; k < 4; ++k) s_g = __builtin_fmaf(g[k], g[k], s_g);     // norm of the gradient as handed in
       if (gi.cols) centralize(g, 4, off + 4 * static_cast<int64_t>(i), gi);
@@ -458,28 +515,30 @@ __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, 
       for (int k = 0; k < 4; ++k) {
         float m_k = m[k], v_k = v[k], m_hat;
         moments(th[k], g[k], m_k, v_k, c, gs);
+        m_k = round_mom<MomS>(m_k);
         const float u = direction(m_k, v_k, c, m_hat);
         s_th = __builtin_fmaf(th[k], th[k], s_th);
         s_u = __builtin_fmaf(u, u, s_u);
         m[k] = m_k; v[k] = v_k;
       }
-      st<NT>(m4 + i, m);
+      st<NT>(m4 + i, f32_to_mom<MomV>(m));
       st<NT>(v4 + i, v);
     }
     done = nvec << 2;
   }
   for (int i = done + threadIdx.x; i < n; i += kScaledBlock) {
     const float th = th_p[i];
-    float m = m_p[i], v = v_p[i], g, m_hat;
+    float m = load_mom<MomS>(m_p + i), v = v_p[i], g, m_hat;
     if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
     else g = g_p[i];
     s_g = __builtin_fmaf(g, g, s_g);
     if (gi.cols) g = centralize_one(g, off + i, gi);
     moments(th, g, m, v, c, gs);
+    m = round_mom<MomS>(m);
     const float u = direction(m, v, c, m_hat);
     s_th = __builtin_fmaf(th, th, s_th);
     s_u = __builtin_fmaf(u, u, s_u);
-    m_p[i] = m;
+    store_mom<MomS>(m_p + i, m);
     v_p[i] = v;
   }
   s_th = wave_sum(s_th);
@@ -682,7 +741,7 @@ __global__ __launch_bounds__(64) void novak_auto_lr_kernel(int n_tensors, const 
   }
 }
 
-template <int LA, bool NT>
+template <int LA, bool NT, typename MomS = float, typename MomV = f32x4>
 __global__ __launch_bounds__(kScaledBlock) void novak_apply_kernel(Tables tb, Consts c, int sub_shift, const float *scale) {
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
   const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kScaledSub;
@@ -692,23 +751,23 @@ __global__ __launch_bounds__(kScaledBlock) void novak_apply_kernel(Tables tb, Co
   const TensorPtrs tp = tb.tensors[ch.tensor];
   const float step = c.step_size * scale[ch.tensor];                    // Eq. 24a
   float *__restrict__ th_p = tp.param + off;
-  const float *__restrict__ m_p = tp.m + off;
+  const MomS *__restrict__ m_p = reinterpret_cast<const MomS *>(tp.m) + off;
   const float *__restrict__ v_p = tp.v + off;
   float *__restrict__ la_p = nullptr;
   if (LA != LA_OFF) la_p = tp.la + off;
-  const uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(m_p) |
-                         reinterpret_cast<uintptr_t>(v_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
+  const uintptr_t mis = ((reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(v_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u) |
+                        (reinterpret_cast<uintptr_t>(m_p) & (sizeof(MomV) - 1));
   int done = 0;
   if (mis == 0) {
     const int nvec = n >> 2;
     f32x4 *th4 = reinterpret_cast<f32x4 *>(th_p);
-    const f32x4 *m4 = reinterpret_cast<const f32x4 *>(m_p);
+    const MomV *m4 = reinterpret_cast<const MomV *>(m_p);
     const f32x4 *v4 = reinterpret_cast<const f32x4 *>(v_p);
     f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
     const int i = threadIdx.x;
     if (i < nvec) {
       f32x4 th = ld<NT>(th4 + i), la;
-      const f32x4 m = ld<NT>(m4 + i), v = ld<NT>(v4 + i);
+      const f32x4 m = mom_to_f32<MomV>(ld<NT>(m4 + i)), v = ld<NT>(v4 + i);
       if (la_reads(LA)) la = ld<NT>(la4 + i);
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
@@ -725,7 +784,7 @@ __global__ __launch_bounds__(kScaledBlock) void novak_apply_kernel(Tables tb, Co
   for (int i = done + threadIdx.x; i < n; i += kScaledBlock) {
     float th = th_p[i], la = 0.0f, m_hat;
     if (la_reads(LA)) la = la_p[i];
-    const float u = direction(m_p[i], v_p[i], c, m_hat);
+    const float u = direction(load_mom<MomS>(m_p + i), v_p[i], c, m_hat);
     apply<LA>(th, u, m_hat, la, c, step);
     th_p[i] = th;
     if (la_writes(LA)) la_p[i] = la;

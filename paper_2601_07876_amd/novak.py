@@ -22,6 +22,7 @@ NOVAK_LOOKAHEAD_NONE, NOVAK_LOOKAHEAD_MEMORY_EFFICIENT, NOVAK_LOOKAHEAD_BASIC = 
 NOVAK_UNRECT_ADAM_DENOM, NOVAK_UNRECT_SGDM = 0, 1
 NOVAK_MODE_FAST, NOVAK_MODE_RESEARCH = 0, 1
 NOVAK_GRAD_F32, NOVAK_GRAD_BF16 = 0, 1
+NOVAK_MOMENT_F32, NOVAK_MOMENT_BF16_M = 0, 1
 NOVAK_WARN_TRUE_NESTEROV_DOWNGRADED, NOVAK_WARN_LOOKAHEAD_DOWNGRADED = 1, 2
 NOVAK_WARN_LAYER_ADAPTATION_DISABLED, NOVAK_WARN_AUTO_LR_DISABLED, NOVAK_WARN_GC_DISABLED = 4, 8, 16
 NOVAK_TUNE_CHUNK_ELEMS, NOVAK_TUNE_NONTEMPORAL, NOVAK_TUNE_VEC_PER_LANE, NOVAK_TUNE_THREADS, NOVAK_TUNE_WAVES_PER_CU = 0, 1, 2, 3, 4
@@ -31,6 +32,7 @@ LOOKAHEAD = {"none": 0, "memory_efficient": 1, "basic": 2}
 UNRECT = {"adam_denom": 0, "sgdm": 1}
 MODE = {"fast": 0, "research": 1}
 GRAD_DTYPE = {"f32": 0, "bf16": 1}
+MOMENT_DTYPE = {"f32": 0, "bf16_m": 1}
 
 
 class novak_hparams(C.Structure):
@@ -45,7 +47,8 @@ class novak_hparams(C.Structure):
                 ("auto_clip_lo", C.c_double), ("auto_clip_hi", C.c_double),
                 ("clip_threshold", C.c_double), ("sparse_threshold", C.c_double),
                 ("use_gc", C.c_int32), ("adaptive_beta", C.c_int32),
-                ("beta_tau1", C.c_double), ("beta_tau2", C.c_double), ("n_taylor", C.c_int64)]
+                ("beta_tau1", C.c_double), ("beta_tau2", C.c_double), ("n_taylor", C.c_int64),
+                ("moment_dtype", C.c_int32), ("reserved0", C.c_int32)]
 
 
 class novak_tensor_desc(C.Structure):
@@ -70,12 +73,12 @@ class novak_info(C.Structure):
                 ("chunk_elems", C.c_int64), ("total_numel", C.c_int64), ("last_step", C.c_int64),
                 ("sync_due", C.c_int32), ("device_id", C.c_int32),
                 ("layer_adaptation", C.c_int32), ("auto_lr", C.c_int32), ("use_gc", C.c_int32),
-                ("n_centralized", C.c_int32)]
+                ("n_centralized", C.c_int32), ("moment_dtype", C.c_int32), ("reserved0", C.c_int32)]
 
 
 EXPORTS = ("novak_validate_hparams", "novak_compute_step_scalars", "novak_plan_chunks",
            "novak_bytes_per_param_step", "novak_bytes_per_param_scaled_step", "novak_bytes_per_param_clip",
-           "novak_bytes_per_param_sync",
+           "novak_bytes_per_param_moment_saving", "novak_bytes_per_param_sync",
            "novak_status_string", "novak_create", "novak_lookahead_init", "novak_step", "novak_lookahead_sync",
            "novak_destroy", "novak_get_info", "novak_set_tuning", "novak_last_error", "novak_set_auto_lr_state",
            "novak_copy_tensor_scales", "novak_nesterov_extrapolate")
@@ -104,6 +107,8 @@ def load_library() -> C.CDLL:
     lib.novak_set_auto_lr_state.argtypes = [vp, vp]
     lib.novak_copy_tensor_scales.argtypes = [vp, C.POINTER(C.c_float), vp]
     lib.novak_nesterov_extrapolate.argtypes = [vp, C.POINTER(vp), vp]
+    lib.novak_bytes_per_param_moment_saving.argtypes = [i32, i32]
+    lib.novak_bytes_per_param_moment_saving.restype = C.c_double
     lib.novak_bytes_per_param_clip.argtypes = [i32]
     lib.novak_bytes_per_param_clip.restype = C.c_double
     lib.novak_bytes_per_param_sync.argtypes = [i32]
@@ -139,7 +144,7 @@ def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, be
                  unrect_fallback="adam_denom", mode="fast", auto_sync=False, layer_adaptation=False, auto_lr=False,
                  auto_lr_gamma=0.1, trust_clip=(0.1, 10.0), auto_clip=(0.1, 2.0), clip_threshold=0.0,
                  sparse_threshold=0.0, use_gc=False, adaptive_beta=False, beta_tau1=1000.0, beta_tau2=5000.0,
-                 n_taylor=0) -> novak_hparams:
+                 n_taylor=0, moment_dtype="f32") -> novak_hparams:
     """Fills a novak_hparams from keyword values (mode names or their integer codes)."""
     def code(table: Dict[str, int], x):
         return table[x] if isinstance(x, str) else int(x)
@@ -148,7 +153,8 @@ def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, be
                          code(UNRECT, unrect_fallback), code(MODE, mode), int(auto_sync), int(layer_adaptation),
                          int(auto_lr), float(auto_lr_gamma), float(trust_clip[0]), float(trust_clip[1]),
                          float(auto_clip[0]), float(auto_clip[1]), float(clip_threshold), float(sparse_threshold),
-                         int(use_gc), int(adaptive_beta), float(beta_tau1), float(beta_tau2), int(n_taylor))
+                         int(use_gc), int(adaptive_beta), float(beta_tau1), float(beta_tau2), int(n_taylor),
+                         code(MOMENT_DTYPE, moment_dtype), 0)
 
 
 # ---- the entry points, same names as the C ABI ------------------------------------------------------
@@ -209,6 +215,10 @@ def novak_nesterov_extrapolate(handle, out_ptrs, stream: int = 0) -> int:
     return load_library().novak_nesterov_extrapolate(handle, out_ptrs, C.c_void_p(stream))
 
 
+def novak_bytes_per_param_moment_saving(moment_dtype: int, two_pass: int) -> float:
+    return load_library().novak_bytes_per_param_moment_saving(moment_dtype, two_pass)
+
+
 def novak_bytes_per_param_clip(grad_dtype: int) -> float:
     return load_library().novak_bytes_per_param_clip(grad_dtype)
 
@@ -265,8 +275,9 @@ def tensor_desc(param, exp_avg, exp_avg_sq, la_buf=None) -> novak_tensor_desc:
     """Descriptor from contiguous fp32 torch tensors that live on the GPU; `rows` (Eq. 26) is the size of
     the parameter's first dimension when it has more than one."""
     for t in (param, exp_avg, exp_avg_sq) + ((la_buf,) if la_buf is not None else ()):
-        if not t.is_contiguous() or str(t.dtype) != "torch.float32" or not t.is_cuda:
-            raise ValueError("state tensors must be contiguous fp32 GPU tensors")
+        ok_dtype = str(t.dtype) == "torch.float32" or (t is exp_avg and str(t.dtype) == "torch.bfloat16")
+        if not t.is_contiguous() or not ok_dtype or not t.is_cuda:
+            raise ValueError("state tensors must be contiguous fp32 GPU tensors (exp_avg may be bfloat16)")
         if t.numel() != param.numel():
             raise ValueError("state tensors must have the parameter's element count")
     return novak_tensor_desc(param.data_ptr(), exp_avg.data_ptr(), exp_avg_sq.data_ptr(),

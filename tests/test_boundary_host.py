@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert C.sizeof(N.novak_hparams) == 8 + 7 * 8 + 10 * 4 + 7 * 8 + 2 * 4 + 3 * 8
+    assert C.sizeof(N.novak_hparams) == 8 + 7 * 8 + 10 * 4 + 7 * 8 + 2 * 4 + 3 * 8 + 2 * 4
     assert C.sizeof(N.novak_tensor_desc) == 48
     assert C.sizeof(N.novak_chunk) == 16
     hp = N.make_hparams()
