@@ -100,7 +100,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the update is elementwise and would shard "
-              "without communication, see DESIGN.md)", file=sys.stderr)
+              "without communication)", file=sys.stderr)
         sys.exit(2)
 
     import torch
