@@ -52,6 +52,8 @@ def parse_args():
     ap.add_argument("--waves-per-cu", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 22, help="elements of the oracle's timed sample")
+    ap.add_argument("--cpu-workers", type=int, default=min(16, os.cpu_count() or 1),
+                    help="processes of the all-cores oracle run reported beside the one-core cpu_baseline (<= 1: skip it)")
     return ap.parse_args()
 
 
@@ -69,8 +71,18 @@ def la_variant(lookahead: str, k: int, t: int, fused: bool) -> str:
     return "step+basic_fused" if (pos == k and fused) else "step"
 
 
-def cpu_baseline(wl, hyper, n_sample: int, budget_s: float = 12.0, max_steps: int = 200):
-    """The oracle, as it stands, on the first n_sample elements of the workload's largest tensor.
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(workload: str, hyper, n_sample: int, budget_s: float = 12.0, max_steps: int = 200, seed: int = 42):
+    """The oracle, as it stands, on n_sample elements shaped like the workload's largest tensor.
 
     Bounded: steps (with their syncs) are run until `budget_s` seconds of oracle time have been spent
     or `max_steps` steps are done; gradient generation is not timed.
@@ -78,14 +90,15 @@ def cpu_baseline(wl, hyper, n_sample: int, budget_s: float = 12.0, max_steps: in
     import workloads as W
     from oracle import novak_oracle as O
 
+    wl = W.get_workload(workload)
     n = min(n_sample, max(wl.numels))
     h = O.Hyper(**{k: v for k, v in hyper.items() if k not in ("mode", "auto_sync")})
-    theta0 = W.host_params([n], 42)
+    theta0 = W.host_params([n], seed)
     states = [O.init_state(theta0[0], h)]
     dt, steps = 0.0, 0
     while steps < max_steps and (dt < budget_s or (h.lookahead != "none" and steps % h.la_k != 0)):
         steps += 1
-        g = W.host_grads([n], steps, wl.grad_std, 42, bf16=(wl.grad_dtype == "bf16"))[0]
+        g = W.host_grads([n], steps, wl.grad_std, seed, bf16=(wl.grad_dtype == "bf16"))[0]
         t0 = time.perf_counter()
         O.step(states[0], g, steps, h)
         if O.sync_due(steps, h):
@@ -93,11 +106,30 @@ def cpu_baseline(wl, hyper, n_sample: int, budget_s: float = 12.0, max_steps: in
         dt += time.perf_counter() - t0
     return {"value": n * steps / dt / 1e9, "unit": "Gparams/s", "cores": 1, "kind": "oracle",
             "sample": f"first {n} elements of the largest tensor, {steps} steps incl. syncs, numpy fp64 arithmetic / "
-                      f"fp32 state, {dt:.1f} s of oracle time", "host_cpus_visible": os.cpu_count()}
+                      f"fp32 state, {dt:.1f} s of oracle time", "host_cpus_visible": os.cpu_count(), "cpu_model": cpu_model()}
+
+
+def _cpu_worker(job):
+    return cpu_baseline(*job)
+
+
+def cpu_baseline_all_cores(pool, workers: int, workload: str, hyper, n_sample: int):
+    """The same oracle, unchanged, as `workers` independent processes, each on its own slice (a plain
+    outer parallel-for over slices: the update is elementwise).  Reported beside the one-core figure."""
+    parts = pool.map(_cpu_worker, [(workload, hyper, n_sample, 8.0, 200, 1000 + i) for i in range(workers)])
+    return {"value": sum(p["value"] for p in parts), "unit": "Gparams/s", "cores": workers, "kind": "oracle",
+            "sample": f"{workers} concurrent processes, each as in cpu_baseline with an 8 s budget on its own "
+                      f"{n_sample}-element slice; sum of their rates"}
 
 
 def main():
     args = parse_args()
+    pool, workers = None, 0
+    if args.gpus == 1 and not args.no_cpu_baseline and args.cpu_workers > 1:
+        # started before anything touches the GPU; the workers idle until the GPU part is over
+        import multiprocessing as mp
+        workers = args.cpu_workers
+        pool = mp.get_context("spawn").Pool(workers)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the update is elementwise and would shard "
               "without communication)", file=sys.stderr)
@@ -257,7 +289,13 @@ def main():
     torch.cuda.synchronize()
     N.novak_destroy(handle)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, {**hyper, "nesterov": nest_name, "lookahead": la_name}, args.cpu_sample)
+        eff = {**hyper, "nesterov": nest_name, "lookahead": la_name, "layer_adaptation": bool(info.layer_adaptation),
+               "auto_lr": bool(info.auto_lr), "use_gc": False}
+        result["cpu_baseline"] = cpu_baseline(wl.name, eff, args.cpu_sample)
+        if pool is not None:
+            result["cpu_baseline_all_cores"] = cpu_baseline_all_cores(pool, workers, wl.name, eff, args.cpu_sample)
+            pool.close()
+            pool.join()
     print(json.dumps(result))
 
 
