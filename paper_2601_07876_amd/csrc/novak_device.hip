@@ -61,8 +61,11 @@ struct novak_handle {
   bool ring_used[kRing] = {};
   int ring_next = 0;
   std::vector<void *> last_grads;
-  std::vector<void *> out_host;        // host copy of the last novak_nesterov_extrapolate pointer list
+  // one more pinned slot (index kRing of h_ring) stages novak_nesterov_extrapolate's pointer list
+  hipEvent_t out_ev = nullptr;
+  bool out_used = false;
   bool grads_uploaded = false;
+  bool broken = false;              // a table rebuild failed half way: every later call is refused
   std::string error;
 };
 
@@ -136,8 +139,20 @@ void free_device_tables(novak_handle *h) {
   h->d_scale = nullptr;
 }
 
-// (Re)build and upload the chunk table for the current chunk_elems.  Synchronous.
+int build_chunk_table_unguarded(novak_handle *h);
+
+// (Re)build and upload the chunk table for the current chunk_elems.  Synchronous.  If it fails after the
+// old tables were released the handle keeps no tables at all and refuses further work.
 int build_chunk_table(novak_handle *h) {
+  const int rc = build_chunk_table_unguarded(h);
+  if (rc != NOVAK_OK && h->broken) {
+    free_device_tables(h);
+    h->n_chunks = 0;
+  }
+  return rc;
+}
+
+int build_chunk_table_unguarded(novak_handle *h) {
   int64_t n = 0;
   int rc = novak_plan_chunks(h->numels.data(), static_cast<int32_t>(h->numels.size()), h->chunk_elems, nullptr, 0, &n);
   if (rc != NOVAK_OK) return fail(h, rc, "chunk planning failed");
@@ -147,6 +162,7 @@ int build_chunk_table(novak_handle *h) {
   rc = novak_plan_chunks(h->numels.data(), static_cast<int32_t>(h->numels.size()), h->chunk_elems, table.data(), n, &n);
   if (rc != NOVAK_OK) return fail(h, rc, "chunk planning failed");
   free_device_tables(h);
+  h->broken = true;                 // until every table below exists
   h->n_chunks = n;
   if (n > 0) {
     NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_chunks), static_cast<size_t>(n) * sizeof(novak_chunk)));
@@ -172,6 +188,7 @@ int build_chunk_table(novak_handle *h) {
       NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_chunk_sums), static_cast<size_t>(n) * sizeof(NormSums)));
     }
   }
+  h->broken = false;
   return NOVAK_OK;
 }
 
@@ -426,8 +443,8 @@ int launch_sync(novak_handle *h, hipStream_t s) {
 // ------------------------------------------------------------------------------------------------
 extern "C" {
 
-int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor_desc *tensors, int32_t n_tensors,
-                 int32_t device_id) {
+static int create_impl(novak_handle **out, const novak_hparams *hp, const novak_tensor_desc *tensors, int32_t n_tensors,
+                       int32_t device_id) {
   if (!out) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "out is NULL");
   *out = nullptr;
   if (!hp) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "hp is NULL");
@@ -454,6 +471,10 @@ int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor
 
   novak_handle *h = new (std::nothrow) novak_handle();
   if (!h) return fail(nullptr, NOVAK_ERR_NO_MEMORY, "host allocation failed");
+  struct Guard {                     // releases the half-built handle on every early exit, exceptions included
+    novak_handle *h;
+    ~Guard() { if (h) novak_destroy(h); }
+  } guard{h};
   h->hp = eff;
   h->warnings = warn;
   h->device_id = device_id;
@@ -467,7 +488,6 @@ int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor
 
   auto bail = [&](int status) {
     g_create_error = h->error;
-    novak_destroy(h);
     return status;
   };
   DeviceScope scope;
@@ -489,10 +509,11 @@ int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor
     }
     if ((e = hipMemcpy(h->d_ptrs, host.data(), bytes, hipMemcpyHostToDevice)) != hipSuccess) return bail(fail_hip(h, e, "hipMemcpy(pointer tables)"));
     if ((e = hipMalloc(reinterpret_cast<void **>(&h->d_out_ptrs), n * sizeof(float *))) != hipSuccess) return bail(fail_hip(h, e, "hipMalloc(output pointers)"));
-    if ((e = hipHostMalloc(reinterpret_cast<void **>(&h->h_ring), novak_handle::kRing * n * sizeof(void *), hipHostMallocDefault)) != hipSuccess)
-      return bail(fail_hip(h, e, "hipHostMalloc(gradient pointer ring)"));
+    if ((e = hipHostMalloc(reinterpret_cast<void **>(&h->h_ring), (novak_handle::kRing + 1) * n * sizeof(void *), hipHostMallocDefault)) != hipSuccess)
+      return bail(fail_hip(h, e, "hipHostMalloc(pointer staging ring)"));
     for (int r = 0; r < novak_handle::kRing; ++r)
       if ((e = hipEventCreateWithFlags(&h->ring_ev[r], hipEventDisableTiming)) != hipSuccess) return bail(fail_hip(h, e, "hipEventCreate"));
+    if ((e = hipEventCreateWithFlags(&h->out_ev, hipEventDisableTiming)) != hipSuccess) return bail(fail_hip(h, e, "hipEventCreate"));
   }
   if (eff.use_gc && n_tensors > 0) {
     const size_t n = static_cast<size_t>(n_tensors);
@@ -529,8 +550,25 @@ int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor
   }
   rc = build_chunk_table(h);
   if (rc != NOVAK_OK) return bail(rc);
+  guard.h = nullptr;
   *out = h;
   return NOVAK_OK;
+}
+
+// No exception leaves the library: host allocation failures become status codes.
+int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor_desc *tensors, int32_t n_tensors,
+                 int32_t device_id) {
+  try {
+    return create_impl(out, hp, tensors, n_tensors, device_id);
+  } catch (const std::bad_alloc &) {
+    if (out) *out = nullptr;
+    g_create_error.clear();
+    return NOVAK_ERR_NO_MEMORY;
+  } catch (...) {
+    if (out) *out = nullptr;
+    g_create_error.clear();
+    return NOVAK_ERR_INVALID_ARG;
+  }
 }
 
 int novak_destroy(novak_handle *h) {
@@ -547,6 +585,7 @@ int novak_destroy(novak_handle *h) {
   if (h->h_ring) (void)hipHostFree(h->h_ring);
   for (int r = 0; r < novak_handle::kRing; ++r)
     if (h->ring_ev[r]) (void)hipEventDestroy(h->ring_ev[r]);
+  if (h->out_ev) (void)hipEventDestroy(h->out_ev);
   delete h;
   return NOVAK_OK;
 }
@@ -574,6 +613,7 @@ int novak_get_info(const novak_handle *h, novak_info *info) {
 
 int novak_nesterov_extrapolate(novak_handle *h, void *const *out, void *hip_stream) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
+  if (h->broken) return fail(h, NOVAK_ERR_STATE, "the handle lost its tables in a failed novak_set_tuning; destroy it");
   const size_t n = h->tensors.size();
   if (n > 0 && !out) return fail(h, NOVAK_ERR_NULL_POINTER, "out is NULL");
   for (size_t i = 0; i < n; ++i) {
@@ -585,9 +625,14 @@ int novak_nesterov_extrapolate(novak_handle *h, void *const *out, void *hip_stre
   DeviceScope scope;
   NOVAK_HIP(h, scope.enter(h->device_id));
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  // the list is copied into the handle first, so the caller's array may be reused as soon as this returns
-  h->out_host.assign(out, out + n);
-  NOVAK_HIP(h, hipMemcpyAsync(h->d_out_ptrs, h->out_host.data(), n * sizeof(float *), hipMemcpyHostToDevice, stream));
+  // the list is staged in pinned memory owned by the handle, so the caller's array may be reused as
+  // soon as this returns; the slot is rewritten only after the previous call's copy has executed
+  if (h->out_used) NOVAK_HIP(h, hipEventSynchronize(h->out_ev));
+  void **staged = h->h_ring + static_cast<size_t>(novak_handle::kRing) * n;
+  std::memcpy(staged, out, n * sizeof(void *));
+  NOVAK_HIP(h, hipMemcpyAsync(h->d_out_ptrs, staged, n * sizeof(float *), hipMemcpyHostToDevice, stream));
+  NOVAK_HIP(h, hipEventRecord(h->out_ev, stream));
+  h->out_used = true;
   const Geometry gm = geometry_of(h, 256, 64, 3.0);
   const float bn = static_cast<float>(h->hp.beta_n);
   const dim3 grid(gm.grid), block(64);
@@ -613,6 +658,7 @@ int novak_set_auto_lr_state(novak_handle *h, void *ema) {
 
 int novak_copy_tensor_scales(novak_handle *h, float *out, void *hip_stream) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
+  if (h->broken) return fail(h, NOVAK_ERR_STATE, "the handle lost its tables in a failed novak_set_tuning; destroy it");
   if (!two_pass(h)) return fail(h, NOVAK_ERR_STATE, "the handle runs the single-pass step: there are no per-tensor scales");
   if (h->tensors.empty()) return NOVAK_OK;
   if (!out) return fail(h, NOVAK_ERR_NULL_POINTER, "out is NULL");
@@ -625,7 +671,7 @@ int novak_copy_tensor_scales(novak_handle *h, float *out, void *hip_stream) {
 
 const char *novak_last_error(const novak_handle *h) { return h ? h->error.c_str() : g_create_error.c_str(); }
 
-int novak_set_tuning(novak_handle *h, int32_t key, int64_t value) {
+static int set_tuning_impl(novak_handle *h, int32_t key, int64_t value) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
   if (key == NOVAK_TUNE_NONTEMPORAL) {
     h->nontemporal = value ? 1 : 0;
@@ -662,8 +708,17 @@ int novak_set_tuning(novak_handle *h, int32_t key, int64_t value) {
   return fail(h, NOVAK_ERR_INVALID_ARG, "unknown tuning key");
 }
 
+int novak_set_tuning(novak_handle *h, int32_t key, int64_t value) {
+  try {
+    return set_tuning_impl(h, key, value);
+  } catch (...) {
+    return NOVAK_ERR_NO_MEMORY;
+  }
+}
+
 int novak_lookahead_init(novak_handle *h, void *hip_stream) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
+  if (h->broken) return fail(h, NOVAK_ERR_STATE, "the handle lost its tables in a failed novak_set_tuning; destroy it");
   if (h->hp.lookahead_mode == NOVAK_LOOKAHEAD_NONE) return fail(h, NOVAK_ERR_STATE, "lookahead is off");
   if (h->n_chunks == 0) return NOVAK_OK;
   DeviceScope scope;
@@ -675,6 +730,7 @@ int novak_lookahead_init(novak_handle *h, void *hip_stream) {
 
 int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t step, void *hip_stream) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
+  if (h->broken) return fail(h, NOVAK_ERR_STATE, "the handle lost its tables in a failed novak_set_tuning; destroy it");
   const size_t n = h->tensors.size();
   if (n > 0 && !grads) return fail(h, NOVAK_ERR_NULL_POINTER, "grads is NULL");
   if (grad_dtype != NOVAK_GRAD_F32 && grad_dtype != NOVAK_GRAD_BF16) return fail(h, NOVAK_ERR_INVALID_ARG, "unknown grad_dtype");
@@ -788,6 +844,7 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
 
 int novak_lookahead_sync(novak_handle *h, void *hip_stream) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
+  if (h->broken) return fail(h, NOVAK_ERR_STATE, "the handle lost its tables in a failed novak_set_tuning; destroy it");
   if (h->hp.lookahead_mode == NOVAK_LOOKAHEAD_NONE) return fail(h, NOVAK_ERR_STATE, "lookahead is off");
   if (!h->sync_due) return fail(h, NOVAK_ERR_STATE, "no lookahead sync is due (sync follows the steps with t mod k == 0)");
   DeviceScope scope;

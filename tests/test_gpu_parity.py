@@ -283,3 +283,18 @@ def test_short_lookahead_windows(lookahead, auto_sync, k):
         H.compare_states(gpu, states)
     finally:
         gpu.close()
+
+
+def test_runs_on_a_side_stream():
+    """Everything is enqueued on the stream the caller passes (here a non-default stream of default
+    priority); nothing relies on the null stream's implicit ordering."""
+    wl = W.get_workload("ragged")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        gpu, states, _ = H.run_pair(wl.numels, dict(wl.hyper, layer_adaptation=True, clip_threshold=0.5), wl.steps, wl.grad_std,
+                                    auto_sync=True)
+        try:
+            assert gpu.stream == side.cuda_stream and gpu.stream != 0
+            H.compare_states(gpu, states)
+        finally:
+            gpu.close()

@@ -77,3 +77,24 @@ def test_extrapolation_point(misalign):
         assert N.novak_nesterov_extrapolate(gpu.handle, [o.data_ptr() + 2 for o in outs], gpu.stream) == N.NOVAK_ERR_MISALIGNED
     finally:
         gpu.close()
+
+
+def test_back_to_back_extrapolations_with_different_output_lists():
+    """Two calls in a row without a synchronisation in between: the second call's pointer list must not
+    overtake the first call's kernel."""
+    wl = W.get_workload("ragged")
+    hyper = dict(wl.hyper, nesterov="true", mode="research", beta_n=0.7)
+    gpu, states, h = H.run_pair(wl.numels, hyper, 3, wl.grad_std)
+    try:
+        a = [torch.full((n,), -5.0, dtype=torch.float32, device="cuda:0") for n in wl.numels]
+        b = [torch.full((n,), -7.0, dtype=torch.float32, device="cuda:0") for n in wl.numels]
+        torch.cuda.synchronize()
+        for outs in (a, b, a):
+            N.check(N.novak_nesterov_extrapolate(gpu.handle, [o.data_ptr() for o in outs], gpu.stream), "extrapolate", gpu.handle)
+        torch.cuda.synchronize()
+        for i, st in enumerate(states):
+            ref = O.extrapolate(st, h)
+            H.assert_close(f"a[{i}]", a[i].cpu().numpy(), ref)
+            H.assert_close(f"b[{i}]", b[i].cpu().numpy(), ref)
+    finally:
+        gpu.close()
