@@ -264,7 +264,8 @@ int novak_copy_tensor_scales(novak_handle *h, float *out, void *hip_stream);
  * caller's buffers (`out` is a HOST array of n_tensors DEVICE pointers to fp32 arrays of numel elements,
  * 4-byte aligned, not overlapping the state).  The caller evaluates the gradient there (Eq. 11) and
  * passes it to novak_step; theta itself is left untouched, so there is nothing to restore.  One launch;
- * 12 bytes per parameter.  Legal in any Nesterov mode. */
+ * 12 bytes per parameter (10 with a bfloat16 m).  Legal in any Nesterov mode.  The list is copied before the
+ * call returns. */
 int novak_nesterov_extrapolate(novak_handle *h, void *const *out, void *hip_stream);
 
 /* Eq. 30-31 over all tensors in one launch: theta <- slow_new, and the buffer is left equal to the
@@ -277,8 +278,11 @@ int novak_destroy(novak_handle *h);
 
 int novak_get_info(const novak_handle *h, novak_info *info);
 
-/* Adjusts a launch parameter (NOVAK_TUNE_*); rebuilds the chunk table when needed.  Results do not
- * depend on tuning values. */
+/* Adjusts a launch parameter (NOVAK_TUNE_*); rebuilds the chunk table when needed (that waits for the
+ * device).  Results do not depend on tuning values.  The bfloat16-moment and the centralizing step kernels
+ * exist only in the default launch shape and ignore THREADS / VEC_PER_LANE.  If a table rebuild fails
+ * after the old tables were released, the handle keeps none: every later call on it but novak_destroy,
+ * novak_get_info and novak_last_error returns NOVAK_ERR_STATE. */
 int novak_set_tuning(novak_handle *h, int32_t key, int64_t value);
 
 /* Text of the most recent failure on this handle (or of the last failed novak_create on this
