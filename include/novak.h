@@ -207,6 +207,32 @@ int novak_compute_step_scalars(const novak_hparams *hp, int64_t step, novak_step
 int novak_plan_chunks(const int64_t *numels, int32_t n_tensors, int64_t chunk_elems,
                       novak_chunk *out, int64_t capacity, int64_t *n_chunks);
 
+/* Recommended placement of the five per-parameter arrays ("roles": theta, exp_avg, exp_avg_sq, la_buf,
+ * gradient) of a tensor list inside ONE device allocation; host arithmetic only, the caller allocates.
+ * Tensor i of role r (element size e_r bytes) starts at byte  r * (*role_stride_bytes) + tensor_offsets[i] * e_r
+ * of the allocation, which must hold (*role_stride_bytes) bytes per role used.  Tensors start at multiples
+ * of NOVAK_ARENA_TENSOR_ALIGN elements inside a role, so that the 1 KB a wave reads of each array never
+ * straddles a 1 KB boundary, and consecutive roles are NOVAK_ARENA_ROLE_SKEW bytes apart modulo
+ * NOVAK_ARENA_ROLE_PERIOD.  The library accepts any placement (see novak_tensor_desc); this one measured
+ * 1-2 % more bandwidth on MI355X than a spacing that is a multiple of the period, and 3-4 % more than
+ * separately allocated arrays, whose relative placement is up to the driver (-10 % .. +1 % from run to run).  `tensor_offsets` (n_tensors entries, elements) may be NULL; `role_elems` receives the padded
+ * element count of one role. */
+#define NOVAK_ARENA_TENSOR_ALIGN 256
+#define NOVAK_ARENA_ROLE_PERIOD 8192
+#define NOVAK_ARENA_ROLE_SKEW 2048
+int novak_plan_arena(const int64_t *numels, int32_t n_tensors, int64_t *tensor_offsets, int64_t *role_elems,
+                     int64_t *role_stride_bytes);
+
+/* Device memory for such an arena: `bytes` bytes on device `device_id`, requested as physically contiguous
+ * memory first (hipExtMallocWithFlags with hipDeviceMallocContiguous) and, if the driver cannot provide
+ * that, as an ordinary hipMalloc allocation.  `*contiguous` (may be NULL) says which one it is.  On MI355X
+ * the step kernel measured 6.73 TB/s on a contiguous arena against 6.5-6.6 TB/s on an ordinary allocation
+ * of the same layout (whose physical placement, and with it the bandwidth, varies with what ran on the
+ * device before).  The contents are NOT initialised.  Release with novak_arena_free after the last kernel
+ * that uses the memory has finished; the library never frees it by itself. */
+int novak_arena_alloc(int32_t device_id, size_t bytes, void **ptr, int32_t *contiguous);
+int novak_arena_free(int32_t device_id, void *ptr);
+
 /* Algorithmic HBM bytes per parameter of one step (section 5.5: 4 streams read + 3 written, 4 B
  * each; gradients 2 B when bf16; plus the lookahead buffer traffic of that step).  `window_pos` is
  * the step's 1-based position in its lookahead window (ignored when lookahead is NONE);

@@ -204,16 +204,23 @@ struct Geometry {
   int sub_shift;
   unsigned lds;   // dynamic LDS bytes requested per workgroup (never touched; bounds residency)
 };
-// `streams16` = 128-bit-per-lane stream equivalents the kernel keeps in flight per wave (reads plus
-// writes; a bf16 gradient stream counts 0.5).  Measured on MI355X, achieved bandwidth peaks when a
-// compute unit has roughly 80 such 1 KB wave-accesses outstanding and falls by 5-10 % at full
-// occupancy, so residency is capped by requesting LDS that the kernel never touches.
-Geometry geometry_of(const novak_handle *h, int sub_elems, int threads, double streams16) {
+// Residency.  `wide` = arrays of 4-byte elements a wave reads plus those it writes (1 KB per wave each),
+// `narrow` = the same count for 2-byte arrays (bf16 gradients, bf16 first moment; 512 bytes per wave).
+// Measured on MI355X, achieved bandwidth peaks when a compute unit has roughly 84 wide wave-accesses
+// outstanding (9 resident waves for 9 arrays, 12 for 7) and falls by 5-10 % at full occupancy; narrow
+// arrays turned out not to count (kernels with one peak two to four waves later than their byte count
+// suggests), with no gain beyond 16 waves.
+// Residency is capped by requesting LDS that the kernel never touches.
+Geometry geometry_of(const novak_handle *h, int sub_elems, int threads, int wide, int narrow = 0) {
   Geometry gm;
   gm.sub_shift = log2_exact(h->chunk_elems / sub_elems);
   gm.grid = static_cast<unsigned>(h->n_chunks << gm.sub_shift);
   int waves = h->waves_per_cu;                       // 0 = automatic
-  if (waves == 0) waves = static_cast<int>(80.0 / (streams16 * h->vec_per_lane) + 0.5);
+  if (waves == 0) {
+    const double per_wave = static_cast<double>(wide > 0 ? wide : 1) * h->vec_per_lane;
+    waves = static_cast<int>(84.0 / per_wave + 0.5);
+    if (narrow > 0 && waves > 16) waves = 16;
+  }
   const int waves_per_wg = threads / 64;
   int wgs = waves / waves_per_wg;
   if (wgs < 1) wgs = 1;
@@ -226,11 +233,17 @@ Geometry geometry_of(const novak_handle *h, int sub_elems, int threads, double s
   return gm;
 }
 
-double step_streams16(int grad_dtype, int la) {
-  double s = 3.0 + (grad_dtype == NOVAK_GRAD_BF16 ? 0.5 : 1.0) + 3.0;   // theta, m, v, g read; theta, m, v written
-  if (la_reads(la)) s += 1.0;
-  if (la_writes(la)) s += 1.0;
-  return s;
+// arrays touched by the fused step: theta, m, v read and written, g read, the lookahead buffer per phase
+struct StreamCount {
+  int wide, narrow;
+};
+StreamCount step_streams(int grad_dtype, int la, bool bf16_m) {
+  StreamCount n{4, 0};                                // theta and v, read and written
+  if (bf16_m) n.narrow += 2; else n.wide += 2;        // m read and written
+  if (grad_dtype == NOVAK_GRAD_BF16) n.narrow += 1; else n.wide += 1;
+  if (la_reads(la)) n.wide += 1;
+  if (la_writes(la)) n.wide += 1;
+  return n;
 }
 
 template <typename GradS, typename GradV, bool NT, int UN, int BLOCK>
@@ -247,7 +260,8 @@ void launch_step_la(int la, const Geometry &gm, hipStream_t s, const Tables &tb,
 
 template <bool NT, int UN, int BLOCK>
 void launch_step_dtype(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
-  const Geometry gm = geometry_of(h, BLOCK * 4 * UN, BLOCK, step_streams16(grad_dtype, la));
+  const StreamCount n = step_streams(grad_dtype, la, false);
+  const Geometry gm = geometry_of(h, BLOCK * 4 * UN, BLOCK, n.wide, n.narrow);
   if (grad_dtype == NOVAK_GRAD_BF16) launch_step_la<unsigned short, u16x4, NT, UN, BLOCK>(la, gm, s, tb, c);
   else launch_step_la<float, f32x4, NT, UN, BLOCK>(la, gm, s, tb, c);
 }
@@ -274,7 +288,8 @@ void launch_step_block(const novak_handle *h, int grad_dtype, int la, hipStream_
 // (one wave64 per 256 elements).
 template <typename GradS, typename GradV, bool NT, bool GC, typename MomS, typename MomV>
 void launch_step_special(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
-  const Geometry gm = geometry_of(h, 256, 64, step_streams16(grad_dtype, la) - (sizeof(MomS) == 2 ? 1.0 : 0.0));
+  const StreamCount n = step_streams(grad_dtype, la, sizeof(MomS) == 2);
+  const Geometry gm = geometry_of(h, 256, 64, n.wide, n.narrow);
   const dim3 grid(gm.grid), block(64);
   switch (la) {
     case LA_OFF: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_OFF, NT, 1, 64, GC, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
@@ -318,7 +333,7 @@ int launch_rowmeans(novak_handle *h, int grad_dtype, hipStream_t s, const Tables
 
 template <int OP, int BLOCK>
 void launch_la_block(const novak_handle *h, hipStream_t s, const Tables &tb, float c0, float c1) {
-  const Geometry gm = geometry_of(h, BLOCK * 4, BLOCK, OP == SYNC_BASIC ? 4.0 : 2.0);
+  const Geometry gm = geometry_of(h, BLOCK * 4, BLOCK, OP == SYNC_BASIC ? 4 : 2);
   if (h->nontemporal) hipLaunchKernelGGL((novak_lookahead_kernel<OP, true, BLOCK>), dim3(gm.grid), dim3(BLOCK), gm.lds, s, tb, c0, c1, gm.sub_shift);
   else hipLaunchKernelGGL((novak_lookahead_kernel<OP, false, BLOCK>), dim3(gm.grid), dim3(BLOCK), gm.lds, s, tb, c0, c1, gm.sub_shift);
 }
@@ -359,7 +374,7 @@ void launch_moments(const novak_handle *h, int grad_dtype, const Geometry &g1, h
 
 // Clipping pre-pass: gradient norm partials -> chunk sums -> tensor sums -> global factor in d_gscale.
 int launch_clip_prepass(novak_handle *h, int grad_dtype, hipStream_t s, const Tables &tb) {
-  const Geometry g0 = geometry_of(h, kNormSub, kScaledBlock, 1.0);      // a single read stream: full residency
+  const Geometry g0 = geometry_of(h, kNormSub, kScaledBlock, 1);        // a single read stream: full residency
   const dim3 grid(g0.grid), block(kScaledBlock);
   const bool nt = h->nontemporal != 0;
   if (grad_dtype == NOVAK_GRAD_BF16) {
@@ -384,9 +399,10 @@ int launch_clip_prepass(novak_handle *h, int grad_dtype, hipStream_t s, const Ta
 // The two-pass step: moments + norm partials, fixed-order reductions, scaled apply.
 int launch_scaled_step(novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
   const novak_hparams &hp = h->hp;
-  const double g16 = grad_dtype == NOVAK_GRAD_BF16 ? 0.5 : 1.0;
   const bool bf16_m = hp.moment_dtype == NOVAK_MOMENT_BF16_M;
-  const Geometry g1 = geometry_of(h, kScaledSub, kScaledBlock, 3.0 + g16 + 2.0 - (bf16_m ? 1.0 : 0.0));
+  const bool bf16_g = grad_dtype == NOVAK_GRAD_BF16;
+  // pass 1: theta, g, m, v read; m, v written
+  const Geometry g1 = geometry_of(h, kScaledSub, kScaledBlock, 3 + (bf16_g ? 0 : 1) + (bf16_m ? 0 : 2), (bf16_g ? 1 : 0) + (bf16_m ? 2 : 0));
   const bool nt = h->nontemporal != 0;
   if (bf16_m) launch_moments<unsigned short, u16x4>(h, grad_dtype, g1, s, tb, c);
   else launch_moments<float, f32x4>(h, grad_dtype, g1, s, tb, c);
@@ -407,10 +423,10 @@ int launch_scaled_step(novak_handle *h, int grad_dtype, int la, hipStream_t s, c
   if (hp.auto_lr)
     hipLaunchKernelGGL(novak_auto_lr_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, h->d_scale, h->d_ema, sp);
   NOVAK_HIP(h, hipGetLastError());
-  double s2 = 3.0 + 1.0 - (bf16_m ? 0.5 : 0.0);   // theta, m, v read; theta written
-  if (la_reads(la)) s2 += 1.0;
-  if (la_writes(la)) s2 += 1.0;
-  const Geometry g2 = geometry_of(h, kScaledSub, kScaledBlock, s2);
+  int s2 = 3 + (bf16_m ? 0 : 1);                    // pass 2: theta, m, v read; theta written
+  if (la_reads(la)) s2 += 1;
+  if (la_writes(la)) s2 += 1;
+  const Geometry g2 = geometry_of(h, kScaledSub, kScaledBlock, s2, bf16_m ? 1 : 0);
   if (bf16_m) {
     if (nt) launch_apply<true, unsigned short, u16x4>(la, g2, s, tb, c, h->d_scale);
     else launch_apply<false, unsigned short, u16x4>(la, g2, s, tb, c, h->d_scale);
@@ -571,6 +587,39 @@ int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor
   }
 }
 
+int novak_arena_alloc(int32_t device_id, size_t bytes, void **ptr, int32_t *contiguous) {
+  if (!ptr) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "ptr is NULL");
+  *ptr = nullptr;
+  if (contiguous) *contiguous = 0;
+  if (device_id < 0 || bytes == 0) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "device_id < 0 or bytes == 0");
+  DeviceScope scope;
+  hipError_t e = scope.enter(device_id);
+  if (e != hipSuccess) return fail_hip(nullptr, e, "hipSetDevice");
+  void *p = nullptr;
+  e = hipExtMallocWithFlags(&p, bytes, hipDeviceMallocContiguous);
+  if (e == hipSuccess && p) {
+    if (contiguous) *contiguous = 1;
+  } else {
+    (void)hipGetLastError();          // the refusal is not an error of this call: fall back
+    p = nullptr;
+    e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "hipMalloc(arena)");
+  }
+  *ptr = p;
+  return NOVAK_OK;
+}
+
+int novak_arena_free(int32_t device_id, void *ptr) {
+  if (!ptr) return NOVAK_OK;
+  if (device_id < 0) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "device_id < 0");
+  DeviceScope scope;
+  hipError_t e = scope.enter(device_id);
+  if (e != hipSuccess) return fail_hip(nullptr, e, "hipSetDevice");
+  e = hipFree(ptr);
+  if (e != hipSuccess) return fail_hip(nullptr, e, "hipFree(arena)");
+  return NOVAK_OK;
+}
+
 int novak_destroy(novak_handle *h) {
   if (!h) return NOVAK_OK;
   DeviceScope scope;
@@ -633,7 +682,8 @@ int novak_nesterov_extrapolate(novak_handle *h, void *const *out, void *hip_stre
   NOVAK_HIP(h, hipMemcpyAsync(h->d_out_ptrs, staged, n * sizeof(float *), hipMemcpyHostToDevice, stream));
   NOVAK_HIP(h, hipEventRecord(h->out_ev, stream));
   h->out_used = true;
-  const Geometry gm = geometry_of(h, 256, 64, 3.0);
+  const bool bf16_m_out = h->hp.moment_dtype == NOVAK_MOMENT_BF16_M;
+  const Geometry gm = geometry_of(h, 256, 64, bf16_m_out ? 2 : 3, bf16_m_out ? 1 : 0);
   const float bn = static_cast<float>(h->hp.beta_n);
   const dim3 grid(gm.grid), block(64);
   if (h->hp.moment_dtype == NOVAK_MOMENT_BF16_M) {

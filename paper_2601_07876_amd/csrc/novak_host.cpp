@@ -5,6 +5,7 @@
 #include "novak_internal.h"
 
 #include <cmath>
+#include <cstdint>
 #include <cstring>
 
 namespace {
@@ -174,6 +175,23 @@ int novak_plan_chunks(const int64_t *numels, int32_t n_tensors, int64_t chunk_el
     }
   }
   *n_chunks = n;
+  return NOVAK_OK;
+}
+
+int novak_plan_arena(const int64_t *numels, int32_t n_tensors, int64_t *tensor_offsets, int64_t *role_elems,
+                     int64_t *role_stride_bytes) {
+  if (n_tensors < 0) return NOVAK_ERR_INVALID_ARG;
+  if ((n_tensors > 0 && !numels) || !role_elems || !role_stride_bytes) return NOVAK_ERR_NULL_POINTER;
+  const int64_t limit = INT64_MAX / 8;
+  int64_t off = 0;
+  for (int32_t i = 0; i < n_tensors; ++i) {
+    if (numels[i] < 0 || numels[i] > limit - off) return NOVAK_ERR_INVALID_ARG;
+    if (tensor_offsets) tensor_offsets[i] = off;
+    off += (numels[i] + NOVAK_ARENA_TENSOR_ALIGN - 1) / NOVAK_ARENA_TENSOR_ALIGN * NOVAK_ARENA_TENSOR_ALIGN;
+  }
+  *role_elems = off;
+  const int64_t bytes = off * 4;    // the widest role holds 4-byte elements
+  *role_stride_bytes = (bytes + NOVAK_ARENA_ROLE_PERIOD - 1) / NOVAK_ARENA_ROLE_PERIOD * NOVAK_ARENA_ROLE_PERIOD + NOVAK_ARENA_ROLE_SKEW;
   return NOVAK_OK;
 }
 

@@ -76,7 +76,8 @@ class novak_info(C.Structure):
                 ("n_centralized", C.c_int32), ("moment_dtype", C.c_int32), ("reserved0", C.c_int32)]
 
 
-EXPORTS = ("novak_validate_hparams", "novak_compute_step_scalars", "novak_plan_chunks",
+EXPORTS = ("novak_validate_hparams", "novak_compute_step_scalars", "novak_plan_chunks", "novak_plan_arena",
+           "novak_arena_alloc", "novak_arena_free",
            "novak_bytes_per_param_step", "novak_bytes_per_param_scaled_step", "novak_bytes_per_param_clip",
            "novak_bytes_per_param_moment_saving", "novak_bytes_per_param_sync",
            "novak_status_string", "novak_create", "novak_lookahead_init", "novak_step", "novak_lookahead_sync",
@@ -100,6 +101,9 @@ def load_library() -> C.CDLL:
     lib.novak_validate_hparams.argtypes = [C.POINTER(novak_hparams), C.POINTER(novak_hparams), C.POINTER(C.c_uint32)]
     lib.novak_compute_step_scalars.argtypes = [C.POINTER(novak_hparams), i64, C.POINTER(novak_step_scalars)]
     lib.novak_plan_chunks.argtypes = [C.POINTER(i64), i32, i64, C.POINTER(novak_chunk), i64, C.POINTER(i64)]
+    lib.novak_plan_arena.argtypes = [C.POINTER(i64), i32, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+    lib.novak_arena_alloc.argtypes = [i32, C.c_size_t, C.POINTER(C.c_void_p), C.POINTER(i32)]
+    lib.novak_arena_free.argtypes = [i32, C.c_void_p]
     lib.novak_bytes_per_param_step.argtypes = [i32, i32, i32, i32, i32]
     lib.novak_bytes_per_param_step.restype = C.c_double
     lib.novak_bytes_per_param_scaled_step.argtypes = [i32, i32, i32, i32, i32]
@@ -187,6 +191,41 @@ def novak_plan_chunks(numels: Sequence[int], chunk_elems: int):
     out = (novak_chunk * max(count.value, 1))()
     rc = lib.novak_plan_chunks(arr, n, int(chunk_elems), out, count.value, C.byref(count))
     return rc, [(out[i].tensor, out[i].offset, out[i].len) for i in range(count.value)]
+
+
+def novak_plan_arena(numels: Sequence[int]):
+    """-> (status, tensor offsets in elements, padded elements per role, bytes between consecutive roles)."""
+    n = len(numels)
+    arr = (C.c_int64 * max(n, 1))(*numels)
+    offs = (C.c_int64 * max(n, 1))()
+    role_elems, stride = C.c_int64(0), C.c_int64(0)
+    rc = load_library().novak_plan_arena(arr, n, offs, C.byref(role_elems), C.byref(stride))
+    return rc, [offs[i] for i in range(n)], role_elems.value, stride.value
+
+
+def novak_arena_alloc(device_id: int, nbytes: int):
+    """-> (status, device pointer as int or None, 1 if physically contiguous else 0)."""
+    ptr, contiguous = C.c_void_p(), C.c_int32(0)
+    rc = load_library().novak_arena_alloc(device_id, nbytes, C.byref(ptr), C.byref(contiguous))
+    return rc, ptr.value, contiguous.value
+
+
+def novak_arena_free(device_id: int, ptr) -> int:
+    return load_library().novak_arena_free(device_id, ptr)
+
+
+class _DeviceBytes:
+    """Exposes raw device memory to torch through the array-interface protocol (no copy, no ownership)."""
+
+    def __init__(self, ptr: int, nbytes: int):
+        self.__cuda_array_interface__ = {"shape": (nbytes,), "typestr": "|u1", "data": (ptr, False), "version": 2}
+
+
+def arena_as_tensor(ptr: int, nbytes: int, device_id: int = 0):
+    """A uint8 torch tensor over memory from novak_arena_alloc.  The tensor does not own the memory: keep
+    it (and every view of it) no longer than until novak_arena_free."""
+    import torch
+    return torch.as_tensor(_DeviceBytes(ptr, nbytes), device=torch.device("cuda", device_id))
 
 
 def novak_bytes_per_param_step(lookahead_mode: int, grad_dtype: int, la_k: int, window_pos: int, fused_sync: int) -> float:

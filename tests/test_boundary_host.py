@@ -219,3 +219,32 @@ def test_product_never_imports_the_oracle():
     bench = open(os.path.join(ROOT, "bench.py")).read()
     body = bench.split("def cpu_baseline(")[0] + bench.split("def main():")[1]
     assert "from oracle" not in body and "import oracle" not in body
+
+
+@pytest.mark.parametrize("name", ["ragged", "c2_resnet50", "c4_vit_b16_bf16", "c5_decoder_1p3b"])
+def test_arena_plan_places_every_tensor_on_its_own_aligned_range(name):
+    numels = W.get_workload(name).numels
+    rc, offs, role_elems, stride = N.novak_plan_arena(numels)
+    assert rc == N.NOVAK_OK
+    end = 0
+    for o, n in zip(offs, numels):
+        assert o % 256 == 0 and o >= end          # 1 KB-aligned for 4-byte elements, no overlap, tensor order kept
+        end = o + n
+    assert role_elems >= end and role_elems % 256 == 0 and role_elems - end < 256
+    assert stride >= role_elems * 4 and stride % 8192 == 2048 and stride - role_elems * 4 < 8192 + 2048
+
+
+def test_arena_plan_edge_cases():
+    assert N.novak_plan_arena([]) == (N.NOVAK_OK, [], 0, 2048)
+    assert N.novak_plan_arena([0, 0]) == (N.NOVAK_OK, [0, 0], 0, 2048)
+    assert N.novak_plan_arena([1]) == (N.NOVAK_OK, [0], 256, 8192 + 2048)
+    assert N.novak_plan_arena([2048, 1])[1:] == ([0, 2048], 2304, 16384 + 2048)
+    assert N.novak_plan_arena([-1])[0] == N.NOVAK_ERR_INVALID_ARG
+    assert N.novak_plan_arena([2 ** 62, 2 ** 62])[0] == N.NOVAK_ERR_INVALID_ARG
+    lib = N.load_library()
+    i64 = C.c_int64
+    arr, a, b = (i64 * 2)(5, 7), i64(0), i64(0)
+    assert lib.novak_plan_arena(arr, 2, None, C.byref(a), C.byref(b)) == N.NOVAK_OK and a.value == 512   # offsets optional
+    assert lib.novak_plan_arena(arr, 2, None, None, C.byref(b)) == N.NOVAK_ERR_NULL_POINTER
+    assert lib.novak_plan_arena(None, 2, None, C.byref(a), C.byref(b)) == N.NOVAK_ERR_NULL_POINTER
+    assert lib.novak_plan_arena(arr, -1, None, C.byref(a), C.byref(b)) == N.NOVAK_ERR_INVALID_ARG

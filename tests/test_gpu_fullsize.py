@@ -32,19 +32,31 @@ def _say(msg):
 class FullRun:
     """Flat device buffers holding a whole workload, a library handle, and the sampled oracle."""
 
-    def __init__(self, wl: W.Workload, samples_per_tensor: int = 2048, seed: int = 42, device="cuda:0"):
+    def __init__(self, wl: W.Workload, samples_per_tensor: int = 2048, seed: int = 42, device="cuda:0", arena: bool = False):
+        """arena=True places all five roles in ONE allocation as novak_plan_arena recommends (the layout
+        bench.py times); otherwise every role is its own allocation with GAP guard elements around each tensor."""
         self.wl, self.seed = wl, seed
         self.dev = torch.device(device)
         self.numels = wl.numels
-        self.offsets = []
-        off = GAP
-        for n in self.numels:
-            self.offsets.append(off)
-            off += ((n + GAP - 1) // GAP) * GAP + GAP
-        self.flat_len = off
-        self.bufs = {r: torch.empty(self.flat_len, dtype=torch.float32, device=self.dev) for r in ("theta", "m", "v", "la")}
+        self.arena = None
+        if arena:
+            rc, self.offsets, self.flat_len, self.stride = N.novak_plan_arena(self.numels)
+            N.check(rc, "novak_plan_arena")
+            torch.zeros(1, device=self.dev)
+            rc, self.arena_ptr, self.arena_contiguous = N.novak_arena_alloc(0, 5 * self.stride)
+            N.check(rc, "novak_arena_alloc")
+            self.arena = N.arena_as_tensor(self.arena_ptr, 5 * self.stride, 0)
+            self.ends = self.offsets[1:] + [self.flat_len]          # padding after a tensor runs up to the next one
+        else:
+            self.offsets = []
+            off = GAP
+            for n in self.numels:
+                self.offsets.append(off)
+                off += ((n + GAP - 1) // GAP) * GAP + GAP
+            self.flat_len = off
         gdt = torch.bfloat16 if wl.grad_dtype == "bf16" else torch.float32
-        self.g = torch.empty(self.flat_len, dtype=gdt, device=self.dev)
+        self.bufs = {r: self._role(i, torch.float32) for i, r in enumerate(("theta", "m", "v", "la"))}
+        self.g = self._role(4, gdt)
         self.gen = torch.Generator(device=self.dev)
         self.chunk_elems = None
         self.handle = None
@@ -58,6 +70,11 @@ class FullRun:
         for i, (o, n) in enumerate(zip(self.offsets, self.numels)):
             self._grad_arr[i] = self.g.data_ptr() + o * self.g.element_size()
 
+    def _role(self, i, dtype):
+        if self.arena is None:
+            return torch.empty(self.flat_len, dtype=dtype, device=self.dev)
+        return self.arena[i * self.stride: i * self.stride + self.flat_len * dtype.itemsize].view(dtype)
+
     def reset(self, hyper, auto_sync=False):
         if self.handle is not None:
             torch.cuda.synchronize()
@@ -67,7 +84,7 @@ class FullRun:
         want = torch.bfloat16 if self.bf16_m else torch.float32
         if self.bufs["m"].dtype != want:
             del self.bufs["m"]
-            self.bufs["m"] = torch.empty(self.flat_len, dtype=want, device=self.dev)
+            self.bufs["m"] = self._role(1, want)
         for r in ("theta", "m", "v", "la"):
             self.bufs[r].fill_(SENTINEL)
         for o, n in zip(self.offsets, self.numels):
@@ -128,10 +145,15 @@ class FullRun:
         if self.h.lookahead == "basic":
             H.assert_close(f"{tag} slow", self.bufs["la"][self.idx].cpu().numpy()[keep], self.state.slow0[keep])
         # whole-buffer properties
-        for o, n in zip(self.offsets[:4] + self.offsets[-4:], self.numels[:4] + self.numels[-4:]):
-            for r in ("theta", "m", "v"):
-                b = self.bufs[r]
-                assert bool((b[o - GAP:o] == SENTINEL).all()) and bool((b[o + n:o + n + 1] == SENTINEL).all()), f"{tag}: {r} guard touched"
+        if self.arena is None:
+            for o, n in zip(self.offsets[:4] + self.offsets[-4:], self.numels[:4] + self.numels[-4:]):
+                for r in ("theta", "m", "v"):
+                    b = self.bufs[r]
+                    assert bool((b[o - GAP:o] == SENTINEL).all()) and bool((b[o + n:o + n + 1] == SENTINEL).all()), f"{tag}: {r} guard touched"
+        else:
+            for o, n, e in zip(self.offsets, self.numels, self.ends):
+                for r in ("theta", "m", "v", "la"):
+                    assert o + n == e or bool((self.bufs[r][o + n:e] == SENTINEL).all()), f"{tag}: {r} padding touched"
         assert bool(torch.isfinite(self.bufs["theta"]).all())
         assert float(self.bufs["v"].min()) >= 0.0
 
@@ -140,6 +162,10 @@ class FullRun:
             torch.cuda.synchronize()
             N.novak_destroy(self.handle)
             self.handle = None
+        if self.arena is not None:
+            torch.cuda.synchronize()
+            self.bufs, self.g, self.arena = {}, None, None
+            N.check(N.novak_arena_free(0, self.arena_ptr), "novak_arena_free")
 
 
 def test_c2_resnet50_fast_path_100_steps():
@@ -173,9 +199,25 @@ def test_c3_vgg16_fast_and_research_modes():
         run.close()
 
 
+@pytest.mark.parametrize("seed", [100, 2025])
+def test_c3_vgg16_other_seeds_of_the_papers_experiments(seed):
+    """Section 9.1 runs every experiment under seeds 42, 100 and 2025; the other tests use 42."""
+    wl = W.get_workload("c3_vgg16")
+    run = FullRun(wl, seed=seed)
+    try:
+        run.reset(wl.hyper, auto_sync=True)
+        for t in range(1, 12):
+            run.step()
+            if t in (5, 11):
+                run.check(f"c3 seed={seed} t={t}")
+        _say(f"c3 seed {seed} done")
+    finally:
+        run.close()
+
+
 def test_c4_vit_b16_bf16_gradients_100_steps():
     wl = W.get_workload("c4_vit_b16_bf16")
-    run = FullRun(wl)
+    run = FullRun(wl, arena=True)          # odd tensor sizes (1000, 197 x 768, ...): padding inside the roles
     try:
         run.reset(wl.hyper)
         for t in range(1, 101):
@@ -201,7 +243,12 @@ def test_c5_decoder_1p3b_sweep():
                     if t in (k - 1, 2 * k, 2 * k + 1):
                         run.check(f"c5 k={k} {nest} t={t}")
                 _say(f"c5 k={k} nesterov={nest} done")
-        # the exact configuration bench.py times: fast mode, approximation, k = 5, sync fused into the k-th step
+        # the exact configuration bench.py times: fast mode, approximation, k = 5, sync fused into the k-th step,
+        # all roles in one allocation placed by novak_plan_arena
+        run.close()
+        del run
+        torch.cuda.empty_cache()
+        run = FullRun(wl, samples_per_tensor=1024, arena=True)
         run.reset(wl.hyper, auto_sync=True)
         for t in range(1, 12):
             run.step()
@@ -215,7 +262,7 @@ def test_c5_decoder_1p3b_sweep():
 def test_c5_bf16_first_moment_bench_config():
     """The reduced-precision configuration bench.py can time: 1.3B parameters, m in bfloat16."""
     wl = W.get_workload("c5_decoder_1p3b")
-    run = FullRun(wl, samples_per_tensor=1024)
+    run = FullRun(wl, samples_per_tensor=1024, arena=True)
     try:
         run.reset(dict(wl.hyper, moment_dtype="bf16_m"), auto_sync=True)
         for t in range(1, 12):

@@ -4,6 +4,7 @@ Bound (per element of theta, m, v and the lookahead buffer): |gpu - ref| <= 1e-7
 tighter scale-aware check (see harness.assert_close_strict).  Sizes here span many chunks of the
 multi-tensor table and ragged tails; full-size workloads are in test_gpu_fullsize.py.
 """
+import ctypes as C
 import itertools
 
 import numpy as np
@@ -298,3 +299,62 @@ def test_runs_on_a_side_stream():
             H.compare_states(gpu, states)
         finally:
             gpu.close()
+
+
+def test_arena_allocation_and_the_planned_layout():
+    """novak_arena_alloc / novak_plan_arena / arena_as_tensor: a whole run inside one library-allocated arena."""
+    wl = W.get_workload("ragged")
+    rc, offs, flat, stride = N.novak_plan_arena(wl.numels)
+    N.check(rc, "novak_plan_arena")
+    torch.zeros(1, device="cuda:0")
+    rc, ptr, contiguous = N.novak_arena_alloc(0, 5 * stride)
+    N.check(rc, "novak_arena_alloc")
+    assert ptr and ptr % 256 == 0 and contiguous in (0, 1)
+    try:
+        arena = N.arena_as_tensor(ptr, 5 * stride, 0)
+        assert arena.data_ptr() == ptr and arena.numel() == 5 * stride and arena.dtype == torch.uint8
+        arena.fill_(0x7B)
+        roles = [arena[i * stride: i * stride + 4 * flat].view(torch.float32) for i in range(5)]
+        theta, m, v, la, g = roles
+        sentinel = float(theta[0])
+        theta0 = W.host_params(wl.numels, 42)
+        for o, n, th in zip(offs, wl.numels, theta0):
+            theta[o:o + n].copy_(torch.from_numpy(th))
+            m[o:o + n].zero_()
+            v[o:o + n].zero_()
+        hp = N.make_hparams(auto_sync=True, **wl.hyper)
+        descs = [N.novak_tensor_desc(*(r.data_ptr() + 4 * o for r in (theta, m, v, la)), n) for o, n in zip(offs, wl.numels)]
+        rc, handle = N.novak_create(hp, descs, 0)
+        N.check(rc, "novak_create")
+        rc, info = N.novak_get_info(handle)
+        h = H.oracle_hyper(wl.hyper, H.NEST_NAMES[info.nesterov_mode], H.LA_NAMES[info.lookahead_mode], info)
+        states = [O.init_state(th, h) for th in theta0]
+        N.check(N.novak_lookahead_init(handle, 0), "init", handle)
+        garr = (C.c_void_p * len(offs))(*[g.data_ptr() + 4 * o for o in offs])
+        for t in range(1, 8):
+            gh = W.host_grads(wl.numels, t, wl.grad_std, 42)
+            for o, n, x in zip(offs, wl.numels, gh):
+                g[o:o + n].copy_(torch.from_numpy(x))
+            N.check(N.novak_step(handle, garr, N.NOVAK_GRAD_F32, t, 0), "step", handle)
+            O.step_all(states, gh, t, h, O.AutoLrState())
+            if O.sync_due(t, h):
+                for st in states:
+                    O.lookahead_sync(st, h)
+        torch.cuda.synchronize()
+        ends = offs[1:] + [flat]
+        for o, n, e, st in zip(offs, wl.numels, ends, states):
+            H.assert_close("theta", theta[o:o + n].cpu().numpy(), st.theta)
+            H.assert_close("m", m[o:o + n].cpu().numpy(), st.m)
+            H.assert_close("v", v[o:o + n].cpu().numpy(), st.v)
+            for r in (theta, m, v, la):            # padding between tensors is never written
+                assert bool((r[o + n:e] == sentinel).all())
+        N.novak_destroy(handle)
+        del roles, theta, m, v, la, g, arena
+    finally:
+        torch.cuda.synchronize()
+        assert N.novak_arena_free(0, ptr) == N.NOVAK_OK
+    # argument errors
+    assert N.novak_arena_alloc(0, 0)[0] == N.NOVAK_ERR_INVALID_ARG
+    assert N.novak_arena_alloc(-1, 1024)[0] == N.NOVAK_ERR_INVALID_ARG
+    assert N.load_library().novak_arena_alloc(0, 1024, None, None) == N.NOVAK_ERR_NULL_POINTER
+    assert N.novak_arena_free(0, None) == N.NOVAK_OK
