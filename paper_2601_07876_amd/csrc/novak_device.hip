@@ -206,20 +206,23 @@ struct Geometry {
 };
 // Residency.  `wide` = arrays of 4-byte elements a wave reads plus those it writes (1 KB per wave each),
 // `narrow` = the same count for 2-byte arrays (bf16 gradients, bf16 first moment; 512 bytes per wave).
-// Measured on MI355X, achieved bandwidth peaks when a compute unit has roughly 84 wide wave-accesses
-// outstanding (9 resident waves for 9 arrays, 12 for 7) and falls by 5-10 % at full occupancy; narrow
-// arrays turned out not to count (kernels with one peak two to four waves later than their byte count
-// suggests), with no gain beyond 16 waves.
-// Residency is capped by requesting LDS that the kernel never touches.
-Geometry geometry_of(const novak_handle *h, int sub_elems, int threads, int wide, int narrow = 0) {
+// Measured on MI355X (physically contiguous arena), bandwidth peaks at 8 resident waves per compute unit
+// for 9 wide arrays, 9-10 for 8, 11 for 7, 12 for 6 and 13-14 for 5, whether or not narrow arrays are
+// touched as well, and falls by 5-10 % towards full occupancy: about 74 wide wave-accesses outstanding
+// per compute unit.  Lists of smaller tensors (0.1-0.4 ms kernels) and the two kernels of the two-pass
+// step peak one or two waves later; the budgets below are the compromise (78, and 84 for the two-pass
+// kernels).  Residency is capped by requesting LDS that the kernel never touches.
+constexpr double kStepBudget = 78.0, kTwoPassBudget = 84.0;
+Geometry geometry_of(const novak_handle *h, int sub_elems, int threads, int wide, int narrow = 0, double budget = kStepBudget) {
   Geometry gm;
   gm.sub_shift = log2_exact(h->chunk_elems / sub_elems);
   gm.grid = static_cast<unsigned>(h->n_chunks << gm.sub_shift);
   int waves = h->waves_per_cu;                       // 0 = automatic
   if (waves == 0) {
     const double per_wave = static_cast<double>(wide > 0 ? wide : 1) * h->vec_per_lane;
-    waves = static_cast<int>(84.0 / per_wave + 0.5);
-    if (narrow > 0 && waves > 16) waves = 16;
+    waves = static_cast<int>(budget / per_wave + 0.5);
+    const int cap = budget > kStepBudget ? 16 : 14;    // no gain beyond these with a narrow array in the mix
+    if (narrow > 0 && waves > cap) waves = cap;
   }
   const int waves_per_wg = threads / 64;
   int wgs = waves / waves_per_wg;
@@ -402,7 +405,7 @@ int launch_scaled_step(novak_handle *h, int grad_dtype, int la, hipStream_t s, c
   const bool bf16_m = hp.moment_dtype == NOVAK_MOMENT_BF16_M;
   const bool bf16_g = grad_dtype == NOVAK_GRAD_BF16;
   // pass 1: theta, g, m, v read; m, v written
-  const Geometry g1 = geometry_of(h, kScaledSub, kScaledBlock, 3 + (bf16_g ? 0 : 1) + (bf16_m ? 0 : 2), (bf16_g ? 1 : 0) + (bf16_m ? 2 : 0));
+  const Geometry g1 = geometry_of(h, kScaledSub, kScaledBlock, 3 + (bf16_g ? 0 : 1) + (bf16_m ? 0 : 2), (bf16_g ? 1 : 0) + (bf16_m ? 2 : 0), kTwoPassBudget);
   const bool nt = h->nontemporal != 0;
   if (bf16_m) launch_moments<unsigned short, u16x4>(h, grad_dtype, g1, s, tb, c);
   else launch_moments<float, f32x4>(h, grad_dtype, g1, s, tb, c);
@@ -426,7 +429,7 @@ int launch_scaled_step(novak_handle *h, int grad_dtype, int la, hipStream_t s, c
   int s2 = 3 + (bf16_m ? 0 : 1);                    // pass 2: theta, m, v read; theta written
   if (la_reads(la)) s2 += 1;
   if (la_writes(la)) s2 += 1;
-  const Geometry g2 = geometry_of(h, kScaledSub, kScaledBlock, s2, bf16_m ? 1 : 0);
+  const Geometry g2 = geometry_of(h, kScaledSub, kScaledBlock, s2, bf16_m ? 1 : 0, kTwoPassBudget);
   if (bf16_m) {
     if (nt) launch_apply<true, unsigned short, u16x4>(la, g2, s, tb, c, h->d_scale);
     else launch_apply<false, unsigned short, u16x4>(la, g2, s, tb, c, h->d_scale);
