@@ -54,6 +54,12 @@ int main(void) {
   for (i = 0; i < (int)needed; ++i) printf("chunk %d tensor %d offset %lld len %d\n", i, (int)table[i].tensor, (long long)table[i].offset, (int)table[i].len);
   printf("bytes %.1f %.1f\n", novak_bytes_per_param_step(NOVAK_LOOKAHEAD_NONE, NOVAK_GRAD_F32, 5, 1, 0),
          novak_bytes_per_param_step(NOVAK_LOOKAHEAD_MEMORY_EFFICIENT, NOVAK_GRAD_BF16, 5, 2, 1));
+  {
+    int64_t offs[3], role_elems = -1, stride = -1;
+    rc = novak_plan_arena(numels, 3, offs, &role_elems, &stride);
+    printf("arena rc %d offsets %lld %lld %lld role_elems %lld stride %lld\n", rc, (long long)offs[0], (long long)offs[1],
+           (long long)offs[2], (long long)role_elems, (long long)stride);
+  }
   printf("status %s\n", novak_status_string(NOVAK_ERR_MISALIGNED));
   {
     novak_handle *h = (novak_handle *)&hp;   /* must come back NULL */

@@ -68,6 +68,8 @@ def test_host_entry_points_called_from_c(probe_output):
     chunks = [tuple(int(x) for x in l.split()[2::2]) for l in _lines(out, "chunk ")]
     assert chunks == [(0, 0, 5), (2, 0, 4096), (2, 4096, 4096), (2, 8192, 1808)]
     assert _lines(out, "bytes ") == ["28.0 34.0"]
+    # sizes (5, 0, 10000): tensors at 0, 256, 256; 10240 + 256 padded elements; 40.5 KiB -> 48 KiB + 2 KiB
+    assert _lines(out, "arena rc ") == ["0 offsets 0 256 256 role_elems 10496 stride 51200"]
     assert _lines(out, "status ")[0] == N.novak_status_string(N.NOVAK_ERR_MISALIGNED)
     bad = _lines(out, "create_bad rc ")[0]
     assert bad.startswith(f"{N.NOVAK_ERR_INVALID_ARG} handle_null 1 msg ") and "device_id" in bad
