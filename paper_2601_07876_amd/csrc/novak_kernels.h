@@ -7,7 +7,7 @@
 // dozen flops), so the kernels are built around memory streams, not arithmetic:
 //   * a chunk-table entry never spans tensors and is covered by short-lived workgroups (one wave64
 //     by default) that each touch 256..4096 consecutive elements once;
-//   * each lane moves 128 bits per stream per access (4 fp32; 4 bf16 gradients = 64 bits), and all
+//   * each lane moves 128 bits per stream per access (4 fp32; 4 bf16 values = 64 bits), and all
 //     loads of a workgroup are issued before any arithmetic;
 //   * per-step scalars arrive as kernel arguments (SGPRs); nothing is read from memory except the
 //     chunk entry, the tensor's pointer record and the streams themselves;
