@@ -1,0 +1,41 @@
+"""bench.py run in-process on a small workload: the JSON line carries the contract's keys and is self-consistent."""
+import json
+import sys
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+CONTRACT = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+            "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline")
+
+
+@pytest.mark.parametrize("extra", [[], ["--moment-dtype", "bf16_m"], ["--layer-adaptation", "--clip", "1.0"], ["--layout", "separate"]])
+def test_bench_line(monkeypatch, capsys, extra):
+    import bench
+    # one in-process oracle run, no worker processes: nothing is spawned from a process that holds the GPU
+    argv = ["bench.py", "--workload", "c2_resnet50", "--steps", "10", "--warmup", "5", "--cpu-workers", "1", "--cpu-sample", "65536"] + extra
+    monkeypatch.setattr(sys, "argv", argv)
+    bench.main()
+    lines = [l for l in capsys.readouterr().out.splitlines() if l.startswith("{")]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in CONTRACT:
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 10 and d["warmup"] == 5 and d["higher_is_better"] is True
+    assert d["unit"] == "Gparams/s" and d["vs_baseline"] is None and d["data"] == "synthetic" and d["dtype"] == "f32"
+    cfg = d["config"]
+    assert cfg["workload"] == "c2_resnet50" and cfg["params"] == 25557032 and "model" not in cfg
+    assert d["value"] == pytest.approx(cfg["params"] / (d["ms_per_step"] * 1e-3) / 1e9, rel=1e-9)
+    r = d["roofline"]
+    assert r["bound"] == "hbm" and r["unit"] == "GB/s" and r["peak"] == 8000.0
+    assert r["frac"] == pytest.approx(r["achieved"] / r["peak"]) and 0.05 < r["frac"] < 1.0
+    k = d["kernels"][r["kernel"]]
+    assert r["achieved"] == pytest.approx(cfg["params"] * k["bytes_per_param"] / (k["avg_ms"] * 1e-3) / 1e9)
+    assert r["algorithmic_bytes_per_launch"] == cfg["params"] * k["bytes_per_param"]
+    assert sum(v["launches"] for v in d["kernels"].values()) == 10
+    c = d["cpu_baseline"]
+    assert c["kind"] == "oracle" and c["cores"] == 1 and c["unit"] == "Gparams/s" and c["value"] > 0 and c["sample"]
+    assert "cpu_baseline_all_cores" not in d
+    if "--layout" not in extra:
+        assert cfg["layout"] == "arena"
