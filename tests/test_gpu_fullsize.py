@@ -129,7 +129,8 @@ class FullRun:
         # some step are flagged by the oracle and held to a few bf16 ulps; everything else as usual
         flagged = self.state.ambiguous if (self.bf16_m and self.state.ambiguous is not None) else np.zeros(self.idx_host.shape, bool)
         keep = ~flagged
-        assert flagged.sum() <= (1.5 * self.t * 8e-4 + 2e-3) * flagged.size, f"{tag}: {int(flagged.sum())} flagged elements"
+        rate = 1e-2 if self.wl.grad_dtype == "bf16" else 8e-4      # bf16 gradients put m on exact rounding ties (see test_gpu_moment_bf16.py)
+        assert flagged.sum() <= (1.5 * self.t * rate + 2e-3) * flagged.size, f"{tag}: {int(flagged.sum())} flagged elements"
         for role, ref in (("theta", self.state.theta), ("m", self.state.m), ("v", self.state.v)):
             got = self.bufs[role][self.idx].float().cpu().numpy()
             H.assert_close(f"{tag} {role}", got[keep], ref[keep])
@@ -270,6 +271,21 @@ def test_c5_bf16_first_moment_bench_config():
             if t in (4, 5, 6, 10, 11):
                 run.check(f"c5 bf16-m t={t}")
         _say("c5 bf16 m done")
+    finally:
+        run.close()
+
+
+def test_c4_bf16_gradients_and_bf16_first_moment():
+    """Both 2-byte streams at once on the ViT-B/16 list (odd tensor sizes, padded arena)."""
+    wl = W.get_workload("c4_vit_b16_bf16")
+    run = FullRun(wl, arena=True)
+    try:
+        run.reset(dict(wl.hyper, moment_dtype="bf16_m"), auto_sync=True)
+        for t in range(1, 8):
+            run.step()
+            if t in (4, 5, 7):
+                run.check(f"c4 bf16 g+m t={t}")
+        _say("c4 bf16 g+m done")
     finally:
         run.close()
 
