@@ -358,3 +358,37 @@ def test_arena_allocation_and_the_planned_layout():
     assert N.novak_arena_alloc(-1, 1024)[0] == N.NOVAK_ERR_INVALID_ARG
     assert N.load_library().novak_arena_alloc(0, 1024, None, None) == N.NOVAK_ERR_NULL_POINTER
     assert N.novak_arena_free(0, None) == N.NOVAK_OK
+
+
+def test_two_parameter_groups_on_two_streams():
+    """Two handles (a decayed group and an undecayed one with other hyper-parameters, as parameter groups
+    are used in practice) stepped alternately on two streams without synchronising in between: handles
+    share no state."""
+    wl = W.get_workload("ragged")
+    groups = [(wl.numels[:7], dict(wl.hyper, weight_decay=1e-2, lr=1e-3, la_k=5)),
+              (wl.numels[7:], dict(wl.hyper, weight_decay=0.0, lr=3e-3, la_k=3, nesterov="classical", layer_adaptation=True))]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    runs = []
+    for (numels, hyper), s in zip(groups, streams):
+        with torch.cuda.stream(s):
+            theta0 = W.host_params(numels, 100)
+            gpu = H.GpuNovak(numels, hyper, "f32", theta0, auto_sync=True)
+            h = H.oracle_hyper(hyper, gpu.eff_nesterov, gpu.eff_lookahead, gpu.info)
+            runs.append((gpu, [O.init_state(th, h) for th in theta0], h, numels, O.AutoLrState()))
+    try:
+        for t in range(1, 13):
+            for (gpu, states, h, numels, aux), s in zip(runs, streams):
+                gh = W.host_grads(numels, t, wl.grad_std, 100)
+                with torch.cuda.stream(s):
+                    gd = gpu.upload_grads(gh)
+                    N.check(gpu.step(t, gd), f"step {t}", gpu.handle)
+                O.step_all(states, gh, t, h, aux)
+                if O.sync_due(t, h):
+                    for st in states:
+                        O.lookahead_sync(st, h)
+        torch.cuda.synchronize()
+        for gpu, states, *_ in runs:
+            H.compare_states(gpu, states)
+    finally:
+        for gpu, *_ in runs:
+            gpu.close()
