@@ -392,3 +392,38 @@ def test_two_parameter_groups_on_two_streams():
     finally:
         for gpu, *_ in runs:
             gpu.close()
+
+
+@pytest.mark.parametrize("t0", [5000, 10 ** 6])
+def test_late_steps_of_a_long_run(t0):
+    """Steps t0 + 1 ... on warmed-up moments: at 5000 the second bias correction and r_t are still a little
+    below one, at 10^6 everything has converged to one; the prologue's log-domain evaluation of 1 - beta^t
+    (section 5.8) feeds the kernel."""
+    wl = W.get_workload("ragged")
+    numels = wl.numels
+    rng = np.random.Generator(np.random.Philox(key=[7, 7]))
+    theta0 = W.host_params(numels, 42)
+    m0 = [rng.normal(0.0, 3e-3, n).astype(np.float32) for n in numels]
+    v0 = [(rng.normal(0.0, 1e-2, n) ** 2).astype(np.float32) for n in numels]
+    gpu = H.GpuNovak(numels, wl.hyper, "f32", theta0, auto_sync=True)
+    try:
+        for i in range(len(numels)):
+            gpu.m[i].copy_(torch.from_numpy(m0[i]))
+            gpu.v[i].copy_(torch.from_numpy(v0[i]))
+        h = H.oracle_hyper(wl.hyper, gpu.eff_nesterov, gpu.eff_lookahead, gpu.info)
+        states = [O.init_state(th, h) for th in theta0]
+        for st, m, v in zip(states, m0, v0):
+            st.m, st.v = m.copy(), v.copy()
+        for t in range(t0 + 1, t0 + 12):
+            gh = W.host_grads(numels, t - t0, wl.grad_std, 42)
+            N.check(gpu.step(t, gpu.upload_grads(gh)), f"step {t}", gpu.handle)
+            O.step_all(states, gh, t, h, O.AutoLrState())
+            if O.sync_due(t, h):
+                for st in states:
+                    O.lookahead_sync(st, h)
+        s = O.step_scalars(h, t0 + 1)
+        assert s.rectified_now and s.bc1 == 1.0
+        assert (0.9 < s.r_t < 1.0 and s.bc2 < 1.0) if t0 == 5000 else (s.r_t == 1.0 and s.bc2 == 1.0)
+        H.compare_states(gpu, states)
+    finally:
+        gpu.close()
