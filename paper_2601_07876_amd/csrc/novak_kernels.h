@@ -170,8 +170,14 @@ __device__ __forceinline__ void moments(float th_in, float g, float &m, float &v
   if (c.flags & F_CLIP) g *= gs;                                        // global-norm clipping comes first
   if (c.flags & F_COUPLED) g = __builtin_fmaf(c.wd, th_in, g);          // classic L2 reading
   if (c.flags & F_APPROX) g = __builtin_fmaf(c.beta_n, g - m, g);       // Eq. 13
+  const float m_in = m, v_in = v;
   m = __builtin_fmaf(c.omb1, g - m, m);                                 // Eq. 1:  m + (1-b1)(g - m)
   v = __builtin_fmaf(c.omb2, __builtin_fmaf(g, g, -v), v);              // Eq. 2:  v + (1-b2)(g^2 - v)
+  // A moment that has overflowed stays infinite under Eq. 1-2 as printed (beta*inf + finite); the
+  // difference form above would turn it into inf - inf.  With v = inf the direction is 0 and theta only decays.
+  const bool g_finite = __builtin_fabsf(g) < __builtin_inff();
+  if (__builtin_isinf(m_in) && g_finite) m = m_in;
+  if (__builtin_isinf(v_in) && g == g) v = v_in;
 }
 
 __device__ __forceinline__ float direction(float m, float v, const Consts &c, float &m_hat) {

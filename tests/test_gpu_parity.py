@@ -427,3 +427,64 @@ def test_late_steps_of_a_long_run(t0):
         H.compare_states(gpu, states)
     finally:
         gpu.close()
+
+
+def test_extreme_gradient_values():
+    """Zeros, values whose square underflows fp32, values near the top of the range whose square still fits:
+    the kernel and the oracle agree element by element.  (From |g~| = 1.8e19 on, g~^2 leaves the fp32 range
+    inside the kernel while double arithmetic still holds it: outside what fp32 arithmetic can match; that
+    regime is covered by the property test below.)"""
+    n = 4096 + 13
+    specials = np.array([0.0, -0.0, 1e-30, -1e-30, 1e-23, 3e-20, 1e-10, 1.0, -1.0, 1e5, 1e10, -1e15, 1e17, 1e18, -1e18], dtype=np.float32)
+    theta0 = W.host_params([n], 42)
+    hyper = dict(W.BASE_HYPER, mode="research")
+    gpu = H.GpuNovak([n], hyper, "f32", theta0, auto_sync=True)
+    try:
+        h = H.oracle_hyper(hyper, gpu.eff_nesterov, gpu.eff_lookahead, gpu.info)
+        states = [O.init_state(theta0[0], h)]
+        for t in range(1, 8):
+            g = W.host_grads([n], t, 1e-2, 42)[0]
+            g[: specials.size] = specials if t % 2 else -specials[::-1]
+            g[-specials.size:] = specials * np.float32(0.5 * t)
+            N.check(gpu.step(t, gpu.upload_grads([g])), f"step {t}", gpu.handle)
+            O.step_all(states, [g], t, h, O.AutoLrState())
+            if O.sync_due(t, h):
+                O.lookahead_sync(states[0], h)
+        st = states[0]
+        assert np.isfinite(st.v).all() and float(st.v.max()) > 1e33 and float(st.v[st.v > 0].min()) < 1e-40
+        H.compare_states(gpu, states, strict=False)
+    finally:
+        gpu.close()
+
+
+def test_an_overflowed_second_moment_freezes_the_element_instead_of_poisoning_it():
+    """A gradient of 1e30 overflows v (Eq. 2 gives inf and keeps it: beta2*inf + finite).  From then on the
+    element's direction is 0 and theta only decays; nothing turns into NaN and the neighbours are unaffected."""
+    n = 1024
+    theta0 = W.host_params([n], 42)
+    hyper = dict(W.BASE_HYPER, lookahead="none", nesterov="none")
+    gpu = H.GpuNovak([n], hyper, "f32", theta0)
+    ref = H.GpuNovak([n], hyper, "f32", theta0)          # the same run without the spike
+    try:
+        hot = [3, 500, 1023]
+        theta_after_spike = None
+        for t in range(1, 9):
+            g = W.host_grads([n], t, 1e-2, 42)[0]
+            N.check(ref.step(t, ref.upload_grads([g])), f"ref step {t}", ref.handle)
+            if t == 2:
+                g = g.copy()
+                g[hot] = [1e30, -1e30, 3e38]
+            N.check(gpu.step(t, gpu.upload_grads([g])), f"step {t}", gpu.handle)
+            if t == 2:
+                theta_after_spike = gpu.host("theta")[0][hot].astype(np.float64)
+        th, m, v = gpu.host("theta")[0], gpu.host("m")[0], gpu.host("v")[0]
+        assert np.isinf(v[hot]).all() and (v[hot] > 0).all()
+        assert np.isfinite(m).all() and np.isfinite(th).all() and np.isfinite(np.delete(v, hot)).all()
+        # six further steps of pure decay: theta * (1 - lr*wd)^6
+        np.testing.assert_allclose(th[hot], theta_after_spike * (1.0 - 1e-3 * 1e-2) ** 6, rtol=1e-6)
+        cold = np.ones(n, bool)
+        cold[hot] = False
+        assert np.array_equal(th[cold], ref.host("theta")[0][cold]) and np.array_equal(v[cold], ref.host("v")[0][cold])
+    finally:
+        gpu.close()
+        ref.close()
