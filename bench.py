@@ -235,7 +235,7 @@ def main():
 
     # ---- timed region: exactly K steps, per-step HIP events on the launch stream ------------------
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    variants = []
+    variants, sync_ev = [], []
     torch.cuda.synchronize()
     t_begin = time.perf_counter()
     for i in range(args.steps):
@@ -246,6 +246,9 @@ def main():
         ev[i][1].record()
         if la_name != "none" and not fused and t % k == 0:
             N.check(N.novak_lookahead_sync(handle, stream), "novak_lookahead_sync", handle)
+            done = torch.cuda.Event(enable_timing=True)
+            done.record()
+            sync_ev.append((ev[i][1], done))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_begin
 
@@ -276,6 +279,10 @@ def main():
         bpp = bytes_of(name)
         kernels[name] = {"launches": len(ms), "avg_ms": avg, "bytes_per_param": bpp,
                          "GBps": p * bpp / (avg * 1e-3) / 1e9}
+    if sync_ev:     # the separate slow-weight synchronisation kernel (Eq. 30-31), timed from the end of its step
+        ms = [a.elapsed_time(b) for a, b in sync_ev]
+        avg, bpp = sum(ms) / len(ms), N.novak_bytes_per_param_sync(la_mode)
+        kernels["lookahead_sync"] = {"launches": len(ms), "avg_ms": avg, "bytes_per_param": bpp, "GBps": p * bpp / (avg * 1e-3) / 1e9}
     dominant = max(kernels, key=lambda n: kernels[n]["launches"] * kernels[n]["avg_ms"])
     dk = kernels[dominant]
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -10,7 +10,8 @@ CONTRACT = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step
             "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline")
 
 
-@pytest.mark.parametrize("extra", [[], ["--moment-dtype", "bf16_m"], ["--layer-adaptation", "--clip", "1.0"], ["--layout", "separate"]])
+@pytest.mark.parametrize("extra", [[], ["--moment-dtype", "bf16_m"], ["--layer-adaptation", "--clip", "1.0"], ["--layout", "separate"],
+                                   ["--separate-sync"]])
 def test_bench_line(monkeypatch, capsys, extra):
     import bench
     # one in-process oracle run, no worker processes: nothing is spawned from a process that holds the GPU
@@ -33,7 +34,10 @@ def test_bench_line(monkeypatch, capsys, extra):
     k = d["kernels"][r["kernel"]]
     assert r["achieved"] == pytest.approx(cfg["params"] * k["bytes_per_param"] / (k["avg_ms"] * 1e-3) / 1e9)
     assert r["algorithmic_bytes_per_launch"] == cfg["params"] * k["bytes_per_param"]
-    assert sum(v["launches"] for v in d["kernels"].values()) == 10
+    assert sum(v["launches"] for n, v in d["kernels"].items() if n != "lookahead_sync") == 10
+    if "--separate-sync" in extra:
+        assert d["kernels"]["lookahead_sync"]["launches"] == 2 and d["kernels"]["lookahead_sync"]["bytes_per_param"] == 8.0
+        assert cfg["sync"] == "separate"
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] == 1 and c["unit"] == "Gparams/s" and c["value"] > 0 and c["sample"]
     assert "cpu_baseline_all_cores" not in d
