@@ -122,3 +122,39 @@ def test_decay_and_step_size_scalars():
     assert not O.step_scalars(O.Hyper(unrect_fallback="sgdm"), 3).denom_on
     assert O.step_scalars(O.Hyper(unrect_fallback="sgdm"), 6).denom_on
     assert O.step_scalars(O.Hyper(unrect_fallback="adam_denom"), 3).denom_on
+
+
+def _decimal_schedule(beta2: str, t: int):
+    """Eq. 6, 7, 9 in 50-digit decimal arithmetic (independent of the oracle's floating-point form)."""
+    from decimal import Decimal as D, getcontext
+    getcontext().prec = 50
+    b2 = D(beta2)
+    rho_inf = 2 / (1 - b2) - 1
+    bt = b2 ** t
+    rho_t = rho_inf - 2 * t * bt / (1 - bt)
+    r_t = ((rho_t - 4) * (rho_t - 2) * rho_inf / ((rho_inf - 4) * (rho_inf - 2) * rho_t)).sqrt() if rho_t >= 5 else D(1)
+    return float(rho_inf), float(rho_t), float(r_t)
+
+
+def test_schedule_landmarks_of_the_default_configuration():
+    """Numbers a reader can check by hand from Eq. 6-9 with beta2 = 0.999: rho_inf = 1999, rho_1..6 =
+    1, 1.9995, 2.9987, 3.9975, 4.9960, 5.9942, so the first rectified step is t = 6 (also for 0.99 and
+    0.95), r_6 = 0.025821, r_100 = 0.215335, r_10000 = 0.999773, and the r_t of the first 100 steps (1 while
+    unrectified) add up to 18.731269 - the factor of the constant-gradient closed form."""
+    assert _decimal_schedule("0.999", 1)[0] == pytest.approx(1999.0, rel=1e-14)
+    for t, want in zip(range(1, 7), (1.0, 1.9995, 2.9987, 3.9975, 4.9960, 5.9942)):
+        assert _decimal_schedule("0.999", t)[1] == pytest.approx(want, abs=6e-5)
+    landmarks = {("0.999", 6): 0.025821, ("0.999", 10): 0.048998, ("0.999", 100): 0.215335, ("0.999", 1000): 0.645326,
+                 ("0.999", 10000): 0.999773, ("0.99", 6): 0.081679, ("0.99", 100): 0.634117}
+    for (b2, t), want in landmarks.items():
+        exact = _decimal_schedule(b2, t)
+        assert exact[2] == pytest.approx(want, abs=6e-7)
+        s = O.step_scalars(O.Hyper(beta2=float(b2)), t)
+        assert s.rectified_now and s.r_t == pytest.approx(exact[2], rel=1e-12) and s.rho_t == pytest.approx(exact[1], rel=1e-12)
+    for b2 in ("0.999", "0.99", "0.95"):
+        h = O.Hyper(beta2=float(b2))
+        first = [t for t in range(1, 30) if O.step_scalars(h, t).rectified_now][0]
+        assert first == 6 and _decimal_schedule(b2, 5)[1] < 5.0 <= _decimal_schedule(b2, 6)[1]
+    total = sum(O.step_scalars(O.Hyper(), t).r_t for t in range(1, 101))
+    assert total == pytest.approx(sum(_decimal_schedule("0.999", t)[2] for t in range(1, 101)), rel=1e-12)
+    assert total == pytest.approx(18.731269, abs=1e-6)
