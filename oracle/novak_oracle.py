@@ -58,19 +58,19 @@ Readings taken where the paper is silent or inconsistent (each is a named switch
   * reduced-precision first moment (the paper's "multi-precision" outlook, sections 3 and 10.3; not part
     of its method): moment_dtype = "bf16_m" stores m as bfloat16, rounded to nearest-even from the
     exactly computed value of Eq. 1; that stored m_t is what bias correction and the direction of the
-    same step use.  All arithmetic stays in double here (fp32 in an implementation).  v stays fp32: with beta2 = 0.999 its per-step change (0.1 % of v) is below half
-    a bfloat16 ulp (0.2-0.4 %), so a round-to-nearest bf16 v would stop moving.  An implementation that
-    forms m in fp32 before rounding can land on the other side of a rounding boundary.  To first order
-    an fp32 evaluation of Eq. 13 and Eq. 1 (each operation and each constant rounded once) is within
-    2^-24 [(1-beta1)(2|g| + 3|g~| + 4|m_prev|) + |m|] of the exact m; the oracle records in
-    TensorState.ambiguous the elements whose exact m ever came within FP32_SLACK times that of a
-    midpoint.  parity unpinned by the paper (it defines no such mode).
+    same step use.  All arithmetic stays in double here (fp32 in an implementation).  v stays fp32: with
+    beta2 = 0.999 its per-step change (0.1 % of v) is below half a bfloat16 ulp (0.2-0.4 %), so a
+    round-to-nearest bf16 v would stop moving.  The rounding is a discontinuous decision: an
+    implementation that forms m in fp32 can land on the other side of a rounding boundary.  The oracle
+    does not model that; it exposes the exact m_t before the rounding (TensorState.trace) and accepts,
+    through `stored_m`, the value an implementation stored, so that a comparison can check the rounding
+    itself and then the rest of the step given that rounding.  parity unpinned by the paper (it defines
+    no such mode).
   * sparse threshold (Eq. 27): the base direction u is zeroed where |u| <= tau, after the trust ratio is
     taken (Phase 7 precedes Phase 8) and before the classical blend (Table 2's order within Phase 8).
     The mask is a discontinuous decision on a floating-point value: an implementation in another
-    precision may decide differently where |u| is within rounding of tau.  For comparisons, the
-    oracle records in TensorState.ambiguous the elements whose |u| ever came within a relative
-    AMBIGUITY_BAND of tau; it does not change any result.
+    precision may decide differently where |u| is within rounding of tau.  The oracle does not model
+    that either; it exposes |u| before the mask (TensorState.trace) for comparisons to judge.
 """
 from __future__ import annotations
 
@@ -83,9 +83,6 @@ import numpy as np
 NESTEROV_MODES = ("none", "approx", "classical", "true")
 LOOKAHEAD_MODES = ("none", "memory_efficient", "basic")
 UNRECT_FALLBACKS = ("adam_denom", "sgdm")
-AMBIGUITY_BAND = 5e-5      # relative half-width around tau in which the Eq. 27 decision is called ambiguous
-FP32_UNIT = 2.0 ** -24     # unit roundoff of fp32
-FP32_SLACK = 2.0           # safety factor on the first-order fp32 error bound used to call a bf16 rounding ambiguous
 MOMENT_DTYPES = ("f32", "bf16_m")
 
 
@@ -147,23 +144,16 @@ def one_minus_pow(beta: float, t: int) -> float:
     return -math.expm1(t * math.log(beta))
 
 
-def round_to_bf16(x: np.ndarray):
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
     """Round double values to the nearest bfloat16 (8 significant bits, ties to even) in ONE rounding.
 
-    Returns (rounded values as float64, distance of x from the nearest rounding midpoint in bf16 ulps).
-    Subnormal bfloat16 results are not handled (the moments here never get below 1e-38).
+    Returns the rounded values as float64.  Subnormal bfloat16 results are not handled (the moments
+    here never get below 1e-38).
     """
     x = np.asarray(x, dtype=np.float64)
     mant, exp = np.frexp(x)                      # x = mant * 2^exp, 0.5 <= |mant| < 1
-    scaled = mant * 256.0                        # 128 <= |scaled| < 256: one unit = one bf16 ulp
-    q = np.rint(scaled)                          # ties to even
-    frac = np.abs(scaled) - np.floor(np.abs(scaled))
-    return np.ldexp(q, exp - 8), np.abs(frac - 0.5)
-
-
-def bf16_ulp(x: np.ndarray) -> np.ndarray:
-    """Spacing of bfloat16 numbers in the binade of x (x != 0)."""
-    return np.ldexp(1.0, np.frexp(np.asarray(x, dtype=np.float64))[1] - 8)
+    q = np.rint(mant * 256.0)                    # 128 <= |mant * 256| < 256: one unit = one bf16 ulp; ties to even
+    return np.ldexp(q, exp - 8)
 
 
 def scheduled_betas(h: Hyper, t: int):
@@ -207,6 +197,16 @@ def step_scalars(h: Hyper, t: int) -> StepScalars:
 
 
 @dataclass
+class StepTrace:
+    """Intermediate values of a tensor's most recent step, kept for comparisons (they change no result)."""
+    g_processed: np.ndarray      # the gradient after clipping, centralization and coupled decay, before Eq. 13
+    g_tilde: np.ndarray          # the gradient that fed the moments (Eq. 13 applied when in force)
+    m_exact: np.ndarray          # Eq. 1 in double, before any storage rounding
+    u_base: np.ndarray           # base direction of Eq. 17 (or m_hat in the momentum fallback), before Eq. 27 / Eq. 16
+    scale: float                 # lambda_trust * alpha_auto of Eq. 24a
+
+
+@dataclass
 class TensorState:
     """State of one parameter tensor (Table 3): theta, m, v and the lookahead window."""
     theta: np.ndarray
@@ -214,8 +214,8 @@ class TensorState:
     v: np.ndarray
     slow0: Optional[np.ndarray] = None                 # theta_0^slow of the open window (Eq. 28)
     window: List[np.ndarray] = field(default_factory=list)   # the fast iterates of the open window
-    ambiguous: Optional[np.ndarray] = None             # bookkeeping for comparisons only (see header, Eq. 27)
     rows: int = 0                                      # size of dim 0 if the tensor has more than one dim, else 0 (Eq. 26)
+    trace: Optional[StepTrace] = None                  # see StepTrace
 
     @property
     def dtype(self):
@@ -268,13 +268,16 @@ def clip_scale(grads, h: Hyper) -> float:
 
 
 def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float = 1.0,
-         g_scale: float = 1.0) -> StepScalars:
+         g_scale: float = 1.0, stored_m: Optional[np.ndarray] = None) -> StepScalars:
     """One update of one tensor at step t (Phases 2-9), then record the iterate for lookahead.
 
     `grad` holds the gradient values (any float dtype; bf16 gradients arrive as the fp32/fp64
     numbers they exactly represent).  The sync of Phase 10 is a separate call: `lookahead_sync`.
     `alpha_auto` is the step-wide auto-LR factor (1 unless h.auto_lr; see `auto_lr_scale`);
     `g_scale` the step-wide clipping factor (see `clip_scale`).
+    `stored_m` (moment_dtype "bf16_m" only; for comparisons): the bfloat16 values an implementation
+    stored as m_t.  When given they stand in for the oracle's own rounding of the exact m_t in the rest
+    of the step; whether they are a legitimate rounding of st.trace.m_exact is for the caller to check.
     """
     s = step_scalars(h, t)
     dt = st.dtype
@@ -288,30 +291,26 @@ def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float 
         g = (g2d - g2d.mean(axis=1, keepdims=True)).reshape(-1)    # Eq. 26
     if (not h.decoupled_decay) and h.weight_decay != 0.0:
         g = g + h.weight_decay * theta                      # coupled L2 (reading; see header)
-    g_in = g
+    g_processed = g
     if effective_nesterov(h, t) == "approx":
         g = g + h.beta_n * (g - m_prev)                     # Eq. 13; replaces g for both moments
     b1_t, b2_t = scheduled_betas(h, t)                      # Eq. 3-4 (Phase 3)
     m = b1_t * m_prev + (1.0 - b1_t) * g                    # Eq. 1
     v = b2_t * v_prev + (1.0 - b2_t) * g * g                # Eq. 2
+    m_exact = m
     if h.moment_dtype == "bf16_m":                          # m_t is what is stored: the rest of the step uses it
-        m_exact = m
-        m, dist = round_to_bf16(m_exact)
-        # bookkeeping only: could an fp32 evaluation of Eq. 13 and Eq. 1 have crossed the midpoint?
-        fp32_error = FP32_SLACK * FP32_UNIT * ((1.0 - b1_t) * (2.0 * np.abs(g_in) + 3.0 * np.abs(g) + 4.0 * np.abs(m_prev))
-                                               + np.abs(m_exact))
-        near = (dist * bf16_ulp(m_exact) <= fp32_error) & (m_exact != 0.0)
-        st.ambiguous = near if st.ambiguous is None else (st.ambiguous | near)
+        m = round_to_bf16(m_exact) if stored_m is None else np.asarray(stored_m, dtype=np.float64).reshape(-1)
+    else:
+        assert stored_m is None
     m_hat = m / s.bc1                                       # Eq. 5
     if s.denom_on:
         v_hat = v / s.bc2                                   # Eq. 5
         u = m_hat / (np.sqrt(v_hat) + h.eps)                # Eq. 17
     else:
         u = m_hat                                           # momentum-SGD fallback while rho_t < 5
+    u_base = u
     lam_trust = trust_ratio(theta, u, h) if h.layer_adaptation else 1.0   # Eq. 19 / 25 (Phase 7)
     if h.sparse_threshold > 0.0:
-        near = np.abs(np.abs(u) - h.sparse_threshold) <= AMBIGUITY_BAND * h.sparse_threshold
-        st.ambiguous = near if st.ambiguous is None else (st.ambiguous | near)
         u = np.where(np.abs(u) > h.sparse_threshold, u, 0.0)   # Eq. 27
     if h.nesterov == "classical":
         u = h.beta1 * m_hat + (1.0 - h.beta1) * u           # Eq. 16
@@ -321,6 +320,7 @@ def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float 
     st.theta = theta.astype(dt)
     st.m = m.astype(dt)
     st.v = v.astype(dt)
+    st.trace = StepTrace(g_processed, g, m_exact, u_base, lam_trust * alpha_auto)
     if h.lookahead != "none":
         st.window.append(st.theta.copy())
     return s
@@ -348,28 +348,19 @@ def lookahead_sync(st: TensorState, h: Hyper) -> None:
     st.window = []
 
 
-def blend_buffer(st: TensorState, h: Hyper) -> np.ndarray:
-    """(1-alpha_LA)*slow_0 + (alpha_LA/k)*sum of the window's iterates so far, in double.
+def step_all(states: List[TensorState], grads, t: int, h: Hyper, aux: Optional[AutoLrState] = None,
+             stored_m: Optional[list] = None) -> float:
+    """One step over a tensor list: the step-wide auto-LR factor first (Phase 7), then every tensor.
 
-    Not part of the method: an observable of the stored window that equals Eq. 30's right-hand side
-    once the window is full.  Tests use it to check single-buffer running-blend implementations.
-    """
-    slow0 = st.slow0.astype(np.float64)
-    acc = (1.0 - h.la_alpha) * slow0
-    for th in st.window:
-        acc = acc + (h.la_alpha / h.la_k) * th.astype(np.float64)
-    return acc
-
-
-def step_all(states: List[TensorState], grads, t: int, h: Hyper, aux: Optional[AutoLrState] = None) -> float:
-    """One step over a tensor list: the step-wide auto-LR factor first (Phase 7), then every tensor."""
+    Returns alpha_auto; every tensor's lambda_trust * alpha_auto is left in its trace.  `stored_m`:
+    one entry per tensor, see `step`."""
     alpha_auto = 1.0
     if h.auto_lr:
         assert aux is not None, "auto_lr needs its two EMA scalars"
         alpha_auto = auto_lr_scale(aux, [st.theta for st in states], grads, h)
     g_scale = clip_scale(grads, h)
-    for st, g in zip(states, grads):
-        step(st, g, t, h, alpha_auto, g_scale)
+    for i, (st, g) in enumerate(zip(states, grads)):
+        step(st, g, t, h, alpha_auto, g_scale, None if stored_m is None else stored_m[i])
     return alpha_auto
 
 

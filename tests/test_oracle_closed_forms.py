@@ -172,12 +172,14 @@ def test_lookahead_sync_leaves_moments_and_timing():
 
 
 def test_blend_buffer_equals_sync_value_at_full_window():
-    """The running blend (1-a)*slow0 + (a/k)*sum(theta_i) is Eq. 30's right-hand side when i = k."""
+    """The running blend (1-a)*slow0 + (a/k)*sum(theta_i) that the harness compares single-buffer
+    implementations with is Eq. 30's right-hand side when i = k."""
+    from tests.harness import blend_buffer
     h = O.Hyper(lookahead="memory_efficient", la_k=4, la_alpha=0.7, nesterov="approx", rectified=True)
     rng = np.random.default_rng(2)
     st = O.init_state(THETA0, h, np.float64)
     for t in range(1, 5):
         O.step(st, rng.normal(0, 1e-2, 4), t, h)
-    blend = O.blend_buffer(st, h)
+    blend = blend_buffer(st, h)
     O.lookahead_sync(st, h)
     np.testing.assert_allclose(st.theta, blend, rtol=1e-13)

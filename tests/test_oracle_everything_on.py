@@ -180,8 +180,8 @@ MUTATIONS = {
                                       "        alpha_auto = auto_lr_scale(aux, [st.theta for st in states], [np.asarray(g) * clip_scale(grads, h) for g in grads], h)\n"),
     "decay_scaled_by_trust": ("theta = theta * s.decay - alpha_eff * u", "theta = theta * (1.0 - (1.0 - s.decay) * lam_trust) - alpha_eff * u"),
     "clip_always_normalises": ("return h.clip_threshold / norm if norm > h.clip_threshold else 1.0", "return h.clip_threshold / norm"),
-    "clip_per_tensor": ("    for st, g in zip(states, grads):\n        step(st, g, t, h, alpha_auto, g_scale)",
-                        "    for st, g in zip(states, grads):\n        step(st, g, t, h, alpha_auto, clip_scale([g], h))"),
+    "clip_per_tensor": ("        step(st, g, t, h, alpha_auto, g_scale, None if stored_m is None else stored_m[i])",
+                        "        step(st, g, t, h, alpha_auto, clip_scale([g], h), None if stored_m is None else stored_m[i])"),
     "centralize_over_rows": ("g2d.mean(axis=1, keepdims=True)", "g2d.mean(axis=0, keepdims=True)"),
     "centralize_whole_tensor": ("g2d.mean(axis=1, keepdims=True)", "g2d.mean()"),
     "centralize_after_nesterov": ("    if h.use_gc and st.rows >= 1:\n", "    if False:\n"),
