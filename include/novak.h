@@ -18,8 +18,14 @@
  *
  * All tensor memory is DEVICE memory owned by the caller (fp32, contiguous).  The library owns only
  * the handle, its chunk table and a small gradient-pointer table.  Every call returns a status
- * code; nothing throws or aborts across this boundary.  Calls on one handle must not overlap.
- * Kernels are enqueued on the HIP stream the caller passes and return without synchronising.
+ * code; nothing throws or aborts across this boundary.
+ *
+ * Ordering.  Every call returns as soon as its kernels are enqueued on the HIP stream the caller passes;
+ * nothing synchronises.  All calls on one handle must therefore be STREAM-ORDERED, not merely
+ * non-overlapping on the host: the handle's device tables (gradient-pointer list, reduction buffers, row
+ * means, clipping factor) are single-buffered and protected only by the order of the stream they were
+ * last used on.  Use one stream per handle, or make the next call's stream wait (hipStreamWaitEvent) on
+ * an event recorded after the previous call.  Two host threads must not call into one handle at once.
  */
 #ifndef NOVAK_H_
 #define NOVAK_H_
@@ -256,9 +262,13 @@ const char *novak_status_string(int status);
 
 /* ---- device entry points ---------------------------------------------------------------------- */
 
-/* Validates and downgrades `hp`, checks every descriptor, builds the chunk table and uploads it to
- * device `device_id`.  Allocates no parameter-sized memory and launches no kernel.  `tensors` is
- * host memory and is copied.  n_tensors >= 0.  On failure *out is NULL. */
+/* Algorithm 1's header (section 5.2: inputs, hyper-parameters, initialisation) as an object: validates
+ * `hp` by the rules of section 5.8 and applies the fast-path downgrades of section 7.3, checks every
+ * descriptor, builds the multi-tensor chunk table and uploads it to device `device_id`.  Allocates no
+ * parameter-sized memory and launches no kernel (m_0 = v_0 = 0 and Eq. 28 are the caller's buffers and
+ * novak_lookahead_init).  `tensors` is host memory and is copied.  n_tensors >= 0.  A list that one
+ * kernel launch cannot cover (more than 2^32 - 1 threads, about 1.7e10 elements) is refused with
+ * NOVAK_ERR_INVALID_ARG.  On failure *out is NULL and novak_last_error(NULL) holds the reason. */
 int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor_desc *tensors,
                  int32_t n_tensors, int32_t device_id);
 
@@ -298,8 +308,9 @@ int novak_nesterov_extrapolate(novak_handle *h, void *const *out, void *hip_stre
  * new slow weights.  Legal only when a sync is due. */
 int novak_lookahead_sync(novak_handle *h, void *hip_stream);
 
-/* Frees the handle and its tables (waits for nothing: the caller synchronises its stream first).
- * NULL is a no-op. */
+/* End of Algorithm 1's loop: frees the handle and its tables.  The optimizer state of Table 3 (theta, m,
+ * v, lookahead buffer) is the caller's and is untouched; together with the step count it is all that
+ * resuming needs.  Waits for nothing: the caller synchronises its stream first.  NULL is a no-op. */
 int novak_destroy(novak_handle *h);
 
 int novak_get_info(const novak_handle *h, novak_info *info);

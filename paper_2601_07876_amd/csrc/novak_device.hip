@@ -16,16 +16,11 @@ namespace {
 thread_local std::string g_create_error = "";
 }  // namespace
 
-// ------------------------------------------------------------------------------------------------
-// handle
-// ------------------------------------------------------------------------------------------------
-struct novak_handle {
+// Everything a kernel launch needs: effective hyper-parameters, geometry, tuning and the device-side
+// tables (kept apart from the handle's host-side bookkeeping so that launches depend on nothing else).
+struct LaunchCtx {
   novak_hparams hp;                 // effective hyper-parameters
-  uint32_t warnings = 0;
-  int32_t device_id = 0;
-  std::vector<novak_tensor_desc> tensors;
-  std::vector<int64_t> numels;
-  int64_t total_numel = 0;
+  int32_t n_tensors = 0;
   int64_t chunk_elems = NOVAK_CHUNK_DEFAULT;
   int64_t n_chunks = 0;
   int nontemporal = 1;
@@ -33,17 +28,14 @@ struct novak_handle {
   int threads = 64;                 // workgroup size: 64, 128 or 256 (one to four wave64)
   int waves_per_cu = 0;             // cap on resident waves per compute unit; 0 = chosen per kernel variant
   int lds_per_cu = 160 * 1024;      // LDS of one compute unit (queried at create)
-  int64_t last_step = 0;
-  int sync_due = 0;
-  // two-pass path (layer adaptation / auto-LR): library-owned reduction scratch, rebuilt with the table
+  // reduction scratch of the two-pass path (layer adaptation / auto-LR) and of the clipping pre-pass
   NormPartial *d_partials = nullptr;   // one per wave of pass 1
   NormSums *d_chunk_sums = nullptr;    // one per chunk
   NormSums *d_tensor_sums = nullptr;   // one per tensor
   int *d_first_chunk = nullptr;        // n_tensors + 1: chunk range of each tensor
   float *d_scale = nullptr;            // n_tensors: lambda_trust * alpha_auto
   float *d_gscale = nullptr;           // one float: gradient-clipping factor of the current step
-  float **d_out_ptrs = nullptr;        // n_tensors output pointers of novak_nesterov_extrapolate (allocated in create)
-  // gradient centralization (built once in novak_create)
+  // gradient centralization
   GcInfo *d_gc = nullptr;              // per tensor
   int *d_gc_tensor = nullptr;          // centralized tensors
   int64_t *d_row_first = nullptr;      // their first rows (prefix sums, n_gc + 1)
@@ -51,9 +43,23 @@ struct novak_handle {
   int n_gc = 0;
   int64_t total_rows = 0;
   double *d_ema = nullptr;             // caller-owned: g_bar, theta_bar
-  // device-side tables (owned)
+  // tables
   novak_chunk *d_chunks = nullptr;
   void *d_ptrs = nullptr;           // n_tensors TensorPtrs records, then n_tensors gradient pointers
+};
+
+// ------------------------------------------------------------------------------------------------
+// handle
+// ------------------------------------------------------------------------------------------------
+struct novak_handle : LaunchCtx {
+  uint32_t warnings = 0;
+  int32_t device_id = 0;
+  std::vector<novak_tensor_desc> tensors;
+  std::vector<int64_t> numels;
+  int64_t total_numel = 0;
+  int64_t last_step = 0;
+  int sync_due = 0;
+  float **d_out_ptrs = nullptr;        // n_tensors output pointers of novak_nesterov_extrapolate (allocated in create)
   // pinned staging ring for the per-step gradient pointer list
   static constexpr int kRing = 4;
   void **h_ring = nullptr;
@@ -106,8 +112,8 @@ struct DeviceScope {
   }
 };
 
-Tables tables_of(const novak_handle *h) {
-  const size_t n = h->tensors.size();
+Tables tables_of(const LaunchCtx *h) {
+  const size_t n = static_cast<size_t>(h->n_tensors);
   char *base = static_cast<char *>(h->d_ptrs);
   Tables tb;
   tb.chunks = h->d_chunks;
@@ -118,9 +124,9 @@ Tables tables_of(const novak_handle *h) {
   return tb;
 }
 
-bool two_pass(const novak_handle *h) { return h->hp.layer_adaptation || h->hp.auto_lr; }
-bool clipping(const novak_handle *h) { return h->hp.clip_threshold > 0.0; }
-bool needs_reductions(const novak_handle *h) { return two_pass(h) || clipping(h); }
+bool two_pass(const LaunchCtx *h) { return h->hp.layer_adaptation || h->hp.auto_lr; }
+bool clipping(const LaunchCtx *h) { return h->hp.clip_threshold > 0.0; }
+bool needs_reductions(const LaunchCtx *h) { return two_pass(h) || clipping(h); }
 
 void free_device_tables(novak_handle *h) {
   if (h->d_chunks) (void)hipFree(h->d_chunks);
@@ -140,6 +146,8 @@ void free_device_tables(novak_handle *h) {
 }
 
 int build_chunk_table_unguarded(novak_handle *h);
+bool fits_one_launch(int64_t n_chunks, int64_t chunk_elems);
+constexpr const char *kTooLarge = "the tensor list needs more than 2^32 - 1 threads in one launch (about 1.7e10 elements); split it over several handles";
 
 // (Re)build and upload the chunk table for the current chunk_elems.  Synchronous.  If it fails after the
 // old tables were released the handle keeps no tables at all and refuses further work.
@@ -156,8 +164,7 @@ int build_chunk_table_unguarded(novak_handle *h) {
   int64_t n = 0;
   int rc = novak_plan_chunks(h->numels.data(), static_cast<int32_t>(h->numels.size()), h->chunk_elems, nullptr, 0, &n);
   if (rc != NOVAK_OK) return fail(h, rc, "chunk planning failed");
-  // one workgroup per 256 elements of a chunk at the finest decomposition
-  if (n * (h->chunk_elems / kMinSub) > 0x7fffffffLL) return fail(h, NOVAK_ERR_INVALID_ARG, "too many workgroups for one launch");
+  if (!fits_one_launch(n, h->chunk_elems)) return fail(h, NOVAK_ERR_INVALID_ARG, kTooLarge);
   std::vector<novak_chunk> table(static_cast<size_t>(n));
   rc = novak_plan_chunks(h->numels.data(), static_cast<int32_t>(h->numels.size()), h->chunk_elems, table.data(), n, &n);
   if (rc != NOVAK_OK) return fail(h, rc, "chunk planning failed");
@@ -213,7 +220,7 @@ struct Geometry {
 // step peak one or two waves later; the budgets below are the compromise (78, and 84 for the two-pass
 // kernels).  Residency is capped by requesting LDS that the kernel never touches.
 constexpr double kStepBudget = 78.0, kTwoPassBudget = 84.0;
-Geometry geometry_of(const novak_handle *h, int sub_elems, int threads, int wide, int narrow = 0, double budget = kStepBudget) {
+Geometry geometry_of(const LaunchCtx *h, int sub_elems, int threads, int wide, int narrow = 0, double budget = kStepBudget) {
   Geometry gm;
   gm.sub_shift = log2_exact(h->chunk_elems / sub_elems);
   gm.grid = static_cast<unsigned>(h->n_chunks << gm.sub_shift);
@@ -262,7 +269,7 @@ void launch_step_la(int la, const Geometry &gm, hipStream_t s, const Tables &tb,
 }
 
 template <bool NT, int UN, int BLOCK>
-void launch_step_dtype(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+void launch_step_dtype(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
   const StreamCount n = step_streams(grad_dtype, la, false);
   const Geometry gm = geometry_of(h, BLOCK * 4 * UN, BLOCK, n.wide, n.narrow);
   if (grad_dtype == NOVAK_GRAD_BF16) launch_step_la<unsigned short, u16x4, NT, UN, BLOCK>(la, gm, s, tb, c);
@@ -270,7 +277,7 @@ void launch_step_dtype(const novak_handle *h, int grad_dtype, int la, hipStream_
 }
 
 template <bool NT, int BLOCK>
-void launch_step_un(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+void launch_step_un(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
   switch (h->vec_per_lane) {
     case 1: launch_step_dtype<NT, 1, BLOCK>(h, grad_dtype, la, s, tb, c); break;
     case 2: launch_step_dtype<NT, 2, BLOCK>(h, grad_dtype, la, s, tb, c); break;
@@ -279,7 +286,7 @@ void launch_step_un(const novak_handle *h, int grad_dtype, int la, hipStream_t s
 }
 
 template <bool NT>
-void launch_step_block(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+void launch_step_block(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
   switch (h->threads) {
     case 64: launch_step_un<NT, 64>(h, grad_dtype, la, s, tb, c); break;
     case 128: launch_step_un<NT, 128>(h, grad_dtype, la, s, tb, c); break;
@@ -290,7 +297,7 @@ void launch_step_block(const novak_handle *h, int grad_dtype, int la, hipStream_
 // Centralization and the bfloat16 first moment are compiled into the default launch shape only
 // (one wave64 per 256 elements).
 template <typename GradS, typename GradV, bool NT, bool GC, typename MomS, typename MomV>
-void launch_step_special(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+void launch_step_special(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
   const StreamCount n = step_streams(grad_dtype, la, sizeof(MomS) == 2);
   const Geometry gm = geometry_of(h, 256, 64, n.wide, n.narrow);
   const dim3 grid(gm.grid), block(64);
@@ -304,7 +311,7 @@ void launch_step_special(const novak_handle *h, int grad_dtype, int la, hipStrea
 }
 
 template <bool GC, typename MomS, typename MomV>
-void launch_step_special_dtype(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+void launch_step_special_dtype(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
   if (grad_dtype == NOVAK_GRAD_BF16) {
     if (h->nontemporal) launch_step_special<unsigned short, u16x4, true, GC, MomS, MomV>(h, grad_dtype, la, s, tb, c);
     else launch_step_special<unsigned short, u16x4, false, GC, MomS, MomV>(h, grad_dtype, la, s, tb, c);
@@ -314,7 +321,7 @@ void launch_step_special_dtype(const novak_handle *h, int grad_dtype, int la, hi
   }
 }
 
-void launch_step(const novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+void launch_step(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
   const bool gc = (c.flags & F_GC) != 0;
   const bool bf16_m = h->hp.moment_dtype == NOVAK_MOMENT_BF16_M;
   if (gc && bf16_m) return launch_step_special_dtype<true, unsigned short, u16x4>(h, grad_dtype, la, s, tb, c);
@@ -324,25 +331,24 @@ void launch_step(const novak_handle *h, int grad_dtype, int la, hipStream_t s, c
   else launch_step_block<false>(h, grad_dtype, la, s, tb, c);
 }
 
-int launch_rowmeans(novak_handle *h, int grad_dtype, hipStream_t s, const Tables &tb) {
+hipError_t launch_rowmeans(const LaunchCtx *h, int grad_dtype, hipStream_t s, const Tables &tb) {
   const dim3 grid(static_cast<unsigned>(h->total_rows)), block(64);
   if (grad_dtype == NOVAK_GRAD_BF16)
     hipLaunchKernelGGL((novak_rowmean_kernel<unsigned short>), grid, block, 0, s, tb.grad, h->d_gc_tensor, h->d_row_first, h->n_gc, h->d_gc, h->d_row_means);
   else
     hipLaunchKernelGGL((novak_rowmean_kernel<float>), grid, block, 0, s, tb.grad, h->d_gc_tensor, h->d_row_first, h->n_gc, h->d_gc, h->d_row_means);
-  NOVAK_HIP(h, hipGetLastError());
-  return NOVAK_OK;
+  return hipGetLastError();
 }
 
 template <int OP, int BLOCK>
-void launch_la_block(const novak_handle *h, hipStream_t s, const Tables &tb, float c0, float c1) {
+void launch_la_block(const LaunchCtx *h, hipStream_t s, const Tables &tb, float c0, float c1) {
   const Geometry gm = geometry_of(h, BLOCK * 4, BLOCK, OP == SYNC_BASIC ? 4 : 2);
   if (h->nontemporal) hipLaunchKernelGGL((novak_lookahead_kernel<OP, true, BLOCK>), dim3(gm.grid), dim3(BLOCK), gm.lds, s, tb, c0, c1, gm.sub_shift);
   else hipLaunchKernelGGL((novak_lookahead_kernel<OP, false, BLOCK>), dim3(gm.grid), dim3(BLOCK), gm.lds, s, tb, c0, c1, gm.sub_shift);
 }
 
 template <int OP>
-void launch_la(const novak_handle *h, hipStream_t s, const Tables &tb, float c0, float c1) {
+void launch_la(const LaunchCtx *h, hipStream_t s, const Tables &tb, float c0, float c1) {
   switch (h->threads) {
     case 64: launch_la_block<OP, 64>(h, s, tb, c0, c1); break;
     case 128: launch_la_block<OP, 128>(h, s, tb, c0, c1); break;
@@ -363,7 +369,7 @@ void launch_apply(int la, const Geometry &gm, hipStream_t s, const Tables &tb, c
 }
 
 template <typename MomS, typename MomV>
-void launch_moments(const novak_handle *h, int grad_dtype, const Geometry &g1, hipStream_t s, const Tables &tb, const Consts &c) {
+void launch_moments(const LaunchCtx *h, int grad_dtype, const Geometry &g1, hipStream_t s, const Tables &tb, const Consts &c) {
   const dim3 grid1(g1.grid), block(kScaledBlock);
   const bool nt = h->nontemporal != 0;
   if (grad_dtype == NOVAK_GRAD_BF16) {
@@ -376,7 +382,7 @@ void launch_moments(const novak_handle *h, int grad_dtype, const Geometry &g1, h
 }
 
 // Clipping pre-pass: gradient norm partials -> chunk sums -> tensor sums -> global factor in d_gscale.
-int launch_clip_prepass(novak_handle *h, int grad_dtype, hipStream_t s, const Tables &tb) {
+hipError_t launch_clip_prepass(const LaunchCtx *h, int grad_dtype, hipStream_t s, const Tables &tb) {
   const Geometry g0 = geometry_of(h, kNormSub, kScaledBlock, 1);        // a single read stream: full residency
   const dim3 grid(g0.grid), block(kScaledBlock);
   const bool nt = h->nontemporal != 0;
@@ -389,18 +395,17 @@ int launch_clip_prepass(novak_handle *h, int grad_dtype, hipStream_t s, const Ta
   }
   ScaleParams sp;
   std::memset(&sp, 0, sizeof(sp));
-  const int nt_count = static_cast<int>(h->tensors.size());
+  const int nt_count = h->n_tensors;
   hipLaunchKernelGGL(novak_reduce_chunks_kernel, dim3(static_cast<unsigned>(h->n_chunks)), dim3(64), 0, s, h->d_chunks, g0.sub_shift,
                      kNormSub, h->d_partials, h->d_chunk_sums);
   hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(64), 0, s, h->d_first_chunk, h->d_chunk_sums,
                      h->d_tensor_sums, h->d_scale, sp);
   hipLaunchKernelGGL(novak_clip_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, static_cast<float>(h->hp.clip_threshold), h->d_gscale);
-  NOVAK_HIP(h, hipGetLastError());
-  return NOVAK_OK;
+  return hipGetLastError();
 }
 
 // The two-pass step: moments + norm partials, fixed-order reductions, scaled apply.
-int launch_scaled_step(novak_handle *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+hipError_t launch_scaled_step(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
   const novak_hparams &hp = h->hp;
   const bool bf16_m = hp.moment_dtype == NOVAK_MOMENT_BF16_M;
   const bool bf16_g = grad_dtype == NOVAK_GRAD_BF16;
@@ -409,7 +414,8 @@ int launch_scaled_step(novak_handle *h, int grad_dtype, int la, hipStream_t s, c
   const bool nt = h->nontemporal != 0;
   if (bf16_m) launch_moments<unsigned short, u16x4>(h, grad_dtype, g1, s, tb, c);
   else launch_moments<float, f32x4>(h, grad_dtype, g1, s, tb, c);
-  NOVAK_HIP(h, hipGetLastError());
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   ScaleParams sp;
   sp.trust_lo = static_cast<float>(hp.trust_clip_lo);
   sp.trust_hi = static_cast<float>(hp.trust_clip_hi);
@@ -418,14 +424,14 @@ int launch_scaled_step(novak_handle *h, int grad_dtype, int la, hipStream_t s, c
   sp.gamma = hp.auto_lr_gamma;
   sp.layer_adaptation = hp.layer_adaptation;
   sp.auto_lr = hp.auto_lr;
-  const int nt_count = static_cast<int>(h->tensors.size());
+  const int nt_count = h->n_tensors;
   hipLaunchKernelGGL(novak_reduce_chunks_kernel, dim3(static_cast<unsigned>(h->n_chunks)), dim3(64), 0, s, h->d_chunks, g1.sub_shift,
                      kScaledSub, h->d_partials, h->d_chunk_sums);
   hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(64), 0, s, h->d_first_chunk, h->d_chunk_sums,
                      h->d_tensor_sums, h->d_scale, sp);
   if (hp.auto_lr)
     hipLaunchKernelGGL(novak_auto_lr_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, h->d_scale, h->d_ema, sp);
-  NOVAK_HIP(h, hipGetLastError());
+  if ((e = hipGetLastError()) != hipSuccess) return e;
   int s2 = 3 + (bf16_m ? 0 : 1);                    // pass 2: theta, m, v read; theta written
   if (la_reads(la)) s2 += 1;
   if (la_writes(la)) s2 += 1;
@@ -437,12 +443,11 @@ int launch_scaled_step(novak_handle *h, int grad_dtype, int la, hipStream_t s, c
     if (nt) launch_apply<true, float, f32x4>(la, g2, s, tb, c, h->d_scale);
     else launch_apply<false, float, f32x4>(la, g2, s, tb, c, h->d_scale);
   }
-  NOVAK_HIP(h, hipGetLastError());
-  return NOVAK_OK;
+  return hipGetLastError();
 }
 
-int launch_sync(novak_handle *h, hipStream_t s) {
-  if (h->n_chunks == 0) return NOVAK_OK;
+hipError_t launch_sync(const LaunchCtx *h, hipStream_t s) {
+  if (h->n_chunks == 0) return hipSuccess;
   const Tables tb = tables_of(h);
   if (h->hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT) {
     launch_la<SYNC_ME>(h, s, tb, 0.0f, 0.0f);
@@ -451,7 +456,131 @@ int launch_sync(novak_handle *h, hipStream_t s) {
     const float c0 = static_cast<float>(1.0 - h->hp.la_alpha);
     launch_la<SYNC_BASIC>(h, s, tb, c0, c1);
   }
-  NOVAK_HIP(h, hipGetLastError());
+  return hipGetLastError();
+}
+
+// What step t does, derived once on the host: the kernel constants (scalar prologue of Phases 5-6 rounded
+// to fp32) and the lookahead phase of the step (its position in the k-step window of section 4.7).
+struct StepPlan {
+  Consts c;
+  int la = LA_OFF;
+  bool window_closes = false;   // t mod k == 0
+  bool sync_after = false;      // k == 1 with auto_sync: the sync cannot be fused into a later step of the window
+};
+
+int plan_step(const novak_hparams &hp, int64_t step, StepPlan *pl) {
+  novak_step_scalars sc;
+  const int rc = novak_compute_step_scalars(&hp, step, &sc);
+  if (rc != NOVAK_OK) return rc;
+  Consts &c = pl->c;
+  std::memset(&c, 0, sizeof(c));
+  c.omb1 = static_cast<float>(1.0 - sc.beta1_t);      // the moment updates follow Eq. 3-4 when scheduled
+  c.omb2 = static_cast<float>(1.0 - sc.beta2_t);
+  c.blend_w = static_cast<float>(1.0 - hp.beta1);
+  c.beta1 = static_cast<float>(hp.beta1);
+  c.beta_n = static_cast<float>(hp.beta_n);
+  c.inv_bc1 = static_cast<float>(1.0 / sc.bc1);
+  c.inv_bc2 = static_cast<float>(1.0 / sc.bc2);
+  c.eps = static_cast<float>(hp.eps);
+  c.step_size = static_cast<float>(sc.step_size);
+  c.lr_wd = hp.decoupled_decay ? static_cast<float>(hp.lr * hp.weight_decay) : 0.0f;
+  c.wd = hp.decoupled_decay ? 0.0f : static_cast<float>(hp.weight_decay);
+  c.flags = 0;
+  if (sc.nesterov_mode == NOVAK_NESTEROV_APPROX) c.flags |= F_APPROX;
+  if (hp.nesterov_mode == NOVAK_NESTEROV_CLASSICAL) c.flags |= F_CLASSICAL;
+  if (sc.denom_on) c.flags |= F_DENOM;
+  if (!hp.decoupled_decay && hp.weight_decay != 0.0) c.flags |= F_COUPLED;
+  if (hp.clip_threshold > 0.0) c.flags |= F_CLIP;
+  if (hp.sparse_threshold > 0.0) {
+    c.flags |= F_SPARSE;
+    c.sparse_tau = static_cast<float>(hp.sparse_threshold);
+  }
+  // lookahead phase of this step: position in the k-step window (section 4.7; sync when t mod k == 0)
+  pl->la = LA_OFF;
+  pl->window_closes = pl->sync_after = false;
+  if (hp.lookahead_mode != NOVAK_LOOKAHEAD_NONE) {
+    const int64_t pos = (step - 1) % hp.la_k + 1;
+    pl->window_closes = pos == hp.la_k;
+    if (hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT) {
+      c.la_c0 = static_cast<float>(1.0 - hp.la_alpha);
+      c.la_c1 = static_cast<float>(hp.la_alpha / hp.la_k);
+      if (pos == 1) {
+        pl->la = LA_FIRST;
+        pl->sync_after = pl->window_closes && hp.auto_sync;   // k == 1: nothing to fuse into
+      } else if (pl->window_closes && hp.auto_sync) {
+        pl->la = LA_LAST_FUSED;
+      } else {
+        pl->la = LA_MID;
+      }
+    } else if (pl->window_closes && hp.auto_sync) {
+      pl->la = LA_BASIC_FUSED;
+      c.la_c0 = static_cast<float>(1.0 - hp.la_alpha);
+      c.la_c1 = static_cast<float>(hp.la_alpha);
+    }
+  }
+  return NOVAK_OK;
+}
+
+// Enqueues every kernel of one step on `stream`: the gradient pre-passes, the single-pass or two-pass
+// update, and the separate sync where the plan asks for one.  The tables of `cx` (gradient pointers
+// included) must already be in place in stream order.
+hipError_t enqueue_step(const LaunchCtx *cx, int grad_dtype, const StepPlan &pl, hipStream_t stream) {
+  if (cx->n_chunks == 0) return hipSuccess;
+  Consts c = pl.c;
+  hipError_t e;
+  if (clipping(cx) && (e = launch_clip_prepass(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
+  if (cx->n_gc > 0) {
+    c.flags |= F_GC;
+    if ((e = launch_rowmeans(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
+  }
+  if (two_pass(cx)) {
+    if ((e = launch_scaled_step(cx, grad_dtype, pl.la, stream, tables_of(cx), c)) != hipSuccess) return e;
+  } else {
+    launch_step(cx, grad_dtype, pl.la, stream, tables_of(cx), c);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  if (pl.sync_after) return launch_sync(cx, stream);
+  return hipSuccess;
+}
+
+// A launch is limited to 2^32 - 1 threads.  At the finest decomposition (one wave64 per 256 elements) a list
+// whose chunks cover `covered` elements needs covered / 4 threads.
+bool fits_one_launch(int64_t n_chunks, int64_t chunk_elems) {
+  return n_chunks <= (int64_t{0xffffffffLL} / 64) / (chunk_elems / kMinSub);
+}
+
+// Descriptor checks of novak_create.  On failure writes the reason.
+int check_descs(const novak_hparams &eff, const novak_tensor_desc *tensors, int32_t n_tensors, std::string *why) {
+  for (int32_t i = 0; i < n_tensors; ++i) {
+    const novak_tensor_desc &d = tensors[i];
+    const std::string who = "tensor " + std::to_string(i);
+    if (d.numel < 0) { *why = who + ": numel < 0"; return NOVAK_ERR_INVALID_ARG; }
+    if (d.numel == 0) continue;
+    if (!d.param || !d.exp_avg || !d.exp_avg_sq) { *why = who + ": param/exp_avg/exp_avg_sq is NULL"; return NOVAK_ERR_NULL_POINTER; }
+    if (eff.lookahead_mode != NOVAK_LOOKAHEAD_NONE && !d.la_buf) { *why = who + ": la_buf is NULL with lookahead on"; return NOVAK_ERR_NULL_POINTER; }
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(d.param) | reinterpret_cast<uintptr_t>(d.exp_avg_sq) | reinterpret_cast<uintptr_t>(d.la_buf);
+    if (bits & 3u) { *why = who + ": pointer not 4-byte aligned"; return NOVAK_ERR_MISALIGNED; }
+    if (reinterpret_cast<uintptr_t>(d.exp_avg) & (eff.moment_dtype == NOVAK_MOMENT_BF16_M ? 1u : 3u)) {
+      *why = who + ": exp_avg not aligned to its element size";
+      return NOVAK_ERR_MISALIGNED;
+    }
+    if (eff.use_gc && (d.rows < 0 || (d.rows > 0 && d.numel % d.rows != 0))) {
+      *why = who + ": rows must be >= 0 and divide numel";
+      return NOVAK_ERR_INVALID_ARG;
+    }
+  }
+  return NOVAK_OK;
+}
+
+int check_grads(const novak_tensor_desc *tensors, size_t n, void *const *grads, int32_t grad_dtype, std::string *why) {
+  if (n > 0 && !grads) { *why = "grads is NULL"; return NOVAK_ERR_NULL_POINTER; }
+  if (grad_dtype != NOVAK_GRAD_F32 && grad_dtype != NOVAK_GRAD_BF16) { *why = "unknown grad_dtype"; return NOVAK_ERR_INVALID_ARG; }
+  const uintptr_t amask = grad_dtype == NOVAK_GRAD_BF16 ? 1u : 3u;
+  for (size_t i = 0; i < n; ++i) {
+    if (tensors[i].numel == 0) continue;
+    if (!grads[i]) { *why = "grads[" + std::to_string(i) + "] is NULL"; return NOVAK_ERR_NULL_POINTER; }
+    if (reinterpret_cast<uintptr_t>(grads[i]) & amask) { *why = "grads[" + std::to_string(i) + "] not aligned to its element size"; return NOVAK_ERR_MISALIGNED; }
+  }
   return NOVAK_OK;
 }
 
@@ -474,18 +603,16 @@ static int create_impl(novak_handle **out, const novak_hparams *hp, const novak_
   uint32_t warn = 0;
   int rc = novak_validate_hparams(hp, &eff, &warn);
   if (rc != NOVAK_OK) return fail(nullptr, rc, "hyper-parameters rejected (section 5.8 validation rules)");
-  for (int32_t i = 0; i < n_tensors; ++i) {
-    const novak_tensor_desc &d = tensors[i];
-    if (d.numel < 0) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "tensor " + std::to_string(i) + ": numel < 0");
-    if (d.numel == 0) continue;
-    if (!d.param || !d.exp_avg || !d.exp_avg_sq) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "tensor " + std::to_string(i) + ": param/exp_avg/exp_avg_sq is NULL");
-    if (eff.lookahead_mode != NOVAK_LOOKAHEAD_NONE && !d.la_buf) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "tensor " + std::to_string(i) + ": la_buf is NULL with lookahead on");
-    const uintptr_t bits = reinterpret_cast<uintptr_t>(d.param) | reinterpret_cast<uintptr_t>(d.exp_avg_sq) | reinterpret_cast<uintptr_t>(d.la_buf);
-    if (bits & 3u) return fail(nullptr, NOVAK_ERR_MISALIGNED, "tensor " + std::to_string(i) + ": pointer not 4-byte aligned");
-    if (reinterpret_cast<uintptr_t>(d.exp_avg) & (eff.moment_dtype == NOVAK_MOMENT_BF16_M ? 1u : 3u))
-      return fail(nullptr, NOVAK_ERR_MISALIGNED, "tensor " + std::to_string(i) + ": exp_avg not aligned to its element size");
-    if (eff.use_gc && (d.rows < 0 || (d.rows > 0 && d.numel % d.rows != 0)))
-      return fail(nullptr, NOVAK_ERR_INVALID_ARG, "tensor " + std::to_string(i) + ": rows must be >= 0 and divide numel");
+  std::string why;
+  rc = check_descs(eff, tensors, n_tensors, &why);
+  if (rc != NOVAK_OK) return fail(nullptr, rc, why);
+  {  // refuse, before anything touches the device, a list that one launch cannot cover
+    int64_t planned = 0;
+    std::vector<int64_t> sizes(static_cast<size_t>(n_tensors));
+    for (int32_t i = 0; i < n_tensors; ++i) sizes[static_cast<size_t>(i)] = tensors[i].numel;
+    rc = novak_plan_chunks(sizes.data(), n_tensors, NOVAK_CHUNK_DEFAULT, nullptr, 0, &planned);
+    if (rc != NOVAK_OK) return fail(nullptr, rc, "chunk planning failed");
+    if (!fits_one_launch(planned, NOVAK_CHUNK_DEFAULT)) return fail(nullptr, NOVAK_ERR_INVALID_ARG, kTooLarge);
   }
 
   novak_handle *h = new (std::nothrow) novak_handle();
@@ -497,6 +624,7 @@ static int create_impl(novak_handle **out, const novak_hparams *hp, const novak_
   h->hp = eff;
   h->warnings = warn;
   h->device_id = device_id;
+  h->n_tensors = n_tensors;
   h->tensors.assign(tensors, tensors + n_tensors);
   h->numels.resize(static_cast<size_t>(n_tensors));
   for (int32_t i = 0; i < n_tensors; ++i) {
@@ -785,71 +913,17 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
   if (!h) return NOVAK_ERR_NULL_POINTER;
   if (h->broken) return fail(h, NOVAK_ERR_STATE, "the handle lost its tables in a failed novak_set_tuning; destroy it");
   const size_t n = h->tensors.size();
-  if (n > 0 && !grads) return fail(h, NOVAK_ERR_NULL_POINTER, "grads is NULL");
-  if (grad_dtype != NOVAK_GRAD_F32 && grad_dtype != NOVAK_GRAD_BF16) return fail(h, NOVAK_ERR_INVALID_ARG, "unknown grad_dtype");
+  std::string why;
+  int rc = check_grads(h->tensors.data(), n, grads, grad_dtype, &why);
+  if (rc != NOVAK_OK) return fail(h, rc, why);
   if (step < 1) return fail(h, NOVAK_ERR_BAD_STEP, "step must be >= 1 (Eq. 5 is undefined at t = 0)");
   if (h->last_step != 0 && step != h->last_step + 1) return fail(h, NOVAK_ERR_BAD_STEP, "step must be the previous step + 1");
   if (h->sync_due) return fail(h, NOVAK_ERR_STATE, "a lookahead sync is due before the next step");
   if (h->hp.auto_lr && !h->d_ema) return fail(h, NOVAK_ERR_STATE, "auto_lr is on but novak_set_auto_lr_state was not called");
-  const uintptr_t amask = grad_dtype == NOVAK_GRAD_BF16 ? 1u : 3u;
-  for (size_t i = 0; i < n; ++i) {
-    if (h->numels[i] == 0) continue;
-    if (!grads[i]) return fail(h, NOVAK_ERR_NULL_POINTER, "grads[" + std::to_string(i) + "] is NULL");
-    if (reinterpret_cast<uintptr_t>(grads[i]) & amask) return fail(h, NOVAK_ERR_MISALIGNED, "grads[" + std::to_string(i) + "] not aligned to its element size");
-  }
 
-  novak_step_scalars sc;
-  int rc = novak_compute_step_scalars(&h->hp, step, &sc);
+  StepPlan pl;
+  rc = plan_step(h->hp, step, &pl);
   if (rc != NOVAK_OK) return fail(h, rc, "scalar prologue failed");
-
-  const novak_hparams &hp = h->hp;
-  Consts c;
-  std::memset(&c, 0, sizeof(c));
-  c.omb1 = static_cast<float>(1.0 - sc.beta1_t);      // the moment updates follow Eq. 3-4 when scheduled
-  c.omb2 = static_cast<float>(1.0 - sc.beta2_t);
-  c.blend_w = static_cast<float>(1.0 - hp.beta1);
-  c.beta1 = static_cast<float>(hp.beta1);
-  c.beta_n = static_cast<float>(hp.beta_n);
-  c.inv_bc1 = static_cast<float>(1.0 / sc.bc1);
-  c.inv_bc2 = static_cast<float>(1.0 / sc.bc2);
-  c.eps = static_cast<float>(hp.eps);
-  c.step_size = static_cast<float>(sc.step_size);
-  c.lr_wd = hp.decoupled_decay ? static_cast<float>(hp.lr * hp.weight_decay) : 0.0f;
-  c.wd = hp.decoupled_decay ? 0.0f : static_cast<float>(hp.weight_decay);
-  c.flags = 0;
-  if (sc.nesterov_mode == NOVAK_NESTEROV_APPROX) c.flags |= F_APPROX;
-  if (hp.nesterov_mode == NOVAK_NESTEROV_CLASSICAL) c.flags |= F_CLASSICAL;
-  if (sc.denom_on) c.flags |= F_DENOM;
-  if (!hp.decoupled_decay && hp.weight_decay != 0.0) c.flags |= F_COUPLED;
-  if (hp.clip_threshold > 0.0) c.flags |= F_CLIP;
-  if (hp.sparse_threshold > 0.0) {
-    c.flags |= F_SPARSE;
-    c.sparse_tau = static_cast<float>(hp.sparse_threshold);
-  }
-
-  // lookahead phase of this step: position in the k-step window (section 4.7; sync when t mod k == 0)
-  int la = LA_OFF;
-  bool window_closes = false, sync_after = false;
-  if (hp.lookahead_mode != NOVAK_LOOKAHEAD_NONE) {
-    const int64_t pos = (step - 1) % hp.la_k + 1;
-    window_closes = pos == hp.la_k;
-    if (hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT) {
-      c.la_c0 = static_cast<float>(1.0 - hp.la_alpha);
-      c.la_c1 = static_cast<float>(hp.la_alpha / hp.la_k);
-      if (pos == 1) {
-        la = LA_FIRST;
-        sync_after = window_closes && hp.auto_sync;   // k == 1: nothing to fuse into
-      } else if (window_closes && hp.auto_sync) {
-        la = LA_LAST_FUSED;
-      } else {
-        la = LA_MID;
-      }
-    } else if (window_closes && hp.auto_sync) {
-      la = LA_BASIC_FUSED;
-      c.la_c0 = static_cast<float>(1.0 - hp.la_alpha);
-      c.la_c1 = static_cast<float>(hp.la_alpha);
-    }
-  }
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (h->n_chunks > 0) {
@@ -869,29 +943,10 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
       std::memcpy(h->last_grads.data(), grads, n * sizeof(void *));
       h->grads_uploaded = true;
     }
-    if (clipping(h)) {
-      rc = launch_clip_prepass(h, grad_dtype, stream, tables_of(h));
-      if (rc != NOVAK_OK) return rc;
-    }
-    if (h->n_gc > 0) {
-      c.flags |= F_GC;
-      rc = launch_rowmeans(h, grad_dtype, stream, tables_of(h));
-      if (rc != NOVAK_OK) return rc;
-    }
-    if (two_pass(h)) {
-      rc = launch_scaled_step(h, grad_dtype, la, stream, tables_of(h), c);
-      if (rc != NOVAK_OK) return rc;
-    } else {
-      launch_step(h, grad_dtype, la, stream, tables_of(h), c);
-      NOVAK_HIP(h, hipGetLastError());
-    }
-    if (sync_after) {
-      rc = launch_sync(h, stream);
-      if (rc != NOVAK_OK) return rc;
-    }
+    NOVAK_HIP(h, enqueue_step(h, grad_dtype, pl, stream));
   }
   h->last_step = step;
-  h->sync_due = (window_closes && !hp.auto_sync) ? 1 : 0;
+  h->sync_due = (pl.window_closes && !h->hp.auto_sync) ? 1 : 0;
   return NOVAK_OK;
 }
 
@@ -902,8 +957,7 @@ int novak_lookahead_sync(novak_handle *h, void *hip_stream) {
   if (!h->sync_due) return fail(h, NOVAK_ERR_STATE, "no lookahead sync is due (sync follows the steps with t mod k == 0)");
   DeviceScope scope;
   NOVAK_HIP(h, scope.enter(h->device_id));
-  const int rc = launch_sync(h, static_cast<hipStream_t>(hip_stream));
-  if (rc != NOVAK_OK) return rc;
+  NOVAK_HIP(h, launch_sync(h, static_cast<hipStream_t>(hip_stream)));
   h->sync_due = 0;
   return NOVAK_OK;
 }

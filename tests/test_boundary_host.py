@@ -189,6 +189,13 @@ def test_create_rejects_bad_arguments_before_touching_the_gpu():
     assert N.novak_create(hp, [N.novak_tensor_desc(258, 512, 768, 1024, 8)])[0] == N.NOVAK_ERR_MISALIGNED
     assert "aligned" in N.novak_last_error(None)
     assert N.novak_create(hp, [d], -1)[0] == N.NOVAK_ERR_INVALID_ARG
+    # a list that one kernel launch cannot cover (a launch holds < 2^32 threads = 2^26 waves of 256 elements
+    # = 2^34 elements) is refused here, with a reason, and not later by the first step; create dereferences
+    # nothing, so made-up addresses do
+    assert N.novak_create(hp, [N.novak_tensor_desc(1 << 40, 1 << 41, 1 << 42, 1 << 43, 1 << 35)])[0] == N.NOVAK_ERR_INVALID_ARG
+    assert "2^32" in N.novak_last_error(None)
+    assert N.novak_create(hp, [N.novak_tensor_desc(1 << 40, 1 << 41, 1 << 42, 1 << 43, 1 << 33)] * 2)[0] == N.NOVAK_ERR_INVALID_ARG
+    assert "2^32" in N.novak_last_error(None)
     # NULL handle arguments
     assert N.novak_destroy(None) == N.NOVAK_OK
     assert N.novak_step(None, [], 0, 1, 0) == N.NOVAK_ERR_NULL_POINTER
