@@ -308,6 +308,33 @@ int novak_nesterov_extrapolate(novak_handle *h, void *const *out, void *hip_stre
  * new slow weights.  Legal only when a sync is due. */
 int novak_lookahead_sync(novak_handle *h, void *hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): ONE complete single-pass step - what novak_create, novak_step with
+ * auto_sync and novak_destroy do together - without a handle and without any allocation.  The chunk
+ * table, the pointer records and the clipping pre-pass's reduction buffers live in a static device array
+ * of NOVAK_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends; the
+ * tables are written there by a small kernel from its arguments (64 tensors per launch), in stream order
+ * before the update.  Calls no hipMalloc / hipFree / allocating library routine and copies nothing
+ * from host memory.
+ *   hp, tensors, grads, grad_dtype, step: as for novak_create / novak_step (host arrays of device pointers;
+ *     the caller owns all tensor memory).  Supported: every single-pass option (rectification, the Nesterov
+ *     variants, decay, bf16 gradients / first moment, clipping, sparse threshold, lookahead with
+ *     auto_sync = 1).  layer_adaptation, auto_lr, use_gc (after the fast-path downgrade) return
+ *     NOVAK_ERR_NOT_IMPLEMENTED; lookahead with auto_sync = 0 returns NOVAK_ERR_INVALID_ARG.
+ *   Limits: n_tensors <= NOVAK_STATIC_MAX_TENSORS and at most NOVAK_STATIC_MAX_CHUNKS chunk-table entries
+ *     (sum over tensors of ceil(numel / 16384), i.e. up to 2^28 elements); beyond them NOVAK_ERR_INVALID_ARG.
+ *   No state is kept between calls: `step` is not checked against an earlier call, and the lookahead buffers
+ *     must have been initialised by the caller (copy of theta) before the first step of the first window.
+ *   All calls on one GPU share that GPU's array.  A call writes every entry it later reads, so nothing
+ *     depends on the previous call's contents and nothing needs clearing; but two calls whose kernels may
+ *     run at the same time on one GPU (different streams without an event dependency) race on it.
+ *   Errors are reported through the return code and novak_last_error(NULL). */
+#define NOVAK_STATIC_MAX_TENSORS 1024
+#define NOVAK_STATIC_MAX_CHUNKS 16384
+#define NOVAK_STATIC_SCRATCH_BYTES (5u << 20)
+int novak_step_static(const novak_hparams *hp, const novak_tensor_desc *tensors, int32_t n_tensors, void *const *grads,
+                      int32_t grad_dtype, int64_t step, int32_t device_id, void *hip_stream);
+
 /* End of Algorithm 1's loop: frees the handle and its tables.  The optimizer state of Table 3 (theta, m,
  * v, lookahead buffer) is the caller's and is untouched; together with the step count it is all that
  * resuming needs.  Waits for nothing: the caller synchronises its stream first.  NULL is a no-op. */

@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -16,8 +17,39 @@ namespace {
 thread_local std::string g_create_error = "";
 }  // namespace
 
+// ------------------------------------------------------------------------------------------------
+// Static scratch of the allocation-free step (novak_step_static): chunk table, pointer records,
+// gradient pointers and the clipping pre-pass's reduction buffers live here instead of in hipMalloc'ed
+// memory.  Every GPU the library runs on holds its own copy of the array until the process ends; host
+// code reaches it only through the address hipGetSymbolAddress returns for the current device.
+// ------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[NOVAK_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char *g_scratch_ptr[kMaxDevices] = {};   // per device, filled on the first call on that device
+
+// Device address of `scratch` on device `dev`, which must be the current device.
+hipError_t scratch_of(int dev, unsigned char **out) {
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+}  // namespace
+
 // Everything a kernel launch needs: effective hyper-parameters, geometry, tuning and the device-side
-// tables (kept apart from the handle's host-side bookkeeping so that launches depend on nothing else).
+// tables.  A handle owns one whose tables come from hipMalloc; the allocation-free entry point builds one
+// over the library's static scratch array.
 struct LaunchCtx {
   novak_hparams hp;                 // effective hyper-parameters
   int32_t n_tensors = 0;
@@ -549,7 +581,7 @@ bool fits_one_launch(int64_t n_chunks, int64_t chunk_elems) {
   return n_chunks <= (int64_t{0xffffffffLL} / 64) / (chunk_elems / kMinSub);
 }
 
-// Descriptor checks of novak_create.  On failure writes the reason.
+// Descriptor checks shared by novak_create and the allocation-free step.  On failure writes the reason.
 int check_descs(const novak_hparams &eff, const novak_tensor_desc *tensors, int32_t n_tensors, std::string *why) {
   for (int32_t i = 0; i < n_tensors; ++i) {
     const novak_tensor_desc &d = tensors[i];
@@ -960,6 +992,126 @@ int novak_lookahead_sync(novak_handle *h, void *hip_stream) {
   NOVAK_HIP(h, launch_sync(h, static_cast<hipStream_t>(hip_stream)));
   h->sync_due = 0;
   return NOVAK_OK;
+}
+
+// Carves the static scratch array into the regions one call needs; false if they do not fit.
+namespace {
+struct StaticLayout {
+  size_t chunks, ptrs, first_chunk, tensor_sums, scale, gscale, chunk_sums, partials, end;
+};
+size_t align256(size_t x) { return (x + 255u) & ~size_t{255u}; }
+StaticLayout static_layout(size_t n_tensors, size_t n_chunks, bool clip) {
+  StaticLayout L;
+  size_t o = 0;
+  L.chunks = o;       o = align256(o + n_chunks * sizeof(novak_chunk));
+  L.ptrs = o;         o = align256(o + n_tensors * (sizeof(TensorPtrs) + sizeof(void *)));
+  L.first_chunk = o;  o = align256(o + (n_tensors + 1) * sizeof(int));
+  L.tensor_sums = L.scale = L.gscale = L.chunk_sums = L.partials = o;
+  if (clip) {
+    L.tensor_sums = o; o = align256(o + n_tensors * sizeof(NormSums));
+    L.scale = o;       o = align256(o + n_tensors * sizeof(float));
+    L.gscale = o;      o = align256(o + sizeof(float));
+    L.chunk_sums = o;  o = align256(o + n_chunks * sizeof(NormSums));
+    L.partials = o;    o = align256(o + n_chunks * (NOVAK_CHUNK_DEFAULT / kNormSub) * sizeof(NormPartial));
+  }
+  L.end = o;
+  return L;
+}
+}  // namespace
+
+static int step_static_impl(const novak_hparams *hp, const novak_tensor_desc *tensors, int32_t n_tensors, void *const *grads,
+                            int32_t grad_dtype, int64_t step, int32_t device_id, void *hip_stream) {
+  if (!hp) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "hp is NULL");
+  if (n_tensors < 0) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "n_tensors < 0");
+  if (n_tensors > 0 && !tensors) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "tensors is NULL");
+  if (device_id < 0 || device_id >= kMaxDevices) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "device_id out of range");
+  LaunchCtx cx;
+  uint32_t warn = 0;
+  int rc = novak_validate_hparams(hp, &cx.hp, &warn);
+  if (rc != NOVAK_OK) return fail(nullptr, rc, "hyper-parameters rejected (section 5.8 validation rules)");
+  if (two_pass(&cx) || cx.hp.use_gc)
+    return fail(nullptr, NOVAK_ERR_NOT_IMPLEMENTED, "the allocation-free step covers the single-pass update (with clipping and the sparse threshold); "
+                                                    "layer adaptation, auto-LR and gradient centralization need a handle");
+  if (cx.hp.lookahead_mode != NOVAK_LOOKAHEAD_NONE && !cx.hp.auto_sync)
+    return fail(nullptr, NOVAK_ERR_INVALID_ARG, "with lookahead on, the allocation-free step needs auto_sync = 1 (there is no handle to remember a due sync)");
+  std::string why;
+  rc = check_descs(cx.hp, tensors, n_tensors, &why);
+  if (rc != NOVAK_OK) return fail(nullptr, rc, why);
+  rc = check_grads(tensors, static_cast<size_t>(n_tensors), grads, grad_dtype, &why);
+  if (rc != NOVAK_OK) return fail(nullptr, rc, why);
+  if (step < 1) return fail(nullptr, NOVAK_ERR_BAD_STEP, "step must be >= 1 (Eq. 5 is undefined at t = 0)");
+  if (n_tensors > NOVAK_STATIC_MAX_TENSORS) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "more than NOVAK_STATIC_MAX_TENSORS tensors");
+  int64_t n_chunks = 0;
+  for (int32_t i = 0; i < n_tensors; ++i) {
+    n_chunks += (tensors[i].numel + NOVAK_CHUNK_DEFAULT - 1) / NOVAK_CHUNK_DEFAULT;
+    if (n_chunks > NOVAK_STATIC_MAX_CHUNKS)
+      return fail(nullptr, NOVAK_ERR_INVALID_ARG, "the list needs more than NOVAK_STATIC_MAX_CHUNKS chunk-table entries (16384 elements each)");
+  }
+  StepPlan pl;
+  rc = plan_step(cx.hp, step, &pl);
+  if (rc != NOVAK_OK) return fail(nullptr, rc, "scalar prologue failed");
+  if (n_chunks == 0) return NOVAK_OK;
+
+  const StaticLayout L = static_layout(static_cast<size_t>(n_tensors), static_cast<size_t>(n_chunks), clipping(&cx));
+  if (L.end > NOVAK_STATIC_SCRATCH_BYTES) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "the tables do not fit the static scratch array");
+  DeviceScope scope;
+  NOVAK_HIP(nullptr, scope.enter(device_id));
+  unsigned char *base = nullptr;
+  NOVAK_HIP(nullptr, scratch_of(device_id, &base));
+  int lds_cu = 0;
+  if (hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, device_id) == hipSuccess && lds_cu >= 65536)
+    cx.lds_per_cu = lds_cu;
+  cx.n_tensors = n_tensors;
+  cx.n_chunks = n_chunks;
+  cx.d_chunks = reinterpret_cast<novak_chunk *>(base + L.chunks);
+  cx.d_ptrs = base + L.ptrs;
+  cx.d_first_chunk = reinterpret_cast<int *>(base + L.first_chunk);
+  if (clipping(&cx)) {
+    cx.d_tensor_sums = reinterpret_cast<NormSums *>(base + L.tensor_sums);
+    cx.d_scale = reinterpret_cast<float *>(base + L.scale);
+    cx.d_gscale = reinterpret_cast<float *>(base + L.gscale);
+    cx.d_chunk_sums = reinterpret_cast<NormSums *>(base + L.chunk_sums);
+    cx.d_partials = reinterpret_cast<NormPartial *>(base + L.partials);
+  }
+  // tables: written by a kernel from its arguments, kFillBatch tensors per launch, in stream order before the step
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  TensorPtrs *d_tensors = reinterpret_cast<TensorPtrs *>(cx.d_ptrs);
+  const void **d_grad = reinterpret_cast<const void **>(static_cast<char *>(cx.d_ptrs) + static_cast<size_t>(n_tensors) * sizeof(TensorPtrs));
+  int64_t next_chunk = 0;
+  for (int32_t first = 0; first < n_tensors; first += kFillBatch) {
+    FillBatch b;
+    b.count = n_tensors - first < kFillBatch ? n_tensors - first : kFillBatch;
+    b.first_tensor = first;
+    b.n_tensors = n_tensors;
+    b.n_chunks = static_cast<int32_t>(n_chunks);
+    b.chunk_elems = NOVAK_CHUNK_DEFAULT;
+    for (int32_t j = 0; j < b.count; ++j) {
+      const novak_tensor_desc &d = tensors[first + j];
+      FillTensor &ft = b.t[j];
+      ft.ptrs.param = static_cast<float *>(d.param);
+      ft.ptrs.m = static_cast<float *>(d.exp_avg);
+      ft.ptrs.v = static_cast<float *>(d.exp_avg_sq);
+      ft.ptrs.la = static_cast<float *>(d.la_buf);
+      ft.grad = grads[first + j];
+      ft.numel = d.numel;
+      ft.first_chunk = next_chunk;
+      next_chunk += (d.numel + NOVAK_CHUNK_DEFAULT - 1) / NOVAK_CHUNK_DEFAULT;
+    }
+    hipLaunchKernelGGL(novak_fill_tables_kernel, dim3(static_cast<unsigned>(b.count)), dim3(64), 0, stream, b, cx.d_chunks, d_tensors, d_grad,
+                       cx.d_first_chunk);
+    NOVAK_HIP(nullptr, hipGetLastError());
+  }
+  NOVAK_HIP(nullptr, enqueue_step(&cx, grad_dtype, pl, stream));
+  return NOVAK_OK;
+}
+
+int novak_step_static(const novak_hparams *hp, const novak_tensor_desc *tensors, int32_t n_tensors, void *const *grads,
+                      int32_t grad_dtype, int64_t step, int32_t device_id, void *hip_stream) {
+  try {
+    return step_static_impl(hp, tensors, n_tensors, grads, grad_dtype, step, device_id, hip_stream);
+  } catch (...) {      // a host-side string allocation failed
+    return NOVAK_ERR_NO_MEMORY;
+  }
 }
 
 }  // extern "C"

@@ -797,6 +797,51 @@ __global__ __launch_bounds__(kScaledBlock) void novak_apply_kernel(Tables tb, Co
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Tables of the allocation-free step, written on the device from kernel arguments (no host-to-device
+// copy, which could allocate staging memory): one workgroup per tensor of the batch writes the
+// tensor's pointer record, its gradient pointer, its chunk range and its chunk-table entries.
+// ------------------------------------------------------------------------------------------------
+constexpr int kFillBatch = 64;   // tensors per launch: 64 x 56 bytes of arguments stay below the 4 KB limit
+
+struct FillTensor {
+  TensorPtrs ptrs;
+  const void *grad;
+  int64_t numel;
+  int64_t first_chunk;           // index of the tensor's first chunk-table entry
+};
+struct FillBatch {
+  int32_t count;                 // tensors in this batch
+  int32_t first_tensor;          // index of the batch's first tensor in the list
+  int32_t n_tensors;             // tensors in the whole list
+  int32_t n_chunks;              // chunk-table entries of the whole list
+  int64_t chunk_elems;
+  FillTensor t[kFillBatch];
+};
+
+__global__ __launch_bounds__(64) void novak_fill_tables_kernel(FillBatch b, novak_chunk *chunks, TensorPtrs *tensors,
+                                                              const void **grad, int *first_chunk) {
+  const int j = blockIdx.x;
+  if (j >= b.count) return;
+  const FillTensor &ft = b.t[j];
+  const int t = b.first_tensor + j;
+  if (threadIdx.x == 0) {
+    tensors[t] = ft.ptrs;
+    grad[t] = ft.grad;
+    first_chunk[t] = static_cast<int>(ft.first_chunk);
+    if (t == b.n_tensors - 1) first_chunk[b.n_tensors] = b.n_chunks;
+  }
+  const int64_t n = (ft.numel + b.chunk_elems - 1) / b.chunk_elems;
+  for (int64_t k = threadIdx.x; k < n; k += 64) {
+    novak_chunk c;
+    c.offset = k * b.chunk_elems;
+    c.tensor = t;
+    const int64_t rest = ft.numel - c.offset;
+    c.len = static_cast<int32_t>(rest < b.chunk_elems ? rest : b.chunk_elems);
+    chunks[ft.first_chunk + k] = c;
+  }
+}
+
 }  // namespace
 
 #endif  // NOVAK_KERNELS_H_

@@ -27,6 +27,8 @@ NOVAK_WARN_TRUE_NESTEROV_DOWNGRADED, NOVAK_WARN_LOOKAHEAD_DOWNGRADED = 1, 2
 NOVAK_WARN_LAYER_ADAPTATION_DISABLED, NOVAK_WARN_AUTO_LR_DISABLED, NOVAK_WARN_GC_DISABLED = 4, 8, 16
 NOVAK_TUNE_CHUNK_ELEMS, NOVAK_TUNE_NONTEMPORAL, NOVAK_TUNE_VEC_PER_LANE, NOVAK_TUNE_THREADS, NOVAK_TUNE_WAVES_PER_CU = 0, 1, 2, 3, 4
 
+NOVAK_STATIC_MAX_TENSORS, NOVAK_STATIC_MAX_CHUNKS, NOVAK_STATIC_SCRATCH_BYTES = 1024, 16384, 5 << 20
+
 NESTEROV = {"none": 0, "approx": 1, "classical": 2, "true": 3}
 LOOKAHEAD = {"none": 0, "memory_efficient": 1, "basic": 2}
 UNRECT = {"adam_denom": 0, "sgdm": 1}
@@ -82,7 +84,7 @@ EXPORTS = ("novak_validate_hparams", "novak_compute_step_scalars", "novak_plan_c
            "novak_bytes_per_param_moment_saving", "novak_bytes_per_param_sync",
            "novak_status_string", "novak_create", "novak_lookahead_init", "novak_step", "novak_lookahead_sync",
            "novak_destroy", "novak_get_info", "novak_set_tuning", "novak_last_error", "novak_set_auto_lr_state",
-           "novak_copy_tensor_scales", "novak_nesterov_extrapolate")
+           "novak_copy_tensor_scales", "novak_nesterov_extrapolate", "novak_step_static")
 
 _lib: Optional[C.CDLL] = None
 
@@ -123,6 +125,7 @@ def load_library() -> C.CDLL:
     lib.novak_lookahead_init.argtypes = [vp, vp]
     lib.novak_step.argtypes = [vp, C.POINTER(vp), i32, i64, vp]
     lib.novak_lookahead_sync.argtypes = [vp, vp]
+    lib.novak_step_static.argtypes = [C.POINTER(novak_hparams), C.POINTER(novak_tensor_desc), i32, C.POINTER(vp), i32, i64, i32, vp]
     lib.novak_destroy.argtypes = [vp]
     lib.novak_get_info.argtypes = [vp, C.POINTER(novak_info)]
     lib.novak_set_tuning.argtypes = [vp, i32, i64]
@@ -285,6 +288,17 @@ def novak_step(handle, grad_ptrs, grad_dtype: int, step: int, stream: int = 0) -
     if not isinstance(grad_ptrs, C.Array):
         grad_ptrs = (C.c_void_p * max(len(grad_ptrs), 1))(*grad_ptrs)
     return load_library().novak_step(handle, grad_ptrs, int(grad_dtype), int(step), C.c_void_p(stream))
+
+
+def novak_step_static(hp: novak_hparams, descs: Sequence[novak_tensor_desc], grad_ptrs, grad_dtype: int, step: int,
+                      device_id: int = 0, stream: int = 0) -> int:
+    """One handle-free, allocation-free step (see include/novak.h)."""
+    n = len(descs)
+    arr = descs if isinstance(descs, C.Array) else (novak_tensor_desc * max(n, 1))(*descs)
+    if not isinstance(grad_ptrs, C.Array):
+        grad_ptrs = (C.c_void_p * max(len(grad_ptrs), 1))(*grad_ptrs)
+    return load_library().novak_step_static(C.byref(hp), arr, n, grad_ptrs, int(grad_dtype), int(step), int(device_id),
+                                            C.c_void_p(stream))
 
 
 def novak_lookahead_sync(handle, stream: int = 0) -> int:

@@ -196,6 +196,12 @@ def test_create_rejects_bad_arguments_before_touching_the_gpu():
     assert "2^32" in N.novak_last_error(None)
     assert N.novak_create(hp, [N.novak_tensor_desc(1 << 40, 1 << 41, 1 << 42, 1 << 43, 1 << 33)] * 2)[0] == N.NOVAK_ERR_INVALID_ARG
     assert "2^32" in N.novak_last_error(None)
+    # the allocation-free step makes the same checks before it touches the device
+    assert N.novak_step_static(N.make_hparams(**dict(GOOD, lr=-1.0)), [d], [256], 0, 1) == N.NOVAK_ERR_INVALID_ARG
+    fused = N.make_hparams(auto_sync=True, **GOOD)
+    assert N.novak_step_static(hp, [d], [256], 0, 1) == N.NOVAK_ERR_INVALID_ARG and "auto_sync" in N.novak_last_error(None)
+    assert N.novak_step_static(fused, [N.novak_tensor_desc(258, 512, 768, 1024, 8)], [256], 0, 1) == N.NOVAK_ERR_MISALIGNED
+    assert N.novak_step_static(fused, [d], [258], 0, 1) == N.NOVAK_ERR_MISALIGNED
     # NULL handle arguments
     assert N.novak_destroy(None) == N.NOVAK_OK
     assert N.novak_step(None, [], 0, 1, 0) == N.NOVAK_ERR_NULL_POINTER

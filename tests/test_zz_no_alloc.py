@@ -1,0 +1,124 @@
+"""The allocation-free step (novak_step_static) against the handle-based path it is a variant of.
+
+Both run the same kernels on the same inputs, so the results must be BIT-IDENTICAL (which also puts
+the new entry point within the parity bound of the path that the other tests hold against the oracle).
+Two calls in a row share the library's static scratch array: the second one uses a smaller tensor list,
+so anything it wrongly picked up from the first call's tables or partial sums would show.
+"""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from paper_2601_07876_amd import novak as N
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _buffers(numels, seed, grad_dtype, moment_dtype):
+    """theta, m, v, la, g per tensor on the GPU (each its own allocation), seeded."""
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    out = []
+    for n in numels:
+        theta = torch.empty(n, dtype=torch.float32, device=DEV).normal_(0.0, W.PARAM_STD, generator=gen)
+        m = torch.zeros(n, dtype=torch.bfloat16 if moment_dtype == "bf16_m" else torch.float32, device=DEV)
+        v = torch.zeros(n, dtype=torch.float32, device=DEV)
+        la = theta.clone()                       # Eq. 28: the lookahead buffer starts as a copy of theta
+        g = torch.empty(n, dtype=torch.float32, device=DEV)
+        out.append([theta, m, v, la, g.to(torch.bfloat16) if grad_dtype == "bf16" else g])
+    return out, gen
+
+
+def _fresh_grads(bufs, gen, std):
+    for b in bufs:
+        tmp = torch.empty(b[4].numel(), dtype=torch.float32, device=DEV).normal_(0.0, std, generator=gen)
+        b[4].copy_(tmp)
+
+
+def _run_both(numels, hyper, steps, grad_dtype="f32", seed=7, std=1e-2):
+    """Runs `steps` steps through the handle and through novak_step_static on identical inputs and
+    requires bit-identical theta, m, v (and lookahead buffers between syncs)."""
+    md = hyper.get("moment_dtype", "f32")
+    a, gen_a = _buffers(numels, seed, grad_dtype, md)
+    b, gen_b = _buffers(numels, seed, grad_dtype, md)
+    hp = N.make_hparams(auto_sync=True, **hyper)
+    descs_a = [N.novak_tensor_desc(x[0].data_ptr(), x[1].data_ptr(), x[2].data_ptr(), x[3].data_ptr(), n) for x, n in zip(a, numels)]
+    descs_b = (N.novak_tensor_desc * max(len(numels), 1))(*[N.novak_tensor_desc(x[0].data_ptr(), x[1].data_ptr(), x[2].data_ptr(),
+                                                                              x[3].data_ptr(), n) for x, n in zip(b, numels)])
+    rc, handle = N.novak_create(hp, descs_a, 0)
+    N.check(rc, "novak_create")
+    stream = torch.cuda.current_stream().cuda_stream
+    gdt = N.GRAD_DTYPE[grad_dtype]
+    ga = (C.c_void_p * max(len(numels), 1))(*[x[4].data_ptr() if x[4].numel() else None for x in a])
+    gb = (C.c_void_p * max(len(numels), 1))(*[x[4].data_ptr() if x[4].numel() else None for x in b])
+    try:
+        for t in range(1, steps + 1):
+            _fresh_grads(a, gen_a, std)
+            _fresh_grads(b, gen_b, std)
+            N.check(N.novak_step(handle, ga, gdt, t, stream), f"novak_step t={t}", handle)
+            torch.cuda.synchronize()
+            free_before = torch.cuda.mem_get_info()[0]
+            N.check(N.novak_step_static(hp, descs_b, gb, gdt, t, 0, stream), f"novak_step_static t={t}")
+            torch.cuda.synchronize()
+            if t > 1:       # the very first call may load the code object; afterwards device memory must not move
+                assert torch.cuda.mem_get_info()[0] == free_before, "device memory was allocated or freed"
+            for i, (x, y) in enumerate(zip(a, b)):
+                for role, j in (("theta", 0), ("m", 1), ("v", 2), ("la", 3)):
+                    if role == "la" and (hyper.get("lookahead", "memory_efficient") == "none" or t % int(hyper.get("la_k", 5)) == 0):
+                        continue        # unspecified between a fused sync and the next step
+                    assert torch.equal(x[j], y[j]), f"t={t} tensor {i} {role} differs"
+    finally:
+        torch.cuda.synchronize()
+        N.novak_destroy(handle)
+    return [x[0].clone() for x in b]
+
+
+def test_two_calls_in_a_row_the_second_smaller():
+    """ResNet-50 list (161 tensors: three table-fill launches, 1.6k chunks) with clipping, then a short odd list."""
+    wl = W.get_workload("c2_resnet50")
+    hyper = dict(wl.hyper, clip_threshold=1.0)
+    big = _run_both(wl.numels, hyper, steps=6)
+    rag = W.get_workload("ragged")
+    small = _run_both(rag.numels, dict(rag.hyper, mode="fast", clip_threshold=0.5, sparse_threshold=0.1), steps=11)
+    assert len(big) == 161 and len(small) == len(rag.numels)
+    # and once more the other way round: a larger list after a smaller one
+    _run_both(wl.numels[:70], dict(wl.hyper, lookahead="none", nesterov="classical"), steps=3)
+
+
+@pytest.mark.parametrize("grad_dtype,moment_dtype,lookahead,k", [("bf16", "f32", "memory_efficient", 1), ("f32", "bf16_m", "basic", 3),
+                                                                 ("bf16", "bf16_m", "memory_efficient", 5)])
+def test_variants(grad_dtype, moment_dtype, lookahead, k):
+    rag = W.get_workload("ragged")
+    hyper = dict(rag.hyper, lookahead=lookahead, la_k=k, moment_dtype=moment_dtype, mode="research")
+    _run_both(rag.numels + [0], hyper, steps=2 * k + 1, grad_dtype=grad_dtype)
+
+
+def test_limits_and_unsupported_options_are_refused_with_a_reason():
+    """Nothing is dereferenced before these checks, so made-up addresses do."""
+    def desc(n):
+        return N.novak_tensor_desc(4096, 8192, 12288, 16384, n)
+
+    def call(hp, descs, step=1):
+        grads = [256] * len(descs)
+        return N.novak_step_static(hp, descs, grads, N.NOVAK_GRAD_F32, step, 0, 0)
+
+    ok = N.make_hparams(auto_sync=True)
+    assert call(ok, [desc(16384)] * (N.NOVAK_STATIC_MAX_TENSORS + 1)) == N.NOVAK_ERR_INVALID_ARG
+    assert "NOVAK_STATIC_MAX_TENSORS" in N.novak_last_error()
+    assert call(ok, [desc(16384 * N.NOVAK_STATIC_MAX_CHUNKS + 1)]) == N.NOVAK_ERR_INVALID_ARG
+    assert "NOVAK_STATIC_MAX_CHUNKS" in N.novak_last_error()
+    assert call(N.make_hparams(auto_sync=False), [desc(64)]) == N.NOVAK_ERR_INVALID_ARG
+    assert call(N.make_hparams(auto_sync=True, mode="research", layer_adaptation=True), [desc(64)]) == N.NOVAK_ERR_NOT_IMPLEMENTED
+    assert call(N.make_hparams(auto_sync=True, mode="research", use_gc=True), [desc(64)]) == N.NOVAK_ERR_NOT_IMPLEMENTED
+    assert call(ok, [desc(64)], step=0) == N.NOVAK_ERR_BAD_STEP
+    assert call(N.make_hparams(auto_sync=True, lr=-1.0), [desc(64)]) == N.NOVAK_ERR_INVALID_ARG
+    assert call(ok, [N.novak_tensor_desc(4096, 8192, 0, 16384, 64)]) == N.NOVAK_ERR_NULL_POINTER
+    assert call(ok, [N.novak_tensor_desc(4098, 8192, 12288, 16384, 64)]) == N.NOVAK_ERR_MISALIGNED
+    assert call(ok, []) == N.NOVAK_OK and call(ok, [desc(0)]) == N.NOVAK_OK          # nothing to do
+    # exactly at the limit the sizes are accepted by the checks (not launched here: the addresses are made up)
+    assert N.NOVAK_STATIC_MAX_CHUNKS * 16384 == 1 << 28
