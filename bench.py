@@ -51,6 +51,7 @@ def parse_args():
     ap.add_argument("--vec-per-lane", type=int, default=None)
     ap.add_argument("--threads", type=int, default=None)
     ap.add_argument("--waves-per-cu", type=int, default=None)
+    ap.add_argument("--prepass-waves-per-cu", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 22, help="elements of the oracle's timed sample")
     ap.add_argument("--cpu-workers", type=int, default=min(16, os.cpu_count() or 1),
@@ -207,6 +208,8 @@ def main():
         N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_THREADS, args.threads), "set_tuning", handle)
     if args.waves_per_cu is not None:
         N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_WAVES_PER_CU, args.waves_per_cu), "set_tuning", handle)
+    if args.prepass_waves_per_cu is not None:
+        N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_PREPASS_WAVES_PER_CU, args.prepass_waves_per_cu), "set_tuning", handle)
     rc, info = N.novak_get_info(handle)
     la_name = {0: "none", 1: "memory_efficient", 2: "basic"}[info.lookahead_mode]
     nest_name = {0: "none", 1: "approx", 2: "classical", 3: "true"}[info.nesterov_mode]

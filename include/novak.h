@@ -190,8 +190,10 @@ enum {
   NOVAK_TUNE_NONTEMPORAL = 1,   /* 0/1: non-temporal hints on the streaming loads and stores */
   NOVAK_TUNE_VEC_PER_LANE = 2,  /* 1, 2 or 4: 128-bit accesses per stream per lane */
   NOVAK_TUNE_THREADS = 3,       /* 64, 128 or 256 threads per workgroup; a workgroup covers threads*4*vec_per_lane elements */
-  NOVAK_TUNE_WAVES_PER_CU = 4   /* 0..32: cap on waves resident per compute unit (bounds the bytes in flight);
+  NOVAK_TUNE_WAVES_PER_CU = 4,  /* 0..32: cap on waves resident per compute unit (bounds the bytes in flight);
                                    0 = chosen per kernel variant from its number of streams */
+  NOVAK_TUNE_PREPASS_WAVES_PER_CU = 5  /* the same for the gradient pre-pass (clipping norm / row means), a read-only
+                                   kernel whose waves hold 16 KB in flight each; 0 = chosen by gradient type */
 };
 
 /* ---- host-only helpers (no GPU needed) -------------------------------------------------------- */
@@ -331,7 +333,7 @@ int novak_lookahead_sync(novak_handle *h, void *hip_stream);
  *   Errors are reported through the return code and novak_last_error(NULL). */
 #define NOVAK_STATIC_MAX_TENSORS 1024
 #define NOVAK_STATIC_MAX_CHUNKS 16384
-#define NOVAK_STATIC_SCRATCH_BYTES (5u << 20)
+#define NOVAK_STATIC_SCRATCH_BYTES (2u << 20)
 int novak_step_static(const novak_hparams *hp, const novak_tensor_desc *tensors, int32_t n_tensors, void *const *grads,
                       int32_t grad_dtype, int64_t step, int32_t device_id, void *hip_stream);
 

@@ -59,6 +59,7 @@ struct LaunchCtx {
   int vec_per_lane = 1;             // 128-bit accesses per stream per lane (UN): 1, 2 or 4
   int threads = 64;                 // workgroup size: 64, 128 or 256 (one to four wave64)
   int waves_per_cu = 0;             // cap on resident waves per compute unit; 0 = chosen per kernel variant
+  int prepass_waves_per_cu = 0;     // the same for the gradient pre-pass
   int lds_per_cu = 160 * 1024;      // LDS of one compute unit (queried at create)
   // reduction scratch of the two-pass path (layer adaptation / auto-LR) and of the clipping pre-pass
   NormPartial *d_partials = nullptr;   // one per wave of pass 1
@@ -72,6 +73,7 @@ struct LaunchCtx {
   int *d_gc_tensor = nullptr;          // centralized tensors
   int64_t *d_row_first = nullptr;      // their first rows (prefix sums, n_gc + 1)
   double *d_row_means = nullptr;       // one double per row
+  RowPartial *d_row_partials = nullptr;   // one per pre-pass wave (rebuilt with the chunk table)
   int n_gc = 0;
   int64_t total_rows = 0;
   double *d_ema = nullptr;             // caller-owned: g_bar, theta_bar
@@ -168,6 +170,8 @@ void free_device_tables(novak_handle *h) {
   if (h->d_first_chunk) (void)hipFree(h->d_first_chunk);
   if (h->d_scale) (void)hipFree(h->d_scale);
   if (h->d_gscale) (void)hipFree(h->d_gscale);
+  if (h->d_row_partials) (void)hipFree(h->d_row_partials);
+  h->d_row_partials = nullptr;
   h->d_gscale = nullptr;
   h->d_chunks = nullptr;
   h->d_partials = nullptr;
@@ -207,21 +211,29 @@ int build_chunk_table_unguarded(novak_handle *h) {
     NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_chunks), static_cast<size_t>(n) * sizeof(novak_chunk)));
     NOVAK_HIP(h, hipMemcpy(h->d_chunks, table.data(), static_cast<size_t>(n) * sizeof(novak_chunk), hipMemcpyHostToDevice));
   }
-  if (needs_reductions(h) && !h->tensors.empty()) {
+  if ((needs_reductions(h) || h->n_gc > 0) && !h->tensors.empty()) {
     const size_t nt = h->tensors.size();
-    const float one = 1.0f;
-    NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_gscale), sizeof(float)));
-    NOVAK_HIP(h, hipMemcpy(h->d_gscale, &one, sizeof(float), hipMemcpyHostToDevice));
     std::vector<int> first(nt + 1, 0);
     for (const novak_chunk &c : table) first[static_cast<size_t>(c.tensor) + 1] += 1;
     for (size_t t = 0; t < nt; ++t) first[t + 1] += first[t];
     NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_first_chunk), (nt + 1) * sizeof(int)));
     NOVAK_HIP(h, hipMemcpy(h->d_first_chunk, first.data(), (nt + 1) * sizeof(int), hipMemcpyHostToDevice));
+    if (h->n_gc > 0 && n > 0) {
+      const size_t waves = static_cast<size_t>(n) * static_cast<size_t>(h->chunk_elems / kPreSub);
+      NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_row_partials), waves * sizeof(RowPartial)));
+    }
+  }
+  if (needs_reductions(h) && !h->tensors.empty()) {
+    const size_t nt = h->tensors.size();
+    const float one = 1.0f;
+    NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_gscale), sizeof(float)));
+    NOVAK_HIP(h, hipMemcpy(h->d_gscale, &one, sizeof(float), hipMemcpyHostToDevice));
     NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_tensor_sums), nt * sizeof(NormSums)));
     NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_scale), nt * sizeof(float)));
     std::vector<float> ones(nt, 1.0f);
     NOVAK_HIP(h, hipMemcpy(h->d_scale, ones.data(), nt * sizeof(float), hipMemcpyHostToDevice));
     if (n > 0) {
+      // one partial per wave of the finest reduction pass (256 elements per wave in the two-pass step)
       const size_t waves = static_cast<size_t>(n) * static_cast<size_t>(h->chunk_elems / kScaledSub);
       NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_partials), waves * sizeof(NormPartial)));
       NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_chunk_sums), static_cast<size_t>(n) * sizeof(NormSums)));
@@ -363,15 +375,6 @@ void launch_step(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, cons
   else launch_step_block<false>(h, grad_dtype, la, s, tb, c);
 }
 
-hipError_t launch_rowmeans(const LaunchCtx *h, int grad_dtype, hipStream_t s, const Tables &tb) {
-  const dim3 grid(static_cast<unsigned>(h->total_rows)), block(64);
-  if (grad_dtype == NOVAK_GRAD_BF16)
-    hipLaunchKernelGGL((novak_rowmean_kernel<unsigned short>), grid, block, 0, s, tb.grad, h->d_gc_tensor, h->d_row_first, h->n_gc, h->d_gc, h->d_row_means);
-  else
-    hipLaunchKernelGGL((novak_rowmean_kernel<float>), grid, block, 0, s, tb.grad, h->d_gc_tensor, h->d_row_first, h->n_gc, h->d_gc, h->d_row_means);
-  return hipGetLastError();
-}
-
 template <int OP, int BLOCK>
 void launch_la_block(const LaunchCtx *h, hipStream_t s, const Tables &tb, float c0, float c1) {
   const Geometry gm = geometry_of(h, BLOCK * 4, BLOCK, OP == SYNC_BASIC ? 4 : 2);
@@ -413,26 +416,52 @@ void launch_moments(const LaunchCtx *h, int grad_dtype, const Geometry &g1, hipS
   }
 }
 
-// Clipping pre-pass: gradient norm partials -> chunk sums -> tensor sums -> global factor in d_gscale.
-hipError_t launch_clip_prepass(const LaunchCtx *h, int grad_dtype, hipStream_t s, const Tables &tb) {
-  const Geometry g0 = geometry_of(h, kNormSub, kScaledBlock, 1);        // a single read stream: full residency
-  const dim3 grid(g0.grid), block(kScaledBlock);
+// Gradient pre-pass: one read of the gradients gives the norm partials (clipping) and the row sums
+// (centralization); then the norm goes chunk sums -> tensor sums -> global factor in d_gscale, and the
+// rows that span several waves get their means from the waves' partial sums.
+// Residency: a read-only stream peaks at 6 resident waves of 16 KB per compute unit (10 - 12 waves of
+// 8 KB with bf16 gradients); the LDS that bounds it doubles as the centralization's staging buffer.
+template <typename GradS, typename GradV, bool NT>
+void launch_prepass_kernel(bool norm, bool gc, const dim3 &grid, unsigned lds, hipStream_t s, const Tables &tb, int sub_shift,
+                           NormPartial *partials, RowPartial *row_partials) {
+  const dim3 block(kScaledBlock);
+  if (norm && gc) hipLaunchKernelGGL((novak_prepass_kernel<GradS, GradV, NT, true, true>), grid, block, lds, s, tb, sub_shift, partials, row_partials);
+  else if (norm) hipLaunchKernelGGL((novak_prepass_kernel<GradS, GradV, NT, true, false>), grid, block, lds, s, tb, sub_shift, partials, row_partials);
+  else hipLaunchKernelGGL((novak_prepass_kernel<GradS, GradV, NT, false, true>), grid, block, lds, s, tb, sub_shift, partials, row_partials);
+}
+
+hipError_t launch_prepass(const LaunchCtx *h, int grad_dtype, hipStream_t s, const Tables &tb) {
+  const bool norm = clipping(h), gc = h->n_gc > 0;
+  const bool bf16_g = grad_dtype == NOVAK_GRAD_BF16;
+  Geometry g0;
+  g0.sub_shift = log2_exact(h->chunk_elems / kPreSub);
+  g0.grid = static_cast<unsigned>(h->n_chunks << g0.sub_shift);
+  int waves = h->prepass_waves_per_cu ? h->prepass_waves_per_cu : (bf16_g ? (gc ? 10 : 12) : 6);
+  unsigned lds = waves >= 32 ? 0u : (static_cast<unsigned>(h->lds_per_cu) / static_cast<unsigned>(waves)) & ~511u;
+  if (lds > 65536u) lds = 65536u;
+  if (gc && lds < kPreStageBytes) lds = kPreStageBytes;
+  const dim3 grid(g0.grid);
   const bool nt = h->nontemporal != 0;
-  if (grad_dtype == NOVAK_GRAD_BF16) {
-    if (nt) hipLaunchKernelGGL((novak_gradnorm_kernel<unsigned short, u16x4, true>), grid, block, g0.lds, s, tb, g0.sub_shift, h->d_partials);
-    else hipLaunchKernelGGL((novak_gradnorm_kernel<unsigned short, u16x4, false>), grid, block, g0.lds, s, tb, g0.sub_shift, h->d_partials);
+  if (bf16_g) {
+    if (nt) launch_prepass_kernel<unsigned short, u16x4, true>(norm, gc, grid, lds, s, tb, g0.sub_shift, h->d_partials, h->d_row_partials);
+    else launch_prepass_kernel<unsigned short, u16x4, false>(norm, gc, grid, lds, s, tb, g0.sub_shift, h->d_partials, h->d_row_partials);
   } else {
-    if (nt) hipLaunchKernelGGL((novak_gradnorm_kernel<float, f32x4, true>), grid, block, g0.lds, s, tb, g0.sub_shift, h->d_partials);
-    else hipLaunchKernelGGL((novak_gradnorm_kernel<float, f32x4, false>), grid, block, g0.lds, s, tb, g0.sub_shift, h->d_partials);
+    if (nt) launch_prepass_kernel<float, f32x4, true>(norm, gc, grid, lds, s, tb, g0.sub_shift, h->d_partials, h->d_row_partials);
+    else launch_prepass_kernel<float, f32x4, false>(norm, gc, grid, lds, s, tb, g0.sub_shift, h->d_partials, h->d_row_partials);
   }
-  ScaleParams sp;
-  std::memset(&sp, 0, sizeof(sp));
-  const int nt_count = h->n_tensors;
-  hipLaunchKernelGGL(novak_reduce_chunks_kernel, dim3(static_cast<unsigned>(h->n_chunks)), dim3(64), 0, s, h->d_chunks, g0.sub_shift,
-                     kNormSub, h->d_partials, h->d_chunk_sums);
-  hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(64), 0, s, h->d_first_chunk, h->d_chunk_sums,
-                     h->d_tensor_sums, h->d_scale, sp);
-  hipLaunchKernelGGL(novak_clip_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, static_cast<float>(h->hp.clip_threshold), h->d_gscale);
+  if (gc)
+    hipLaunchKernelGGL(novak_rowfinal_kernel, dim3(static_cast<unsigned>((h->total_rows + 63) / 64)), dim3(64), 0, s, h->d_gc_tensor, h->d_row_first,
+                       h->n_gc, h->d_gc, h->d_first_chunk, g0.sub_shift, h->total_rows, h->d_row_partials, h->d_row_means);
+  if (norm) {
+    ScaleParams sp;
+    std::memset(&sp, 0, sizeof(sp));
+    const int nt_count = h->n_tensors;
+    hipLaunchKernelGGL(novak_reduce_chunks_kernel, dim3(static_cast<unsigned>(h->n_chunks)), dim3(64), 0, s, h->d_chunks, g0.sub_shift,
+                       kPreSub, h->d_partials, h->d_chunk_sums);
+    hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(64), 0, s, h->d_first_chunk, h->d_chunk_sums,
+                       h->d_tensor_sums, h->d_scale, sp);
+    hipLaunchKernelGGL(novak_clip_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, static_cast<float>(h->hp.clip_threshold), h->d_gscale);
+  }
   return hipGetLastError();
 }
 
@@ -560,11 +589,8 @@ hipError_t enqueue_step(const LaunchCtx *cx, int grad_dtype, const StepPlan &pl,
   if (cx->n_chunks == 0) return hipSuccess;
   Consts c = pl.c;
   hipError_t e;
-  if (clipping(cx) && (e = launch_clip_prepass(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
-  if (cx->n_gc > 0) {
-    c.flags |= F_GC;
-    if ((e = launch_rowmeans(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
-  }
+  if (cx->n_gc > 0) c.flags |= F_GC;
+  if ((clipping(cx) || cx->n_gc > 0) && (e = launch_prepass(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
   if (two_pass(cx)) {
     if ((e = launch_scaled_step(cx, grad_dtype, pl.la, stream, tables_of(cx), c)) != hipSuccess) return e;
   } else {
@@ -895,6 +921,11 @@ static int set_tuning_impl(novak_handle *h, int32_t key, int64_t value) {
     h->waves_per_cu = static_cast<int>(value);
     return NOVAK_OK;
   }
+  if (key == NOVAK_TUNE_PREPASS_WAVES_PER_CU) {
+    if (value < 0 || value > 32) return fail(h, NOVAK_ERR_INVALID_ARG, "prepass_waves_per_cu must be in [0, 32]");
+    h->prepass_waves_per_cu = static_cast<int>(value);
+    return NOVAK_OK;
+  }
   if (key == NOVAK_TUNE_THREADS) {
     if (value != 64 && value != 128 && value != 256) return fail(h, NOVAK_ERR_INVALID_ARG, "threads must be 64, 128 or 256");
     h->threads = static_cast<int>(value);
@@ -1012,7 +1043,7 @@ StaticLayout static_layout(size_t n_tensors, size_t n_chunks, bool clip) {
     L.scale = o;       o = align256(o + n_tensors * sizeof(float));
     L.gscale = o;      o = align256(o + sizeof(float));
     L.chunk_sums = o;  o = align256(o + n_chunks * sizeof(NormSums));
-    L.partials = o;    o = align256(o + n_chunks * (NOVAK_CHUNK_DEFAULT / kNormSub) * sizeof(NormPartial));
+    L.partials = o;    o = align256(o + n_chunks * (NOVAK_CHUNK_DEFAULT / kPreSub) * sizeof(NormPartial));
   }
   L.end = o;
   return L;

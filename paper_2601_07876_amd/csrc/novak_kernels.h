@@ -577,39 +577,143 @@ __global__ __launch_bounds__(64) void novak_reduce_chunks_kernel(const novak_chu
   }
 }
 
-// Clipping pre-pass (sections 5.8, 7.3): one read of the gradients, one partial (sum g^2) per wave; the
-// chunk and tensor reductions above are reused, then novak_clip_kernel turns the global norm into the
-// factor min(1, c_clip/||g||) that every later kernel of the step multiplies the gradients by.
-constexpr int kNormUnroll = 4;                          // 128-bit loads in flight per lane in the read-only pre-pass
-constexpr int kNormSub = kScaledSub * kNormUnroll;      // elements per wave there
+// Gradient pre-pass (Phase 2): ONE read of the gradients serves both consumers that need a whole-array
+// statistic before any element may be updated - the global norm of gradient clipping (sections 5.8, 7.3)
+// and the row means of gradient centralization (Eq. 26).
+//   * A wave streams kPreSub = 4096 consecutive elements with 16 independent 128-bit loads per lane in
+//     flight: a read-only stream needs about 100 KB outstanding per compute unit, and 16 KB per wave at a
+//     residency of 6 waves measured best on MI355X (7.35 TB/s against 6.8 TB/s for 4 KB per wave).
+//   * NORM: one partial sum of squares per wave; the chunk and tensor reductions below are shared with
+//     the two-pass step, then novak_clip_kernel turns the norm into the factor min(1, c_clip/||g||).
+//   * GC: the wave parks its elements in LDS and sums, in double and in a fixed order, every row piece
+//     that lies in its span.  Rows that lie entirely inside the span get their mean written here; a row
+//     that sticks out at the front ("head") or at the back ("tail") leaves a partial sum, and
+//     novak_rowfinal_kernel adds those up in wave order.  Nothing depends on timing.
+constexpr int kPreUnroll = 16;
+constexpr int kPreSub = kScaledSub * kPreUnroll;        // elements per wave
+constexpr unsigned kPreStageBytes = kPreSub * sizeof(float);
 
-template <typename GradS, typename GradV, bool NT>
-__global__ __launch_bounds__(kScaledBlock) void novak_gradnorm_kernel(Tables tb, int sub_shift, NormPartial *partials) {
+struct RowPartial {   // per pre-pass wave: the pieces of the (at most two) rows that stick out of its span
+  double head, tail;
+};
+
+// Wave-wide sums through the data-parallel-primitive lane shifts instead of LDS permutes: an inclusive scan
+// inside each row of 16 lanes (shift right by 1, 2, 4, 8; lanes without a source add 0), then lane 15 of
+// rows 0 and 2 is added into rows 1 and 3, then lane 31 into rows 2 and 3.  The TOTAL ENDS UP IN LANE 63
+// ONLY.  About four times shorter than six permute rounds, which matters to a kernel whose waves are few
+// and end with this reduction.  The order of the additions is fixed.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_take(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, false));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_take(double x) {
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, ROW_MASK, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, ROW_MASK, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+template <typename T>
+__device__ __forceinline__ T wave_total_in_lane63(T x) {
+  x += dpp_take<0x111, 0xf>(x);    // row_shr:1
+  x += dpp_take<0x112, 0xf>(x);    // row_shr:2
+  x += dpp_take<0x114, 0xf>(x);    // row_shr:4
+  x += dpp_take<0x118, 0xf>(x);    // row_shr:8
+  x += dpp_take<0x142, 0xa>(x);    // row_bcast:15 into rows 1 and 3
+  x += dpp_take<0x143, 0xc>(x);    // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
+// Sum of stage[a, b) over the wave, in double, fixed order: lanes take a strided share, then the scan above.
+__device__ __forceinline__ double stage_sum_wave(const float *stage, int a, int b) {
+  double acc = 0.0;
+  if (((a | b) & 3) == 0) {
+    for (int i = a + 4 * static_cast<int>(threadIdx.x); i < b; i += 256) {
+      const f32x4 x = *reinterpret_cast<const f32x4 *>(stage + i);
+      acc += (static_cast<double>(x[0]) + x[1]) + (static_cast<double>(x[2]) + x[3]);
+    }
+  } else {
+    for (int i = a + static_cast<int>(threadIdx.x); i < b; i += 64) acc += static_cast<double>(stage[i]);
+  }
+  return wave_total_in_lane63(acc);
+}
+
+// Where the sum of one row piece goes: a row that lies entirely in the span [off, end) gets its mean, a row
+// that begins before the span leaves a head piece, one that runs past its end a tail piece.
+__device__ __forceinline__ void emit_row(double sum, int64_t r, int64_t cols, int64_t off, int64_t end, double *means, RowPartial *rp) {
+  const int64_t lo = r * cols, hi = lo + cols;
+  if (lo >= off && hi <= end) means[r] = sum / static_cast<double>(cols);
+  else if (lo < off) rp->head = sum;
+  else rp->tail = sum;
+}
+
+template <typename GradS, typename GradV, bool NT, bool NORM, bool GC>
+__global__ __launch_bounds__(kScaledBlock) void novak_prepass_kernel(Tables tb, int sub_shift, NormPartial *partials,
+                                                                     RowPartial *row_partials) {
+  extern __shared__ float stage[];                      // kPreSub floats, touched only on the staged centralization path
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
-  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kNormSub;
+  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kPreSub;
   if (start >= ch.len) return;
-  const int n = min(kNormSub, ch.len - start);
-  const GradS *__restrict__ g_p = static_cast<const GradS *>(tb.grad[ch.tensor]) + (ch.offset + start);
-  float s_g = 0.0f;
+  const int n = min(kPreSub, ch.len - start);
+  const int64_t off = ch.offset + start, end = off + n;
+  const GradS *__restrict__ g_p = static_cast<const GradS *>(tb.grad[ch.tensor]) + off;
+  GcInfo gi;
+  gi.cols = 0;
+  if (GC) gi = tb.gc[ch.tensor];
+  const bool gc = GC && gi.cols > 0;
+  const int64_t cols = gi.cols;
+  double *means = const_cast<double *>(gi.means);
+  RowPartial *rp = row_partials + blockIdx.x;
+  float s_g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  bool staged = gc;                                     // false once the row sums were formed in registers
   int done = 0;
   if ((reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1)) == 0) {
-    const int nvec = n >> 2;
     const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
-    if (n == kNormSub) {
-      GradV g[kNormUnroll];
+    const int nvec = n >> 2;
+    if (n == kPreSub) {
+      GradV g[kPreUnroll];
 #pragma unroll
-      for (int u = 0; u < kNormUnroll; ++u) g[u] = ld<NT>(g4 + threadIdx.x + u * kScaledBlock);
+      for (int u = 0; u < kPreUnroll; ++u) g[u] = ld<NT>(g4 + threadIdx.x + u * kScaledBlock);
+      if (NORM) {
 #pragma unroll
-      for (int u = 0; u < kNormUnroll; ++u) {
-        const f32x4 gf = grad_to_f32<GradV>(g[u]);
+        for (int u = 0; u < kPreUnroll; ++u) {
+          const f32x4 gf = grad_to_f32<GradV>(g[u]);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) s_g = __builtin_fmaf(gf[k], gf[k], s_g);
+          for (int k = 0; k < 4; ++k) s_g[u & 3] = __builtin_fmaf(gf[k], gf[k], s_g[u & 3]);
+        }
+      }
+      if (gc && (cols & 255) == 0) {
+        // Rows made of whole 256-element pieces: piece u is what the wave's u-th load fetched and lies inside
+        // one row, so the row sums form in registers - lanes add their vectors over a row's pieces, then one
+        // tree per row.  Every branch is uniform.
+        staged = false;
+        int64_t r = row_of(off, cols, gi.inv_cols);
+        int left = static_cast<int>((r * cols + cols - off) >> 8);     // pieces of row r from the span's start on
+        double acc = 0.0;
+#pragma unroll
+        for (int u = 0; u < kPreUnroll; ++u) {
+          const f32x4 gf = grad_to_f32<GradV>(g[u]);
+          acc += (static_cast<double>(gf[0]) + gf[1]) + (static_cast<double>(gf[2]) + gf[3]);
+          if (--left == 0 || u == kPreUnroll - 1) {
+            const double sum = wave_total_in_lane63(acc);
+            if (threadIdx.x == 63) emit_row(sum, r, cols, off, end, means, rp);
+            ++r;
+            left = static_cast<int>(cols >> 8);
+            acc = 0.0;
+          }
+        }
+      } else if (gc) {
+#pragma unroll
+        for (int u = 0; u < kPreUnroll; ++u)
+          *reinterpret_cast<f32x4 *>(stage + 4 * (threadIdx.x + u * kScaledBlock)) = grad_to_f32<GradV>(g[u]);
       }
     } else {
       for (int i = threadIdx.x; i < nvec; i += kScaledBlock) {
         const f32x4 gf = grad_to_f32<GradV>(ld<NT>(g4 + i));
+        if (NORM) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) s_g = __builtin_fmaf(gf[k], gf[k], s_g);
+          for (int k = 0; k < 4; ++k) s_g[0] = __builtin_fmaf(gf[k], gf[k], s_g[0]);
+        }
+        if (gc) *reinterpret_cast<f32x4 *>(stage + 4 * i) = gf;
       }
     }
     done = nvec << 2;
@@ -618,14 +722,65 @@ __global__ __launch_bounds__(kScaledBlock) void novak_gradnorm_kernel(Tables tb,
     float g;
     if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
     else g = g_p[i];
-    s_g = __builtin_fmaf(g, g, s_g);
+    if (NORM) s_g[0] = __builtin_fmaf(g, g, s_g[0]);
+    if (gc) stage[i] = g;
   }
-  s_g = wave_sum(s_g);
-  if (threadIdx.x == 0) {
-    NormPartial p;
-    p.theta2 = 0.0f; p.u2 = 0.0f; p.g2 = s_g; p.pad = 0.0f;
-    partials[blockIdx.x] = p;
+  if (NORM) {
+    const float total = wave_total_in_lane63((s_g[0] + s_g[1]) + (s_g[2] + s_g[3]));
+    if (threadIdx.x == 63) {
+      NormPartial p;
+      p.theta2 = 0.0f; p.u2 = 0.0f; p.g2 = total; p.pad = 0.0f;
+      partials[blockIdx.x] = p;
+    }
   }
+  if (!staged) return;
+  __syncthreads();                                      // one wave: orders the LDS writes before the reads
+  // rows r_first..r_last meet the span
+  const int64_t r_first = row_of(off, cols, gi.inv_cols), r_last = row_of(end - 1, cols, gi.inv_cols);
+  if (r_last - r_first >= 64) {
+    // many short rows: one lane per row, elements summed in order
+    for (int64_t r = r_first + threadIdx.x; r <= r_last; r += kScaledBlock) {
+      const int64_t lo = r * cols, hi = lo + cols;
+      const int a = static_cast<int>((lo > off ? lo : off) - off), b = static_cast<int>((hi < end ? hi : end) - off);
+      double acc = 0.0;
+      for (int i = a; i < b; ++i) acc += static_cast<double>(stage[i]);
+      emit_row(acc, r, cols, off, end, means, rp);
+    }
+  } else {
+    // few long rows: the whole wave sums one row piece after the other
+    for (int64_t r = r_first; r <= r_last; ++r) {
+      const int64_t lo = r * cols, hi = lo + cols;
+      const int a = static_cast<int>((lo > off ? lo : off) - off), b = static_cast<int>((hi < end ? hi : end) - off);
+      const double sum = stage_sum_wave(stage, a, b);
+      if (threadIdx.x == 63) emit_row(sum, r, cols, off, end, means, rp);
+    }
+  }
+}
+
+// Means of the rows whose elements are spread over several pre-pass waves: the first wave's tail piece,
+// then the head pieces of the following waves, in order.  One lane per row of the centralized tensors;
+// `gc_tensor[j]` lists them, `row_first[j]` is the index of tensor j's first row (prefix sums, n_gc + 1
+// entries), `first_chunk[t]` the tensor's first chunk-table entry.
+__global__ __launch_bounds__(64) void novak_rowfinal_kernel(const int *gc_tensor, const int64_t *row_first, int n_gc, const GcInfo *gc,
+                                                           const int *first_chunk, int sub_shift, int64_t total_rows,
+                                                           const RowPartial *row_partials, double *means) {
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * 64 + threadIdx.x;
+  if (row >= total_rows) return;
+  int lo = 0, hi = n_gc - 1;                     // largest j with row_first[j] <= row
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (row_first[mid] <= row) lo = mid;
+    else hi = mid - 1;
+  }
+  const int t = gc_tensor[lo];
+  const int64_t r = row - row_first[lo];
+  const int64_t cols = gc[t].cols;
+  const int64_t w_a = (r * cols) / kPreSub, w_b = (r * cols + cols - 1) / kPreSub;   // pre-pass waves of this tensor
+  if (w_a == w_b) return;                        // the row lies inside one wave's span: its mean is already there
+  const RowPartial *p = row_partials + (static_cast<int64_t>(first_chunk[t]) << sub_shift);
+  double sum = p[w_a].tail;
+  for (int64_t w = w_a + 1; w <= w_b; ++w) sum += p[w].head;
+  means[row] = sum / static_cast<double>(cols);
 }
 
 __global__ __launch_bounds__(64) void novak_clip_kernel(int n_tensors, const NormSums *tensor_sums, float c_clip, float *gscale) {
@@ -636,54 +791,6 @@ __global__ __launch_bounds__(64) void novak_clip_kernel(int n_tensors, const Nor
     const double norm = sqrt(g);
     gscale[0] = norm > static_cast<double>(c_clip) ? static_cast<float>(static_cast<double>(c_clip) / norm) : 1.0f;
   }
-}
-
-// Row means for gradient centralization (Eq. 26): one wave per row of a centralized tensor.
-// `gc_tensor[j]` lists the centralized tensors, `row_first[j]` the index of tensor j's first row in
-// the launch (prefix sums, n_gc + 1 entries).
-template <typename GradS>
-__global__ __launch_bounds__(64) void novak_rowmean_kernel(const void *const *grad, const int *gc_tensor, const int64_t *row_first,
-                                                          int n_gc, const GcInfo *gc, double *means) {
-  const int64_t row = blockIdx.x;
-  int lo = 0, hi = n_gc - 1;                     // largest j with row_first[j] <= row
-  while (lo < hi) {
-    const int mid = (lo + hi + 1) >> 1;
-    if (row_first[mid] <= row) lo = mid;
-    else hi = mid - 1;
-  }
-  const int t = gc_tensor[lo];
-  const int64_t local = row - row_first[lo];
-  const int64_t cols = gc[t].cols;
-  const GradS *__restrict__ p = static_cast<const GradS *>(grad[t]) + local * cols;
-  double acc = 0.0;
-  int64_t done = 0;
-  if constexpr (sizeof(GradS) == 4) {
-    // 128-bit path for rows that start 16-byte aligned; four loads in flight per lane
-    if ((reinterpret_cast<uintptr_t>(p) & 15u) == 0) {
-      const f32x4 *p4 = reinterpret_cast<const f32x4 *>(p);
-      const int64_t nvec = cols >> 2;
-      int64_t i = threadIdx.x;
-      for (; i + 3 * 64 < nvec; i += 4 * 64) {
-        const f32x4 a = __builtin_nontemporal_load(p4 + i), b = __builtin_nontemporal_load(p4 + i + 64),
-                    c4 = __builtin_nontemporal_load(p4 + i + 128), d = __builtin_nontemporal_load(p4 + i + 192);
-        acc += (static_cast<double>(a[0]) + a[1]) + (static_cast<double>(a[2]) + a[3]);
-        acc += (static_cast<double>(b[0]) + b[1]) + (static_cast<double>(b[2]) + b[3]);
-        acc += (static_cast<double>(c4[0]) + c4[1]) + (static_cast<double>(c4[2]) + c4[3]);
-        acc += (static_cast<double>(d[0]) + d[1]) + (static_cast<double>(d[2]) + d[3]);
-      }
-      for (; i < nvec; i += 64) {
-        const f32x4 a = __builtin_nontemporal_load(p4 + i);
-        acc += (static_cast<double>(a[0]) + a[1]) + (static_cast<double>(a[2]) + a[3]);
-      }
-      done = nvec << 2;
-    }
-  }
-  for (int64_t i = done + threadIdx.x; i < cols; i += 64) {
-    if constexpr (sizeof(GradS) == 2) acc += static_cast<double>(bf16_to_f32(p[i]));
-    else acc += static_cast<double>(p[i]);
-  }
-  const double sum = wave_sum(acc);
-  if (threadIdx.x == 0) means[row] = sum / static_cast<double>(cols);
 }
 
 struct ScaleParams {

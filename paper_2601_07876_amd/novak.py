@@ -26,8 +26,9 @@ NOVAK_MOMENT_F32, NOVAK_MOMENT_BF16_M = 0, 1
 NOVAK_WARN_TRUE_NESTEROV_DOWNGRADED, NOVAK_WARN_LOOKAHEAD_DOWNGRADED = 1, 2
 NOVAK_WARN_LAYER_ADAPTATION_DISABLED, NOVAK_WARN_AUTO_LR_DISABLED, NOVAK_WARN_GC_DISABLED = 4, 8, 16
 NOVAK_TUNE_CHUNK_ELEMS, NOVAK_TUNE_NONTEMPORAL, NOVAK_TUNE_VEC_PER_LANE, NOVAK_TUNE_THREADS, NOVAK_TUNE_WAVES_PER_CU = 0, 1, 2, 3, 4
+NOVAK_TUNE_PREPASS_WAVES_PER_CU = 5
 
-NOVAK_STATIC_MAX_TENSORS, NOVAK_STATIC_MAX_CHUNKS, NOVAK_STATIC_SCRATCH_BYTES = 1024, 16384, 5 << 20
+NOVAK_STATIC_MAX_TENSORS, NOVAK_STATIC_MAX_CHUNKS, NOVAK_STATIC_SCRATCH_BYTES = 1024, 16384, 2 << 20
 
 NESTEROV = {"none": 0, "approx": 1, "classical": 2, "true": 3}
 LOOKAHEAD = {"none": 0, "memory_efficient": 1, "basic": 2}

@@ -150,7 +150,9 @@ def _full_size_scaled(workload, steps, layer, auto, auto_sync=True, nesterov=Non
     gdt = torch.bfloat16 if wl.grad_dtype == "bf16" else torch.float32
     g = torch.empty(off, dtype=gdt, device=dev)
     hp = N.make_hparams(auto_sync=auto_sync, **hyper)
-    descs = [N.novak_tensor_desc(*(bufs[r].data_ptr() + 4 * o for r in ("theta", "m", "v", "la")), n) for o, n in zip(offs, numels)]
+    rows = wl.rows if hyper.get("use_gc") else [0] * len(numels)
+    descs = [N.novak_tensor_desc(*(bufs[r].data_ptr() + 4 * o for r in ("theta", "m", "v", "la")), n, r0)
+             for o, n, r0 in zip(offs, numels, rows)]
     rc, handle = N.novak_create(hp, descs, 0)
     N.check(rc, "create")
     ema = torch.zeros(2, dtype=torch.float64, device=dev)
@@ -160,7 +162,7 @@ def _full_size_scaled(workload, steps, layer, auto, auto_sync=True, nesterov=Non
         N.check(N.novak_lookahead_init(handle, 0), "init", handle)
         h = H.oracle_hyper(hyper)
         theta_host = bufs["theta"].cpu().numpy()
-        states = [O.init_state(theta_host[o:o + n], h) for o, n in zip(offs, numels)]
+        states = [O.init_state(theta_host[o:o + n], h, rows=r0) for o, n, r0 in zip(offs, numels, rows)]
         aux = O.AutoLrState()
         # a run with a discontinuous decision (here Eq. 27) is compared after every step from a common state
         checked = H.CheckedOracle(states, h, wl.grad_dtype, aux) if H.needs_common_state(h) else None
@@ -221,3 +223,14 @@ def test_c2_resnet50_clipping_and_sparse_threshold_full_oracle():
     """Global-norm clipping (active: ||g|| ~ 5 for this workload) and Eq. 27, single-pass and two-pass."""
     _full_size_scaled("c2_resnet50", 6, layer=False, auto=False, clip_threshold=1.0, sparse_threshold=0.05)
     _full_size_scaled("c2_resnet50", 3, layer=True, auto=True, clip_threshold=1.0, sparse_threshold=0.05)
+
+
+def test_c3_vgg16_centralization_and_clipping_full_oracle():
+    """The fused gradient pre-pass at full size: rows of 27 ... 25088 elements (Eq. 26) and the global norm
+    (the clip bites: ||g|| ~ 11.8 on this list), single-pass step, every element against the oracle."""
+    _full_size_scaled("c3_vgg16", 3, layer=False, auto=False, use_gc=True, clip_threshold=1.0)
+
+
+def test_c4_vit_b16_bf16_centralization_full_oracle():
+    """bf16 gradients, rows of 768 and 3072 elements, one row of 151296 (position embedding), no clipping."""
+    _full_size_scaled("c4_vit_b16_bf16", 2, layer=False, auto=False, use_gc=True)
