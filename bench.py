@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--nesterov", default=None, help="override: none | approx | classical | true")
     ap.add_argument("--la-k", type=int, default=None)
     ap.add_argument("--separate-sync", action="store_true", help="call novak_lookahead_sync instead of fusing the sync")
+    ap.add_argument("--extrapolate", action="store_true",
+                    help="true Nesterov: call novak_nesterov_extrapolate (Eq. 10) before every step, as a caller that evaluates the "
+                         "gradient at the extrapolated point would; timed as its own kernel line")
     ap.add_argument("--layer-adaptation", action="store_true", help="research mode: per-tensor trust ratio (two-pass step)")
     ap.add_argument("--auto-lr", action="store_true", help="research mode: auto-LR factor (two-pass step)")
     ap.add_argument("--use-gc", action="store_true", help="research mode: gradient centralization of the multi-dimensional tensors")
@@ -44,14 +47,18 @@ def parse_args():
     ap.add_argument("--sparse", type=float, default=0.0, help="sparse threshold tau of Eq. 27 (0 = off)")
     ap.add_argument("--moment-dtype", default="f32", choices=("f32", "bf16_m"),
                     help="storage of the first moment: fp32, or bfloat16 (reduced-precision state; not the headline configuration)")
-    ap.add_argument("--layout", default="arena", choices=("arena", "separate"),
-                    help="arena: one allocation for all roles with a fixed spacing; separate: one allocation per role")
+    ap.add_argument("--layout", default="arena", choices=("arena", "torch_one", "separate"),
+                    help="arena: one allocation from the library for all roles with a fixed spacing; torch_one: the same spacing "
+                         "inside one ordinary torch allocation; separate: one torch allocation per role")
     ap.add_argument("--chunk-elems", type=int, default=None)
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--vec-per-lane", type=int, default=None)
     ap.add_argument("--threads", type=int, default=None)
     ap.add_argument("--waves-per-cu", type=int, default=None)
     ap.add_argument("--prepass-waves-per-cu", type=int, default=None)
+    ap.add_argument("--mode", default=None, choices=("fast", "research"), help="override the workload's dual-mode setting (section 7.1)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the comparison runs reported beside the headline (PyTorch-allocated layouts, separate sync kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 22, help="elements of the oracle's timed sample")
     ap.add_argument("--cpu-workers", type=int, default=min(16, os.cpu_count() or 1),
@@ -124,6 +131,180 @@ def cpu_baseline_all_cores(pool, workers: int, workload: str, hyper, n_sample: i
                       f"{n_sample}-element slice; sum of their rates"}
 
 
+class Setup:
+    """Device buffers of one workload in one layout, a library handle over them, and the timing loop.
+
+    layout: "arena"  - one allocation from novak_arena_alloc (physically contiguous when the driver can),
+                       roles placed by novak_plan_arena;
+            "torch_one" - the same placement inside ONE ordinary torch allocation;
+            "separate"  - five separate torch allocations (what a framework's optimizer usually holds).
+    """
+
+    def __init__(self, wl, hyper, layout, fused, args, torch, N, W):
+        self.torch, self.N, self.wl, self.layout, self.fused = torch, N, wl, layout, fused
+        dev = torch.device("cuda:0")
+        numels = wl.numels
+        self.p = wl.total
+        rc, offsets, flat, stride = N.novak_plan_arena(numels)
+        N.check(rc, "novak_plan_arena")
+        flat = max(flat, 1)
+        m_dtype = torch.bfloat16 if hyper["moment_dtype"] == "bf16_m" else torch.float32
+        g_dtype = torch.bfloat16 if wl.grad_dtype == "bf16" else torch.float32
+        self.arena_ptr, self.arena_contiguous, self.arena = None, 0, None
+        if layout == "arena":
+            torch.zeros(1, device=dev)       # the device context exists before the library allocates on it
+            rc, self.arena_ptr, self.arena_contiguous = N.novak_arena_alloc(0, 5 * stride)
+            N.check(rc, "novak_arena_alloc")
+            self.arena = N.arena_as_tensor(self.arena_ptr, 5 * stride, 0)
+        elif layout == "torch_one":
+            self.arena = torch.empty(5 * stride, dtype=torch.uint8, device=dev)
+        if self.arena is not None:
+            self.arena.zero_()
+            arena = self.arena
+
+            def role(i, dtype):
+                return arena[i * stride: i * stride + flat * dtype.itemsize].view(dtype)
+        else:
+            def role(i, dtype):
+                return torch.zeros(flat, dtype=dtype, device=dev)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(42)
+        theta, m, v, la, grad = role(0, torch.float32), role(1, m_dtype), role(2, torch.float32), role(3, torch.float32), role(4, g_dtype)
+        theta.normal_(0.0, W.PARAM_STD, generator=gen)
+        g32 = torch.empty(flat, dtype=torch.float32, device=dev).normal_(0.0, wl.grad_std, generator=gen)
+        grad.copy_(g32)          # rounds to nearest-even when the gradients are bfloat16
+        del g32
+        self.bufs = (theta, m, v, la, grad)
+
+        hp = N.make_hparams(auto_sync=fused, **hyper)
+        descs = [N.novak_tensor_desc(theta.data_ptr() + 4 * o, m.data_ptr() + m.element_size() * o, v.data_ptr() + 4 * o,
+                                     la.data_ptr() + 4 * o, n, r) for o, n, r in zip(offsets, numels, wl.rows)]
+        rc, self.handle = N.novak_create(hp, descs, 0)
+        N.check(rc, "novak_create")
+        handle = self.handle
+        for key, val in ((N.NOVAK_TUNE_CHUNK_ELEMS, args.chunk_elems), (N.NOVAK_TUNE_NONTEMPORAL, args.nontemporal),
+                         (N.NOVAK_TUNE_VEC_PER_LANE, args.vec_per_lane), (N.NOVAK_TUNE_THREADS, args.threads),
+                         (N.NOVAK_TUNE_WAVES_PER_CU, args.waves_per_cu), (N.NOVAK_TUNE_PREPASS_WAVES_PER_CU, args.prepass_waves_per_cu)):
+            if val is not None:
+                N.check(N.novak_set_tuning(handle, key, val), "set_tuning", handle)
+        rc, self.info = N.novak_get_info(handle)
+        info = self.info
+        self.la_name = {0: "none", 1: "memory_efficient", 2: "basic"}[info.lookahead_mode]
+        self.nest_name = {0: "none", 1: "approx", 2: "classical", 3: "true"}[info.nesterov_mode]
+        self.k = int(hyper["la_k"])
+        self.gdt = N.GRAD_DTYPE[wl.grad_dtype]
+        self.grad_arr = (C.c_void_p * len(numels))(*[grad.data_ptr() + grad.element_size() * o for o in offsets])
+        self.stream = torch.cuda.current_stream().cuda_stream
+        if self.la_name != "none":
+            N.check(N.novak_lookahead_init(handle, self.stream), "lookahead_init", handle)
+        self.ema = torch.zeros(2, dtype=torch.float64, device=dev)
+        if info.auto_lr:
+            N.check(N.novak_set_auto_lr_state(handle, self.ema.data_ptr()), "set_auto_lr_state", handle)
+        self.extrapolate_arr = None
+        if args.extrapolate:
+            self.extra_out = torch.empty(flat, dtype=torch.float32, device=dev)
+            self.extrapolate_arr = (C.c_void_p * len(numels))(*[self.extra_out.data_ptr() + 4 * o for o in offsets])
+        self.scaled = bool(info.layer_adaptation or info.auto_lr)
+        self.m_tag = "+bf16_m" if info.moment_dtype == N.NOVAK_MOMENT_BF16_M else ""
+        self.t = 0
+        # extra gradient reads of the pre-pass (one read serves clipping and centralization; with centralization
+        # alone only the centralized tensors are read)
+        self.extra_bpp = 0.0
+        if hyper["clip_threshold"] > 0:
+            self.extra_bpp = N.novak_bytes_per_param_clip(self.gdt)
+        elif info.use_gc:
+            self.extra_bpp = N.novak_bytes_per_param_clip(self.gdt) * sum(n for n, r in zip(numels, wl.rows) if r >= 1) / max(self.p, 1)
+
+    def one_step(self):
+        N, handle = self.N, self.handle
+        self.t += 1
+        N.check(N.novak_step(handle, self.grad_arr, self.gdt, self.t, self.stream), "novak_step", handle)
+        if self.la_name != "none" and not self.fused and self.t % self.k == 0:
+            N.check(N.novak_lookahead_sync(handle, self.stream), "novak_lookahead_sync", handle)
+            return True
+        return False
+
+    def bytes_of(self, name):
+        """Algorithmic bytes per parameter of a step variant (a two-pass "scaled_" step is timed as a whole)."""
+        N, info, k = self.N, self.info, self.k
+        two = name.startswith("scaled_")
+        fn = N.novak_bytes_per_param_scaled_step if two else N.novak_bytes_per_param_step
+        base = name[len("scaled_"):] if two else name
+        base = base[:len(base) - len(self.m_tag)] if self.m_tag else base
+        pos = {"step": 2 if self.la_name == "basic" else 1, "step+la_first": 1, "step+la_mid": 2,
+               "step+la_last_fused": k, "step+basic_fused": k}[base]
+        saved = N.novak_bytes_per_param_moment_saving(info.moment_dtype, int(two))
+        la_mode = info.lookahead_mode
+        return self.extra_bpp - saved + (fn(la_mode, self.gdt, k, pos, int(self.fused)) if self.la_name != "none" else fn(0, self.gdt, k, 1, 0))
+
+    def timed(self, warmup, steps):
+        """W untimed steps, then exactly K steps between synchronisations, each bracketed by HIP events on the launch stream."""
+        torch, N = self.torch, self.N
+        for _ in range(warmup):
+            if self.extrapolate_arr is not None:
+                N.check(N.novak_nesterov_extrapolate(self.handle, self.extrapolate_arr, self.stream), "novak_nesterov_extrapolate", self.handle)
+            self.one_step()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        variants, sync_ev, extra_ev = [], [], []
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for i in range(steps):
+            variants.append(("scaled_" if self.scaled else "") + la_variant(self.la_name, self.k, self.t + 1, self.fused) + self.m_tag)
+            if self.extrapolate_arr is not None:
+                x0 = torch.cuda.Event(enable_timing=True)
+                x0.record()
+                N.check(N.novak_nesterov_extrapolate(self.handle, self.extrapolate_arr, self.stream), "novak_nesterov_extrapolate", self.handle)
+                extra_ev.append((x0, ev[i][0]))
+            ev[i][0].record()
+            self.t += 1
+            N.check(N.novak_step(self.handle, self.grad_arr, self.gdt, self.t, self.stream), "novak_step", self.handle)
+            ev[i][1].record()
+            if self.la_name != "none" and not self.fused and self.t % self.k == 0:
+                N.check(N.novak_lookahead_sync(self.handle, self.stream), "novak_lookahead_sync", self.handle)
+                done = torch.cuda.Event(enable_timing=True)
+                done.record()
+                sync_ev.append((ev[i][1], done))
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t_begin
+        per = {}
+        for name, (a, b) in zip(variants, ev):
+            per.setdefault(name, []).append(a.elapsed_time(b))     # ms
+        p = self.p
+        kernels = {}
+        for name, ms in per.items():
+            avg, bpp = sum(ms) / len(ms), self.bytes_of(name)
+            kernels[name] = {"launches": len(ms), "avg_ms": avg, "bytes_per_param": bpp, "GBps": p * bpp / (avg * 1e-3) / 1e9}
+        if sync_ev:     # the separate slow-weight synchronisation kernel (Eq. 30-31), timed from the end of its step
+            ms = [a.elapsed_time(b) for a, b in sync_ev]
+            avg, bpp = sum(ms) / len(ms), N.novak_bytes_per_param_sync(self.info.lookahead_mode)
+            kernels["lookahead_sync"] = {"launches": len(ms), "avg_ms": avg, "bytes_per_param": bpp, "GBps": p * bpp / (avg * 1e-3) / 1e9}
+        if extra_ev:    # Eq. 10: theta and m read, the extrapolated point written
+            ms = [a.elapsed_time(b) for a, b in extra_ev]
+            avg, bpp = sum(ms) / len(ms), 12.0 - (2.0 if self.m_tag else 0.0)
+            kernels["nesterov_extrapolate"] = {"launches": len(ms), "avg_ms": avg, "bytes_per_param": bpp, "GBps": p * bpp / (avg * 1e-3) / 1e9}
+        dominant = max(kernels, key=lambda n: kernels[n]["launches"] * kernels[n]["avg_ms"])
+        return {"elapsed": elapsed, "value": p * steps / elapsed / 1e9, "ms_per_step": elapsed / steps * 1e3,
+                "kernels": kernels, "dominant": dominant}
+
+    def close(self):
+        self.torch.cuda.synchronize()
+        self.N.novak_destroy(self.handle)
+        self.bufs = None
+        if self.arena_ptr is not None:
+            self.arena = None
+            self.N.check(self.N.novak_arena_free(0, self.arena_ptr), "novak_arena_free")
+        self.arena = None
+        self.torch.cuda.empty_cache()
+
+
+def brief(r):
+    """The figures of a comparison run that go beside the headline."""
+    k = r["kernels"][r["dominant"]]
+    return {"value": r["value"], "unit": "Gparams/s", "ms_per_step": r["ms_per_step"], "dominant_kernel": r["dominant"],
+            "GBps": k["GBps"], "frac": k["GBps"] / HBM_PEAK_GBS}
+
+
 def main():
     args = parse_args()
     pool, workers = None, 0
@@ -144,8 +325,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
+    torch.cuda.set_device(torch.device("cuda:0"))
 
     wl = W.get_workload(args.workload)
     hyper = dict(wl.hyper)
@@ -155,154 +335,41 @@ def main():
         hyper["nesterov"] = args.nesterov
     if args.la_k:
         hyper["la_k"] = args.la_k
-    scaled = args.layer_adaptation or args.auto_lr
-    if scaled or args.use_gc:
+    if args.mode:
+        hyper["mode"] = args.mode
+    if args.layer_adaptation or args.auto_lr or args.use_gc:
         hyper.update(mode="research", layer_adaptation=args.layer_adaptation, auto_lr=args.auto_lr, use_gc=args.use_gc)
     hyper.update(clip_threshold=args.clip, sparse_threshold=args.sparse, moment_dtype=args.moment_dtype)
     fused = not args.separate_sync
-    numels = wl.numels
     p = wl.total
 
-    # ---- device buffers: ONE allocation for all five roles, placed as novak_plan_arena recommends ---------
-    # (tensors at 1 KB multiples inside a role, roles 2 KB apart modulo 8 KB, physically contiguous when the
-    # driver can; with separately allocated buffers the same kernel measured between 5.9 and 6.6 TB/s
-    # depending on where the driver put them)
-    rc, offsets, flat, stride = N.novak_plan_arena(numels)
-    N.check(rc, "novak_plan_arena")
-    flat = max(flat, 1)
-    m_dtype = torch.bfloat16 if args.moment_dtype == "bf16_m" else torch.float32
-    g_dtype = torch.bfloat16 if wl.grad_dtype == "bf16" else torch.float32
-    arena_ptr, arena_contiguous = None, 0
-    if args.layout == "arena":
-        torch.zeros(1, device=dev)       # the device context exists before the library allocates on it
-        rc, arena_ptr, arena_contiguous = N.novak_arena_alloc(0, 5 * stride)
-        N.check(rc, "novak_arena_alloc")
-        arena = N.arena_as_tensor(arena_ptr, 5 * stride, 0)
-        arena.zero_()
-
-        def role(i, dtype):
-            return arena[i * stride: i * stride + flat * dtype.itemsize].view(dtype)
-    else:
-        def role(i, dtype):
-            return torch.zeros(flat, dtype=dtype, device=dev)
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(42)
-    theta, m, v, la, grad = role(0, torch.float32), role(1, m_dtype), role(2, torch.float32), role(3, torch.float32), role(4, g_dtype)
-    theta.normal_(0.0, W.PARAM_STD, generator=gen)
-    g32 = torch.empty(flat, dtype=torch.float32, device=dev).normal_(0.0, wl.grad_std, generator=gen)
-    grad.copy_(g32)          # rounds to nearest-even when the gradients are bfloat16
-    del g32
-
-    hp = N.make_hparams(auto_sync=fused, **hyper)
-    descs = [N.novak_tensor_desc(theta.data_ptr() + 4 * o, m.data_ptr() + m.element_size() * o, v.data_ptr() + 4 * o,
-                                 la.data_ptr() + 4 * o, n, r) for o, n, r in zip(offsets, numels, wl.rows)]
-    rc, handle = N.novak_create(hp, descs, 0)
-    N.check(rc, "novak_create")
-    if args.chunk_elems:
-        N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_CHUNK_ELEMS, args.chunk_elems), "set_tuning", handle)
-    if args.nontemporal is not None:
-        N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_NONTEMPORAL, args.nontemporal), "set_tuning", handle)
-    if args.vec_per_lane is not None:
-        N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_VEC_PER_LANE, args.vec_per_lane), "set_tuning", handle)
-    if args.threads is not None:
-        N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_THREADS, args.threads), "set_tuning", handle)
-    if args.waves_per_cu is not None:
-        N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_WAVES_PER_CU, args.waves_per_cu), "set_tuning", handle)
-    if args.prepass_waves_per_cu is not None:
-        N.check(N.novak_set_tuning(handle, N.NOVAK_TUNE_PREPASS_WAVES_PER_CU, args.prepass_waves_per_cu), "set_tuning", handle)
-    rc, info = N.novak_get_info(handle)
-    la_name = {0: "none", 1: "memory_efficient", 2: "basic"}[info.lookahead_mode]
-    nest_name = {0: "none", 1: "approx", 2: "classical", 3: "true"}[info.nesterov_mode]
-    k = int(hyper["la_k"])
-    gdt = N.GRAD_DTYPE[wl.grad_dtype]
-    grad_arr = (C.c_void_p * len(numels))(*[grad.data_ptr() + grad.element_size() * o for o in offsets])
-    stream = torch.cuda.current_stream().cuda_stream
-    if la_name != "none":
-        N.check(N.novak_lookahead_init(handle, stream), "lookahead_init", handle)
-    ema = torch.zeros(2, dtype=torch.float64, device=dev)
-    if info.auto_lr:
-        N.check(N.novak_set_auto_lr_state(handle, ema.data_ptr()), "set_auto_lr_state", handle)
-    scaled = bool(info.layer_adaptation or info.auto_lr)
-    m_tag = "+bf16_m" if info.moment_dtype == N.NOVAK_MOMENT_BF16_M else ""
-
-    def one_step(t):
-        N.check(N.novak_step(handle, grad_arr, gdt, t, stream), "novak_step", handle)
-        if la_name != "none" and not fused and t % k == 0:
-            N.check(N.novak_lookahead_sync(handle, stream), "novak_lookahead_sync", handle)
-
-    t = 0
-    for _ in range(args.warmup):
-        t += 1
-        one_step(t)
-    torch.cuda.synchronize()
-
-    # ---- timed region: exactly K steps, per-step HIP events on the launch stream ------------------
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    variants, sync_ev = [], []
-    torch.cuda.synchronize()
-    t_begin = time.perf_counter()
-    for i in range(args.steps):
-        t += 1
-        variants.append(("scaled_" if scaled else "") + la_variant(la_name, k, t, fused) + m_tag)
-        ev[i][0].record()
-        N.check(N.novak_step(handle, grad_arr, gdt, t, stream), "novak_step", handle)
-        ev[i][1].record()
-        if la_name != "none" and not fused and t % k == 0:
-            N.check(N.novak_lookahead_sync(handle, stream), "novak_lookahead_sync", handle)
-            done = torch.cuda.Event(enable_timing=True)
-            done.record()
-            sync_ev.append((ev[i][1], done))
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_begin
-
-    # ---- per-variant kernel time and the roofline of the dominant one -----------------------------
-    per = {}
-    for name, (a, b) in zip(variants, ev):
-        per.setdefault(name, []).append(a.elapsed_time(b))     # ms
-    la_mode = info.lookahead_mode
-
-    # extra gradient reads of the pre-passes (clipping: all tensors; centralization: the centralized ones)
-    extra_bpp = (N.novak_bytes_per_param_clip(gdt) if args.clip > 0 else 0.0)
-    if info.use_gc:
-        extra_bpp += N.novak_bytes_per_param_clip(gdt) * sum(n for n, r in zip(numels, wl.rows) if r >= 1) / max(p, 1)
-
-    def bytes_of(name):
-        # a two-pass ("scaled_") step is timed as a whole: both passes and the small reductions between them
-        fn = N.novak_bytes_per_param_scaled_step if name.startswith("scaled_") else N.novak_bytes_per_param_step
-        base = name[len("scaled_"):] if name.startswith("scaled_") else name
-        base = base[:len(base) - len(m_tag)] if m_tag else base
-        pos = {"step": 2 if la_name == "basic" else 1, "step+la_first": 1, "step+la_mid": 2,
-               "step+la_last_fused": k, "step+basic_fused": k}[base]
-        saved = N.novak_bytes_per_param_moment_saving(info.moment_dtype, int(name.startswith("scaled_")))
-        return extra_bpp - saved + (fn(la_mode, gdt, k, pos, int(fused)) if la_name != "none" else fn(0, gdt, k, 1, 0))
-
-    kernels = {}
-    for name, ms in per.items():
-        avg = sum(ms) / len(ms)
-        bpp = bytes_of(name)
-        kernels[name] = {"launches": len(ms), "avg_ms": avg, "bytes_per_param": bpp,
-                         "GBps": p * bpp / (avg * 1e-3) / 1e9}
-    if sync_ev:     # the separate slow-weight synchronisation kernel (Eq. 30-31), timed from the end of its step
-        ms = [a.elapsed_time(b) for a, b in sync_ev]
-        avg, bpp = sum(ms) / len(ms), N.novak_bytes_per_param_sync(la_mode)
-        kernels["lookahead_sync"] = {"launches": len(ms), "avg_ms": avg, "bytes_per_param": bpp, "GBps": p * bpp / (avg * 1e-3) / 1e9}
-    dominant = max(kernels, key=lambda n: kernels[n]["launches"] * kernels[n]["avg_ms"])
+    # ---- the headline: the requested layout (default: the library's arena) and sync mode (default: fused) ----
+    run = Setup(wl, hyper, args.layout, fused, args, torch, N, W)
+    info, la_name, nest_name, k = run.info, run.la_name, run.nest_name, run.k
+    arena_contiguous = run.arena_contiguous
+    res = run.timed(args.warmup, args.steps)
+    run.close()
+    kernels, dominant = res["kernels"], res["dominant"]
     dk = kernels[dominant]
+    running = profiled_config_of(args, fused)
+    traffic, traffic_file = measured_traffic(args.workload, dominant, running)
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": dk["GBps"] / HBM_PEAK_GBS, "avg_kernel_ms": dk["avg_ms"],
-                "algorithmic_bytes_per_launch": p * dk["bytes_per_param"], "traffic": measured_traffic(args.workload, dominant)}
-    if roofline["traffic"]:
-        roofline["traffic_GBps"] = roofline["traffic"] / (dk["avg_ms"] * 1e-3) / 1e9   # counter-derived bandwidth
+                "algorithmic_bytes_per_launch": p * dk["bytes_per_param"], "traffic": traffic}
+    if traffic:
+        # counters come from a separate rocprofv3 --pmc run of this same configuration, committed under profiles/
+        roofline["traffic_source"] = traffic_file
+        roofline["traffic_over_algorithmic"] = traffic / (p * dk["bytes_per_param"])
 
     result = {
         "metric": "Gparams updated/s per NOVAK step",
-        "value": p * args.steps / elapsed / 1e9,
+        "value": res["value"],
         "unit": "Gparams/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": elapsed / args.steps * 1e3,
+        "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": wl.name, "params": p, "tensors": len(numels), "grad_dtype": wl.grad_dtype,
+        "config": {"workload": wl.name, "params": p, "tensors": len(wl.numels), "grad_dtype": wl.grad_dtype,
                    "nesterov": nest_name, "lookahead": la_name, "la_k": k, "sync": "fused" if fused else "separate",
                    "mode": hyper["mode"], "rectified": bool(hyper["rectified"]),
                    "layer_adaptation": bool(info.layer_adaptation), "auto_lr": bool(info.auto_lr),
@@ -312,11 +379,25 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
-    torch.cuda.synchronize()
-    N.novak_destroy(handle)
-    if arena_ptr is not None:
-        del theta, m, v, la, grad, arena
-        N.check(N.novak_arena_free(0, arena_ptr), "novak_arena_free")
+
+    # ---- beside it, in the same process: what a caller gets whose memory comes from PyTorch, and the sync as a
+    # ---- separate kernel (the benchmark spec names both); skipped when a specific layout / sync mode was asked for
+    if not args.no_extras and args.layout == "arena" and fused:
+        others = {}
+        for name, layout in (("torch_one_allocation_planned_layout", "torch_one"), ("torch_five_separate_allocations", "separate")):
+            r2 = Setup(wl, hyper, layout, True, args, torch, N, W)
+            others[name] = brief(r2.timed(args.warmup, args.steps))
+            r2.close()
+        result["other_layouts"] = others
+        if la_name != "none":
+            r3 = Setup(wl, hyper, "arena", False, args, torch, N, W)
+            t3 = r3.timed(args.warmup, args.steps)
+            r3.close()
+            sk = t3["kernels"].get("lookahead_sync")
+            result["separate_sync"] = {"value": t3["value"], "unit": "Gparams/s", "ms_per_step": t3["ms_per_step"],
+                                       "note": "novak_lookahead_sync as its own kernel after every k-th step, amortised over the timed steps",
+                                       "sync_kernel": ({**sk, "frac": sk["GBps"] / HBM_PEAK_GBS} if sk else None)}
+
     if not args.no_cpu_baseline:
         eff = {**hyper, "nesterov": nest_name, "lookahead": la_name, "layer_adaptation": bool(info.layer_adaptation),
                "auto_lr": bool(info.auto_lr), "use_gc": False}
@@ -328,16 +409,30 @@ def main():
     print(json.dumps(result))
 
 
-def measured_traffic(workload: str, kernel: str):
-    """HBM bytes per launch from committed rocprofv3 counter summaries (profiles/traffic_*.txt), or None."""
-    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+def profiled_config_of(args, fused) -> str:
+    """The launch configuration as the profiles/ summaries state it (a counter figure is only carried over
+    to a run of the same configuration)."""
+    auto = lambda x, d: d if x is None else x
+    return (f"layout={args.layout} chunk_elems={auto(args.chunk_elems, 16384)} waves_per_cu={auto(args.waves_per_cu, 0)} "
+            f"nontemporal={auto(args.nontemporal, 1)} vec_per_lane={auto(args.vec_per_lane, 1)} threads={auto(args.threads, 64)} "
+            f"sync={'fused' if fused else 'separate'}")
+
+
+def measured_traffic(workload: str, kernel: str, running_config: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this workload
+    (profiles/traffic_*.txt), if that summary was taken in the running launch configuration; else (None, None)."""
+    name = f"traffic_{workload}.txt"
+    path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
-        return None
-    for line in open(path):
+        return None, None
+    lines = open(path).read().splitlines()
+    if not any(l.strip() == "profiled_config " + running_config for l in lines):
+        return None, None
+    for line in lines:
         parts = line.split()
         if len(parts) >= 3 and parts[0] == "hbm_bytes_per_launch" and parts[1] == kernel:
-            return float(parts[2])
-    return None
+            return float(parts[2]), "profiles/" + name
+    return None, None
 
 
 if __name__ == "__main__":

@@ -13,6 +13,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libnovak.so")
+HOSTCOST_PATH = os.path.join(PKG_DIR, "novak_hostcost")     # plain C++ timing loop over novak_step (no Python in the way)
 
 SOURCES = ["novak_host.cpp", "novak_device.hip"]
 
@@ -52,7 +53,22 @@ def build_library(verbose: bool = True) -> str:
         if lines:
             print("\n".join(lines))
     os.replace(tmp, LIB_PATH)
+    build_hostcost(verbose)
     return LIB_PATH
+
+
+def build_hostcost(verbose: bool = True) -> str:
+    """The host-cost timing tool: a host-only program against include/novak.h, linked to the library beside it."""
+    cmd = [hipcc_path(), "-O2", "-std=c++17", "-Wall", "-Wextra", "-I", os.path.join(ROOT, "include"),
+           os.path.join(CSRC, "novak_hostcost.cpp"), "-L", PKG_DIR, "-lnovak", "-Wl,-rpath,$ORIGIN", "-o", HOSTCOST_PATH + ".tmp"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stdout + res.stderr)
+        raise RuntimeError("hipcc failed (novak_hostcost)")
+    os.replace(HOSTCOST_PATH + ".tmp", HOSTCOST_PATH)
+    return HOSTCOST_PATH
 
 
 if __name__ == "__main__":

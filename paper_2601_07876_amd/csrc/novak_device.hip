@@ -435,7 +435,7 @@ hipError_t launch_prepass(const LaunchCtx *h, int grad_dtype, hipStream_t s, con
   const bool bf16_g = grad_dtype == NOVAK_GRAD_BF16;
   Geometry g0;
   g0.sub_shift = log2_exact(h->chunk_elems / kPreSub);
-  g0.grid = static_cast<unsigned>(h->n_chunks << g0.sub_shift);
+  g0.grid = static_cast<unsigned>(h->n_chunks);          // one wave per chunk-table entry
   int waves = h->prepass_waves_per_cu ? h->prepass_waves_per_cu : (bf16_g ? (gc ? 10 : 12) : 6);
   unsigned lds = waves >= 32 ? 0u : (static_cast<unsigned>(h->lds_per_cu) / static_cast<unsigned>(waves)) & ~511u;
   if (lds > 65536u) lds = 65536u;

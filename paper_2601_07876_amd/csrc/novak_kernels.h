@@ -580,20 +580,21 @@ __global__ __launch_bounds__(64) void novak_reduce_chunks_kernel(const novak_chu
 // Gradient pre-pass (Phase 2): ONE read of the gradients serves both consumers that need a whole-array
 // statistic before any element may be updated - the global norm of gradient clipping (sections 5.8, 7.3)
 // and the row means of gradient centralization (Eq. 26).
-//   * A wave streams kPreSub = 4096 consecutive elements with 16 independent 128-bit loads per lane in
-//     flight: a read-only stream needs about 100 KB outstanding per compute unit, and 16 KB per wave at a
-//     residency of 6 waves measured best on MI355X (7.35 TB/s against 6.8 TB/s for 4 KB per wave).
-//   * NORM: one partial sum of squares per wave; the chunk and tensor reductions below are shared with
+//   * A wave takes one chunk-table entry in spans of kPreSub = 4096 consecutive elements, 16 independent
+//     128-bit loads per lane in flight: a read-only stream needs about 100 KB outstanding per compute unit,
+//     and 16 KB per wave at a residency of 6 waves measured best on MI355X (7.35 TB/s against 6.8 TB/s for
+//     4 KB per wave).  The next span's loads are issued before the current span is reduced.
+//   * NORM: one partial sum of squares per span; the chunk and tensor reductions below are shared with
 //     the two-pass step, then novak_clip_kernel turns the norm into the factor min(1, c_clip/||g||).
-//   * GC: the wave parks its elements in LDS and sums, in double and in a fixed order, every row piece
-//     that lies in its span.  Rows that lie entirely inside the span get their mean written here; a row
+//   * GC: every row piece that lies in a span is summed in double and in a fixed order - in registers when
+//     rows are made of whole 256-element pieces, else from a copy of the span parked in LDS.  Rows that lie entirely inside the span get their mean written here; a row
 //     that sticks out at the front ("head") or at the back ("tail") leaves a partial sum, and
 //     novak_rowfinal_kernel adds those up in wave order.  Nothing depends on timing.
 constexpr int kPreUnroll = 16;
 constexpr int kPreSub = kScaledSub * kPreUnroll;        // elements per wave
 constexpr unsigned kPreStageBytes = kPreSub * sizeof(float);
 
-struct RowPartial {   // per pre-pass wave: the pieces of the (at most two) rows that stick out of its span
+struct RowPartial {   // per pre-pass span: the pieces of the (at most two) rows that stick out of its span
   double head, tail;
 };
 
@@ -646,96 +647,34 @@ __device__ __forceinline__ void emit_row(double sum, int64_t r, int64_t cols, in
   else rp->tail = sum;
 }
 
-template <typename GradS, typename GradV, bool NT, bool NORM, bool GC>
-__global__ __launch_bounds__(kScaledBlock) void novak_prepass_kernel(Tables tb, int sub_shift, NormPartial *partials,
-                                                                     RowPartial *row_partials) {
-  extern __shared__ float stage[];                      // kPreSub floats, touched only on the staged centralization path
-  const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
-  const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kPreSub;
-  if (start >= ch.len) return;
-  const int n = min(kPreSub, ch.len - start);
-  const int64_t off = ch.offset + start, end = off + n;
-  const GradS *__restrict__ g_p = static_cast<const GradS *>(tb.grad[ch.tensor]) + off;
+// What the spans of one chunk share.
+template <typename GradS>
+struct PreChunk {
+  const GradS *g;          // the chunk's first gradient element
+  int64_t offset;          // its element offset inside the tensor
+  int len;
+  bool gc;                 // this tensor is centralized
   GcInfo gi;
-  gi.cols = 0;
-  if (GC) gi = tb.gc[ch.tensor];
-  const bool gc = GC && gi.cols > 0;
-  const int64_t cols = gi.cols;
-  double *means = const_cast<double *>(gi.means);
-  RowPartial *rp = row_partials + blockIdx.x;
-  float s_g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-  bool staged = gc;                                     // false once the row sums were formed in registers
-  int done = 0;
-  if ((reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1)) == 0) {
-    const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
-    const int nvec = n >> 2;
-    if (n == kPreSub) {
-      GradV g[kPreUnroll];
-#pragma unroll
-      for (int u = 0; u < kPreUnroll; ++u) g[u] = ld<NT>(g4 + threadIdx.x + u * kScaledBlock);
-      if (NORM) {
-#pragma unroll
-        for (int u = 0; u < kPreUnroll; ++u) {
-          const f32x4 gf = grad_to_f32<GradV>(g[u]);
-#pragma unroll
-          for (int k = 0; k < 4; ++k) s_g[u & 3] = __builtin_fmaf(gf[k], gf[k], s_g[u & 3]);
-        }
-      }
-      if (gc && (cols & 255) == 0) {
-        // Rows made of whole 256-element pieces: piece u is what the wave's u-th load fetched and lies inside
-        // one row, so the row sums form in registers - lanes add their vectors over a row's pieces, then one
-        // tree per row.  Every branch is uniform.
-        staged = false;
-        int64_t r = row_of(off, cols, gi.inv_cols);
-        int left = static_cast<int>((r * cols + cols - off) >> 8);     // pieces of row r from the span's start on
-        double acc = 0.0;
-#pragma unroll
-        for (int u = 0; u < kPreUnroll; ++u) {
-          const f32x4 gf = grad_to_f32<GradV>(g[u]);
-          acc += (static_cast<double>(gf[0]) + gf[1]) + (static_cast<double>(gf[2]) + gf[3]);
-          if (--left == 0 || u == kPreUnroll - 1) {
-            const double sum = wave_total_in_lane63(acc);
-            if (threadIdx.x == 63) emit_row(sum, r, cols, off, end, means, rp);
-            ++r;
-            left = static_cast<int>(cols >> 8);
-            acc = 0.0;
-          }
-        }
-      } else if (gc) {
-#pragma unroll
-        for (int u = 0; u < kPreUnroll; ++u)
-          *reinterpret_cast<f32x4 *>(stage + 4 * (threadIdx.x + u * kScaledBlock)) = grad_to_f32<GradV>(g[u]);
-      }
-    } else {
-      for (int i = threadIdx.x; i < nvec; i += kScaledBlock) {
-        const f32x4 gf = grad_to_f32<GradV>(ld<NT>(g4 + i));
-        if (NORM) {
-#pragma unroll
-          for (int k = 0; k < 4; ++k) s_g[0] = __builtin_fmaf(gf[k], gf[k], s_g[0]);
-        }
-        if (gc) *reinterpret_cast<f32x4 *>(stage + 4 * i) = gf;
-      }
-    }
-    done = nvec << 2;
+  NormPartial *partials;   // one per span of this chunk
+  RowPartial *row_partials;
+};
+
+template <bool NORM>
+__device__ __forceinline__ void emit_norm(const float (&s_g)[4], NormPartial *out) {
+  if (!NORM) return;
+  const float total = wave_total_in_lane63((s_g[0] + s_g[1]) + (s_g[2] + s_g[3]));
+  if (threadIdx.x == 63) {
+    NormPartial p;
+    p.theta2 = 0.0f; p.u2 = 0.0f; p.g2 = total; p.pad = 0.0f;
+    *out = p;
   }
-  for (int i = done + threadIdx.x; i < n; i += kScaledBlock) {
-    float g;
-    if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
-    else g = g_p[i];
-    if (NORM) s_g[0] = __builtin_fmaf(g, g, s_g[0]);
-    if (gc) stage[i] = g;
-  }
-  if (NORM) {
-    const float total = wave_total_in_lane63((s_g[0] + s_g[1]) + (s_g[2] + s_g[3]));
-    if (threadIdx.x == 63) {
-      NormPartial p;
-      p.theta2 = 0.0f; p.u2 = 0.0f; p.g2 = total; p.pad = 0.0f;
-      partials[blockIdx.x] = p;
-    }
-  }
-  if (!staged) return;
+}
+
+// Row sums of a span whose n elements are parked in LDS.
+__device__ __forceinline__ void rows_from_stage(const float *stage, int64_t off, int n, const GcInfo &gi, RowPartial *rp) {
   __syncthreads();                                      // one wave: orders the LDS writes before the reads
-  // rows r_first..r_last meet the span
+  const int64_t cols = gi.cols, end = off + n;
+  double *means = const_cast<double *>(gi.means);
   const int64_t r_first = row_of(off, cols, gi.inv_cols), r_last = row_of(end - 1, cols, gi.inv_cols);
   if (r_last - r_first >= 64) {
     // many short rows: one lane per row, elements summed in order
@@ -754,6 +693,127 @@ __global__ __launch_bounds__(kScaledBlock) void novak_prepass_kernel(Tables tb, 
       const double sum = stage_sum_wave(stage, a, b);
       if (threadIdx.x == 63) emit_row(sum, r, cols, off, end, means, rp);
     }
+  }
+  __syncthreads();                                      // the next span of this wave reuses the buffer
+}
+
+// A full, aligned span whose 16 vectors per lane are already in registers.  (Norm first, row sums in a second
+// sweep: one merged sweep measured 1-13 % slower, the scans between the pieces hold up the arriving loads.)
+template <typename GradS, typename GradV, bool NORM>
+__device__ __forceinline__ void span_from_registers(const GradV (&g)[kPreUnroll], int s, const PreChunk<GradS> &pc, float *stage) {
+  const int64_t off = pc.offset + static_cast<int64_t>(s) * kPreSub, end = off + kPreSub;
+  float s_g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (NORM) {
+#pragma unroll
+    for (int u = 0; u < kPreUnroll; ++u) {
+      const f32x4 gf = grad_to_f32<GradV>(g[u]);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) s_g[u & 3] = __builtin_fmaf(gf[k], gf[k], s_g[u & 3]);
+    }
+  }
+  emit_norm<NORM>(s_g, pc.partials + s);
+  if (!pc.gc) return;
+  const int64_t cols = pc.gi.cols;
+  RowPartial *rp = pc.row_partials + s;
+  if ((cols & 255) == 0) {
+    // Rows made of whole 256-element pieces: piece u is what the wave's u-th load fetched and lies inside one
+    // row, so the row sums form in registers - lanes add their vectors over a row's pieces, then one scan per
+    // row.  Every branch is uniform.
+    double *means = const_cast<double *>(pc.gi.means);
+    int64_t r = row_of(off, cols, pc.gi.inv_cols);
+    int left = static_cast<int>((r * cols + cols - off) >> 8);     // pieces of row r from the span's start on
+    double acc = 0.0;
+#pragma unroll
+    for (int u = 0; u < kPreUnroll; ++u) {
+      const f32x4 gf = grad_to_f32<GradV>(g[u]);
+      acc += (static_cast<double>(gf[0]) + gf[1]) + (static_cast<double>(gf[2]) + gf[3]);
+      if (--left == 0 || u == kPreUnroll - 1) {
+        const double sum = wave_total_in_lane63(acc);
+        if (threadIdx.x == 63) emit_row(sum, r, cols, off, end, means, rp);
+        ++r;
+        left = static_cast<int>(cols >> 8);
+        acc = 0.0;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int u = 0; u < kPreUnroll; ++u)
+      *reinterpret_cast<f32x4 *>(stage + 4 * (threadIdx.x + u * kScaledBlock)) = grad_to_f32<GradV>(g[u]);
+    rows_from_stage(stage, off, kPreSub, pc.gi, rp);
+  }
+}
+
+// Any other span (the ragged last one of a tensor, or a gradient that is not 16-byte aligned): loads as it goes.
+template <typename GradS, typename GradV, bool NT, bool NORM>
+__device__ __forceinline__ void span_generic(int s, const PreChunk<GradS> &pc, float *stage) {
+  const int start = s * kPreSub;
+  const int n = min(kPreSub, pc.len - start);
+  const GradS *__restrict__ g_p = pc.g + start;
+  float s_g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  int done = 0;
+  if ((reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1)) == 0) {
+    const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
+    const int nvec = n >> 2;
+    for (int i = threadIdx.x; i < nvec; i += kScaledBlock) {
+      const f32x4 gf = grad_to_f32<GradV>(ld<NT>(g4 + i));
+      if (NORM) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s_g[k] = __builtin_fmaf(gf[k], gf[k], s_g[k]);
+      }
+      if (pc.gc) *reinterpret_cast<f32x4 *>(stage + 4 * i) = gf;
+    }
+    done = nvec << 2;
+  }
+  for (int i = done + threadIdx.x; i < n; i += kScaledBlock) {
+    float g;
+    if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
+    else g = g_p[i];
+    if (NORM) s_g[0] = __builtin_fmaf(g, g, s_g[0]);
+    if (pc.gc) stage[i] = g;
+  }
+  emit_norm<NORM>(s_g, pc.partials + s);
+  if (pc.gc) rows_from_stage(stage, pc.offset + start, n, pc.gi, pc.row_partials + s);
+}
+
+// One wave per chunk-table entry.  The chunk's spans are taken in order, and the loads of the next full span
+// are issued before the current one is reduced, so the wave's memory pipe does not idle while it adds up.
+template <typename GradS, typename GradV, bool NT, bool NORM, bool GC>
+__global__ __launch_bounds__(kScaledBlock) void novak_prepass_kernel(Tables tb, int sub_shift, NormPartial *partials,
+                                                                     RowPartial *row_partials) {
+  extern __shared__ float stage[];                      // kPreSub floats, touched only on the staged centralization path
+  const novak_chunk ch = tb.chunks[blockIdx.x];
+  PreChunk<GradS> pc;
+  pc.g = static_cast<const GradS *>(tb.grad[ch.tensor]) + ch.offset;
+  pc.offset = ch.offset;
+  pc.len = ch.len;
+  pc.gi.cols = 0;
+  if (GC) pc.gi = tb.gc[ch.tensor];
+  pc.gc = GC && pc.gi.cols > 0;
+  pc.partials = partials + (static_cast<size_t>(blockIdx.x) << sub_shift);
+  pc.row_partials = row_partials + (static_cast<size_t>(blockIdx.x) << sub_shift);
+  const int nspans = (ch.len + kPreSub - 1) / kPreSub;
+  const int nfull = (reinterpret_cast<uintptr_t>(pc.g) & (sizeof(GradV) - 1)) == 0 ? ch.len / kPreSub : 0;
+  const GradV *g4 = reinterpret_cast<const GradV *>(pc.g) + threadIdx.x;
+  constexpr int kSpanVecs = kPreSub / 4;
+  GradV a[kPreUnroll], b[kPreUnroll];
+  if (nfull > 0) {
+#pragma unroll
+    for (int u = 0; u < kPreUnroll; ++u) a[u] = ld<NT>(g4 + u * kScaledBlock);
+  }
+  for (int s = 0; s < nspans; s += 2) {
+    if (s + 1 < nfull) {
+#pragma unroll
+      for (int u = 0; u < kPreUnroll; ++u) b[u] = ld<NT>(g4 + (s + 1) * kSpanVecs + u * kScaledBlock);
+    }
+    if (s < nfull) span_from_registers<GradS, GradV, NORM>(a, s, pc, stage);
+    else span_generic<GradS, GradV, NT, NORM>(s, pc, stage);
+    if (s + 1 >= nspans) break;
+    if (s + 2 < nfull) {
+#pragma unroll
+      for (int u = 0; u < kPreUnroll; ++u) a[u] = ld<NT>(g4 + (s + 2) * kSpanVecs + u * kScaledBlock);
+    }
+    if (s + 1 < nfull) span_from_registers<GradS, GradV, NORM>(b, s + 1, pc, stage);
+    else span_generic<GradS, GradV, NT, NORM>(s + 1, pc, stage);
   }
 }
 

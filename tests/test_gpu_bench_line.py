@@ -10,8 +10,9 @@ CONTRACT = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step
             "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline")
 
 
-@pytest.mark.parametrize("extra", [[], ["--moment-dtype", "bf16_m"], ["--layer-adaptation", "--clip", "1.0"], ["--layout", "separate"],
-                                   ["--separate-sync"]])
+@pytest.mark.parametrize("extra", [[], ["--moment-dtype", "bf16_m", "--no-extras"], ["--layer-adaptation", "--clip", "1.0", "--no-extras"],
+                                   ["--layout", "separate"], ["--layout", "torch_one"], ["--separate-sync"], ["--use-gc", "--clip", "1.0", "--no-extras"],
+                                   ["--nesterov", "true", "--mode", "research", "--extrapolate", "--no-extras"]])
 def test_bench_line(monkeypatch, capsys, extra):
     import bench
     # one in-process oracle run, no worker processes: nothing is spawned from a process that holds the GPU
@@ -34,7 +35,10 @@ def test_bench_line(monkeypatch, capsys, extra):
     k = d["kernels"][r["kernel"]]
     assert r["achieved"] == pytest.approx(cfg["params"] * k["bytes_per_param"] / (k["avg_ms"] * 1e-3) / 1e9)
     assert r["algorithmic_bytes_per_launch"] == cfg["params"] * k["bytes_per_param"]
-    assert sum(v["launches"] for n, v in d["kernels"].items() if n != "lookahead_sync") == 10
+    assert sum(v["launches"] for n, v in d["kernels"].items() if n not in ("lookahead_sync", "nesterov_extrapolate")) == 10
+    if "--extrapolate" in extra:
+        assert cfg["nesterov"] == "true" and d["kernels"]["nesterov_extrapolate"]["launches"] == 10
+        assert d["kernels"]["nesterov_extrapolate"]["bytes_per_param"] == 12.0
     if "--separate-sync" in extra:
         assert d["kernels"]["lookahead_sync"]["launches"] == 2 and d["kernels"]["lookahead_sync"]["bytes_per_param"] == 8.0
         assert cfg["sync"] == "separate"
@@ -43,3 +47,16 @@ def test_bench_line(monkeypatch, capsys, extra):
     assert "cpu_baseline_all_cores" not in d
     if "--layout" not in extra:
         assert cfg["layout"] == "arena"
+    else:
+        assert cfg["layout"] == extra[1] and r["traffic"] is None        # counters were taken on the arena only
+    if not extra:
+        # beside the headline: the layouts a PyTorch caller has, and the sync as its own kernel, from the same process
+        o = d["other_layouts"]
+        assert set(o) == {"torch_one_allocation_planned_layout", "torch_five_separate_allocations"}
+        for v in o.values():
+            assert v["unit"] == "Gparams/s" and v["value"] > 0 and 0.05 < v["frac"] < 1.0
+            assert v["value"] == pytest.approx(cfg["params"] / (v["ms_per_step"] * 1e-3) / 1e9, rel=1e-9)
+        ss = d["separate_sync"]
+        assert ss["value"] > 0 and ss["sync_kernel"]["launches"] == 2 and ss["sync_kernel"]["bytes_per_param"] == 8.0
+    else:
+        assert "other_layouts" not in d and "separate_sync" not in d
