@@ -60,3 +60,18 @@ def test_bench_line(monkeypatch, capsys, extra):
         assert ss["value"] > 0 and ss["sync_kernel"]["launches"] == 2 and ss["sync_kernel"]["bytes_per_param"] == 8.0
     else:
         assert "other_layouts" not in d and "separate_sync" not in d
+
+
+def test_host_cost_tool_runs_and_reports(tmp_path):
+    """novak_hostcost (C++ over the C ABI, built by paper_2601_07876_amd.build): a child process, JSON on stdout."""
+    import os
+    import subprocess
+    import workloads as W
+    from paper_2601_07876_amd import build as B
+    assert os.path.exists(B.HOSTCOST_PATH), "build it with `python -m paper_2601_07876_amd.build`"
+    f = tmp_path / "numels.txt"
+    f.write_text("\n".join(str(n) for n in W.get_workload("ragged").numels) + "\n")
+    out = subprocess.run([B.HOSTCOST_PATH, str(f), "200"], check=True, capture_output=True, text=True, timeout=120).stdout
+    d = json.loads(out.strip().splitlines()[-1])
+    assert d["tensors"] == len(W.get_workload("ragged").numels) and d["steps"] == 200
+    assert 0.0 < d["host_us_per_step"] <= d["total_us_per_step"] < 1e4

@@ -102,3 +102,33 @@ def test_rows_must_divide_numel():
     hp = N.make_hparams(mode="research", use_gc=True, lookahead="none")
     assert N.novak_create(hp, [N.novak_tensor_desc(256, 512, 768, None, 10, 3)])[0] == N.NOVAK_ERR_INVALID_ARG
     assert N.novak_create(hp, [N.novak_tensor_desc(256, 512, 768, None, 10, -1)])[0] == N.NOVAK_ERR_INVALID_ARG
+
+
+def test_row_means_do_not_depend_on_chunking_or_prepass_residency():
+    """The pre-pass sums rows in spans of 4096 elements counted from the tensor's start, whatever the chunk
+    size (1, 4 or 16 spans per chunk-table entry: the last exercises the pipelined two-buffer loop) and
+    whatever its residency: centralized results are bit-identical.  With clipping on, only the grouping of
+    the norm's partial sums changes, so those runs are compared with the oracle instead."""
+    shapes = GC_SHAPES + [(96, 1024), (40, 4096 + 256), (3, 70000)]
+    numels = [int(np.prod(s)) for s in shapes]
+    rows = [s[0] if len(s) > 1 else 0 for s in shapes]
+    hyper = dict(W.BASE_HYPER, mode="research", use_gc=True)
+    outs = []
+    for chunk, waves in ((4096, 0), (16384, 0), (65536, 0), (65536, 3), (16384, 32)):
+        gpu, states, _ = H.run_pair(numels, hyper, 6, 1e-2, auto_sync=True, rows=rows, chunk_elems=chunk)
+        N.check(N.novak_set_tuning(gpu.handle, N.NOVAK_TUNE_PREPASS_WAVES_PER_CU, waves), "set_tuning", gpu.handle)
+        gh = W.host_grads(numels, 7, 1e-2)
+        N.check(gpu.step(7, gpu.upload_grads(gh)), "step 7", gpu.handle)
+        outs.append([gpu.host(r) for r in ("theta", "m", "v")])
+        gpu.close()
+    for other in outs[1:]:
+        for role_a, role_b in zip(outs[0], other):
+            for x, y in zip(role_a, role_b):
+                assert np.array_equal(x, y)
+    for chunk in (4096, 65536):
+        gpu, states, _ = H.run_pair(numels, dict(hyper, clip_threshold=0.7), 6, 1e-2, auto_sync=True, rows=rows, chunk_elems=chunk, guard=8)
+        try:
+            H.compare_states(gpu, states)
+            assert gpu.guards_intact()
+        finally:
+            gpu.close()
