@@ -47,9 +47,11 @@ def parse_args():
     ap.add_argument("--sparse", type=float, default=0.0, help="sparse threshold tau of Eq. 27 (0 = off)")
     ap.add_argument("--moment-dtype", default="f32", choices=("f32", "bf16_m"),
                     help="storage of the first moment: fp32, or bfloat16 (reduced-precision state; not the headline configuration)")
-    ap.add_argument("--layout", default="arena", choices=("arena", "torch_one", "separate"),
+    ap.add_argument("--layout", default="arena", choices=("arena", "torch_one", "separate", "separate_contiguous", "torch_pool"),
                     help="arena: one allocation from the library for all roles with a fixed spacing; torch_one: the same spacing "
-                         "inside one ordinary torch allocation; separate: one torch allocation per role")
+                         "inside one ordinary torch allocation; separate: one torch allocation per role; separate_contiguous: one "
+                         "novak_arena_alloc allocation per role; torch_pool: five separate torch allocations inside a torch.cuda.MemPool "
+                         "whose segments come from the library (novak_torch_malloc)")
     ap.add_argument("--chunk-elems", type=int, default=None)
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--vec-per-lane", type=int, default=None)
@@ -151,6 +153,17 @@ class Setup:
         m_dtype = torch.bfloat16 if hyper["moment_dtype"] == "bf16_m" else torch.float32
         g_dtype = torch.bfloat16 if wl.grad_dtype == "bf16" else torch.float32
         self.arena_ptr, self.arena_contiguous, self.arena = None, 0, None
+        self.role_ptrs, self.pool, self.views = [], None, None
+        if layout == "separate_contiguous":
+            torch.zeros(1, device=dev)
+            views = []
+            for i in range(5):      # each role its own physically contiguous allocation, bases 2 KB apart modulo 8 KB
+                rc, ptr, contig = N.novak_arena_alloc(0, flat * 4 + 8192)
+                N.check(rc, "novak_arena_alloc")
+                self.role_ptrs.append(ptr)
+                self.arena_contiguous = contig
+                views.append(N.arena_as_tensor(ptr, flat * 4 + 8192, 0)[i * 2048:])
+            self.views = views
         if layout == "arena":
             torch.zeros(1, device=dev)       # the device context exists before the library allocates on it
             rc, self.arena_ptr, self.arena_contiguous = N.novak_arena_alloc(0, 5 * stride)
@@ -164,6 +177,17 @@ class Setup:
 
             def role(i, dtype):
                 return arena[i * stride: i * stride + flat * dtype.itemsize].view(dtype)
+        elif layout == "separate_contiguous":
+            def role(i, dtype):
+                t = self.views[i][: flat * dtype.itemsize].view(dtype)
+                t.zero_()
+                return t
+        elif layout == "torch_pool":
+            self.pool = N.torch_mem_pool()
+
+            def role(i, dtype):
+                with torch.cuda.use_mem_pool(self.pool):
+                    return torch.zeros(flat, dtype=dtype, device=dev)
         else:
             def role(i, dtype):
                 return torch.zeros(flat, dtype=dtype, device=dev)
@@ -295,6 +319,11 @@ class Setup:
             self.arena = None
             self.N.check(self.N.novak_arena_free(0, self.arena_ptr), "novak_arena_free")
         self.arena = None
+        self.pool = None
+        self.views = None
+        for ptr in self.role_ptrs:
+            self.N.check(self.N.novak_arena_free(0, ptr), "novak_arena_free")
+        self.role_ptrs = []
         self.torch.cuda.empty_cache()
 
 
@@ -384,8 +413,15 @@ def main():
     # ---- separate kernel (the benchmark spec names both); skipped when a specific layout / sync mode was asked for
     if not args.no_extras and args.layout == "arena" and fused:
         others = {}
-        for name, layout in (("torch_one_allocation_planned_layout", "torch_one"), ("torch_five_separate_allocations", "separate")):
-            r2 = Setup(wl, hyper, layout, True, args, torch, N, W)
+        for name, layout in (("torch_one_allocation_planned_layout", "torch_one"), ("torch_five_separate_allocations", "separate"),
+                             ("torch_five_allocations_in_a_mem_pool_fed_by_the_library", "torch_pool")):
+            try:
+                r2 = Setup(wl, hyper, layout, True, args, torch, N, W)
+            except (RuntimeError, AttributeError) as e:      # a torch build without MemPool / pluggable allocators
+                if layout != "torch_pool":
+                    raise
+                others[name] = {"unavailable": str(e)[:200]}
+                continue
             others[name] = brief(r2.timed(args.warmup, args.steps))
             r2.close()
         result["other_layouts"] = others

@@ -8,6 +8,7 @@
 #include <mutex>
 #include <new>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "novak_internal.h"
@@ -807,6 +808,81 @@ int novak_arena_free(int32_t device_id, void *ptr) {
   e = hipFree(ptr);
   if (e != hipSuccess) return fail_hip(nullptr, e, "hipFree(arena)");
   return NOVAK_OK;
+}
+
+// ---- allocator hooks for torch.cuda.memory.CUDAPluggableAllocator / torch.cuda.MemPool ----------------------
+namespace {
+struct TorchBlock {
+  void *base;
+  bool contiguous;
+};
+std::mutex g_torch_mutex;
+std::unordered_map<void *, TorchBlock> g_torch_blocks;     // returned address -> what to free
+unsigned g_torch_large_count = 0;
+constexpr ptrdiff_t kTorchLarge = ptrdiff_t{1} << 20;
+}  // namespace
+
+void *novak_torch_malloc(ptrdiff_t size, int device, void * /*stream*/) {
+  if (size < 0 || device < 0) return nullptr;
+  if (size == 0) size = 1;
+  try {
+    DeviceScope scope;
+    if (scope.enter(device) != hipSuccess) return nullptr;
+    TorchBlock blk{nullptr, false};
+    size_t skew = 0;
+    if (size >= kTorchLarge) {
+      {
+        std::lock_guard<std::mutex> lock(g_torch_mutex);
+        skew = (static_cast<size_t>(g_torch_large_count++) * NOVAK_ARENA_ROLE_SKEW) % NOVAK_ARENA_ROLE_PERIOD;
+      }
+      const size_t bytes = static_cast<size_t>(size) + NOVAK_ARENA_ROLE_PERIOD;
+      if (hipExtMallocWithFlags(&blk.base, bytes, hipDeviceMallocContiguous) == hipSuccess && blk.base) {
+        blk.contiguous = true;
+      } else {
+        (void)hipGetLastError();
+        blk.base = nullptr;
+        if (hipMalloc(&blk.base, bytes) != hipSuccess) {
+          (void)hipGetLastError();
+          return nullptr;
+        }
+      }
+    } else if (hipMalloc(&blk.base, static_cast<size_t>(size)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    void *ret = static_cast<char *>(blk.base) + skew;
+    std::lock_guard<std::mutex> lock(g_torch_mutex);
+    g_torch_blocks[ret] = blk;
+    return ret;
+  } catch (...) {
+    return nullptr;
+  }
+}
+
+void novak_torch_free(void *ptr, ptrdiff_t /*size*/, int device, void * /*stream*/) {
+  if (!ptr) return;
+  TorchBlock blk{ptr, false};
+  {
+    std::lock_guard<std::mutex> lock(g_torch_mutex);
+    auto it = g_torch_blocks.find(ptr);
+    if (it == g_torch_blocks.end()) return;        // not ours: leave it alone
+    blk = it->second;
+    g_torch_blocks.erase(it);
+  }
+  DeviceScope scope;
+  if (device >= 0) (void)scope.enter(device);
+  (void)hipFree(blk.base);
+}
+
+void novak_torch_alloc_stats(int64_t *live, int64_t *live_contiguous) {
+  std::lock_guard<std::mutex> lock(g_torch_mutex);
+  int64_t n = 0, c = 0;
+  for (const auto &kv : g_torch_blocks) {
+    ++n;
+    if (kv.second.contiguous) ++c;
+  }
+  if (live) *live = n;
+  if (live_contiguous) *live_contiguous = c;
 }
 
 int novak_destroy(novak_handle *h) {

@@ -29,6 +29,7 @@ NOVAK_TUNE_CHUNK_ELEMS, NOVAK_TUNE_NONTEMPORAL, NOVAK_TUNE_VEC_PER_LANE, NOVAK_T
 NOVAK_TUNE_PREPASS_WAVES_PER_CU = 5
 
 NOVAK_STATIC_MAX_TENSORS, NOVAK_STATIC_MAX_CHUNKS, NOVAK_STATIC_SCRATCH_BYTES = 1024, 16384, 2 << 20
+NOVAK_ARENA_TENSOR_ALIGN, NOVAK_ARENA_ROLE_PERIOD, NOVAK_ARENA_ROLE_SKEW = 256, 8192, 2048
 
 NESTEROV = {"none": 0, "approx": 1, "classical": 2, "true": 3}
 LOOKAHEAD = {"none": 0, "memory_efficient": 1, "basic": 2}
@@ -85,7 +86,8 @@ EXPORTS = ("novak_validate_hparams", "novak_compute_step_scalars", "novak_plan_c
            "novak_bytes_per_param_moment_saving", "novak_bytes_per_param_sync",
            "novak_status_string", "novak_create", "novak_lookahead_init", "novak_step", "novak_lookahead_sync",
            "novak_destroy", "novak_get_info", "novak_set_tuning", "novak_last_error", "novak_set_auto_lr_state",
-           "novak_copy_tensor_scales", "novak_nesterov_extrapolate", "novak_step_static")
+           "novak_copy_tensor_scales", "novak_nesterov_extrapolate", "novak_step_static",
+           "novak_torch_malloc", "novak_torch_free", "novak_torch_alloc_stats")
 
 _lib: Optional[C.CDLL] = None
 
@@ -107,6 +109,12 @@ def load_library() -> C.CDLL:
     lib.novak_plan_arena.argtypes = [C.POINTER(i64), i32, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     lib.novak_arena_alloc.argtypes = [i32, C.c_size_t, C.POINTER(C.c_void_p), C.POINTER(i32)]
     lib.novak_arena_free.argtypes = [i32, C.c_void_p]
+    lib.novak_torch_malloc.argtypes = [C.c_ssize_t, C.c_int, vp]
+    lib.novak_torch_malloc.restype = vp
+    lib.novak_torch_free.argtypes = [vp, C.c_ssize_t, C.c_int, vp]
+    lib.novak_torch_free.restype = None
+    lib.novak_torch_alloc_stats.argtypes = [C.POINTER(i64), C.POINTER(i64)]
+    lib.novak_torch_alloc_stats.restype = None
     lib.novak_bytes_per_param_step.argtypes = [i32, i32, i32, i32, i32]
     lib.novak_bytes_per_param_step.restype = C.c_double
     lib.novak_bytes_per_param_scaled_step.argtypes = [i32, i32, i32, i32, i32]
@@ -216,6 +224,28 @@ def novak_arena_alloc(device_id: int, nbytes: int):
 
 def novak_arena_free(device_id: int, ptr) -> int:
     return load_library().novak_arena_free(device_id, ptr)
+
+
+def novak_torch_alloc_stats():
+    """-> (allocations alive that were made through novak_torch_malloc, how many of them are physically contiguous)."""
+    live, contig = C.c_int64(0), C.c_int64(0)
+    load_library().novak_torch_alloc_stats(C.byref(live), C.byref(contig))
+    return live.value, contig.value
+
+
+_torch_pool_allocator = None
+
+
+def torch_mem_pool():
+    """A torch.cuda.MemPool whose segments come from novak_torch_malloc (argument marshalling only: the pool and
+    the caching on top of it are torch's).  Use as `with torch.cuda.use_mem_pool(pool): ...allocate...`; keep the
+    pool alive as long as its tensors."""
+    global _torch_pool_allocator
+    import torch
+    load_library()
+    if _torch_pool_allocator is None:      # one allocator object per process: torch keeps function pointers into it
+        _torch_pool_allocator = torch.cuda.memory.CUDAPluggableAllocator(LIB_PATH, "novak_torch_malloc", "novak_torch_free")
+    return torch.cuda.MemPool(_torch_pool_allocator.allocator())
 
 
 class _DeviceBytes:

@@ -11,7 +11,7 @@ CONTRACT = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step
 
 
 @pytest.mark.parametrize("extra", [[], ["--moment-dtype", "bf16_m", "--no-extras"], ["--layer-adaptation", "--clip", "1.0", "--no-extras"],
-                                   ["--layout", "separate"], ["--layout", "torch_one"], ["--separate-sync"], ["--use-gc", "--clip", "1.0", "--no-extras"],
+                                   ["--layout", "separate"], ["--layout", "torch_one"], ["--layout", "torch_pool"], ["--layout", "separate_contiguous"], ["--separate-sync"], ["--use-gc", "--clip", "1.0", "--no-extras"],
                                    ["--nesterov", "true", "--mode", "research", "--extrapolate", "--no-extras"]])
 def test_bench_line(monkeypatch, capsys, extra):
     import bench
@@ -52,7 +52,8 @@ def test_bench_line(monkeypatch, capsys, extra):
     if not extra:
         # beside the headline: the layouts a PyTorch caller has, and the sync as its own kernel, from the same process
         o = d["other_layouts"]
-        assert set(o) == {"torch_one_allocation_planned_layout", "torch_five_separate_allocations"}
+        assert set(o) == {"torch_one_allocation_planned_layout", "torch_five_separate_allocations",
+                          "torch_five_allocations_in_a_mem_pool_fed_by_the_library"}
         for v in o.values():
             assert v["unit"] == "Gparams/s" and v["value"] > 0 and 0.05 < v["frac"] < 1.0
             assert v["value"] == pytest.approx(cfg["params"] / (v["ms_per_step"] * 1e-3) / 1e9, rel=1e-9)
