@@ -180,3 +180,30 @@ def test_brute_force_two_tensors(layer, auto, nesterov):
                   O.Hyper(lr=1e-3, beta1=0.9, beta2=0.99, weight_decay=0.01, beta_n=0.8, la_k=K, nesterov=nesterov),
                   state_dtype=np.float64)
     assert max(np.max(np.abs(a.theta - b.theta)) for a, b in zip(sts, plain)) > 1e-5
+
+
+def test_trace_holds_the_per_tensor_scale_and_the_steps_intermediates():
+    """TensorState.trace after a step: lambda_trust * alpha_auto of Eq. 24a (what GPU tests compare the library's
+    per-tensor scales with), and the intermediates the comparison policy reads - pinned here by closed forms at t = 1."""
+    th = [np.full(4, 2.0), np.full(9, 0.5)]
+    g = [np.full(4, 1e-2), np.full(9, 1e-2)]
+    h = _h(layer_adaptation=True, auto_lr=True, trust_clip=(0.1, 1e3), auto_clip=(1e-6, 1e3))
+    aux = O.AutoLrState()
+    states = [O.init_state(x, h, np.float64) for x in th]
+    a = O.step_all(states, g, 1, h, aux)
+    u = 1e-2 / (1e-2 + 1e-8)                                  # m_hat = g, v_hat = g^2 at t = 1 (no Nesterov in _h)
+    ratio = np.sqrt(13 * 1e-4) / np.sqrt(4 * 4.0 + 9 * 0.25)  # ||g|| / ||theta|| over both tensors
+    assert a == pytest.approx(ratio, rel=1e-13)
+    assert states[0].trace.scale == pytest.approx((2.0 / u) * ratio, rel=1e-13)     # eta = ||theta|| / ||u|| per tensor
+    assert states[1].trace.scale == pytest.approx((0.5 / u) * ratio, rel=1e-13)
+    tr = states[0].trace
+    np.testing.assert_allclose(tr.u_base, u, rtol=1e-14)
+    np.testing.assert_allclose(tr.m_exact, (1 - h.beta1) * 1e-2, rtol=1e-14)
+    assert np.array_equal(tr.g_processed, tr.g_tilde) and np.array_equal(tr.g_tilde, np.full(4, 1e-2))
+    # with the Nesterov approximation g_tilde = (1 + beta_n) g at t = 1 and g_processed stays the gradient handed in
+    h2 = O.Hyper(lookahead="none", nesterov="approx", beta_n=0.7)
+    st = O.init_state(np.ones(3), h2, np.float64)
+    O.step(st, np.full(3, 0.2), 1, h2)
+    np.testing.assert_allclose(st.trace.g_tilde, 1.7 * 0.2, rtol=1e-15)
+    np.testing.assert_allclose(st.trace.g_processed, 0.2, rtol=1e-15)
+    assert st.trace.scale == 1.0
