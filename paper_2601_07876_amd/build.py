@@ -59,7 +59,8 @@ def build_library(verbose: bool = True) -> str:
 
 def build_hostcost(verbose: bool = True) -> str:
     """The host-cost timing tool: a host-only program against include/novak.h, linked to the library beside it."""
-    cmd = [hipcc_path(), "-O2", "-std=c++17", "-Wall", "-Wextra", "-I", os.path.join(ROOT, "include"),
+    cmd = [hipcc_path(), "-O2", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wall", "-Wextra", "-Wno-unknown-warning-option", "-I", os.path.join(ROOT, "include"),
            os.path.join(CSRC, "novak_hostcost.cpp"), "-L", PKG_DIR, "-lnovak", "-Wl,-rpath,$ORIGIN", "-o", HOSTCOST_PATH + ".tmp"]
     if verbose:
         print(" ".join(cmd), flush=True)
