@@ -781,7 +781,7 @@ __device__ __forceinline__ void span_generic(int s, const PreChunk<GradS> &pc, f
 template <typename GradS, typename GradV, bool NT, bool NORM, bool GC>
 __global__ __launch_bounds__(kScaledBlock) void novak_prepass_kernel(Tables tb, int sub_shift, NormPartial *partials,
                                                                      RowPartial *row_partials) {
-  extern __shared__ float stage[];                      // kPreSub floats, touched only on the staged centralization path
+  extern __shared__ __align__(16) float stage[];                      // kPreSub floats, touched only on the staged centralization path
   const novak_chunk ch = tb.chunks[blockIdx.x];
   PreChunk<GradS> pc;
   pc.g = static_cast<const GradS *>(tb.grad[ch.tensor]) + ch.offset;

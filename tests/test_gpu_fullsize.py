@@ -294,6 +294,24 @@ def test_c2_resnet50_every_element_fast_path():
         run.close()
 
 
+@pytest.mark.parametrize("name,steps,auto_sync", [("c4_vit_b16_bf16", 6, True), ("c3_vgg16", 6, False)])
+def test_every_element_of_the_other_large_lists(name, steps, auto_sync):
+    """Every element of the ViT-B/16 list (bf16 gradients: the 64-bit gradient path, odd tensor sizes in a padded
+    arena) and of the VGG-16 list (one tensor of 102.8M elements: 6272 chunks; separate sync kernel) across a sync."""
+    wl = W.get_workload(name)
+    run = FullRun(wl, arena=True, dense="all")
+    try:
+        assert run.idx_host.size == wl.total
+        run.reset(wl.hyper, auto_sync=auto_sync)
+        for t in range(1, steps + 1):
+            run.step()
+            if t in (4, 5, steps):
+                run.check(f"{name} dense t={t}")
+            _say(f"{name} dense step {t} done")
+    finally:
+        run.close()
+
+
 def test_c5_one_whole_large_tensor_every_element():
     """Every element of one 8192 x 2048 tensor (16.7M elements, 1024 chunks) in the middle of the 1.3B list, in the
     configuration bench.py times (arena, sync fused), over 2k+1 steps; the other tensors are sampled."""
