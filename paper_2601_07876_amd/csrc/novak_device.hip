@@ -459,7 +459,7 @@ hipError_t launch_prepass(const LaunchCtx *h, int grad_dtype, hipStream_t s, con
     const int nt_count = h->n_tensors;
     hipLaunchKernelGGL(novak_reduce_chunks_kernel, dim3(static_cast<unsigned>(h->n_chunks)), dim3(64), 0, s, h->d_chunks, g0.sub_shift,
                        kPreSub, h->d_partials, h->d_chunk_sums);
-    hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(64), 0, s, h->d_first_chunk, h->d_chunk_sums,
+    hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(kTensorReduceBlock), 0, s, h->d_first_chunk, h->d_chunk_sums,
                        h->d_tensor_sums, h->d_scale, sp);
     hipLaunchKernelGGL(novak_clip_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, static_cast<float>(h->hp.clip_threshold), h->d_gscale);
   }
@@ -489,7 +489,7 @@ hipError_t launch_scaled_step(const LaunchCtx *h, int grad_dtype, int la, hipStr
   const int nt_count = h->n_tensors;
   hipLaunchKernelGGL(novak_reduce_chunks_kernel, dim3(static_cast<unsigned>(h->n_chunks)), dim3(64), 0, s, h->d_chunks, g1.sub_shift,
                      kScaledSub, h->d_partials, h->d_chunk_sums);
-  hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(64), 0, s, h->d_first_chunk, h->d_chunk_sums,
+  hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(kTensorReduceBlock), 0, s, h->d_first_chunk, h->d_chunk_sums,
                      h->d_tensor_sums, h->d_scale, sp);
   if (hp.auto_lr)
     hipLaunchKernelGGL(novak_auto_lr_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, h->d_scale, h->d_ema, sp);
