@@ -48,7 +48,7 @@ enum {
   NOVAK_ERR_BAD_STEP = 4,         /* step < 1, or not last step + 1 on this handle */
   NOVAK_ERR_STATE = 5,            /* call not legal now (sync not due / sync pending / no lookahead) */
   NOVAK_ERR_HIP = 6,              /* a HIP runtime call failed; see novak_last_error() */
-  NOVAK_ERR_NOT_IMPLEMENTED = 7,  /* a feature outside the update step was requested */
+  NOVAK_ERR_NOT_IMPLEMENTED = 7,  /* the entry point does not cover a requested feature (novak_step_static: two-pass scalings, centralization) */
   NOVAK_ERR_NO_MEMORY = 8
 };
 
