@@ -160,6 +160,41 @@ def test_resume_is_bitwise():
         part.close()
 
 
+@pytest.mark.parametrize("t0", [995, 9_995, 999_995, 49_999_995])
+def test_late_steps_start_from_a_given_state(t0):
+    """Steps far into a run (a fresh handle accepts any first step): the bias corrections go through
+    expm1(t log beta) (section 5.8), r_t approaches 1 (Eq. 9) and the window position is t mod k.  Both sides
+    start from the same theta, m, v at step t0 (a multiple of k, so a window opens) and take 11 steps."""
+    wl = W.get_workload("ragged")
+    numels = wl.numels
+    hyper = dict(wl.hyper, nesterov="classical")
+    theta0 = W.host_params(numels, 100)
+    rng = np.random.default_rng(t0)
+    m0 = [rng.normal(0, 3e-3, n).astype(np.float32) for n in numels]
+    v0 = [(rng.normal(0, 1e-2, n) ** 2).astype(np.float32) for n in numels]
+    gpu = H.GpuNovak(numels, hyper, "f32", theta0, auto_sync=True, guard=8)
+    h = H.oracle_hyper(hyper, gpu.eff_nesterov, gpu.eff_lookahead, gpu.info)
+    states = [O.init_state(th, h) for th in theta0]
+    try:
+        for i, st in enumerate(states):
+            st.m, st.v = m0[i].copy(), v0[i].copy()
+            gpu.m[i].copy_(torch.from_numpy(m0[i]))
+            gpu.v[i].copy_(torch.from_numpy(v0[i]))
+        for t in range(t0 + 1, t0 + 12):
+            gh = W.host_grads(numels, t - t0, wl.grad_std, 100)
+            N.check(gpu.step(t, gpu.upload_grads(gh)), f"step {t}", gpu.handle)
+            O.step_all(states, gh, t, h)
+            if O.sync_due(t, h):
+                for st in states:
+                    O.lookahead_sync(st, h)
+        H.compare_states(gpu, states)
+        assert gpu.guards_intact()
+        rc, sc = N.novak_compute_step_scalars(N.make_hparams(**hyper), t0 + 11)
+        assert sc.r_t == pytest.approx(O.step_scalars(h, t0 + 11).r_t, rel=1e-13) and sc.r_t > 0.64
+    finally:
+        gpu.close()
+
+
 def test_alpha_one_fixed_points_on_gpu():
     """alpha_LA = 1: basic returns the fast weights bit for bit; memory_efficient does so for k = 1."""
     wl = W.get_workload("ragged")
