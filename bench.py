@@ -58,6 +58,11 @@ def parse_args():
     ap.add_argument("--threads", type=int, default=None)
     ap.add_argument("--waves-per-cu", type=int, default=None)
     ap.add_argument("--prepass-waves-per-cu", type=int, default=None)
+    ap.add_argument("--device-step", action="store_true",
+                    help="device-step mode: the step count lives in device memory and a one-lane kernel evaluates the scalar prologue")
+    ap.add_argument("--graph-steps", type=int, default=0,
+                    help="with --device-step: capture this many steps (a multiple of the lookahead window) into ONE HIP graph and time "
+                         "its replays; --steps must be a multiple of it")
     ap.add_argument("--mode", default=None, choices=("fast", "research"), help="override the workload's dual-mode setting (section 7.1)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the comparison runs reported beside the headline (PyTorch-allocated layouts, separate sync kernel)")
@@ -200,7 +205,8 @@ class Setup:
         del g32
         self.bufs = (theta, m, v, la, grad)
 
-        hp = N.make_hparams(auto_sync=fused, **hyper)
+        self.device_step = bool(args.device_step)
+        hp = N.make_hparams(auto_sync=fused, device_step=self.device_step, **hyper)
         descs = [N.novak_tensor_desc(theta.data_ptr() + 4 * o, m.data_ptr() + m.element_size() * o, v.data_ptr() + 4 * o,
                                      la.data_ptr() + 4 * o, n, r) for o, n, r in zip(offsets, numels, wl.rows)]
         rc, self.handle = N.novak_create(hp, descs, 0)
@@ -221,6 +227,10 @@ class Setup:
         self.stream = torch.cuda.current_stream().cuda_stream
         if self.la_name != "none":
             N.check(N.novak_lookahead_init(handle, self.stream), "lookahead_init", handle)
+        self.counter = torch.zeros(1, dtype=torch.int64, device=dev)
+        if self.device_step:
+            N.check(N.novak_set_step_counter(handle, self.counter.data_ptr()), "set_step_counter", handle)
+        self.graph_steps = int(args.graph_steps) if self.device_step else 0
         self.ema = torch.zeros(2, dtype=torch.float64, device=dev)
         if info.auto_lr:
             N.check(N.novak_set_auto_lr_state(handle, self.ema.data_ptr()), "set_auto_lr_state", handle)
@@ -242,11 +252,49 @@ class Setup:
     def one_step(self):
         N, handle = self.N, self.handle
         self.t += 1
-        N.check(N.novak_step(handle, self.grad_arr, self.gdt, self.t, self.stream), "novak_step", handle)
+        N.check(N.novak_step(handle, self.grad_arr, self.gdt, 0 if self.device_step else self.t, self.stream), "novak_step", handle)
         if self.la_name != "none" and not self.fused and self.t % self.k == 0:
             N.check(N.novak_lookahead_sync(handle, self.stream), "novak_lookahead_sync", handle)
             return True
         return False
+
+    def timed_graph(self, warmup, steps):
+        """Device-step mode: graph_steps steps captured into ONE HIP graph (through torch's stream capture), replayed
+        steps / graph_steps times; every replay continues from the device's own step counter."""
+        torch, N, g = self.torch, self.N, self.graph_steps
+        if steps % g or (self.la_name != "none" and g % self.k):
+            raise SystemExit("bench.py: --steps must be a multiple of --graph-steps, and that of the lookahead window")
+        for _ in range(max(warmup, 1) + (-max(warmup, 1)) % (self.k if self.la_name != "none" else 1)):
+            self.one_step()               # eager: uploads the gradient-pointer list; ends on a window boundary
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            cap_stream = torch.cuda.current_stream().cuda_stream
+            for _ in range(g):
+                N.check(N.novak_step(self.handle, self.grad_arr, self.gdt, 0, cap_stream), "novak_step (capture)", self.handle)
+        replays = steps // g
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(replays)]
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for a, b in ev:
+            a.record()
+            graph.replay()
+            b.record()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t_begin
+        expect = self.t + steps
+        assert int(self.counter.item()) == expect, "the replays did not advance the device's step counter"
+        names = [la_variant(self.la_name, self.k, self.t + 1 + i, self.fused) + self.m_tag for i in range(g)]
+        self.t = expect
+        bpp = sum(self.bytes_of(n) for n in names)
+        ms = [a.elapsed_time(b) for a, b in ev]
+        avg = sum(ms) / len(ms)
+        name = f"graph_of_{g}_steps"
+        kernels = {name: {"launches": replays, "avg_ms": avg, "bytes_per_param": bpp, "GBps": self.p * bpp / (avg * 1e-3) / 1e9,
+                          "avg_ms_per_step": avg / g}}
+        del graph
+        return {"elapsed": elapsed, "value": self.p * steps / elapsed / 1e9, "ms_per_step": elapsed / steps * 1e3,
+                "kernels": kernels, "dominant": name}
 
     def bytes_of(self, name):
         """Algorithmic bytes per parameter of a step variant (a two-pass "scaled_" step is timed as a whole)."""
@@ -264,6 +312,8 @@ class Setup:
     def timed(self, warmup, steps):
         """W untimed steps, then exactly K steps between synchronisations, each bracketed by HIP events on the launch stream."""
         torch, N = self.torch, self.N
+        if self.graph_steps:
+            return self.timed_graph(warmup, steps)
         for _ in range(warmup):
             if self.extrapolate_arr is not None:
                 N.check(N.novak_nesterov_extrapolate(self.handle, self.extrapolate_arr, self.stream), "novak_nesterov_extrapolate", self.handle)
@@ -282,7 +332,7 @@ class Setup:
                 extra_ev.append((x0, ev[i][0]))
             ev[i][0].record()
             self.t += 1
-            N.check(N.novak_step(self.handle, self.grad_arr, self.gdt, self.t, self.stream), "novak_step", self.handle)
+            N.check(N.novak_step(self.handle, self.grad_arr, self.gdt, 0 if self.device_step else self.t, self.stream), "novak_step", self.handle)
             ev[i][1].record()
             if self.la_name != "none" and not self.fused and self.t % self.k == 0:
                 N.check(N.novak_lookahead_sync(self.handle, self.stream), "novak_lookahead_sync", self.handle)
@@ -403,6 +453,7 @@ def main():
                    "mode": hyper["mode"], "rectified": bool(hyper["rectified"]),
                    "layer_adaptation": bool(info.layer_adaptation), "auto_lr": bool(info.auto_lr),
                    "use_gc": bool(info.use_gc), "moment_dtype": args.moment_dtype, "clip_threshold": args.clip, "sparse_threshold": args.sparse,
+                   "step_count": "device" if args.device_step else "host", "graph_steps": int(args.graph_steps) if args.device_step else 0,
                    "chunk_elems": int(info.chunk_elems), "chunks": int(info.n_chunks), "layout": args.layout,
                    "arena_contiguous": bool(arena_contiguous)},
         "roofline": roofline,
@@ -411,7 +462,7 @@ def main():
 
     # ---- beside it, in the same process: what a caller gets whose memory comes from PyTorch, and the sync as a
     # ---- separate kernel (the benchmark spec names both); skipped when a specific layout / sync mode was asked for
-    if not args.no_extras and args.layout == "arena" and fused:
+    if not args.no_extras and args.layout == "arena" and fused and not args.device_step:
         others = {}
         for name, layout in (("torch_one_allocation_planned_layout", "torch_one"), ("torch_five_separate_allocations", "separate"),
                              ("torch_five_allocations_in_a_mem_pool_fed_by_the_library", "torch_pool")):
@@ -449,6 +500,8 @@ def profiled_config_of(args, fused) -> str:
     """The launch configuration as the profiles/ summaries state it (a counter figure is only carried over
     to a run of the same configuration)."""
     auto = lambda x, d: d if x is None else x
+    if args.device_step:
+        return "device_step"          # another kernel variant than the one the counters were taken on
     return (f"layout={args.layout} chunk_elems={auto(args.chunk_elems, 16384)} waves_per_cu={auto(args.waves_per_cu, 0)} "
             f"nontemporal={auto(args.nontemporal, 1)} vec_per_lane={auto(args.vec_per_lane, 1)} threads={auto(args.threads, 64)} "
             f"sync={'fused' if fused else 'separate'}")

@@ -120,7 +120,10 @@ typedef struct novak_hparams {
   int64_t n_taylor;         /* TRUE Nesterov behaves as APPROX for steps t > n_taylor (sections 4.4, 5.8: 100-200);
                                0 = never; ignored for the other modes */
   int32_t moment_dtype;     /* NOVAK_MOMENT_*: element type of every tensor's exp_avg array */
-  int32_t reserved0;        /* must be 0 */
+  int32_t device_step;      /* 1: the step count t lives in DEVICE memory (novak_set_step_counter) and the scalar prologue runs
+                               in a one-lane kernel in front of the step, so that a novak_step captured into a HIP graph
+                               advances by itself on every replay; novak_step's `step` argument must then be 0.  Single-pass
+                               step only; lookahead needs auto_sync = 1 (nobody on the host knows when a sync is due). */
 } novak_hparams;
 
 /* One parameter tensor.  All pointers are DEVICE pointers to contiguous fp32 arrays of `numel`
@@ -302,7 +305,7 @@ int novak_lookahead_init(novak_handle *h, void *hip_stream);
  * to the element size.  `step` is t, 1-based; on a fresh handle any t >= 1 is accepted (resume),
  * afterwards it must be the previous step + 1.  With lookahead on and auto_sync off, the step with
  * t mod k == 0 leaves the handle in "sync due" state and the next call must be
- * novak_lookahead_sync; with auto_sync on, that step applies Eq. 30-31 itself. */
+ * novak_lookahead_sync; with auto_sync on, that step applies Eq. 30-31 itself.  In device-step mode `step` must be 0. */
 int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t step, void *hip_stream);
 
 /* Auto-LR state (Table 3: two scalars): `ema` is a DEVICE pointer to two doubles owned by the caller,
@@ -310,6 +313,18 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
  * Required before the first novak_step when auto_lr is on (else NOVAK_ERR_STATE there).  Keeping the
  * two values is what resuming needs. */
 int novak_set_auto_lr_state(novak_handle *h, void *ema);
+
+/* Device-step mode (hp.device_step = 1): `counter` is a DEVICE pointer to one int64 owned by the caller, 8-byte aligned: the
+ * number of steps taken so far (0 before the first step; when resuming, the last t).  Every novak_step increments it first and
+ * uses the new value as t (Eq. 5-9 evaluated in double by a one-lane kernel, rounded once to fp32 like the host prologue).
+ * Required before the first novak_step in that mode (else NOVAK_ERR_STATE there); NOVAK_ERR_STATE on a handle in host-step
+ * mode.  To capture a step into a HIP graph: take one step eagerly first (it uploads the gradient-pointer list, which a capture
+ * cannot), keep the gradient buffers and the list fixed, then capture novak_step on the capture stream; each replay is one
+ * more step.  In this mode the handle does not track t: novak_get_info reports last_step = 0, the residency of the step
+ * kernel is chosen for the lookahead phase with the most streams, and with the memory-efficient lookahead the kernel loads
+ * the running-blend buffer on every step (the first step of a window does not use it: 4 bytes per parameter more than the
+ * host-step kernel reads there). */
+int novak_set_step_counter(novak_handle *h, void *counter);
 
 /* Monitoring: copies lambda_trust * alpha_auto of the last two-pass step, one float per tensor, to HOST
  * memory `out` (n_tensors floats).  Waits for `hip_stream` first.  NOVAK_ERR_STATE on a single-pass handle. */

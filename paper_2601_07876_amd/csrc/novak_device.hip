@@ -78,6 +78,9 @@ struct LaunchCtx {
   int n_gc = 0;
   int64_t total_rows = 0;
   double *d_ema = nullptr;             // caller-owned: g_bar, theta_bar
+  // device-step mode
+  DeviceStep *d_step = nullptr;        // what the current step is, written by novak_prologue_kernel
+  int64_t *d_counter = nullptr;        // caller-owned: steps taken so far
   // tables
   novak_chunk *d_chunks = nullptr;
   void *d_ptrs = nullptr;           // n_tensors TensorPtrs records, then n_tensors gradient pointers
@@ -376,6 +379,44 @@ void launch_step(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, cons
   else launch_step_block<false>(h, grad_dtype, la, s, tb, c);
 }
 
+// Device-step mode: the kernel that takes constants and lookahead phase from device memory (default shape).
+template <typename GradS, typename GradV, int LA, bool NT, bool GC>
+void launch_step_device_mom(const LaunchCtx *h, const dim3 &grid, unsigned lds, int sub_shift, hipStream_t s, const Tables &tb) {
+  if (h->hp.moment_dtype == NOVAK_MOMENT_BF16_M)
+    hipLaunchKernelGGL((novak_step_device_kernel<GradS, GradV, LA, NT, GC, unsigned short, u16x4>), grid, dim3(64), lds, s, tb, h->d_step, sub_shift);
+  else
+    hipLaunchKernelGGL((novak_step_device_kernel<GradS, GradV, LA, NT, GC, float, f32x4>), grid, dim3(64), lds, s, tb, h->d_step, sub_shift);
+}
+
+template <typename GradS, typename GradV, int LA>
+void launch_step_device_la(const LaunchCtx *h, const dim3 &grid, unsigned lds, int sub_shift, hipStream_t s, const Tables &tb) {
+  const bool nt = h->nontemporal != 0, gc = h->n_gc > 0;
+  if (nt && gc) launch_step_device_mom<GradS, GradV, LA, true, true>(h, grid, lds, sub_shift, s, tb);
+  else if (nt) launch_step_device_mom<GradS, GradV, LA, true, false>(h, grid, lds, sub_shift, s, tb);
+  else if (gc) launch_step_device_mom<GradS, GradV, LA, false, true>(h, grid, lds, sub_shift, s, tb);
+  else launch_step_device_mom<GradS, GradV, LA, false, false>(h, grid, lds, sub_shift, s, tb);
+}
+
+template <typename GradS, typename GradV>
+void launch_step_device_dtype(const LaunchCtx *h, const dim3 &grid, unsigned lds, int sub_shift, hipStream_t s, const Tables &tb) {
+  switch (h->hp.lookahead_mode) {
+    case NOVAK_LOOKAHEAD_MEMORY_EFFICIENT: launch_step_device_la<GradS, GradV, LA_RUNTIME_ME>(h, grid, lds, sub_shift, s, tb); break;
+    case NOVAK_LOOKAHEAD_BASIC: launch_step_device_la<GradS, GradV, LA_RUNTIME_BASIC>(h, grid, lds, sub_shift, s, tb); break;
+    default: launch_step_device_la<GradS, GradV, LA_OFF>(h, grid, lds, sub_shift, s, tb); break;
+  }
+}
+
+void launch_step_device(const LaunchCtx *h, int grad_dtype, hipStream_t s, const Tables &tb) {
+  // the host does not know the step's lookahead phase: residency for the phase with the most streams
+  const int la = h->hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT ? LA_MID : LA_OFF;
+  const StreamCount n = step_streams(grad_dtype, la, h->hp.moment_dtype == NOVAK_MOMENT_BF16_M);
+  LaunchCtx shape = *h;                       // this kernel exists in the default launch shape only
+  shape.vec_per_lane = 1;
+  const Geometry gm = geometry_of(&shape, 256, 64, n.wide, n.narrow);
+  if (grad_dtype == NOVAK_GRAD_BF16) launch_step_device_dtype<unsigned short, u16x4>(h, dim3(gm.grid), gm.lds, gm.sub_shift, s, tb);
+  else launch_step_device_dtype<float, f32x4>(h, dim3(gm.grid), gm.lds, gm.sub_shift, s, tb);
+}
+
 template <int OP, int BLOCK>
 void launch_la_block(const LaunchCtx *h, hipStream_t s, const Tables &tb, float c0, float c1) {
   const Geometry gm = geometry_of(h, BLOCK * 4, BLOCK, OP == SYNC_BASIC ? 4 : 2);
@@ -521,68 +562,6 @@ hipError_t launch_sync(const LaunchCtx *h, hipStream_t s) {
   return hipGetLastError();
 }
 
-// What step t does, derived once on the host: the kernel constants (scalar prologue of Phases 5-6 rounded
-// to fp32) and the lookahead phase of the step (its position in the k-step window of section 4.7).
-struct StepPlan {
-  Consts c;
-  int la = LA_OFF;
-  bool window_closes = false;   // t mod k == 0
-  bool sync_after = false;      // k == 1 with auto_sync: the sync cannot be fused into a later step of the window
-};
-
-int plan_step(const novak_hparams &hp, int64_t step, StepPlan *pl) {
-  novak_step_scalars sc;
-  const int rc = novak_compute_step_scalars(&hp, step, &sc);
-  if (rc != NOVAK_OK) return rc;
-  Consts &c = pl->c;
-  std::memset(&c, 0, sizeof(c));
-  c.omb1 = static_cast<float>(1.0 - sc.beta1_t);      // the moment updates follow Eq. 3-4 when scheduled
-  c.omb2 = static_cast<float>(1.0 - sc.beta2_t);
-  c.blend_w = static_cast<float>(1.0 - hp.beta1);
-  c.beta1 = static_cast<float>(hp.beta1);
-  c.beta_n = static_cast<float>(hp.beta_n);
-  c.inv_bc1 = static_cast<float>(1.0 / sc.bc1);
-  c.inv_bc2 = static_cast<float>(1.0 / sc.bc2);
-  c.eps = static_cast<float>(hp.eps);
-  c.step_size = static_cast<float>(sc.step_size);
-  c.lr_wd = hp.decoupled_decay ? static_cast<float>(hp.lr * hp.weight_decay) : 0.0f;
-  c.wd = hp.decoupled_decay ? 0.0f : static_cast<float>(hp.weight_decay);
-  c.flags = 0;
-  if (sc.nesterov_mode == NOVAK_NESTEROV_APPROX) c.flags |= F_APPROX;
-  if (hp.nesterov_mode == NOVAK_NESTEROV_CLASSICAL) c.flags |= F_CLASSICAL;
-  if (sc.denom_on) c.flags |= F_DENOM;
-  if (!hp.decoupled_decay && hp.weight_decay != 0.0) c.flags |= F_COUPLED;
-  if (hp.clip_threshold > 0.0) c.flags |= F_CLIP;
-  if (hp.sparse_threshold > 0.0) {
-    c.flags |= F_SPARSE;
-    c.sparse_tau = static_cast<float>(hp.sparse_threshold);
-  }
-  // lookahead phase of this step: position in the k-step window (section 4.7; sync when t mod k == 0)
-  pl->la = LA_OFF;
-  pl->window_closes = pl->sync_after = false;
-  if (hp.lookahead_mode != NOVAK_LOOKAHEAD_NONE) {
-    const int64_t pos = (step - 1) % hp.la_k + 1;
-    pl->window_closes = pos == hp.la_k;
-    if (hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT) {
-      c.la_c0 = static_cast<float>(1.0 - hp.la_alpha);
-      c.la_c1 = static_cast<float>(hp.la_alpha / hp.la_k);
-      if (pos == 1) {
-        pl->la = LA_FIRST;
-        pl->sync_after = pl->window_closes && hp.auto_sync;   // k == 1: nothing to fuse into
-      } else if (pl->window_closes && hp.auto_sync) {
-        pl->la = LA_LAST_FUSED;
-      } else {
-        pl->la = LA_MID;
-      }
-    } else if (pl->window_closes && hp.auto_sync) {
-      pl->la = LA_BASIC_FUSED;
-      c.la_c0 = static_cast<float>(1.0 - hp.la_alpha);
-      c.la_c1 = static_cast<float>(hp.la_alpha);
-    }
-  }
-  return NOVAK_OK;
-}
-
 // Enqueues every kernel of one step on `stream`: the gradient pre-passes, the single-pass or two-pass
 // update, and the separate sync where the plan asks for one.  The tables of `cx` (gradient pointers
 // included) must already be in place in stream order.
@@ -599,6 +578,22 @@ hipError_t enqueue_step(const LaunchCtx *cx, int grad_dtype, const StepPlan &pl,
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (pl.sync_after) return launch_sync(cx, stream);
+  return hipSuccess;
+}
+
+// The same in device-step mode: a one-lane prologue advances the caller's counter and writes the step's constants
+// and lookahead phase, then the kernels follow; which of them run does not depend on t.
+hipError_t enqueue_step_device(const LaunchCtx *cx, int grad_dtype, hipStream_t stream) {
+  if (cx->n_chunks == 0) return hipSuccess;
+  hipError_t e;
+  const uint32_t extra = cx->n_gc > 0 ? F_GC : 0u;
+  hipLaunchKernelGGL(novak_prologue_kernel, dim3(1), dim3(64), 0, stream, cx->hp, extra, cx->d_counter, cx->d_step);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if ((clipping(cx) || cx->n_gc > 0) && (e = launch_prepass(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
+  launch_step_device(cx, grad_dtype, stream, tables_of(cx));
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  // a window of one step: the sync follows every step as its own kernel
+  if (cx->hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT && cx->hp.la_k == 1) return launch_sync(cx, stream);
   return hipSuccess;
 }
 
@@ -662,6 +657,12 @@ static int create_impl(novak_handle **out, const novak_hparams *hp, const novak_
   uint32_t warn = 0;
   int rc = novak_validate_hparams(hp, &eff, &warn);
   if (rc != NOVAK_OK) return fail(nullptr, rc, "hyper-parameters rejected (section 5.8 validation rules)");
+  if (eff.device_step) {
+    if (eff.layer_adaptation || eff.auto_lr)
+      return fail(nullptr, NOVAK_ERR_NOT_IMPLEMENTED, "device_step covers the single-pass step; layer_adaptation / auto_lr need the host-step mode");
+    if (eff.lookahead_mode != NOVAK_LOOKAHEAD_NONE && !eff.auto_sync)
+      return fail(nullptr, NOVAK_ERR_INVALID_ARG, "device_step with lookahead needs auto_sync = 1 (the host does not know when a sync is due)");
+  }
   std::string why;
   rc = check_descs(eff, tensors, n_tensors, &why);
   if (rc != NOVAK_OK) return fail(nullptr, rc, why);
@@ -702,6 +703,8 @@ static int create_impl(novak_handle **out, const novak_hparams *hp, const novak_
   int lds_cu = 0;
   if (hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, device_id) == hipSuccess && lds_cu >= 65536)
     h->lds_per_cu = lds_cu;
+  if (eff.device_step && (e = hipMalloc(reinterpret_cast<void **>(&h->d_step), sizeof(DeviceStep))) != hipSuccess)
+    return bail(fail_hip(h, e, "hipMalloc(device step record)"));
   if (n_tensors > 0) {
     const size_t n = static_cast<size_t>(n_tensors);
     const size_t bytes = 5 * n * sizeof(void *);
@@ -891,6 +894,7 @@ int novak_destroy(novak_handle *h) {
   (void)scope.enter(h->device_id);
   free_device_tables(h);
   if (h->d_ptrs) (void)hipFree(h->d_ptrs);
+  if (h->d_step) (void)hipFree(h->d_step);
   if (h->d_out_ptrs) (void)hipFree(h->d_out_ptrs);
   if (h->d_gc) (void)hipFree(h->d_gc);
   if (h->d_gc_tensor) (void)hipFree(h->d_gc_tensor);
@@ -968,6 +972,15 @@ int novak_set_auto_lr_state(novak_handle *h, void *ema) {
   if (!ema) return fail(h, NOVAK_ERR_NULL_POINTER, "ema is NULL");
   if (reinterpret_cast<uintptr_t>(ema) & 7u) return fail(h, NOVAK_ERR_MISALIGNED, "ema must be 8-byte aligned");
   h->d_ema = static_cast<double *>(ema);
+  return NOVAK_OK;
+}
+
+int novak_set_step_counter(novak_handle *h, void *counter) {
+  if (!h) return NOVAK_ERR_NULL_POINTER;
+  if (!h->hp.device_step) return fail(h, NOVAK_ERR_STATE, "the handle counts steps on the host (device_step is off)");
+  if (!counter) return fail(h, NOVAK_ERR_NULL_POINTER, "counter is NULL");
+  if (reinterpret_cast<uintptr_t>(counter) & 7u) return fail(h, NOVAK_ERR_MISALIGNED, "counter must be 8-byte aligned");
+  h->d_counter = static_cast<int64_t *>(counter);
   return NOVAK_OK;
 }
 
@@ -1055,14 +1068,19 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
   std::string why;
   int rc = check_grads(h->tensors.data(), n, grads, grad_dtype, &why);
   if (rc != NOVAK_OK) return fail(h, rc, why);
-  if (step < 1) return fail(h, NOVAK_ERR_BAD_STEP, "step must be >= 1 (Eq. 5 is undefined at t = 0)");
-  if (h->last_step != 0 && step != h->last_step + 1) return fail(h, NOVAK_ERR_BAD_STEP, "step must be the previous step + 1");
+  const bool device_step = h->hp.device_step != 0;
+  if (device_step) {
+    if (step != 0) return fail(h, NOVAK_ERR_BAD_STEP, "in device-step mode the step count lives in device memory: pass step = 0");
+    if (!h->d_counter) return fail(h, NOVAK_ERR_STATE, "device_step is on but novak_set_step_counter was not called");
+  } else {
+    if (step < 1) return fail(h, NOVAK_ERR_BAD_STEP, "step must be >= 1 (Eq. 5 is undefined at t = 0)");
+    if (h->last_step != 0 && step != h->last_step + 1) return fail(h, NOVAK_ERR_BAD_STEP, "step must be the previous step + 1");
+  }
   if (h->sync_due) return fail(h, NOVAK_ERR_STATE, "a lookahead sync is due before the next step");
   if (h->hp.auto_lr && !h->d_ema) return fail(h, NOVAK_ERR_STATE, "auto_lr is on but novak_set_auto_lr_state was not called");
 
   StepPlan pl;
-  rc = plan_step(h->hp, step, &pl);
-  if (rc != NOVAK_OK) return fail(h, rc, "scalar prologue failed");
+  if (!device_step) plan_step(h->hp, step, &pl);
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (h->n_chunks > 0) {
@@ -1082,8 +1100,10 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
       std::memcpy(h->last_grads.data(), grads, n * sizeof(void *));
       h->grads_uploaded = true;
     }
-    NOVAK_HIP(h, enqueue_step(h, grad_dtype, pl, stream));
+    if (device_step) NOVAK_HIP(h, enqueue_step_device(h, grad_dtype, stream));
+    else NOVAK_HIP(h, enqueue_step(h, grad_dtype, pl, stream));
   }
+  if (device_step) return NOVAK_OK;          // t is the device's business
   h->last_step = step;
   h->sync_due = (pl.window_closes && !h->hp.auto_sync) ? 1 : 0;
   return NOVAK_OK;
@@ -1139,6 +1159,7 @@ static int step_static_impl(const novak_hparams *hp, const novak_tensor_desc *te
   if (two_pass(&cx) || cx.hp.use_gc)
     return fail(nullptr, NOVAK_ERR_NOT_IMPLEMENTED, "the allocation-free step covers the single-pass update (with clipping and the sparse threshold); "
                                                     "layer adaptation, auto-LR and gradient centralization need a handle");
+  if (cx.hp.device_step) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "the allocation-free step takes t as an argument: device_step must be 0");
   if (cx.hp.lookahead_mode != NOVAK_LOOKAHEAD_NONE && !cx.hp.auto_sync)
     return fail(nullptr, NOVAK_ERR_INVALID_ARG, "with lookahead on, the allocation-free step needs auto_sync = 1 (there is no handle to remember a due sync)");
   std::string why;
@@ -1155,8 +1176,7 @@ static int step_static_impl(const novak_hparams *hp, const novak_tensor_desc *te
       return fail(nullptr, NOVAK_ERR_INVALID_ARG, "the list needs more than NOVAK_STATIC_MAX_CHUNKS chunk-table entries (16384 elements each)");
   }
   StepPlan pl;
-  rc = plan_step(cx.hp, step, &pl);
-  if (rc != NOVAK_OK) return fail(nullptr, rc, "scalar prologue failed");
+  plan_step(cx.hp, step, &pl);
   if (n_chunks == 0) return NOVAK_OK;
 
   const StaticLayout L = static_layout(static_cast<size_t>(n_tensors), static_cast<size_t>(n_chunks), clipping(&cx));

@@ -3,6 +3,7 @@
 // multi-tensor chunk planner and the algorithmic byte accounting (section 5.5).  No HIP calls here,
 // so these entry points work on machines without a GPU.
 #include "novak_internal.h"
+#include "novak_prologue.h"
 
 #include <cmath>
 #include <cstdint>
@@ -17,12 +18,6 @@ bool finite_all(const novak_hparams &hp) {
   for (double x : vals)
     if (!std::isfinite(x)) return false;
   return true;
-}
-
-// 1 - beta^t evaluated through the logarithm (section 5.8), which keeps full precision for large t.
-double one_minus_pow(double beta, int64_t t) {
-  if (beta == 0.0) return 1.0;
-  return -std::expm1(static_cast<double>(t) * std::log(beta));
 }
 
 }  // namespace
@@ -69,7 +64,6 @@ int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, ui
   if (hp->adaptive_beta && !(hp->beta_tau1 > 0.0 && hp->beta_tau2 > 0.0)) return NOVAK_ERR_INVALID_ARG;
   if (hp->n_taylor < 0) return NOVAK_ERR_INVALID_ARG;
   if (hp->moment_dtype != NOVAK_MOMENT_F32 && hp->moment_dtype != NOVAK_MOMENT_BF16_M) return NOVAK_ERR_INVALID_ARG;
-  if (hp->reserved0 != 0) return NOVAK_ERR_INVALID_ARG;
   if (hp->layer_adaptation && !(hp->trust_clip_lo > 0.0 && hp->trust_clip_lo <= hp->trust_clip_hi)) return NOVAK_ERR_INVALID_ARG;
   if (hp->auto_lr) {
     if (!(hp->auto_lr_gamma > 0.0 && hp->auto_lr_gamma <= 1.0)) return NOVAK_ERR_INVALID_ARG;
@@ -111,6 +105,7 @@ int novak_validate_hparams(const novak_hparams *hp, novak_hparams *effective, ui
   eff.rectified = eff.rectified ? 1 : 0;
   eff.decoupled_decay = eff.decoupled_decay ? 1 : 0;
   eff.auto_sync = eff.auto_sync ? 1 : 0;
+  eff.device_step = eff.device_step ? 1 : 0;
   if (effective) *effective = eff;
   if (warnings) *warnings = warn;
   return NOVAK_OK;
@@ -120,37 +115,7 @@ int novak_compute_step_scalars(const novak_hparams *hp, int64_t step, novak_step
   if (!hp || !out) return NOVAK_ERR_NULL_POINTER;
   if (hp->struct_size != sizeof(novak_hparams)) return NOVAK_ERR_INVALID_ARG;
   if (step < 1) return NOVAK_ERR_BAD_STEP;
-  novak_step_scalars s;
-  std::memset(&s, 0, sizeof(s));
-  s.bc1 = one_minus_pow(hp->beta1, step);
-  s.bc2 = one_minus_pow(hp->beta2, step);
-  s.rho_inf = 2.0 / (1.0 - hp->beta2) - 1.0;                         // Eq. 6
-  const double beta2_pow_t = 1.0 - s.bc2;
-  s.rho_t = s.rho_inf - 2.0 * static_cast<double>(step) * beta2_pow_t / s.bc2;  // Eq. 7
-  s.r_t = 1.0;
-  s.rectified_now = 0;
-  s.denom_on = 1;
-  if (hp->rectified) {
-    if (s.rho_t >= 5.0) {                                            // Eq. 8, rectified branch
-      s.rectified_now = 1;
-      const double num = (s.rho_t - 4.0) * (s.rho_t - 2.0) * s.rho_inf;
-      const double den = (s.rho_inf - 4.0) * (s.rho_inf - 2.0) * s.rho_t;
-      s.r_t = std::sqrt(num / den);                                  // Eq. 9
-    } else if (hp->unrect_fallback == NOVAK_UNRECT_SGDM) {
-      s.denom_on = 0;
-    }
-  }
-  s.beta1_t = hp->beta1;
-  s.beta2_t = hp->beta2;
-  if (hp->adaptive_beta) {                                           // Eq. 3-4
-    s.beta1_t = hp->beta1 * (1.0 - std::exp(-static_cast<double>(step) / hp->beta_tau1));
-    s.beta2_t = hp->beta2 * (1.0 - std::exp(-static_cast<double>(step) / hp->beta_tau2));
-  }
-  s.nesterov_mode = hp->nesterov_mode;                               // automatic fallback of the true variant
-  if (hp->nesterov_mode == NOVAK_NESTEROV_TRUE && hp->n_taylor > 0 && step > hp->n_taylor) s.nesterov_mode = NOVAK_NESTEROV_APPROX;
-  s.step_size = hp->lr * s.r_t;                                      // Eq. 24a
-  s.decay = hp->decoupled_decay ? 1.0 - hp->lr * hp->weight_decay : 1.0;  // Eq. 18
-  *out = s;
+  novak_step_scalars_impl(*hp, step, out);
   return NOVAK_OK;
 }
 

@@ -22,6 +22,7 @@
 #include <cstdint>
 
 #include "novak_internal.h"
+#include "novak_prologue.h"
 
 namespace {
 
@@ -36,8 +37,13 @@ enum : int {
   LA_FIRST = 1,        // first step of a window:  A  = c0*theta_in + c1*theta_new      (A written)
   LA_MID = 2,          // later steps:             A += c1*theta_new                    (A read, written)
   LA_LAST_FUSED = 3,   // k-th step, sync fused:   theta_out = A + c1*theta_new         (A read)
-  LA_BASIC_FUSED = 4   // k-th step, basic mode:   S = c1*theta_new + c0*S; theta_out=S (S read, written)
+  LA_BASIC_FUSED = 4,  // k-th step, basic mode:   S = c1*theta_new + c0*S; theta_out=S (S read, written)
+  // template arguments only (device-step mode): the phase is a run-time, wave-uniform value
+  LA_RUNTIME_ME = 5,   // one of LA_FIRST / LA_MID / LA_LAST_FUSED; the buffer is always loaded (a load behind a branch is
+                       // issued late and cost 9-13 %; the first step of a window then reads 4 bytes it does not need)
+  LA_RUNTIME_BASIC = 6 // LA_OFF or LA_BASIC_FUSED; the slow weights are loaded only at the sync (one step in k)
 };
+constexpr bool la_runtime(int la) { return la >= LA_RUNTIME_ME; }
 
 enum : uint32_t { F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u, F_CLIP = 16u, F_SPARSE = 32u, F_GC = 64u };
 
@@ -109,6 +115,13 @@ struct Consts {
   float sparse_tau;      // tau of Eq. 27 (used when F_SPARSE is set)
   float blend_w;         // 1-beta1 of Eq. 16 (base beta1; omb1 follows the schedule of Eq. 3)
   uint32_t flags;
+};
+
+// Device-step mode: what the current step is, written by novak_prologue_kernel, read by the step kernel.
+struct DeviceStep {
+  Consts c;
+  int la;              // LA_* phase of this step
+  int pad[3];
 };
 
 __device__ __forceinline__ float bf16_to_f32(unsigned short b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
@@ -193,7 +206,7 @@ __device__ __forceinline__ float direction(float m, float v, const Consts &c, fl
 // `step` is alpha*r_t, times the tensor's trust ratio and the auto-LR factor on the scaled path (Eq. 24a).
 // `la` is the lookahead buffer value (read when the phase reads it, returned updated when it writes it).
 template <int LA>
-__device__ __forceinline__ void apply(float &th, float u, float m_hat, float &la, const Consts &c, float step) {
+__device__ __forceinline__ void apply(float &th, float u, float m_hat, float &la, const Consts &c, float step, int la_rt = LA_OFF) {
   const float th_in = th;
   if ((c.flags & F_SPARSE) && !(__builtin_fabsf(u) > c.sparse_tau)) u = 0.0f;  // Eq. 27
   if (c.flags & F_CLASSICAL) u = __builtin_fmaf(c.beta1, m_hat, c.blend_w * u);  // Eq. 16
@@ -209,16 +222,24 @@ __device__ __forceinline__ void apply(float &th, float u, float m_hat, float &la
   } else if (LA == LA_BASIC_FUSED) {
     la = __builtin_fmaf(c.la_c1, th_new, c.la_c0 * la);
     th = la;
+  } else if (la_runtime(LA)) {
+    // the same expressions, selected by a wave-uniform phase: results are bit-identical to the compiled-in phases
+    const float la_in = la;
+    const float scaled = c.la_c0 * (la_rt == LA_FIRST ? th_in : la_in);
+    const float base = (la_rt == LA_FIRST || la_rt == LA_BASIC_FUSED) ? scaled : la_in;
+    const float blend = __builtin_fmaf(c.la_c1, th_new, base);
+    if (la_rt == LA_FIRST || la_rt == LA_MID || la_rt == LA_BASIC_FUSED) la = blend;
+    if (la_rt == LA_LAST_FUSED || la_rt == LA_BASIC_FUSED) th = blend;
   }
 }
 
 template <int LA, typename MomS = float>
-__device__ __forceinline__ void update_one(float &th, float g, float &m, float &v, float &la, const Consts &c, float gs) {
+__device__ __forceinline__ void update_one(float &th, float g, float &m, float &v, float &la, const Consts &c, float gs, int la_rt = LA_OFF) {
   moments(th, g, m, v, c, gs);
   m = round_mom<MomS>(m);          // the stored m_t is what the rest of the step uses
   float m_hat;
   const float u = direction(m, v, c, m_hat);
-  apply<LA>(th, u, m_hat, la, c, c.step_size);
+  apply<LA>(th, u, m_hat, la, c, c.step_size, la_rt);
 }
 
 template <bool NT, typename T>
@@ -245,17 +266,17 @@ __device__ __forceinline__ f32x4 grad_to_f32<u16x4>(u16x4 g) {
 }
 
 template <int LA, typename MomS = float>
-__device__ __forceinline__ void update_vec(f32x4 &th, f32x4 g, f32x4 &m, f32x4 &v, f32x4 &la, const Consts &c, float gs) {
+__device__ __forceinline__ void update_vec(f32x4 &th, f32x4 g, f32x4 &m, f32x4 &v, f32x4 &la, const Consts &c, float gs, int la_rt = LA_OFF) {
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     float th_k = th[k], m_k = m[k], v_k = v[k], la_k = la[k];
-    update_one<LA, MomS>(th_k, g[k], m_k, v_k, la_k, c, gs);
+    update_one<LA, MomS>(th_k, g[k], m_k, v_k, la_k, c, gs, la_rt);
     th[k] = th_k; m[k] = m_k; v[k] = v_k; la[k] = la_k;
   }
 }
 
-constexpr bool la_reads(int la) { return la == LA_MID || la == LA_LAST_FUSED || la == LA_BASIC_FUSED; }
-constexpr bool la_writes(int la) { return la == LA_FIRST || la == LA_MID || la == LA_BASIC_FUSED; }
+__host__ __device__ constexpr bool la_reads(int la) { return la == LA_MID || la == LA_LAST_FUSED || la == LA_BASIC_FUSED; }
+__host__ __device__ constexpr bool la_writes(int la) { return la == LA_FIRST || la == LA_MID || la == LA_BASIC_FUSED; }
 
 // Work decomposition.  A chunk-table entry covers up to chunk_elems (a power of two) elements of one
 // tensor; it is processed by chunk_elems / SUB workgroups ("sub-blocks"), each of which touches
@@ -271,8 +292,8 @@ constexpr bool la_writes(int la) { return la == LA_FIRST || la == LA_MID || la =
 // MomS / MomV: storage type of the first moment and its 4-vector (float / f32x4, or unsigned short /
 // u16x4 for bfloat16; the latter also only for UN = 1, BLOCK = 64).
 template <typename GradS, typename GradV, int LA, bool NT, int UN, int BLOCK, bool GC = false, typename MomS = float,
-          typename MomV = f32x4>
-__global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, int sub_shift) {
+          typename MomV = f32x4, bool DEV = false>
+__device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg, int sub_shift, const DeviceStep *ds = nullptr) {
   constexpr int SUB = BLOCK * 4 * UN;
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
   const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * SUB;
@@ -281,6 +302,19 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
   const int64_t off = ch.offset + start;
   const TensorPtrs tp = tb.tensors[ch.tensor];          // one scalar load, issued together with the next
   const void *const g_base = tb.grad[ch.tensor];
+  // Device-step mode (DEV): constants and lookahead phase come from device memory; their scalar load is issued
+  // here, together with the two table loads above, so that the wave waits once for all three.
+  Consts c_dev;
+  int la_rt = LA_OFF;
+  if constexpr (DEV) {
+    const DeviceStep d = *ds;
+    c_dev = d.c;
+    la_rt = d.la;
+  }
+  const Consts &c = DEV ? c_dev : c_arg;
+  // which lookahead stream this step reads / writes: compiled in, or a wave-uniform run-time value
+  const int phase = la_runtime(LA) ? la_rt : LA;
+  const bool reads = LA == LA_RUNTIME_ME ? true : la_reads(phase), writes = la_writes(phase);
   const float gs = (c.flags & F_CLIP) ? *tb.gscale : 1.0f;
   GcInfo gi;
   gi.cols = 0;
@@ -290,7 +324,7 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
   float *__restrict__ v_p = tp.v + off;
   const GradS *__restrict__ g_p = static_cast<const GradS *>(g_base) + off;
   float *__restrict__ la_p = nullptr;
-  if (LA != LA_OFF) la_p = tp.la + off;
+  if (phase != LA_OFF) la_p = tp.la + off;
 
   uintptr_t mis = (reinterpret_cast<uintptr_t>(th_p) | reinterpret_cast<uintptr_t>(v_p) | reinterpret_cast<uintptr_t>(la_p)) & 15u;
   mis |= reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1);
@@ -315,7 +349,7 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
         g[u] = ld<NT>(g4 + j);
         m[u] = ld<NT>(m4 + j);
         v[u] = ld<NT>(v4 + j);
-        if (la_reads(LA)) la[u] = ld<NT>(la4 + j);
+        if (reads) la[u] = ld<NT>(la4 + j);
       }
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
@@ -323,11 +357,11 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
         f32x4 gf = grad_to_f32<GradV>(g[u]);
         if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(j), gi);
         f32x4 mf = mom_to_f32<MomV>(m[u]);
-        update_vec<LA, MomS>(th[u], gf, mf, v[u], la[u], c, gs);
+        update_vec<LA, MomS>(th[u], gf, mf, v[u], la[u], c, gs, la_rt);
         st<NT>(th4 + j, th[u]);
         st<NT>(m4 + j, f32_to_mom<MomV>(mf));
         st<NT>(v4 + j, v[u]);
-        if (la_writes(LA)) st<NT>(la4 + j, la[u]);
+        if (writes) st<NT>(la4 + j, la[u]);
       }
       return;
     }
@@ -335,14 +369,14 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
     for (int i = threadIdx.x; i < nvec; i += BLOCK) {
       f32x4 th = ld<NT>(th4 + i), m = mom_to_f32<MomV>(ld<NT>(m4 + i)), v = ld<NT>(v4 + i), la;
       GradV g = ld<NT>(g4 + i);
-      if (la_reads(LA)) la = ld<NT>(la4 + i);
+      if (reads) la = ld<NT>(la4 + i);
       f32x4 gf = grad_to_f32<GradV>(g);
       if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(i), gi);
-      update_vec<LA, MomS>(th, gf, m, v, la, c, gs);
+      update_vec<LA, MomS>(th, gf, m, v, la, c, gs, la_rt);
       st<NT>(th4 + i, th);
       st<NT>(m4 + i, f32_to_mom<MomV>(m));
       st<NT>(v4 + i, v);
-      if (la_writes(LA)) st<NT>(la4 + i, la);
+      if (writes) st<NT>(la4 + i, la);
     }
     done = nvec << 2;
   }
@@ -351,14 +385,106 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
     float th = th_p[i], m = load_mom<MomS>(m_p + i), v = v_p[i], la = 0.0f, g;
     if constexpr (sizeof(GradS) == 2) g = bf16_to_f32(g_p[i]);
     else g = g_p[i];
-    if (la_reads(LA)) la = la_p[i];
+    if (reads) la = la_p[i];
     if (GC && gi.cols) g = centralize_one(g, off + i, gi);
-    update_one<LA, MomS>(th, g, m, v, la, c, gs);
+    update_one<LA, MomS>(th, g, m, v, la, c, gs, la_rt);
     th_p[i] = th;
     store_mom<MomS>(m_p + i, m);
     v_p[i] = v;
-    if (la_writes(LA)) la_p[i] = la;
+    if (writes) la_p[i] = la;
   }
+}
+
+template <typename GradS, typename GradV, int LA, bool NT, int UN, int BLOCK, bool GC = false, typename MomS = float,
+          typename MomV = f32x4>
+__global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, int sub_shift) {
+  step_body<GradS, GradV, LA, NT, UN, BLOCK, GC, MomS, MomV>(tb, c, sub_shift);
+}
+
+// Device-step mode: what the step is (constants, lookahead phase) was written to device memory by
+// novak_prologue_kernel just before; every wave fetches it with one scalar load.  LA is LA_OFF (no lookahead),
+// LA_RUNTIME_ME or LA_RUNTIME_BASIC: one body in which the lookahead blend and store are selected by the wave-uniform
+// phase (compiling the phase bodies behind a switch made the compiler merge them and lose the "all loads first"
+// order: -10 %).  Default launch shape only (one wave64 per 256 elements).
+template <typename GradS, typename GradV, int LA, bool NT, bool GC, typename MomS, typename MomV>
+__global__ __launch_bounds__(64) void novak_step_device_kernel(Tables tb, const DeviceStep *ds, int sub_shift) {
+  step_body<GradS, GradV, LA, NT, 1, 64, GC, MomS, MomV, true>(tb, Consts(), sub_shift, ds);
+}
+
+// What step t does: the kernel constants (scalar prologue of Phases 5-6 rounded to fp32) and the lookahead
+// phase of the step (its position in the k-step window of section 4.7).  Evaluated on the host by novak_step, and
+// by novak_prologue_kernel on the device in device-step mode.
+struct StepPlan {
+  Consts c;
+  int la = LA_OFF;
+  bool window_closes = false;   // t mod k == 0
+  bool sync_after = false;      // k == 1 with auto_sync: the sync cannot be fused into a later step of the window
+};
+
+__host__ __device__ inline void plan_step(const novak_hparams &hp, int64_t step, StepPlan *pl) {
+  novak_step_scalars sc;
+  novak_step_scalars_impl(hp, step, &sc);
+  Consts c = Consts();
+  c.omb1 = static_cast<float>(1.0 - sc.beta1_t);      // the moment updates follow Eq. 3-4 when scheduled
+  c.omb2 = static_cast<float>(1.0 - sc.beta2_t);
+  c.blend_w = static_cast<float>(1.0 - hp.beta1);
+  c.beta1 = static_cast<float>(hp.beta1);
+  c.beta_n = static_cast<float>(hp.beta_n);
+  c.inv_bc1 = static_cast<float>(1.0 / sc.bc1);
+  c.inv_bc2 = static_cast<float>(1.0 / sc.bc2);
+  c.eps = static_cast<float>(hp.eps);
+  c.step_size = static_cast<float>(sc.step_size);
+  c.lr_wd = hp.decoupled_decay ? static_cast<float>(hp.lr * hp.weight_decay) : 0.0f;
+  c.wd = hp.decoupled_decay ? 0.0f : static_cast<float>(hp.weight_decay);
+  c.flags = 0;
+  if (sc.nesterov_mode == NOVAK_NESTEROV_APPROX) c.flags |= F_APPROX;
+  if (hp.nesterov_mode == NOVAK_NESTEROV_CLASSICAL) c.flags |= F_CLASSICAL;
+  if (sc.denom_on) c.flags |= F_DENOM;
+  if (!hp.decoupled_decay && hp.weight_decay != 0.0) c.flags |= F_COUPLED;
+  if (hp.clip_threshold > 0.0) c.flags |= F_CLIP;
+  if (hp.sparse_threshold > 0.0) {
+    c.flags |= F_SPARSE;
+    c.sparse_tau = static_cast<float>(hp.sparse_threshold);
+  }
+  // lookahead phase of this step: position in the k-step window (section 4.7; sync when t mod k == 0)
+  pl->la = LA_OFF;
+  pl->window_closes = pl->sync_after = false;
+  if (hp.lookahead_mode != NOVAK_LOOKAHEAD_NONE) {
+    const int64_t pos = (step - 1) % hp.la_k + 1;
+    pl->window_closes = pos == hp.la_k;
+    if (hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT) {
+      c.la_c0 = static_cast<float>(1.0 - hp.la_alpha);
+      c.la_c1 = static_cast<float>(hp.la_alpha / hp.la_k);
+      if (pos == 1) {
+        pl->la = LA_FIRST;
+        pl->sync_after = pl->window_closes && hp.auto_sync;   // k == 1: nothing to fuse into
+      } else if (pl->window_closes && hp.auto_sync) {
+        pl->la = LA_LAST_FUSED;
+      } else {
+        pl->la = LA_MID;
+      }
+    } else if (pl->window_closes && hp.auto_sync) {
+      pl->la = LA_BASIC_FUSED;
+      c.la_c0 = static_cast<float>(1.0 - hp.la_alpha);
+      c.la_c1 = static_cast<float>(hp.la_alpha);
+    }
+  }
+  pl->c = c;
+}
+
+// Device-step mode: one lane advances the caller's step counter and writes what the step is.
+__global__ __launch_bounds__(64) void novak_prologue_kernel(novak_hparams hp, uint32_t extra_flags, int64_t *counter, DeviceStep *out) {
+  if (threadIdx.x != 0) return;
+  const int64_t t = *counter + 1;
+  *counter = t;
+  StepPlan pl;
+  plan_step(hp, t, &pl);
+  DeviceStep d;
+  d.c = pl.c;
+  d.c.flags |= extra_flags;
+  d.la = pl.la;
+  d.pad[0] = d.pad[1] = d.pad[2] = 0;
+  *out = d;
 }
 
 // Lookahead kernels over the same chunk table and sub-block decomposition (UN = 1).

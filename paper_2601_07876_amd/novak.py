@@ -52,7 +52,7 @@ class novak_hparams(C.Structure):
                 ("clip_threshold", C.c_double), ("sparse_threshold", C.c_double),
                 ("use_gc", C.c_int32), ("adaptive_beta", C.c_int32),
                 ("beta_tau1", C.c_double), ("beta_tau2", C.c_double), ("n_taylor", C.c_int64),
-                ("moment_dtype", C.c_int32), ("reserved0", C.c_int32)]
+                ("moment_dtype", C.c_int32), ("device_step", C.c_int32)]
 
 
 class novak_tensor_desc(C.Structure):
@@ -87,7 +87,7 @@ EXPORTS = ("novak_validate_hparams", "novak_compute_step_scalars", "novak_plan_c
            "novak_status_string", "novak_create", "novak_lookahead_init", "novak_step", "novak_lookahead_sync",
            "novak_destroy", "novak_get_info", "novak_set_tuning", "novak_last_error", "novak_set_auto_lr_state",
            "novak_copy_tensor_scales", "novak_nesterov_extrapolate", "novak_step_static",
-           "novak_torch_malloc", "novak_torch_free", "novak_torch_alloc_stats")
+           "novak_torch_malloc", "novak_torch_free", "novak_torch_alloc_stats", "novak_set_step_counter")
 
 _lib: Optional[C.CDLL] = None
 
@@ -120,6 +120,7 @@ def load_library() -> C.CDLL:
     lib.novak_bytes_per_param_scaled_step.argtypes = [i32, i32, i32, i32, i32]
     lib.novak_bytes_per_param_scaled_step.restype = C.c_double
     lib.novak_set_auto_lr_state.argtypes = [vp, vp]
+    lib.novak_set_step_counter.argtypes = [vp, vp]
     lib.novak_copy_tensor_scales.argtypes = [vp, C.POINTER(C.c_float), vp]
     lib.novak_nesterov_extrapolate.argtypes = [vp, C.POINTER(vp), vp]
     lib.novak_bytes_per_param_moment_saving.argtypes = [i32, i32]
@@ -160,7 +161,7 @@ def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, be
                  unrect_fallback="adam_denom", mode="fast", auto_sync=False, layer_adaptation=False, auto_lr=False,
                  auto_lr_gamma=0.1, trust_clip=(0.1, 10.0), auto_clip=(0.1, 2.0), clip_threshold=0.0,
                  sparse_threshold=0.0, use_gc=False, adaptive_beta=False, beta_tau1=1000.0, beta_tau2=5000.0,
-                 n_taylor=0, moment_dtype="f32") -> novak_hparams:
+                 n_taylor=0, moment_dtype="f32", device_step=False) -> novak_hparams:
     """Fills a novak_hparams from keyword values (mode names or their integer codes)."""
     def code(table: Dict[str, int], x):
         return table[x] if isinstance(x, str) else int(x)
@@ -170,7 +171,7 @@ def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, be
                          int(auto_lr), float(auto_lr_gamma), float(trust_clip[0]), float(trust_clip[1]),
                          float(auto_clip[0]), float(auto_clip[1]), float(clip_threshold), float(sparse_threshold),
                          int(use_gc), int(adaptive_beta), float(beta_tau1), float(beta_tau2), int(n_taylor),
-                         code(MOMENT_DTYPE, moment_dtype), 0)
+                         code(MOMENT_DTYPE, moment_dtype), int(device_step))
 
 
 # ---- the entry points, same names as the C ABI ------------------------------------------------------
@@ -272,6 +273,10 @@ def novak_bytes_per_param_scaled_step(lookahead_mode: int, grad_dtype: int, la_k
 
 def novak_set_auto_lr_state(handle, ema_ptr: int) -> int:
     return load_library().novak_set_auto_lr_state(handle, C.c_void_p(ema_ptr))
+
+
+def novak_set_step_counter(handle, counter_ptr: int) -> int:
+    return load_library().novak_set_step_counter(handle, C.c_void_p(counter_ptr))
 
 
 def novak_copy_tensor_scales(handle, n_tensors: int, stream: int = 0):

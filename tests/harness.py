@@ -31,7 +31,7 @@ ATOL, RTOL = 1e-7, 1e-5
 def oracle_hyper(hyper: Dict[str, object], effective_nesterov: Optional[str] = None,
                  effective_lookahead: Optional[str] = None, info=None) -> O.Hyper:
     """Oracle hyper-parameters for what the library says it effectively runs (after fast-path downgrades)."""
-    h = {k: v for k, v in hyper.items() if k not in ("mode", "auto_sync")}
+    h = {k: v for k, v in hyper.items() if k not in ("mode", "auto_sync", "device_step")}
     if effective_nesterov is not None:
         h["nesterov"] = effective_nesterov
     if effective_lookahead is not None:
@@ -99,6 +99,12 @@ class GpuNovak:
         self.auto_sync = auto_sync
         self.la_k = int(self.hyper.get("la_k", 5))
         self._grad_arr = (C.c_void_p * max(len(self.numels), 1))()
+        # device-step mode: t lives in device memory and novak_step is told 0
+        self.device_step = bool(self.hyper.get("device_step", False))
+        self.counter = None
+        if self.device_step:
+            self.counter = torch.zeros(1, dtype=torch.int64, device=self.device)
+            N.check(N.novak_set_step_counter(self.handle, self.counter.data_ptr()), "novak_set_step_counter", self.handle)
         self.ema = None
         if info.auto_lr:
             self.ema = torch.zeros(2, dtype=torch.float64, device=self.device)
@@ -126,7 +132,7 @@ class GpuNovak:
     def step(self, t: int, grads: List[torch.Tensor], sync: bool = True) -> int:
         for i, g in enumerate(grads):
             self._grad_arr[i] = g.data_ptr() if g.numel() else None
-        rc = N.novak_step(self.handle, self._grad_arr, N.GRAD_DTYPE[self.grad_dtype], t, self.stream)
+        rc = N.novak_step(self.handle, self._grad_arr, N.GRAD_DTYPE[self.grad_dtype], 0 if self.device_step else t, self.stream)
         if rc != N.NOVAK_OK:
             return rc
         if sync and not self.auto_sync and self.eff_lookahead != "none" and t % self.la_k == 0:

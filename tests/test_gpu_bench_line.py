@@ -12,7 +12,8 @@ CONTRACT = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step
 
 @pytest.mark.parametrize("extra", [[], ["--moment-dtype", "bf16_m", "--no-extras"], ["--layer-adaptation", "--clip", "1.0", "--no-extras"],
                                    ["--layout", "separate"], ["--layout", "torch_one"], ["--layout", "torch_pool"], ["--layout", "separate_contiguous"], ["--separate-sync"], ["--use-gc", "--clip", "1.0", "--no-extras"],
-                                   ["--nesterov", "true", "--mode", "research", "--extrapolate", "--no-extras"]])
+                                   ["--nesterov", "true", "--mode", "research", "--extrapolate", "--no-extras"],
+                                   ["--device-step"], ["--device-step", "--graph-steps", "5"]])
 def test_bench_line(monkeypatch, capsys, extra):
     import bench
     # one in-process oracle run, no worker processes: nothing is spawned from a process that holds the GPU
@@ -35,7 +36,10 @@ def test_bench_line(monkeypatch, capsys, extra):
     k = d["kernels"][r["kernel"]]
     assert r["achieved"] == pytest.approx(cfg["params"] * k["bytes_per_param"] / (k["avg_ms"] * 1e-3) / 1e9)
     assert r["algorithmic_bytes_per_launch"] == cfg["params"] * k["bytes_per_param"]
-    assert sum(v["launches"] for n, v in d["kernels"].items() if n not in ("lookahead_sync", "nesterov_extrapolate")) == 10
+    if "--graph-steps" in extra:
+        assert d["kernels"]["graph_of_5_steps"]["launches"] == 2 and cfg["step_count"] == "device" and r["traffic"] is None
+    else:
+        assert sum(v["launches"] for n, v in d["kernels"].items() if n not in ("lookahead_sync", "nesterov_extrapolate")) == 10
     if "--extrapolate" in extra:
         assert cfg["nesterov"] == "true" and d["kernels"]["nesterov_extrapolate"]["launches"] == 10
         assert d["kernels"]["nesterov_extrapolate"]["bytes_per_param"] == 12.0
@@ -49,7 +53,9 @@ def test_bench_line(monkeypatch, capsys, extra):
         assert cfg["layout"] == "arena"
     else:
         assert cfg["layout"] == extra[1] and r["traffic"] is None        # counters were taken on the arena only
-    if not extra:
+    if "--device-step" in extra:
+        assert cfg["step_count"] == "device" and "other_layouts" not in d
+    elif not extra:
         # beside the headline: the layouts a PyTorch caller has, and the sync as its own kernel, from the same process
         o = d["other_layouts"]
         assert set(o) == {"torch_one_allocation_planned_layout", "torch_five_separate_allocations",
