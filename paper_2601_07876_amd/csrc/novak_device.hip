@@ -584,11 +584,11 @@ hipError_t enqueue_step(const LaunchCtx *cx, int grad_dtype, const StepPlan &pl,
 // The same in device-step mode: a one-lane prologue advances the caller's counter and writes the step's constants
 // and lookahead phase, then the kernels follow; which of them run does not depend on t.
 hipError_t enqueue_step_device(const LaunchCtx *cx, int grad_dtype, hipStream_t stream) {
-  if (cx->n_chunks == 0) return hipSuccess;
   hipError_t e;
   const uint32_t extra = cx->n_gc > 0 ? F_GC : 0u;
   hipLaunchKernelGGL(novak_prologue_kernel, dim3(1), dim3(64), 0, stream, cx->hp, extra, cx->d_counter, cx->d_step);
   if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (cx->n_chunks == 0) return hipSuccess;          // a list without elements: the step still counts
   if ((clipping(cx) || cx->n_gc > 0) && (e = launch_prepass(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
   launch_step_device(cx, grad_dtype, stream, tables_of(cx));
   if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -1083,11 +1083,11 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
   if (!device_step) plan_step(h->hp, step, &pl);
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (h->n_chunks > 0) {
+  if (h->n_chunks > 0 || device_step) {         // (a list without elements still counts its steps on the device)
     DeviceScope scope;
     NOVAK_HIP(h, scope.enter(h->device_id));
     // gradient pointers: upload only when the list changed since the previous step
-    if (!h->grads_uploaded || std::memcmp(h->last_grads.data(), grads, n * sizeof(void *)) != 0) {
+    if (h->n_chunks > 0 && (!h->grads_uploaded || std::memcmp(h->last_grads.data(), grads, n * sizeof(void *)) != 0)) {
       const int slot = h->ring_next;
       h->ring_next = (slot + 1) % novak_handle::kRing;
       if (h->ring_used[slot]) NOVAK_HIP(h, hipEventSynchronize(h->ring_ev[slot]));

@@ -104,6 +104,21 @@ def test_rules_of_the_mode():
     N.novak_destroy(h)
 
 
+def test_a_list_without_elements_still_counts_its_steps():
+    counter = torch.full((1,), 7, dtype=torch.int64, device="cuda:0")
+    for descs, grads in (([], []), ([N.novak_tensor_desc(0, 0, 0, 0, 0)], (C.c_void_p * 1)(0))):
+        rc, h = N.novak_create(N.make_hparams(device_step=True, auto_sync=True), descs, 0)
+        N.check(rc, "create")
+        try:
+            N.check(N.novak_set_step_counter(h, counter.data_ptr()), "counter", h)
+            before = int(counter.item())
+            for _ in range(3):
+                N.check(N.novak_step(h, grads, N.NOVAK_GRAD_F32, 0, torch.cuda.current_stream().cuda_stream), "step", h)
+            assert int(counter.item()) == before + 3
+        finally:
+            N.novak_destroy(h)
+
+
 @pytest.mark.parametrize("lookahead,k", [("memory_efficient", 5), ("none", 5), ("basic", 2)])
 def test_captured_step_advances_on_every_replay(lookahead, k):
     """One novak_step captured into a HIP graph (through torch's stream capture) and replayed 17 times; before every
