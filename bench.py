@@ -284,7 +284,7 @@ class Setup:
         elapsed = time.perf_counter() - t_begin
         expect = self.t + steps
         assert int(self.counter.item()) == expect, "the replays did not advance the device's step counter"
-        names = [la_variant(self.la_name, self.k, self.t + 1 + i, self.fused) + self.m_tag for i in range(g)]
+        names = [("scaled_" if self.scaled else "") + la_variant(self.la_name, self.k, self.t + 1 + i, self.fused) + self.m_tag for i in range(g)]
         self.t = expect
         bpp = sum(self.bytes_of(n) for n in names)
         ms = [a.elapsed_time(b) for a, b in ev]

@@ -122,8 +122,9 @@ typedef struct novak_hparams {
   int32_t moment_dtype;     /* NOVAK_MOMENT_*: element type of every tensor's exp_avg array */
   int32_t device_step;      /* 1: the step count t lives in DEVICE memory (novak_set_step_counter) and the scalar prologue runs
                                in a one-lane kernel in front of the step, so that a novak_step captured into a HIP graph
-                               advances by itself on every replay; novak_step's `step` argument must then be 0.  Single-pass
-                               step only; lookahead needs auto_sync = 1 (nobody on the host knows when a sync is due). */
+                               advances by itself on every replay; novak_step's `step` argument must then be 0.  Every
+                               option of the step is available; lookahead needs auto_sync = 1 (nobody on the host knows
+                               when a sync is due). */
 } novak_hparams;
 
 /* One parameter tensor.  All pointers are DEVICE pointers to contiguous fp32 arrays of `numel`

@@ -507,16 +507,24 @@ hipError_t launch_prepass(const LaunchCtx *h, int grad_dtype, hipStream_t s, con
   return hipGetLastError();
 }
 
-// The two-pass step: moments + norm partials, fixed-order reductions, scaled apply.
-hipError_t launch_scaled_step(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+// The two-pass step: moments + norm partials, fixed-order reductions, scaled apply.  `device_step`: constants and
+// lookahead phase are in h->d_step (`la` is then the phase with the most streams, for the residency, and `c` unused).
+template <typename MomS, typename MomV> void launch_moments_device(const LaunchCtx *, int, const Geometry &, hipStream_t, const Tables &);
+template <typename MomS, typename MomV> void launch_apply_device_la(const LaunchCtx *, const Geometry &, hipStream_t, const Tables &);
+hipError_t launch_scaled_step(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c, bool device_step = false) {
   const novak_hparams &hp = h->hp;
   const bool bf16_m = hp.moment_dtype == NOVAK_MOMENT_BF16_M;
   const bool bf16_g = grad_dtype == NOVAK_GRAD_BF16;
   // pass 1: theta, g, m, v read; m, v written
   const Geometry g1 = geometry_of(h, kScaledSub, kScaledBlock, 3 + (bf16_g ? 0 : 1) + (bf16_m ? 0 : 2), (bf16_g ? 1 : 0) + (bf16_m ? 2 : 0), kTwoPassBudget);
   const bool nt = h->nontemporal != 0;
-  if (bf16_m) launch_moments<unsigned short, u16x4>(h, grad_dtype, g1, s, tb, c);
-  else launch_moments<float, f32x4>(h, grad_dtype, g1, s, tb, c);
+  if (device_step) {
+    if (bf16_m) launch_moments_device<unsigned short, u16x4>(h, grad_dtype, g1, s, tb);
+    else launch_moments_device<float, f32x4>(h, grad_dtype, g1, s, tb);
+  } else {
+    if (bf16_m) launch_moments<unsigned short, u16x4>(h, grad_dtype, g1, s, tb, c);
+    else launch_moments<float, f32x4>(h, grad_dtype, g1, s, tb, c);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ScaleParams sp;
@@ -539,7 +547,10 @@ hipError_t launch_scaled_step(const LaunchCtx *h, int grad_dtype, int la, hipStr
   if (la_reads(la)) s2 += 1;
   if (la_writes(la)) s2 += 1;
   const Geometry g2 = geometry_of(h, kScaledSub, kScaledBlock, s2, bf16_m ? 1 : 0, kTwoPassBudget);
-  if (bf16_m) {
+  if (device_step) {
+    if (bf16_m) launch_apply_device_la<unsigned short, u16x4>(h, g2, s, tb);
+    else launch_apply_device_la<float, f32x4>(h, g2, s, tb);
+  } else if (bf16_m) {
     if (nt) launch_apply<true, unsigned short, u16x4>(la, g2, s, tb, c, h->d_scale);
     else launch_apply<false, unsigned short, u16x4>(la, g2, s, tb, c, h->d_scale);
   } else {
@@ -547,6 +558,36 @@ hipError_t launch_scaled_step(const LaunchCtx *h, int grad_dtype, int la, hipStr
     else launch_apply<false, float, f32x4>(la, g2, s, tb, c, h->d_scale);
   }
   return hipGetLastError();
+}
+
+// The two-pass step in device-step mode: constants and lookahead phase come from the record the prologue kernel wrote.
+template <int LA, typename MomS, typename MomV>
+void launch_apply_device(const LaunchCtx *h, const Geometry &gm, hipStream_t s, const Tables &tb) {
+  const dim3 grid(gm.grid), block(kScaledBlock);
+  if (h->nontemporal) hipLaunchKernelGGL((novak_apply_device_kernel<LA, true, MomS, MomV>), grid, block, gm.lds, s, tb, h->d_step, gm.sub_shift, h->d_scale);
+  else hipLaunchKernelGGL((novak_apply_device_kernel<LA, false, MomS, MomV>), grid, block, gm.lds, s, tb, h->d_step, gm.sub_shift, h->d_scale);
+}
+
+template <typename MomS, typename MomV>
+void launch_apply_device_la(const LaunchCtx *h, const Geometry &gm, hipStream_t s, const Tables &tb) {
+  switch (h->hp.lookahead_mode) {
+    case NOVAK_LOOKAHEAD_MEMORY_EFFICIENT: launch_apply_device<LA_RUNTIME_ME, MomS, MomV>(h, gm, s, tb); break;
+    case NOVAK_LOOKAHEAD_BASIC: launch_apply_device<LA_RUNTIME_BASIC, MomS, MomV>(h, gm, s, tb); break;
+    default: launch_apply_device<LA_OFF, MomS, MomV>(h, gm, s, tb); break;
+  }
+}
+
+template <typename MomS, typename MomV>
+void launch_moments_device(const LaunchCtx *h, int grad_dtype, const Geometry &g1, hipStream_t s, const Tables &tb) {
+  const dim3 grid1(g1.grid), block(kScaledBlock);
+  const bool nt = h->nontemporal != 0;
+  if (grad_dtype == NOVAK_GRAD_BF16) {
+    if (nt) hipLaunchKernelGGL((novak_moments_device_kernel<unsigned short, u16x4, true, MomS, MomV>), grid1, block, g1.lds, s, tb, h->d_step, g1.sub_shift, h->d_partials);
+    else hipLaunchKernelGGL((novak_moments_device_kernel<unsigned short, u16x4, false, MomS, MomV>), grid1, block, g1.lds, s, tb, h->d_step, g1.sub_shift, h->d_partials);
+  } else {
+    if (nt) hipLaunchKernelGGL((novak_moments_device_kernel<float, f32x4, true, MomS, MomV>), grid1, block, g1.lds, s, tb, h->d_step, g1.sub_shift, h->d_partials);
+    else hipLaunchKernelGGL((novak_moments_device_kernel<float, f32x4, false, MomS, MomV>), grid1, block, g1.lds, s, tb, h->d_step, g1.sub_shift, h->d_partials);
+  }
 }
 
 hipError_t launch_sync(const LaunchCtx *h, hipStream_t s) {
@@ -590,8 +631,14 @@ hipError_t enqueue_step_device(const LaunchCtx *cx, int grad_dtype, hipStream_t 
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (cx->n_chunks == 0) return hipSuccess;          // a list without elements: the step still counts
   if ((clipping(cx) || cx->n_gc > 0) && (e = launch_prepass(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
-  launch_step_device(cx, grad_dtype, stream, tables_of(cx));
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (two_pass(cx)) {
+    // the host does not know the step's lookahead phase: residency for the phase with the most streams
+    const int la = cx->hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT ? LA_MID : LA_OFF;
+    if ((e = launch_scaled_step(cx, grad_dtype, la, stream, tables_of(cx), Consts(), true)) != hipSuccess) return e;
+  } else {
+    launch_step_device(cx, grad_dtype, stream, tables_of(cx));
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   // a window of one step: the sync follows every step as its own kernel
   if (cx->hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT && cx->hp.la_k == 1) return launch_sync(cx, stream);
   return hipSuccess;
@@ -658,8 +705,6 @@ static int create_impl(novak_handle **out, const novak_hparams *hp, const novak_
   int rc = novak_validate_hparams(hp, &eff, &warn);
   if (rc != NOVAK_OK) return fail(nullptr, rc, "hyper-parameters rejected (section 5.8 validation rules)");
   if (eff.device_step) {
-    if (eff.layer_adaptation || eff.auto_lr)
-      return fail(nullptr, NOVAK_ERR_NOT_IMPLEMENTED, "device_step covers the single-pass step; layer_adaptation / auto_lr need the host-step mode");
     if (eff.lookahead_mode != NOVAK_LOOKAHEAD_NONE && !eff.auto_sync)
       return fail(nullptr, NOVAK_ERR_INVALID_ARG, "device_step with lookahead needs auto_sync = 1 (the host does not know when a sync is due)");
   }

@@ -605,8 +605,9 @@ __device__ __forceinline__ double wave_sum(double x) {
   return x;
 }
 
-template <typename GradS, typename GradV, bool NT, typename MomS = float, typename MomV = f32x4>
-__global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, Consts c, int sub_shift, NormPartial *partials) {
+// `c_arg` holds the step's constants, or (DEV, device-step mode) `ds` points to them in device memory.
+template <typename GradS, typename GradV, bool NT, typename MomS, typename MomV, bool DEV>
+__device__ __forceinline__ void moments_body(const Tables &tb, const Consts &c_arg, int sub_shift, NormPartial *partials, const DeviceStep *ds) {
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
   const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kScaledSub;
   if (start >= ch.len) return;
@@ -614,6 +615,9 @@ __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, 
   const int64_t off = ch.offset + start;
   const TensorPtrs tp = tb.tensors[ch.tensor];
   const void *const g_base = tb.grad[ch.tensor];
+  Consts c_dev;
+  if constexpr (DEV) c_dev = ds->c;
+  const Consts &c = DEV ? c_dev : c_arg;
   const float gs = (c.flags & F_CLIP) ? *tb.gscale : 1.0f;
   GcInfo gi;
   gi.cols = 0;
@@ -681,6 +685,15 @@ __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, 
     p.theta2 = s_th; p.u2 = s_u; p.g2 = s_g; p.pad = 0.0f;
     partials[blockIdx.x] = p;
   }
+}
+
+template <typename GradS, typename GradV, bool NT, typename MomS = float, typename MomV = f32x4>
+__global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, Consts c, int sub_shift, NormPartial *partials) {
+  moments_body<GradS, GradV, NT, MomS, MomV, false>(tb, c, sub_shift, partials, nullptr);
+}
+template <typename GradS, typename GradV, bool NT, typename MomS = float, typename MomV = f32x4>
+__global__ __launch_bounds__(kScaledBlock) void novak_moments_device_kernel(Tables tb, const DeviceStep *ds, int sub_shift, NormPartial *partials) {
+  moments_body<GradS, GradV, NT, MomS, MomV, true>(tb, Consts(), sub_shift, partials, ds);
 }
 
 // one wave per chunk: sums the chunk's per-wave partials in a fixed order
@@ -1051,14 +1064,25 @@ __global__ __launch_bounds__(64) void novak_auto_lr_kernel(int n_tensors, const 
   }
 }
 
-template <int LA, bool NT, typename MomS = float, typename MomV = f32x4>
-__global__ __launch_bounds__(kScaledBlock) void novak_apply_kernel(Tables tb, Consts c, int sub_shift, const float *scale) {
+// LA is a phase, or (device-step mode) LA_RUNTIME_ME / LA_RUNTIME_BASIC with the phase in `ds`, as in step_body.
+template <int LA, bool NT, typename MomS, typename MomV, bool DEV>
+__device__ __forceinline__ void apply_body(const Tables &tb, const Consts &c_arg, int sub_shift, const float *scale, const DeviceStep *ds) {
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
   const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kScaledSub;
   if (start >= ch.len) return;
   const int n = min(kScaledSub, ch.len - start);
   const int64_t off = ch.offset + start;
   const TensorPtrs tp = tb.tensors[ch.tensor];
+  Consts c_dev;
+  int la_rt = LA_OFF;
+  if constexpr (DEV) {
+    const DeviceStep d = *ds;
+    c_dev = d.c;
+    la_rt = d.la;
+  }
+  const Consts &c = DEV ? c_dev : c_arg;
+  const int phase = la_runtime(LA) ? la_rt : LA;
+  const bool reads = LA == LA_RUNTIME_ME ? true : la_reads(phase), writes = la_writes(phase);
   const float step = c.step_size * scale[ch.tensor];                    // Eq. 24a
   float *__restrict__ th_p = tp.param + off;
   const MomS *__restrict__ m_p = reinterpret_cast<const MomS *>(tp.m) + off;
@@ -1076,29 +1100,38 @@ __global__ __launch_bounds__(kScaledBlock) void novak_apply_kernel(Tables tb, Co
     f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
     const int i = threadIdx.x;
     if (i < nvec) {
-      f32x4 th = ld<NT>(th4 + i), la;
+      f32x4 th = ld<NT>(th4 + i), la = {0.0f, 0.0f, 0.0f, 0.0f};
       const f32x4 m = mom_to_f32<MomV>(ld<NT>(m4 + i)), v = ld<NT>(v4 + i);
-      if (la_reads(LA)) la = ld<NT>(la4 + i);
+      if (reads) la = ld<NT>(la4 + i);
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         float th_k = th[k], la_k = la[k], m_hat;
         const float u = direction(m[k], v[k], c, m_hat);
-        apply<LA>(th_k, u, m_hat, la_k, c, step);
+        apply<LA>(th_k, u, m_hat, la_k, c, step, la_rt);
         th[k] = th_k; la[k] = la_k;
       }
       st<NT>(th4 + i, th);
-      if (la_writes(LA)) st<NT>(la4 + i, la);
+      if (writes) st<NT>(la4 + i, la);
     }
     done = nvec << 2;
   }
   for (int i = done + threadIdx.x; i < n; i += kScaledBlock) {
     float th = th_p[i], la = 0.0f, m_hat;
-    if (la_reads(LA)) la = la_p[i];
+    if (reads) la = la_p[i];
     const float u = direction(load_mom<MomS>(m_p + i), v_p[i], c, m_hat);
-    apply<LA>(th, u, m_hat, la, c, step);
+    apply<LA>(th, u, m_hat, la, c, step, la_rt);
     th_p[i] = th;
-    if (la_writes(LA)) la_p[i] = la;
+    if (writes) la_p[i] = la;
   }
+}
+
+template <int LA, bool NT, typename MomS = float, typename MomV = f32x4>
+__global__ __launch_bounds__(kScaledBlock) void novak_apply_kernel(Tables tb, Consts c, int sub_shift, const float *scale) {
+  apply_body<LA, NT, MomS, MomV, false>(tb, c, sub_shift, scale, nullptr);
+}
+template <int LA, bool NT, typename MomS = float, typename MomV = f32x4>
+__global__ __launch_bounds__(kScaledBlock) void novak_apply_device_kernel(Tables tb, const DeviceStep *ds, int sub_shift, const float *scale) {
+  apply_body<LA, NT, MomS, MomV, true>(tb, Consts(), sub_shift, scale, ds);
 }
 
 // ------------------------------------------------------------------------------------------------

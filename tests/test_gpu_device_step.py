@@ -24,6 +24,11 @@ pytestmark = pytest.mark.gpu
     ("approx", "memory_efficient", 4, "bf16", {"moment_dtype": "bf16_m"}),
     ("approx", "memory_efficient", 5, "f32", {"adaptive_beta": True, "clip_threshold": 0.5, "sparse_threshold": 0.1}),
     ("approx", "memory_efficient", 5, "f32", {"use_gc": True, "clip_threshold": 0.7}),
+    # the two-pass step (trust ratio, automatic rate): research mode
+    ("approx", "memory_efficient", 5, "f32", {"mode": "research", "layer_adaptation": True, "auto_lr": True}),
+    ("classical", "basic", 3, "bf16", {"mode": "research", "layer_adaptation": True, "clip_threshold": 0.6}),
+    ("none", "none", 5, "f32", {"mode": "research", "auto_lr": True, "moment_dtype": "bf16_m"}),
+    ("approx", "memory_efficient", 1, "f32", {"mode": "research", "layer_adaptation": True, "auto_lr": True, "use_gc": True}),
 ])
 def test_ragged_against_the_oracle(nesterov, lookahead, k, grad_dtype, extra):
     wl = W.get_workload("ragged")
@@ -86,7 +91,6 @@ def test_rules_of_the_mode():
     d = N.novak_tensor_desc(4096, 8192, 12288, 16384, 64)
     assert N.novak_create(N.make_hparams(device_step=True, auto_sync=False), [d])[0] == N.NOVAK_ERR_INVALID_ARG
     assert "auto_sync" in N.novak_last_error()
-    assert N.novak_create(N.make_hparams(device_step=True, auto_sync=True, mode="research", layer_adaptation=True), [d])[0] == N.NOVAK_ERR_NOT_IMPLEMENTED
     t = torch.zeros(4, 64, device="cuda:0")
     real = N.novak_tensor_desc(t[0].data_ptr(), t[1].data_ptr(), t[2].data_ptr(), t[3].data_ptr(), 64)
     rc, h = N.novak_create(N.make_hparams(device_step=True, auto_sync=True), [real], 0)
@@ -119,14 +123,15 @@ def test_a_list_without_elements_still_counts_its_steps():
             N.novak_destroy(h)
 
 
-@pytest.mark.parametrize("lookahead,k", [("memory_efficient", 5), ("none", 5), ("basic", 2)])
-def test_captured_step_advances_on_every_replay(lookahead, k):
+@pytest.mark.parametrize("lookahead,k,extra", [("memory_efficient", 5, {}), ("none", 5, {}), ("basic", 2, {}),
+                                               ("memory_efficient", 4, {"mode": "research", "layer_adaptation": True, "auto_lr": True})])
+def test_captured_step_advances_on_every_replay(lookahead, k, extra):
     """One novak_step captured into a HIP graph (through torch's stream capture) and replayed 17 times; before every
     replay new gradients are written into the captured buffers by ordinary eager work, after it the program
     synchronises and compares the whole state with an eager host-step twin that took the same steps."""
     wl = W.get_workload("ragged")
     numels = wl.numels
-    hyper = dict(wl.hyper, lookahead=lookahead, la_k=k, clip_threshold=0.8)
+    hyper = dict(wl.hyper, lookahead=lookahead, la_k=k, clip_threshold=0.8, **extra)
     theta0 = W.host_params(numels, 7)
     cap = H.GpuNovak(numels, dict(hyper, device_step=True), "f32", theta0, auto_sync=True)
     twin = H.GpuNovak(numels, hyper, "f32", theta0, auto_sync=True)
