@@ -321,10 +321,8 @@ int novak_set_auto_lr_state(novak_handle *h, void *ema);
  * Required before the first novak_step in that mode (else NOVAK_ERR_STATE there); NOVAK_ERR_STATE on a handle in host-step
  * mode.  To capture a step into a HIP graph: take one step eagerly first (it uploads the gradient-pointer list, which a capture
  * cannot), keep the gradient buffers and the list fixed, then capture novak_step on the capture stream; each replay is one
- * more step.  In this mode the handle does not track t: novak_get_info reports last_step = 0, the residency of the step
- * kernel is chosen for the lookahead phase with the most streams, and with the memory-efficient lookahead the kernel loads
- * the running-blend buffer on every step (the first step of a window does not use it: 4 bytes per parameter more than the
- * host-step kernel reads there). */
+ * more step.  In this mode the handle does not track t: novak_get_info reports last_step = 0, and the residency of the step
+ * kernel is chosen for the lookahead phase with the most streams. */
 int novak_set_step_counter(novak_handle *h, void *counter);
 
 /* Monitoring: copies lambda_trust * alpha_auto of the last two-pass step, one float per tensor, to HOST

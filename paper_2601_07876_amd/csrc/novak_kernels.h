@@ -39,9 +39,8 @@ enum : int {
   LA_LAST_FUSED = 3,   // k-th step, sync fused:   theta_out = A + c1*theta_new         (A read)
   LA_BASIC_FUSED = 4,  // k-th step, basic mode:   S = c1*theta_new + c0*S; theta_out=S (S read, written)
   // template arguments only (device-step mode): the phase is a run-time, wave-uniform value
-  LA_RUNTIME_ME = 5,   // one of LA_FIRST / LA_MID / LA_LAST_FUSED; the buffer is always loaded (a load behind a branch is
-                       // issued late and cost 9-13 %; the first step of a window then reads 4 bytes it does not need)
-  LA_RUNTIME_BASIC = 6 // LA_OFF or LA_BASIC_FUSED; the slow weights are loaded only at the sync (one step in k)
+  LA_RUNTIME_ME = 5,   // one of LA_FIRST / LA_MID / LA_LAST_FUSED
+  LA_RUNTIME_BASIC = 6 // LA_OFF or LA_BASIC_FUSED
 };
 constexpr bool la_runtime(int la) { return la >= LA_RUNTIME_ME; }
 
@@ -314,7 +313,7 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
   const Consts &c = DEV ? c_dev : c_arg;
   // which lookahead stream this step reads / writes: compiled in, or a wave-uniform run-time value
   const int phase = la_runtime(LA) ? la_rt : LA;
-  const bool reads = LA == LA_RUNTIME_ME ? true : la_reads(phase), writes = la_writes(phase);
+  const bool reads = la_reads(phase), writes = la_writes(phase);
   const float gs = (c.flags & F_CLIP) ? *tb.gscale : 1.0f;
   GcInfo gi;
   gi.cols = 0;
@@ -338,7 +337,11 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
     f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
     const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
     if (n == SUB) {
-      // full sub-block: every load is issued before any arithmetic
+      // full sub-block: every load is issued before any arithmetic.  With a run-time phase the lookahead load is
+      // issued whatever the phase (behind a uniform branch it was issued late: -9 ... -13 %): from the buffer when
+      // the phase reads it, else from theta's own address, whose line is on its way already.
+      const f32x4 *la_src = (la_runtime(LA) && !reads) ? th4 : la4;
+      const bool load_la = la_runtime(LA) ? true : reads;
       f32x4 th[UN], v[UN], la[UN];
       MomV m[UN];
       GradV g[UN];
@@ -349,7 +352,7 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
         g[u] = ld<NT>(g4 + j);
         m[u] = ld<NT>(m4 + j);
         v[u] = ld<NT>(v4 + j);
-        if (reads) la[u] = ld<NT>(la4 + j);
+        if (load_la) la[u] = ld<NT>(la_src + j);
       }
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
@@ -1082,7 +1085,7 @@ __device__ __forceinline__ void apply_body(const Tables &tb, const Consts &c_arg
   }
   const Consts &c = DEV ? c_dev : c_arg;
   const int phase = la_runtime(LA) ? la_rt : LA;
-  const bool reads = LA == LA_RUNTIME_ME ? true : la_reads(phase), writes = la_writes(phase);
+  const bool reads = la_reads(phase), writes = la_writes(phase);
   const float step = c.step_size * scale[ch.tensor];                    // Eq. 24a
   float *__restrict__ th_p = tp.param + off;
   const MomS *__restrict__ m_p = reinterpret_cast<const MomS *>(tp.m) + off;
@@ -1100,9 +1103,11 @@ __device__ __forceinline__ void apply_body(const Tables &tb, const Consts &c_arg
     f32x4 *la4 = reinterpret_cast<f32x4 *>(la_p);
     const int i = threadIdx.x;
     if (i < nvec) {
+      // (run-time phase: the lookahead load is issued whatever the phase, from theta's address when unused - see step_body)
+      const f32x4 *la_src = (la_runtime(LA) && !reads) ? th4 : la4;
       f32x4 th = ld<NT>(th4 + i), la = {0.0f, 0.0f, 0.0f, 0.0f};
       const f32x4 m = mom_to_f32<MomV>(ld<NT>(m4 + i)), v = ld<NT>(v4 + i);
-      if (reads) la = ld<NT>(la4 + i);
+      if (la_runtime(LA) || reads) la = ld<NT>(la_src + i);
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         float th_k = th[k], la_k = la[k], m_hat;
