@@ -200,6 +200,7 @@ def step_scalars(h: Hyper, t: int) -> StepScalars:
 class StepTrace:
     """Intermediate values of a tensor's most recent step, kept for comparisons (they change no result)."""
     g_processed: np.ndarray      # the gradient after clipping, centralization and coupled decay, before Eq. 13
+    g_terms: np.ndarray          # |scaled g| + |row mean| + lambda |theta|: magnitudes of the terms g_processed is made of
     g_tilde: np.ndarray          # the gradient that fed the moments (Eq. 13 applied when in force)
     m_exact: np.ndarray          # Eq. 1 in double, before any storage rounding
     u_base: np.ndarray           # base direction of Eq. 17 (or m_hat in the momentum fallback), before Eq. 27 / Eq. 16
@@ -285,12 +286,16 @@ def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float 
     m_prev = st.m.astype(np.float64)
     v_prev = st.v.astype(np.float64)
     g = np.asarray(grad).reshape(-1).astype(np.float64) * g_scale   # clipping comes first (section 7.3)
+    g_terms = np.abs(g)
 
     if h.use_gc and st.rows >= 1:
         g2d = g.reshape(st.rows, -1)
-        g = (g2d - g2d.mean(axis=1, keepdims=True)).reshape(-1)    # Eq. 26
+        row_mean = g2d.mean(axis=1, keepdims=True)
+        g = (g2d - row_mean).reshape(-1)                    # Eq. 26
+        g_terms = g_terms + np.broadcast_to(np.abs(row_mean), g2d.shape).reshape(-1)
     if (not h.decoupled_decay) and h.weight_decay != 0.0:
         g = g + h.weight_decay * theta                      # coupled L2 (reading; see header)
+        g_terms = g_terms + h.weight_decay * np.abs(theta)
     g_processed = g
     if effective_nesterov(h, t) == "approx":
         g = g + h.beta_n * (g - m_prev)                     # Eq. 13; replaces g for both moments
@@ -320,7 +325,7 @@ def step(st: TensorState, grad: np.ndarray, t: int, h: Hyper, alpha_auto: float 
     st.theta = theta.astype(dt)
     st.m = m.astype(dt)
     st.v = v.astype(dt)
-    st.trace = StepTrace(g_processed, g, m_exact, u_base, lam_trust * alpha_auto)
+    st.trace = StepTrace(g_processed, g_terms, g, m_exact, u_base, lam_trust * alpha_auto)
     if h.lookahead != "none":
         st.window.append(st.theta.copy())
     return s

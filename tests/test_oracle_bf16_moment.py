@@ -144,7 +144,7 @@ def test_rounding_range_is_one_value_away_from_midpoints_and_two_near_them():
     from tests.harness import bf16_rounding_range
     z = np.zeros(3)
     # m_exact = 1 + 2^-8 (a midpoint), 1 + 2^-8 + 2^-20 (2^-20 above it: outside fp32 error), 1.0 (a bfloat16 value)
-    tr = O.StepTrace(z, z, np.array([1.0 + 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0]), z, 1.0)
+    tr = O.StepTrace(z, z, z, np.array([1.0 + 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0]), z, 1.0)
     lo, hi = bf16_rounding_range(tr, z, 0.9)
     assert (lo[0], hi[0]) == (1.0, 1.0 + 2.0 ** -7)
     assert lo[1] == hi[1] == 1.0 + 2.0 ** -7
