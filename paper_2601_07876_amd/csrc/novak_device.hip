@@ -237,10 +237,11 @@ int build_chunk_table_unguarded(novak_handle *h) {
     std::vector<float> ones(nt, 1.0f);
     NOVAK_HIP(h, hipMemcpy(h->d_scale, ones.data(), nt * sizeof(float), hipMemcpyHostToDevice));
     if (n > 0) {
-      // one partial per wave of the finest reduction pass (256 elements per wave in the two-pass step)
-      const size_t waves = static_cast<size_t>(n) * static_cast<size_t>(h->chunk_elems / kScaledSub);
-      NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_partials), waves * sizeof(NormPartial)));
       NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_chunk_sums), static_cast<size_t>(n) * sizeof(NormSums)));
+      if (two_pass(h)) {   // one partial per wave of pass 1 (256 elements per wave); the pre-pass writes chunk sums itself
+        const size_t waves = static_cast<size_t>(n) * static_cast<size_t>(h->chunk_elems / kScaledSub);
+        NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_partials), waves * sizeof(NormPartial)));
+      }
     }
   }
   h->broken = false;
@@ -458,18 +459,18 @@ void launch_moments(const LaunchCtx *h, int grad_dtype, const Geometry &g1, hipS
   }
 }
 
-// Gradient pre-pass: one read of the gradients gives the norm partials (clipping) and the row sums
+// Gradient pre-pass: one read of the gradients gives each chunk's sum of squares (clipping) and the row sums
 // (centralization); then the norm goes chunk sums -> tensor sums -> global factor in d_gscale, and the
 // rows that span several waves get their means from the waves' partial sums.
 // Residency: a read-only stream peaks at 6 resident waves of 16 KB per compute unit (10 - 12 waves of
 // 8 KB with bf16 gradients); the LDS that bounds it doubles as the centralization's staging buffer.
 template <typename GradS, typename GradV, bool NT>
 void launch_prepass_kernel(bool norm, bool gc, const dim3 &grid, unsigned lds, hipStream_t s, const Tables &tb, int sub_shift,
-                           NormPartial *partials, RowPartial *row_partials) {
+                           NormSums *chunk_sums, RowPartial *row_partials) {
   const dim3 block(kScaledBlock);
-  if (norm && gc) hipLaunchKernelGGL((novak_prepass_kernel<GradS, GradV, NT, true, true>), grid, block, lds, s, tb, sub_shift, partials, row_partials);
-  else if (norm) hipLaunchKernelGGL((novak_prepass_kernel<GradS, GradV, NT, true, false>), grid, block, lds, s, tb, sub_shift, partials, row_partials);
-  else hipLaunchKernelGGL((novak_prepass_kernel<GradS, GradV, NT, false, true>), grid, block, lds, s, tb, sub_shift, partials, row_partials);
+  if (norm && gc) hipLaunchKernelGGL((novak_prepass_kernel<GradS, GradV, NT, true, true>), grid, block, lds, s, tb, sub_shift, chunk_sums, row_partials);
+  else if (norm) hipLaunchKernelGGL((novak_prepass_kernel<GradS, GradV, NT, true, false>), grid, block, lds, s, tb, sub_shift, chunk_sums, row_partials);
+  else hipLaunchKernelGGL((novak_prepass_kernel<GradS, GradV, NT, false, true>), grid, block, lds, s, tb, sub_shift, chunk_sums, row_partials);
 }
 
 hipError_t launch_prepass(const LaunchCtx *h, int grad_dtype, hipStream_t s, const Tables &tb) {
@@ -485,11 +486,11 @@ hipError_t launch_prepass(const LaunchCtx *h, int grad_dtype, hipStream_t s, con
   const dim3 grid(g0.grid);
   const bool nt = h->nontemporal != 0;
   if (bf16_g) {
-    if (nt) launch_prepass_kernel<unsigned short, u16x4, true>(norm, gc, grid, lds, s, tb, g0.sub_shift, h->d_partials, h->d_row_partials);
-    else launch_prepass_kernel<unsigned short, u16x4, false>(norm, gc, grid, lds, s, tb, g0.sub_shift, h->d_partials, h->d_row_partials);
+    if (nt) launch_prepass_kernel<unsigned short, u16x4, true>(norm, gc, grid, lds, s, tb, g0.sub_shift, h->d_chunk_sums, h->d_row_partials);
+    else launch_prepass_kernel<unsigned short, u16x4, false>(norm, gc, grid, lds, s, tb, g0.sub_shift, h->d_chunk_sums, h->d_row_partials);
   } else {
-    if (nt) launch_prepass_kernel<float, f32x4, true>(norm, gc, grid, lds, s, tb, g0.sub_shift, h->d_partials, h->d_row_partials);
-    else launch_prepass_kernel<float, f32x4, false>(norm, gc, grid, lds, s, tb, g0.sub_shift, h->d_partials, h->d_row_partials);
+    if (nt) launch_prepass_kernel<float, f32x4, true>(norm, gc, grid, lds, s, tb, g0.sub_shift, h->d_chunk_sums, h->d_row_partials);
+    else launch_prepass_kernel<float, f32x4, false>(norm, gc, grid, lds, s, tb, g0.sub_shift, h->d_chunk_sums, h->d_row_partials);
   }
   if (gc)
     hipLaunchKernelGGL(novak_rowfinal_kernel, dim3(static_cast<unsigned>((h->total_rows + 63) / 64)), dim3(64), 0, s, h->d_gc_tensor, h->d_row_first,
@@ -498,8 +499,6 @@ hipError_t launch_prepass(const LaunchCtx *h, int grad_dtype, hipStream_t s, con
     ScaleParams sp;
     std::memset(&sp, 0, sizeof(sp));
     const int nt_count = h->n_tensors;
-    hipLaunchKernelGGL(novak_reduce_chunks_kernel, dim3(static_cast<unsigned>(h->n_chunks)), dim3(64), 0, s, h->d_chunks, g0.sub_shift,
-                       kPreSub, h->d_partials, h->d_chunk_sums);
     hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(kTensorReduceBlock), 0, s, h->d_first_chunk, h->d_chunk_sums,
                        h->d_tensor_sums, h->d_scale, sp);
     hipLaunchKernelGGL(novak_clip_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, static_cast<float>(h->hp.clip_threshold), h->d_gscale);
@@ -1169,7 +1168,7 @@ int novak_lookahead_sync(novak_handle *h, void *hip_stream) {
 // Carves the static scratch array into the regions one call needs; false if they do not fit.
 namespace {
 struct StaticLayout {
-  size_t chunks, ptrs, first_chunk, tensor_sums, scale, gscale, chunk_sums, partials, end;
+  size_t chunks, ptrs, first_chunk, tensor_sums, scale, gscale, chunk_sums, end;
 };
 size_t align256(size_t x) { return (x + 255u) & ~size_t{255u}; }
 StaticLayout static_layout(size_t n_tensors, size_t n_chunks, bool clip) {
@@ -1178,13 +1177,12 @@ StaticLayout static_layout(size_t n_tensors, size_t n_chunks, bool clip) {
   L.chunks = o;       o = align256(o + n_chunks * sizeof(novak_chunk));
   L.ptrs = o;         o = align256(o + n_tensors * (sizeof(TensorPtrs) + sizeof(void *)));
   L.first_chunk = o;  o = align256(o + (n_tensors + 1) * sizeof(int));
-  L.tensor_sums = L.scale = L.gscale = L.chunk_sums = L.partials = o;
+  L.tensor_sums = L.scale = L.gscale = L.chunk_sums = o;
   if (clip) {
     L.tensor_sums = o; o = align256(o + n_tensors * sizeof(NormSums));
     L.scale = o;       o = align256(o + n_tensors * sizeof(float));
     L.gscale = o;      o = align256(o + sizeof(float));
     L.chunk_sums = o;  o = align256(o + n_chunks * sizeof(NormSums));
-    L.partials = o;    o = align256(o + n_chunks * (NOVAK_CHUNK_DEFAULT / kPreSub) * sizeof(NormPartial));
   }
   L.end = o;
   return L;
@@ -1243,7 +1241,6 @@ static int step_static_impl(const novak_hparams *hp, const novak_tensor_desc *te
     cx.d_scale = reinterpret_cast<float *>(base + L.scale);
     cx.d_gscale = reinterpret_cast<float *>(base + L.gscale);
     cx.d_chunk_sums = reinterpret_cast<NormSums *>(base + L.chunk_sums);
-    cx.d_partials = reinterpret_cast<NormPartial *>(base + L.partials);
   }
   // tables: written by a kernel from its arguments, kFillBatch tensors per launch, in stream order before the step
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);

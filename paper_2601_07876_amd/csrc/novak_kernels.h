@@ -241,15 +241,21 @@ __device__ __forceinline__ void update_one(float &th, float g, float &m, float &
   apply<LA>(th, u, m_hat, la, c, c.step_size, la_rt);
 }
 
+// Vector loads and stores of tensor data.  Every tensor pointer is device (global) memory, which the compiler cannot
+// know of a pointer it read from a table: said here, so that it emits global_load / global_store (results return in
+// issue order, and a wait can name how many later loads may stay in flight) instead of flat accesses.
+#define NOVAK_GLOBAL __attribute__((address_space(1)))
 template <bool NT, typename T>
 __device__ __forceinline__ T ld(const T *p) {
-  if (NT) return __builtin_nontemporal_load(p);
-  return *p;
+  const NOVAK_GLOBAL T *q = (const NOVAK_GLOBAL T *)p;
+  if (NT) return __builtin_nontemporal_load(q);
+  return *q;
 }
 template <bool NT, typename T>
 __device__ __forceinline__ void st(T *p, T x) {
-  if (NT) __builtin_nontemporal_store(x, p);
-  else *p = x;
+  NOVAK_GLOBAL T *q = (NOVAK_GLOBAL T *)p;
+  if (NT) __builtin_nontemporal_store(x, q);
+  else *q = x;
 }
 
 template <typename GradV>
@@ -726,8 +732,9 @@ __global__ __launch_bounds__(64) void novak_reduce_chunks_kernel(const novak_chu
 //     128-bit loads per lane in flight: a read-only stream needs about 100 KB outstanding per compute unit,
 //     and 16 KB per wave at a residency of 6 waves measured best on MI355X (7.35 TB/s against 6.8 TB/s for
 //     4 KB per wave).  The next span's loads are issued before the current span is reduced.
-//   * NORM: one partial sum of squares per span; the chunk and tensor reductions below are shared with
-//     the two-pass step, then novak_clip_kernel turns the norm into the factor min(1, c_clip/||g||).
+//   * NORM: a sum of squares per span (fp32), added up in double over the chunk's spans in order: the wave writes
+//     its chunk's sum itself; the tensor reduction is shared with the two-pass step, then novak_clip_kernel
+//     turns the norm into the factor min(1, c_clip/||g||).
 //   * GC: every row piece that lies in a span is summed in double and in a fixed order - in registers when
 //     rows are made of whole 256-element pieces, else from a copy of the span parked in LDS.  Rows that lie entirely inside the span get their mean written here; a row
 //     that sticks out at the front ("head") or at the back ("tail") leaves a partial sum, and
@@ -798,19 +805,15 @@ struct PreChunk {
   int len;
   bool gc;                 // this tensor is centralized
   GcInfo gi;
-  NormPartial *partials;   // one per span of this chunk
   RowPartial *row_partials;
 };
 
+// Adds a span's sum of squares to the wave's running sum for its chunk (meaningful in lane 63 only; the spans of
+// a chunk are taken in order by one wave, so the chunk's sum has a fixed order of additions).
 template <bool NORM>
-__device__ __forceinline__ void emit_norm(const float (&s_g)[4], NormPartial *out) {
+__device__ __forceinline__ void add_norm(const float (&s_g)[4], float &chunk_g2) {
   if (!NORM) return;
-  const float total = wave_total_in_lane63((s_g[0] + s_g[1]) + (s_g[2] + s_g[3]));
-  if (threadIdx.x == 63) {
-    NormPartial p;
-    p.theta2 = 0.0f; p.u2 = 0.0f; p.g2 = total; p.pad = 0.0f;
-    *out = p;
-  }
+  chunk_g2 += wave_total_in_lane63((s_g[0] + s_g[1]) + (s_g[2] + s_g[3]));
 }
 
 // Row sums of a span whose n elements are parked in LDS.
@@ -843,7 +846,7 @@ __device__ __forceinline__ void rows_from_stage(const float *stage, int64_t off,
 // A full, aligned span whose 16 vectors per lane are already in registers.  (Norm first, row sums in a second
 // sweep: one merged sweep measured 1-13 % slower, the scans between the pieces hold up the arriving loads.)
 template <typename GradS, typename GradV, bool NORM>
-__device__ __forceinline__ void span_from_registers(const GradV (&g)[kPreUnroll], int s, const PreChunk<GradS> &pc, float *stage) {
+__device__ __forceinline__ void span_from_registers(const GradV (&g)[kPreUnroll], int s, const PreChunk<GradS> &pc, float *stage, float &chunk_g2) {
   const int64_t off = pc.offset + static_cast<int64_t>(s) * kPreSub, end = off + kPreSub;
   float s_g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   if (NORM) {
@@ -854,7 +857,7 @@ __device__ __forceinline__ void span_from_registers(const GradV (&g)[kPreUnroll]
       for (int k = 0; k < 4; ++k) s_g[u & 3] = __builtin_fmaf(gf[k], gf[k], s_g[u & 3]);
     }
   }
-  emit_norm<NORM>(s_g, pc.partials + s);
+  add_norm<NORM>(s_g, chunk_g2);
   if (!pc.gc) return;
   const int64_t cols = pc.gi.cols;
   RowPartial *rp = pc.row_partials + s;
@@ -888,7 +891,7 @@ __device__ __forceinline__ void span_from_registers(const GradV (&g)[kPreUnroll]
 
 // Any other span (the ragged last one of a tensor, or a gradient that is not 16-byte aligned): loads as it goes.
 template <typename GradS, typename GradV, bool NT, bool NORM>
-__device__ __forceinline__ void span_generic(int s, const PreChunk<GradS> &pc, float *stage) {
+__device__ __forceinline__ void span_generic(int s, const PreChunk<GradS> &pc, float *stage, float &chunk_g2) {
   const int start = s * kPreSub;
   const int n = min(kPreSub, pc.len - start);
   const GradS *__restrict__ g_p = pc.g + start;
@@ -914,14 +917,14 @@ __device__ __forceinline__ void span_generic(int s, const PreChunk<GradS> &pc, f
     if (NORM) s_g[0] = __builtin_fmaf(g, g, s_g[0]);
     if (pc.gc) stage[i] = g;
   }
-  emit_norm<NORM>(s_g, pc.partials + s);
+  add_norm<NORM>(s_g, chunk_g2);
   if (pc.gc) rows_from_stage(stage, pc.offset + start, n, pc.gi, pc.row_partials + s);
 }
 
 // One wave per chunk-table entry.  The chunk's spans are taken in order, and the loads of the next full span
 // are issued before the current one is reduced, so the wave's memory pipe does not idle while it adds up.
 template <typename GradS, typename GradV, bool NT, bool NORM, bool GC>
-__global__ __launch_bounds__(kScaledBlock) void novak_prepass_kernel(Tables tb, int sub_shift, NormPartial *partials,
+__global__ __launch_bounds__(kScaledBlock) void novak_prepass_kernel(Tables tb, int sub_shift, NormSums *chunk_sums,
                                                                      RowPartial *row_partials) {
   extern __shared__ __align__(16) float stage[];                      // kPreSub floats, touched only on the staged centralization path
   const novak_chunk ch = tb.chunks[blockIdx.x];
@@ -932,7 +935,7 @@ __global__ __launch_bounds__(kScaledBlock) void novak_prepass_kernel(Tables tb, 
   pc.gi.cols = 0;
   if (GC) pc.gi = tb.gc[ch.tensor];
   pc.gc = GC && pc.gi.cols > 0;
-  pc.partials = partials + (static_cast<size_t>(blockIdx.x) << sub_shift);
+  float chunk_g2 = 0.0f;
   pc.row_partials = row_partials + (static_cast<size_t>(blockIdx.x) << sub_shift);
   const int nspans = (ch.len + kPreSub - 1) / kPreSub;
   const int nfull = (reinterpret_cast<uintptr_t>(pc.g) & (sizeof(GradV) - 1)) == 0 ? ch.len / kPreSub : 0;
@@ -948,15 +951,20 @@ __global__ __launch_bounds__(kScaledBlock) void novak_prepass_kernel(Tables tb, 
 #pragma unroll
       for (int u = 0; u < kPreUnroll; ++u) b[u] = ld<NT>(g4 + (s + 1) * kSpanVecs + u * kScaledBlock);
     }
-    if (s < nfull) span_from_registers<GradS, GradV, NORM>(a, s, pc, stage);
-    else span_generic<GradS, GradV, NT, NORM>(s, pc, stage);
+    if (s < nfull) span_from_registers<GradS, GradV, NORM>(a, s, pc, stage, chunk_g2);
+    else span_generic<GradS, GradV, NT, NORM>(s, pc, stage, chunk_g2);
     if (s + 1 >= nspans) break;
     if (s + 2 < nfull) {
 #pragma unroll
       for (int u = 0; u < kPreUnroll; ++u) a[u] = ld<NT>(g4 + (s + 2) * kSpanVecs + u * kScaledBlock);
     }
-    if (s + 1 < nfull) span_from_registers<GradS, GradV, NORM>(b, s + 1, pc, stage);
-    else span_generic<GradS, GradV, NT, NORM>(s + 1, pc, stage);
+    if (s + 1 < nfull) span_from_registers<GradS, GradV, NORM>(b, s + 1, pc, stage, chunk_g2);
+    else span_generic<GradS, GradV, NT, NORM>(s + 1, pc, stage, chunk_g2);
+  }
+  if (NORM && threadIdx.x == 63) {
+    NormSums sums;
+    sums.theta2 = 0.0; sums.u2 = 0.0; sums.g2 = static_cast<double>(chunk_g2);
+    chunk_sums[blockIdx.x] = sums;
   }
 }
 
