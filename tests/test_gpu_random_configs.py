@@ -66,3 +66,35 @@ def test_random_option_combinations(first):
             assert gpu.guards_intact(), f"seed {seed}: a guard band was written"
         finally:
             gpu.close()
+
+
+def draw_centralized_case(seed):
+    """Larger centralized (and clipped) tensors whose rows cross vector, wave, span and chunk boundaries in every way."""
+    rnd = random.Random(seed)
+    base = dict(W.get_workload("ragged").hyper)
+    numels, rows = [], []
+    for _ in range(rnd.randint(1, 4)):
+        cols = rnd.choice([1, 3, 17, 63, 64, 65, 255, 256, 257, 512, 1000, 2048, 4095, 4096, 4097, 8192, 25088, 50000, 100003])
+        r = rnd.randint(1, max(1, min(3000, 3_000_000 // cols)))
+        numels.append(r * cols)
+        rows.append(r if rnd.random() < 0.85 else 0)
+    k = rnd.choice([1, 2, 3])
+    hyper = dict(base, mode="research", use_gc=True, clip_threshold=rnd.choice([0.0, 0.3]), la_k=k,
+                 lookahead=rnd.choice(["none", "memory_efficient"]), moment_dtype=rnd.choice(["f32", "bf16_m"]),
+                 layer_adaptation=rnd.random() < 0.3, device_step=rnd.random() < 0.3)
+    kw = dict(grad_dtype=rnd.choice(["f32", "bf16"]), seed=seed, auto_sync=True, guard=8, rows=rows,
+              grad_misalign=rnd.choice([0, 0, 1]), chunk_elems=rnd.choice([None, 4096, 65536, 1 << 20]))
+    return numels, hyper, k + 2, kw
+
+
+@pytest.mark.parametrize("first", range(0, 30, 10))
+def test_random_centralized_shapes(first):
+    for seed in range(first, first + 10):
+        numels, hyper, steps, kw = draw_centralized_case(seed)
+        print(f"seed {seed}: numels={numels} steps={steps} hyper={hyper} {kw}", flush=True)
+        gpu, states, _ = H.run_pair(numels, hyper, steps, 1e-2, **kw)
+        try:
+            H.compare_states(gpu, states, tag=f"seed {seed}: ")
+            assert gpu.guards_intact(), f"seed {seed}: a guard band was written"
+        finally:
+            gpu.close()
