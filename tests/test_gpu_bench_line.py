@@ -81,4 +81,9 @@ def test_host_cost_tool_runs_and_reports(tmp_path):
     out = subprocess.run([B.HOSTCOST_PATH, str(f), "200"], check=True, capture_output=True, text=True, timeout=120).stdout
     d = json.loads(out.strip().splitlines()[-1])
     assert d["tensors"] == len(W.get_workload("ragged").numels) and d["steps"] == 200
-    assert 0.0 < d["host_us_per_step"] <= d["total_us_per_step"] < 1e4
+    assert 0.0 < d["host_us_per_step"] <= d["total_us_per_step"] < 1e4 and d["step_count"] == "host"
+    # device-step mode, eager and as a captured graph of 10 steps replayed 20 times (the tool checks the device's count itself)
+    out = subprocess.run([B.HOSTCOST_PATH, str(f), "200", "10"], check=True, capture_output=True, text=True, timeout=120).stdout
+    d = json.loads(out.strip().splitlines()[-1])
+    assert d["step_count"] == "device" and d["graph_steps"] == 10
+    assert 0.0 < d["graph_host_us_per_step"] <= d["graph_us_per_step"] < 1e4 and 0.0 < d["total_us_per_step"] < 1e4
