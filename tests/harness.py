@@ -190,7 +190,7 @@ def assert_close_strict(name: str, got: np.ndarray, ref: np.ndarray, rtol: float
                              f"got {got64[j]!r} ref {ref64[j]!r} err {err[j]:.3e} bound {bound[j]:.3e}")
 
 
-# ---- comparison policy for the two discontinuous decisions a step can take ---------------------------------
+# ---- comparison policy for what a step decides discontinuously (1, 2) or nearly so (3) ---------------------
 # (1) bfloat16 storage of m: the oracle rounds the exact m_t; a kernel rounds its fp32 m_t.  To first order an
 #     fp32 evaluation of Eq. 13 and Eq. 1 (each operation and constant rounded once) is within
 #     FP32_UNIT * [(1-beta1)(2|g| + 3|g~| + 4|m_prev|) + |m|] of the exact value; a stored m_t is correct
