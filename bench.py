@@ -392,6 +392,8 @@ def main():
         import multiprocessing as mp
         workers = args.cpu_workers
         pool = mp.get_context("spawn").Pool(workers)
+    from paper_2601_07876_amd import build as B
+    B.ensure_built()                 # loads what was built beforehand; builds only where nothing is there
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the update is elementwise and would shard "
               "without communication)", file=sys.stderr)

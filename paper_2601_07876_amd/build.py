@@ -35,6 +35,13 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
+def ensure_built(verbose: bool = False) -> str:
+    """For drivers (tests, smoke, bench): builds only where nothing has been built yet; the library itself never does."""
+    if not os.path.exists(LIB_PATH):
+        build_library(verbose)
+    return LIB_PATH
+
+
 def build_library(verbose: bool = True) -> str:
     cmd = [hipcc_path()] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
     # the host-only source is C++ without device code; -x hip compiles both uniformly

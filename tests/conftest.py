@@ -16,8 +16,7 @@ def pytest_sessionstart(session):
     """The tests load the library that `python -m paper_2601_07876_amd.build` left in the tree; only where nothing
     has been built yet it is built here (the library itself has no fallback path and fails loudly when absent)."""
     from paper_2601_07876_amd import build as B
-    if not os.path.exists(B.LIB_PATH):
-        B.build_library(verbose=False)
+    B.ensure_built()
 
 
 def pytest_collection_modifyitems(config, items):
