@@ -98,3 +98,22 @@ def test_random_centralized_shapes(first):
             assert gpu.guards_intact(), f"seed {seed}: a guard band was written"
         finally:
             gpu.close()
+
+
+@pytest.mark.parametrize("first", range(1000, 1024, 8))
+def test_random_long_horizons(first):
+    """The option draws of test_random_option_combinations over 40-100 steps (many lookahead windows, the
+    rectification switching on, the schedules of Eq. 3-4 moving), tensors capped at 30000 elements."""
+    for seed in range(first, first + 8):
+        numels, hyper, _, kw = draw_case(seed)
+        steps = random.Random(seed * 7 + 1).randint(40, 100)
+        numels = [min(n, 30000) for n in numels]
+        if kw.get("rows"):
+            kw["rows"] = [r if (n and r and n % r == 0) else 0 for n, r in zip(numels, kw["rows"])]
+        print(f"seed {seed}: numels={numels} steps={steps} hyper={hyper} {kw}", flush=True)
+        gpu, states, _ = H.run_pair(numels, hyper, steps, 1e-2, **kw)
+        try:
+            H.compare_states(gpu, states, strict=False, tag=f"seed {seed}: ")
+            assert gpu.guards_intact(), f"seed {seed}: a guard band was written"
+        finally:
+            gpu.close()
