@@ -523,3 +523,34 @@ def test_an_overflowed_second_moment_freezes_the_element_instead_of_poisoning_it
     finally:
         gpu.close()
         ref.close()
+
+
+@pytest.mark.parametrize("extra", [{}, {"clip_threshold": 0.5, "use_gc": True, "mode": "research"},
+                                   {"layer_adaptation": True, "auto_lr": True, "mode": "research"}, {"device_step": True}])
+def test_retuning_between_steps_changes_no_result(extra):
+    """novak_set_tuning rebuilds the device tables (chunk size) or changes launch parameters in the middle of a
+    run; the state lives in the caller's arrays, so the trajectory must stay the oracle's."""
+    wl = W.get_workload("ragged")
+    hyper = dict(wl.hyper, **extra)
+    theta0 = W.host_params(wl.numels, 3)
+    gpu = H.GpuNovak(wl.numels, hyper, "f32", theta0, auto_sync=True, guard=8, rows=wl.rows if extra.get("use_gc") else None)
+    try:
+        h = H.oracle_hyper(hyper, gpu.eff_nesterov, gpu.eff_lookahead, gpu.info)
+        states = [O.init_state(th, h, rows=gpu.rows[i]) for i, th in enumerate(theta0)]
+        aux = O.AutoLrState()
+        tune = {4: (N.NOVAK_TUNE_CHUNK_ELEMS, 4096), 7: (N.NOVAK_TUNE_CHUNK_ELEMS, 65536), 9: (N.NOVAK_TUNE_NONTEMPORAL, 0),
+                12: (N.NOVAK_TUNE_WAVES_PER_CU, 16), 14: (N.NOVAK_TUNE_CHUNK_ELEMS, 16384)}
+        for t in range(1, 18):
+            if t in tune:
+                torch.cuda.synchronize()          # set_tuning is not stream-ordered: the caller waits for earlier steps
+                N.check(N.novak_set_tuning(gpu.handle, *tune[t]), "novak_set_tuning", gpu.handle)
+            gh = W.host_grads(wl.numels, t, wl.grad_std, 3)
+            N.check(gpu.step(t, gpu.upload_grads(gh)), f"step {t}", gpu.handle)
+            O.step_all(states, gh, t, h, aux)
+            if O.sync_due(t, h):
+                for st in states:
+                    O.lookahead_sync(st, h)
+        H.compare_states(gpu, states)
+        assert gpu.guards_intact()
+    finally:
+        gpu.close()
