@@ -732,9 +732,10 @@ __global__ __launch_bounds__(64) void novak_reduce_chunks_kernel(const novak_chu
 //     128-bit loads per lane in flight: a read-only stream needs about 100 KB outstanding per compute unit,
 //     and 16 KB per wave at a residency of 6 waves measured best on MI355X (7.35 TB/s against 6.8 TB/s for
 //     4 KB per wave).  The next span's loads are issued before the current span is reduced.
-//   * NORM: a sum of squares per span (fp32), added up in double over the chunk's spans in order: the wave writes
-//     its chunk's sum itself; the tensor reduction is shared with the two-pass step, then novak_clip_kernel
-//     turns the norm into the factor min(1, c_clip/||g||).
+//   * NORM: every lane keeps four fp32 sums of squares across spans; once per four spans (a chunk of the default
+//     size) they are added up over the wave and into the chunk's sum (double), which the wave writes itself; the
+//     tensor reduction is shared with the two-pass step, then novak_clip_kernel turns the norm into the factor
+//     min(1, c_clip/||g||).
 //   * GC: every row piece that lies in a span is summed in double and in a fixed order - in registers when
 //     rows are made of whole 256-element pieces, else from a copy of the span parked in LDS.  Rows that lie entirely inside the span get their mean written here; a row
 //     that sticks out at the front ("head") or at the back ("tail") leaves a partial sum, and
@@ -808,12 +809,16 @@ struct PreChunk {
   RowPartial *row_partials;
 };
 
-// Adds a span's sum of squares to the wave's running sum for its chunk (meaningful in lane 63 only; the spans of
-// a chunk are taken in order by one wave, so the chunk's sum has a fixed order of additions).
+// The lanes' sums of squares (four fp32 accumulators each, kept across spans) are added up over the wave once per
+// kFlushSpans spans, i.e. once per chunk of the default size: 64 squares per accumulator between two flushes.  The
+// spans of a chunk are taken in order by one wave, so the chunk's sum has a fixed order of additions.  (Total
+// meaningful in lane 63 only.)
+constexpr int kFlushSpans = 4;
 template <bool NORM>
-__device__ __forceinline__ void add_norm(const float (&s_g)[4], float &chunk_g2) {
+__device__ __forceinline__ void flush_norm(float (&s_g)[4], double &chunk_g2) {
   if (!NORM) return;
-  chunk_g2 += wave_total_in_lane63((s_g[0] + s_g[1]) + (s_g[2] + s_g[3]));
+  chunk_g2 += static_cast<double>(wave_total_in_lane63((s_g[0] + s_g[1]) + (s_g[2] + s_g[3])));
+  s_g[0] = s_g[1] = s_g[2] = s_g[3] = 0.0f;
 }
 
 // Row sums of a span whose n elements are parked in LDS.
@@ -846,9 +851,8 @@ __device__ __forceinline__ void rows_from_stage(const float *stage, int64_t off,
 // A full, aligned span whose 16 vectors per lane are already in registers.  (Norm first, row sums in a second
 // sweep: one merged sweep measured 1-13 % slower, the scans between the pieces hold up the arriving loads.)
 template <typename GradS, typename GradV, bool NORM>
-__device__ __forceinline__ void span_from_registers(const GradV (&g)[kPreUnroll], int s, const PreChunk<GradS> &pc, float *stage, float &chunk_g2) {
+__device__ __forceinline__ void span_from_registers(const GradV (&g)[kPreUnroll], int s, const PreChunk<GradS> &pc, float *stage, float (&s_g)[4]) {
   const int64_t off = pc.offset + static_cast<int64_t>(s) * kPreSub, end = off + kPreSub;
-  float s_g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   if (NORM) {
 #pragma unroll
     for (int u = 0; u < kPreUnroll; ++u) {
@@ -857,7 +861,6 @@ __device__ __forceinline__ void span_from_registers(const GradV (&g)[kPreUnroll]
       for (int k = 0; k < 4; ++k) s_g[u & 3] = __builtin_fmaf(gf[k], gf[k], s_g[u & 3]);
     }
   }
-  add_norm<NORM>(s_g, chunk_g2);
   if (!pc.gc) return;
   const int64_t cols = pc.gi.cols;
   RowPartial *rp = pc.row_partials + s;
@@ -891,11 +894,10 @@ __device__ __forceinline__ void span_from_registers(const GradV (&g)[kPreUnroll]
 
 // Any other span (the ragged last one of a tensor, or a gradient that is not 16-byte aligned): loads as it goes.
 template <typename GradS, typename GradV, bool NT, bool NORM>
-__device__ __forceinline__ void span_generic(int s, const PreChunk<GradS> &pc, float *stage, float &chunk_g2) {
+__device__ __forceinline__ void span_generic(int s, const PreChunk<GradS> &pc, float *stage, float (&s_g)[4]) {
   const int start = s * kPreSub;
   const int n = min(kPreSub, pc.len - start);
   const GradS *__restrict__ g_p = pc.g + start;
-  float s_g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   int done = 0;
   if ((reinterpret_cast<uintptr_t>(g_p) & (sizeof(GradV) - 1)) == 0) {
     const GradV *g4 = reinterpret_cast<const GradV *>(g_p);
@@ -917,7 +919,6 @@ __device__ __forceinline__ void span_generic(int s, const PreChunk<GradS> &pc, f
     if (NORM) s_g[0] = __builtin_fmaf(g, g, s_g[0]);
     if (pc.gc) stage[i] = g;
   }
-  add_norm<NORM>(s_g, chunk_g2);
   if (pc.gc) rows_from_stage(stage, pc.offset + start, n, pc.gi, pc.row_partials + s);
 }
 
@@ -935,7 +936,8 @@ __global__ __launch_bounds__(kScaledBlock) void novak_prepass_kernel(Tables tb, 
   pc.gi.cols = 0;
   if (GC) pc.gi = tb.gc[ch.tensor];
   pc.gc = GC && pc.gi.cols > 0;
-  float chunk_g2 = 0.0f;
+  double chunk_g2 = 0.0;
+  float s_g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   pc.row_partials = row_partials + (static_cast<size_t>(blockIdx.x) << sub_shift);
   const int nspans = (ch.len + kPreSub - 1) / kPreSub;
   const int nfull = (reinterpret_cast<uintptr_t>(pc.g) & (sizeof(GradV) - 1)) == 0 ? ch.len / kPreSub : 0;
@@ -951,19 +953,21 @@ __global__ __launch_bounds__(kScaledBlock) void novak_prepass_kernel(Tables tb, 
 #pragma unroll
       for (int u = 0; u < kPreUnroll; ++u) b[u] = ld<NT>(g4 + (s + 1) * kSpanVecs + u * kScaledBlock);
     }
-    if (s < nfull) span_from_registers<GradS, GradV, NORM>(a, s, pc, stage, chunk_g2);
-    else span_generic<GradS, GradV, NT, NORM>(s, pc, stage, chunk_g2);
+    if (s < nfull) span_from_registers<GradS, GradV, NORM>(a, s, pc, stage, s_g);
+    else span_generic<GradS, GradV, NT, NORM>(s, pc, stage, s_g);
     if (s + 1 >= nspans) break;
     if (s + 2 < nfull) {
 #pragma unroll
       for (int u = 0; u < kPreUnroll; ++u) a[u] = ld<NT>(g4 + (s + 2) * kSpanVecs + u * kScaledBlock);
     }
-    if (s + 1 < nfull) span_from_registers<GradS, GradV, NORM>(b, s + 1, pc, stage, chunk_g2);
-    else span_generic<GradS, GradV, NT, NORM>(s + 1, pc, stage, chunk_g2);
+    if (s + 1 < nfull) span_from_registers<GradS, GradV, NORM>(b, s + 1, pc, stage, s_g);
+    else span_generic<GradS, GradV, NT, NORM>(s + 1, pc, stage, s_g);
+    if (((s + 2) & (kFlushSpans - 1)) == 0) flush_norm<NORM>(s_g, chunk_g2);
   }
+  flush_norm<NORM>(s_g, chunk_g2);
   if (NORM && threadIdx.x == 63) {
     NormSums sums;
-    sums.theta2 = 0.0; sums.u2 = 0.0; sums.g2 = static_cast<double>(chunk_g2);
+    sums.theta2 = 0.0; sums.u2 = 0.0; sums.g2 = chunk_g2;
     chunk_sums[blockIdx.x] = sums;
   }
 }
