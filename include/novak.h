@@ -316,13 +316,17 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
 int novak_set_auto_lr_state(novak_handle *h, void *ema);
 
 /* Device-step mode (hp.device_step = 1): `counter` is a DEVICE pointer to one int64 owned by the caller, 8-byte aligned: the
- * number of steps taken so far (0 before the first step; when resuming, the last t).  Every novak_step increments it first and
- * uses the new value as t (Eq. 5-9 evaluated in double by a one-lane kernel, rounded once to fp32 like the host prologue).
+ * number of steps taken so far (0 before the first step; when resuming, the last t).  A step is number counter + 1: a small
+ * prologue kernel reads the counter and evaluates Eq. 5-9 in double (rounded once to fp32 like the host prologue), and the
+ * step's last kernel stores the new count.  Eagerly that prologue runs in front of every step.  Under stream capture the
+ * first novak_step of a capture writes the records of the next 64 steps at once and the following captured steps use them in
+ * turn, so a replayed graph reads the counter when it starts and is otherwise self-contained (one prologue per 64 steps).
  * Required before the first novak_step in that mode (else NOVAK_ERR_STATE there); NOVAK_ERR_STATE on a handle in host-step
- * mode.  To capture a step into a HIP graph: take one step eagerly first (it uploads the gradient-pointer list, which a capture
- * cannot), keep the gradient buffers and the list fixed, then capture novak_step on the capture stream; each replay is one
- * more step.  In this mode the handle does not track t: novak_get_info reports last_step = 0, and the residency of the step
- * kernel is chosen for the lookahead phase with the most streams. */
+ * mode.  Whoever changes the counter's value calls this function again.  To capture steps into a HIP graph: take one step
+ * eagerly first (it uploads the gradient-pointer list, which a capture cannot), keep the gradient buffers and the list fixed,
+ * then capture any number of novak_step calls on the capture stream; each replay takes that many more steps.  In this mode the
+ * handle does not track t: novak_get_info reports last_step = 0, and the residency of the step kernel is chosen for the
+ * lookahead phase with the most streams. */
 int novak_set_step_counter(novak_handle *h, void *counter);
 
 /* Monitoring: copies lambda_trust * alpha_auto of the last two-pass step, one float per tensor, to HOST

@@ -79,7 +79,7 @@ struct LaunchCtx {
   int64_t total_rows = 0;
   double *d_ema = nullptr;             // caller-owned: g_bar, theta_bar
   // device-step mode
-  DeviceStep *d_step = nullptr;        // what the current step is, written by novak_prologue_kernel
+  DeviceStep *d_step = nullptr;        // the record of the step being enqueued (a slot of the handle's ring of kDeviceRing)
   int64_t *d_counter = nullptr;        // caller-owned: steps taken so far
   // tables
   novak_chunk *d_chunks = nullptr;
@@ -109,6 +109,13 @@ struct novak_handle : LaunchCtx {
   hipEvent_t out_ev = nullptr;
   bool out_used = false;
   bool grads_uploaded = false;
+  // device-step mode: the ring of step records.  Eagerly every step has its record written just before it (slot 0);
+  // under stream capture one prologue writes kDeviceRing records ahead and the captured steps take consecutive slots,
+  // so a replayed graph is self-contained: it starts by reading the counter and needs no further prologue.
+  DeviceStep *d_ring = nullptr;
+  int dev_slot = 0;                          // next slot of the capture in progress
+  unsigned long long dev_capture_id = 0;     // which capture the slots belong to
+  bool dev_in_capture = false;
   bool broken = false;              // a table rebuild failed half way: every later call is refused
   std::string error;
 };
@@ -623,12 +630,17 @@ hipError_t enqueue_step(const LaunchCtx *cx, int grad_dtype, const StepPlan &pl,
 
 // The same in device-step mode: a one-lane prologue advances the caller's counter and writes the step's constants
 // and lookahead phase, then the kernels follow; which of them run does not depend on t.
-hipError_t enqueue_step_device(const LaunchCtx *cx, int grad_dtype, hipStream_t stream) {
+hipError_t enqueue_step_device(const LaunchCtx *cx, int grad_dtype, hipStream_t stream, int n_records) {
   hipError_t e;
   const uint32_t extra = cx->n_gc > 0 ? F_GC : 0u;
-  hipLaunchKernelGGL(novak_prologue_kernel, dim3(1), dim3(64), 0, stream, cx->hp, extra, cx->d_counter, cx->d_step);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (cx->n_chunks == 0) return hipSuccess;          // a list without elements: the step still counts
+  if (n_records > 0) {      // cx->d_step is the first of the n_records slots to fill
+    hipLaunchKernelGGL(novak_prologue_kernel, dim3(1), dim3(kDeviceRing), 0, stream, cx->hp, extra, cx->d_counter, cx->d_step, n_records);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  if (cx->n_chunks == 0) {                           // a list without elements: the step still counts
+    hipLaunchKernelGGL(novak_count_kernel, dim3(1), dim3(64), 0, stream, cx->d_step);
+    return hipGetLastError();
+  }
   if ((clipping(cx) || cx->n_gc > 0) && (e = launch_prepass(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
   if (two_pass(cx)) {
     // the host does not know the step's lookahead phase: residency for the phase with the most streams
@@ -747,8 +759,8 @@ static int create_impl(novak_handle **out, const novak_hparams *hp, const novak_
   int lds_cu = 0;
   if (hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, device_id) == hipSuccess && lds_cu >= 65536)
     h->lds_per_cu = lds_cu;
-  if (eff.device_step && (e = hipMalloc(reinterpret_cast<void **>(&h->d_step), sizeof(DeviceStep))) != hipSuccess)
-    return bail(fail_hip(h, e, "hipMalloc(device step record)"));
+  if (eff.device_step && (e = hipMalloc(reinterpret_cast<void **>(&h->d_ring), kDeviceRing * sizeof(DeviceStep))) != hipSuccess)
+    return bail(fail_hip(h, e, "hipMalloc(device step records)"));
   if (n_tensors > 0) {
     const size_t n = static_cast<size_t>(n_tensors);
     const size_t bytes = 5 * n * sizeof(void *);
@@ -938,7 +950,7 @@ int novak_destroy(novak_handle *h) {
   (void)scope.enter(h->device_id);
   free_device_tables(h);
   if (h->d_ptrs) (void)hipFree(h->d_ptrs);
-  if (h->d_step) (void)hipFree(h->d_step);
+  if (h->d_ring) (void)hipFree(h->d_ring);
   if (h->d_out_ptrs) (void)hipFree(h->d_out_ptrs);
   if (h->d_gc) (void)hipFree(h->d_gc);
   if (h->d_gc_tensor) (void)hipFree(h->d_gc_tensor);
@@ -1144,8 +1156,34 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
       std::memcpy(h->last_grads.data(), grads, n * sizeof(void *));
       h->grads_uploaded = true;
     }
-    if (device_step) NOVAK_HIP(h, enqueue_step_device(h, grad_dtype, stream));
-    else NOVAK_HIP(h, enqueue_step(h, grad_dtype, pl, stream));
+    if (device_step) {
+      // Which record this step reads.  Eagerly: slot 0, written by a prologue just before.  Under capture: the
+      // first step of a capture writes kDeviceRing records ahead and the following ones take the next slots.
+      hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+      unsigned long long capture_id = 0;
+      if (stream && hipStreamGetCaptureInfo(stream, &cs, &capture_id) != hipSuccess) {
+        (void)hipGetLastError();
+        cs = hipStreamCaptureStatusNone;
+      }
+      int slot = 0, n_records = 1;
+      if (cs == hipStreamCaptureStatusActive) {
+        if (!h->dev_in_capture || h->dev_capture_id != capture_id || h->dev_slot >= kDeviceRing) {
+          h->dev_in_capture = true;
+          h->dev_capture_id = capture_id;
+          h->dev_slot = 0;
+          n_records = kDeviceRing;
+        } else {
+          n_records = 0;
+        }
+        slot = h->dev_slot++;
+      } else {
+        h->dev_in_capture = false;
+      }
+      h->d_step = h->d_ring + slot;
+      NOVAK_HIP(h, enqueue_step_device(h, grad_dtype, stream, n_records));
+    } else {
+      NOVAK_HIP(h, enqueue_step(h, grad_dtype, pl, stream));
+    }
   }
   if (device_step) return NOVAK_OK;          // t is the device's business
   h->last_step = step;

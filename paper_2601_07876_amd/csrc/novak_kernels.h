@@ -116,12 +116,22 @@ struct Consts {
   uint32_t flags;
 };
 
-// Device-step mode: what the current step is, written by novak_prologue_kernel, read by the step kernel.
+// Device-step mode: what one step is, written by novak_prologue_kernel, read by the step's kernels.  The records of
+// up to kDeviceRing consecutive steps sit side by side (one per 128 bytes).
+constexpr int kDeviceRing = 64;
 struct DeviceStep {
   Consts c;
   int la;              // LA_* phase of this step
-  int pad[3];
+  int64_t t;           // the step's number
+  int64_t *counter;    // the caller's step counter: the step's last kernel stores t there
+  int pad[12];
 };
+static_assert(sizeof(DeviceStep) == 128, "one record per 128 bytes");
+
+// One lane of the step's last kernel records that step d.t has been taken.
+__device__ __forceinline__ void device_step_done(const DeviceStep &d) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *d.counter = d.t;
+}
 
 __device__ __forceinline__ float bf16_to_f32(unsigned short b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 
@@ -315,6 +325,7 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
     const DeviceStep d = *ds;
     c_dev = d.c;
     la_rt = d.la;
+    device_step_done(d);
   }
   const Consts &c = DEV ? c_dev : c_arg;
   // which lookahead stream this step reads / writes: compiled in, or a wave-uniform run-time value
@@ -481,19 +492,27 @@ __host__ __device__ inline void plan_step(const novak_hparams &hp, int64_t step,
   pl->c = c;
 }
 
-// Device-step mode: one lane advances the caller's step counter and writes what the step is.
-__global__ __launch_bounds__(64) void novak_prologue_kernel(novak_hparams hp, uint32_t extra_flags, int64_t *counter, DeviceStep *out) {
-  if (threadIdx.x != 0) return;
-  const int64_t t = *counter + 1;
-  *counter = t;
+// Device-step mode: lane i writes what step counter + 1 + i is, for i < count <= kDeviceRing.  The counter itself is
+// advanced by the steps: the last kernel of each stores its t there (device_step_done).
+__global__ __launch_bounds__(kDeviceRing) void novak_prologue_kernel(novak_hparams hp, uint32_t extra_flags, int64_t *counter, DeviceStep *out, int count) {
+  if (static_cast<int>(threadIdx.x) >= count) return;
+  const int64_t t = *counter + 1 + threadIdx.x;
   StepPlan pl;
   plan_step(hp, t, &pl);
   DeviceStep d;
   d.c = pl.c;
   d.c.flags |= extra_flags;
   d.la = pl.la;
-  d.pad[0] = d.pad[1] = d.pad[2] = 0;
-  *out = d;
+  d.t = t;
+  d.counter = counter;
+#pragma unroll
+  for (int i = 0; i < 12; ++i) d.pad[i] = 0;
+  out[threadIdx.x] = d;
+}
+
+// A list without elements launches no kernel that could do it.
+__global__ __launch_bounds__(64) void novak_count_kernel(const DeviceStep *ds) {
+  device_step_done(*ds);
 }
 
 // Lookahead kernels over the same chunk table and sub-block decomposition (UN = 1).
@@ -1094,6 +1113,7 @@ __device__ __forceinline__ void apply_body(const Tables &tb, const Consts &c_arg
     const DeviceStep d = *ds;
     c_dev = d.c;
     la_rt = d.la;
+    device_step_done(d);
   }
   const Consts &c = DEV ? c_dev : c_arg;
   const int phase = la_runtime(LA) ? la_rt : LA;

@@ -172,3 +172,63 @@ def test_captured_step_advances_on_every_replay(lookahead, k, extra):
     finally:
         cap.close()
         twin.close()
+
+
+def test_captures_are_self_contained():
+    """Under capture one prologue writes the records of 64 steps ahead and the captured steps take them in turn.  So:
+    a capture that was never replayed must leave nothing behind for the eager steps that follow; two graphs captured
+    back to back must not share records; a graph of more than 64 steps writes records twice; and graphs, replayed in
+    any order between eager steps, must each continue from the device's counter.  An eager host-step twin takes the
+    same steps on the same gradients."""
+    wl = W.get_workload("ragged")
+    numels = wl.numels[:8]
+    hyper = dict(wl.hyper, lookahead="memory_efficient", la_k=3)
+    theta0 = W.host_params(numels, 11)
+    cap = H.GpuNovak(numels, dict(hyper, device_step=True), "f32", theta0, auto_sync=True)
+    twin = H.GpuNovak(numels, hyper, "f32", theta0, auto_sync=True)
+    try:
+        static_g = cap.upload_grads(W.host_grads(numels, 1, wl.grad_std, 11))
+        state = {"t": 0}
+
+        def twin_steps(n):
+            for _ in range(n):
+                state["t"] += 1
+                N.check(twin.step(state["t"], static_g), f"twin step {state['t']}", twin.handle)
+
+        def eager():
+            N.check(cap.step(state["t"] + 1, static_g), "eager step", cap.handle)
+            twin_steps(1)
+
+        def capture(n):
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for _ in range(n):
+                    N.check(N.novak_step(cap.handle, cap._grad_arr, N.NOVAK_GRAD_F32, 0, torch.cuda.current_stream().cuda_stream),
+                            "captured step", cap.handle)
+            return g
+
+        def check(tag):
+            torch.cuda.synchronize()
+            assert int(cap.counter.item()) == state["t"], tag
+            for role in ("theta", "m", "v"):
+                for i, (x, y) in enumerate(zip(cap.host(role), twin.host(role))):
+                    np.testing.assert_allclose(x, y, rtol=2e-6, atol=1e-9, err_msg=f"{tag}: {role}[{i}]")
+
+        eager()                                   # t = 1: uploads the gradient-pointer list
+        graph_a = capture(3)
+        graph_b = capture(70)                     # right behind the first capture; crosses the 64-record boundary
+        check("captures execute nothing")
+        eager()                                   # t = 2, although 73 steps were captured in between
+        check("eager step after two captures that never ran")
+        graph_a.replay(); twin_steps(3); check("first replay of the short graph")
+        eager(); check("eager step after a replay")
+        graph_b.replay(); twin_steps(70); check("the long graph")
+        graph_a.replay(); twin_steps(3); check("the short graph after the long one")
+        graph_b.replay(); twin_steps(70)
+        eager(); check("at the end")
+        assert state["t"] == 150
+        del graph_a, graph_b
+    finally:
+        cap.close()
+        twin.close()
