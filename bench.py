@@ -59,7 +59,7 @@ def parse_args():
     ap.add_argument("--waves-per-cu", type=int, default=None)
     ap.add_argument("--prepass-waves-per-cu", type=int, default=None)
     ap.add_argument("--device-step", action="store_true",
-                    help="device-step mode: the step count lives in device memory and a one-lane kernel evaluates the scalar prologue")
+                    help="device-step mode: the step count lives in device memory and a small kernel evaluates the scalar prologue")
     ap.add_argument("--graph-steps", type=int, default=0,
                     help="with --device-step: capture this many steps (a multiple of the lookahead window) into ONE HIP graph and time "
                          "its replays; --steps must be a multiple of it")

@@ -121,7 +121,7 @@ typedef struct novak_hparams {
                                0 = never; ignored for the other modes */
   int32_t moment_dtype;     /* NOVAK_MOMENT_*: element type of every tensor's exp_avg array */
   int32_t device_step;      /* 1: the step count t lives in DEVICE memory (novak_set_step_counter) and the scalar prologue runs
-                               in a one-lane kernel in front of the step, so that a novak_step captured into a HIP graph
+                               in a small kernel on the device, so that a novak_step captured into a HIP graph
                                advances by itself on every replay; novak_step's `step` argument must then be 0.  Every
                                option of the step is available; lookahead needs auto_sync = 1 (nobody on the host knows
                                when a sync is due). */

@@ -628,7 +628,7 @@ hipError_t enqueue_step(const LaunchCtx *cx, int grad_dtype, const StepPlan &pl,
   return hipSuccess;
 }
 
-// The same in device-step mode: a one-lane prologue advances the caller's counter and writes the step's constants
+// The same in device-step mode: a prologue kernel (when asked for) reads the caller's counter and writes the constants
 // and lookahead phase, then the kernels follow; which of them run does not depend on t.
 hipError_t enqueue_step_device(const LaunchCtx *cx, int grad_dtype, hipStream_t stream, int n_records) {
   hipError_t e;

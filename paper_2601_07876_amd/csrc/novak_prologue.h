@@ -1,7 +1,7 @@
 // The per-step scalar prologue (Phases 3, 5, 6 and the constants of Phases 8-10) as one function that compiles
 // for the host AND for the device: novak_compute_step_scalars / novak_step evaluate it on the host, the
 // device-step mode (step count in device memory, for callers that replay a captured HIP graph) evaluates it in a
-// one-lane kernel.  Double arithmetic in both places; 1 - beta^t through expm1(t log beta) (section 5.8).
+// prologue kernel (one lane per step).  Double arithmetic in both places; 1 - beta^t through expm1(t log beta) (section 5.8).
 #ifndef NOVAK_PROLOGUE_H_
 #define NOVAK_PROLOGUE_H_
 

@@ -1,4 +1,4 @@
-"""Device-step mode: the step count lives in device memory and the scalar prologue runs in a one-lane kernel, so a
+"""Device-step mode: the step count lives in device memory and the scalar prologue runs in a small kernel on the device, so a
 captured novak_step advances by itself on every graph replay.  Checked against the oracle like the host-step path,
 against the host-step path itself, and - captured into a HIP graph through torch - on every one of many replays with
 eager work and synchronisations in between."""
