@@ -324,7 +324,8 @@ int novak_set_auto_lr_state(novak_handle *h, void *ema);
  * Required before the first novak_step in that mode (else NOVAK_ERR_STATE there); NOVAK_ERR_STATE on a handle in host-step
  * mode.  Whoever changes the counter's value calls this function again.  To capture steps into a HIP graph: take one step
  * eagerly first (it uploads the gradient-pointer list, which a capture cannot), keep the gradient buffers and the list fixed,
- * then capture any number of novak_step calls on the capture stream; each replay takes that many more steps.  In this mode the
+ * then capture any number of novak_step calls on the capture stream (a call whose gradient-pointer list differs from the
+ * previous call's is refused under capture with NOVAK_ERR_STATE); each replay takes that many more steps.  In this mode the
  * handle does not track t: novak_get_info reports last_step = 0, and the residency of the step kernel is chosen for the
  * lookahead phase with the most streams. */
 int novak_set_step_counter(novak_handle *h, void *counter);

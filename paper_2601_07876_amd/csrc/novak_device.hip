@@ -1144,6 +1144,12 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
     NOVAK_HIP(h, scope.enter(h->device_id));
     // gradient pointers: upload only when the list changed since the previous step
     if (h->n_chunks > 0 && (!h->grads_uploaded || std::memcmp(h->last_grads.data(), grads, n * sizeof(void *)) != 0)) {
+      // (the upload goes through a pinned staging slot that later calls reuse: not something a graph may replay)
+      hipStreamCaptureStatus up_cs = hipStreamCaptureStatusNone;
+      if (stream && hipStreamIsCapturing(stream, &up_cs) != hipSuccess) (void)hipGetLastError();
+      if (up_cs == hipStreamCaptureStatusActive)
+        return fail(h, NOVAK_ERR_STATE, "the gradient-pointer list differs from the previous step's while the stream is being captured: "
+                                        "take one step with this list before the capture and keep the list fixed");
       const int slot = h->ring_next;
       h->ring_next = (slot + 1) % novak_handle::kRing;
       if (h->ring_used[slot]) NOVAK_HIP(h, hipEventSynchronize(h->ring_ev[slot]));

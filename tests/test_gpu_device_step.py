@@ -3,6 +3,7 @@ captured novak_step advances by itself on every graph replay.  Checked against t
 against the host-step path itself, and - captured into a HIP graph through torch - on every one of many replays with
 eager work and synchronisations in between."""
 import ctypes as C
+import warnings
 
 import numpy as np
 import pytest
@@ -215,6 +216,17 @@ def test_captures_are_self_contained():
                 for i, (x, y) in enumerate(zip(cap.host(role), twin.host(role))):
                     np.testing.assert_allclose(x, y, rtol=2e-6, atol=1e-9, err_msg=f"{tag}: {role}[{i}]")
 
+        # a capture may not upload a gradient-pointer list: refused with a reason, and the capture goes on
+        other_g = [g.clone() for g in static_g]
+        other = (C.c_void_p * len(numels))(*[g.data_ptr() for g in other_g])
+        torch.cuda.synchronize()
+        probe = torch.cuda.CUDAGraph()
+        with warnings.catch_warnings():
+            warnings.simplefilter("ignore")           # torch remarks that the captured graph is empty: that is the point
+            with torch.cuda.graph(probe):
+                rc = N.novak_step(cap.handle, other, N.NOVAK_GRAD_F32, 0, torch.cuda.current_stream().cuda_stream)
+        assert rc == N.NOVAK_ERR_STATE and "captured" in N.novak_last_error(cap.handle)
+        del probe
         eager()                                   # t = 1: uploads the gradient-pointer list
         graph_a = capture(3)
         graph_b = capture(70)                     # right behind the first capture; crosses the 64-record boundary
