@@ -275,7 +275,7 @@ struct Geometry {
 // per compute unit.  Lists of smaller tensors (0.1-0.4 ms kernels) and the two kernels of the two-pass
 // step peak one or two waves later; the budgets below are the compromise (78, and 84 for the two-pass
 // kernels).  Residency is capped by requesting LDS that the kernel never touches.
-constexpr double kStepBudget = 78.0, kTwoPassBudget = 84.0;
+constexpr double kStepBudget = 78.0, kTwoPassBudget = 84.0, kDeviceStepBudget = 99.0;
 Geometry geometry_of(const LaunchCtx *h, int sub_elems, int threads, int wide, int narrow = 0, double budget = kStepBudget) {
   Geometry gm;
   gm.sub_shift = log2_exact(h->chunk_elems / sub_elems);
@@ -420,7 +420,10 @@ void launch_step_device(const LaunchCtx *h, int grad_dtype, hipStream_t s, const
   const StreamCount n = step_streams(grad_dtype, la, h->hp.moment_dtype == NOVAK_MOMENT_BF16_M);
   LaunchCtx shape = *h;                       // this kernel exists in the default launch shape only
   shape.vec_per_lane = 1;
-  const Geometry gm = geometry_of(&shape, 256, 64, n.wide, n.narrow);
+  // With the run-time phase the kernel peaks two waves later than its host-step counterparts (11 instead of 9 per
+  // compute unit with fp32 gradients, 12 with bfloat16 gradients: measured on the four multi-tensor lists).
+  const double budget = h->hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT ? kDeviceStepBudget : kStepBudget;
+  const Geometry gm = geometry_of(&shape, 256, 64, n.wide, n.narrow, budget);
   if (grad_dtype == NOVAK_GRAD_BF16) launch_step_device_dtype<unsigned short, u16x4>(h, dim3(gm.grid), gm.lds, gm.sub_shift, s, tb);
   else launch_step_device_dtype<float, f32x4>(h, dim3(gm.grid), gm.lds, gm.sub_shift, s, tb);
 }
