@@ -238,16 +238,20 @@ class Setup:
         if args.extrapolate:
             self.extra_out = torch.empty(flat, dtype=torch.float32, device=dev)
             self.extrapolate_arr = (C.c_void_p * len(numels))(*[self.extra_out.data_ptr() + 4 * o for o in offsets])
-        self.scaled = bool(info.layer_adaptation or info.auto_lr)
+        # the trust ratio makes the step two-pass; auto-LR alone is the single-pass step behind a norms pre-pass
+        self.scaled = bool(info.layer_adaptation)
+        self.auto_only = bool(info.auto_lr and not info.layer_adaptation)
         self.m_tag = "+bf16_m" if info.moment_dtype == N.NOVAK_MOMENT_BF16_M else ""
         self.t = 0
         # extra gradient reads of the pre-pass (one read serves clipping and centralization; with centralization
         # alone only the centralized tensors are read)
         self.extra_bpp = 0.0
-        if hyper["clip_threshold"] > 0:
+        if hyper["clip_threshold"] > 0 or self.auto_only:
             self.extra_bpp = N.novak_bytes_per_param_clip(self.gdt)
         elif info.use_gc:
             self.extra_bpp = N.novak_bytes_per_param_clip(self.gdt) * sum(n for n, r in zip(numels, wl.rows) if r >= 1) / max(self.p, 1)
+        if self.auto_only:
+            self.extra_bpp += 4.0        # the pre-pass over the parameters (fp32) for their global norm
 
     def one_step(self):
         N, handle = self.N, self.handle

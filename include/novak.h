@@ -100,7 +100,9 @@ typedef struct novak_hparams {
   int32_t mode;            /* NOVAK_MODE_* */
   int32_t auto_sync;       /* 1: novak_step performs the sync itself, fused into the k-th step's pass */
   /* Full-features scalings of alpha_eff = alpha * r_t * lambda_trust * alpha_auto (Eq. 24a); RESEARCH mode only.
-   * Either one turns the step into two passes over the state (norms first, then the update). */
+   * The trust ratio turns the step into two passes over the state (per-tensor norms of the direction first, then the
+   * update).  Auto-LR alone needs global norms of inputs only: one extra read of the gradients and of the parameters,
+   * then the single-pass step. */
   int32_t layer_adaptation; /* 1: per-tensor trust ratio ||theta||/||u||, u of Eq. 17, clipped (Eq. 19, 25); 1 when a norm is 0 */
   int32_t auto_lr;          /* 1: alpha_auto = clip(g_bar/theta_bar) from EMAs of the global gradient and parameter
                                norms (Eq. 20-22); needs novak_set_auto_lr_state */
@@ -331,7 +333,7 @@ int novak_set_auto_lr_state(novak_handle *h, void *ema);
 int novak_set_step_counter(novak_handle *h, void *counter);
 
 /* Monitoring: copies lambda_trust * alpha_auto of the last two-pass step, one float per tensor, to HOST
- * memory `out` (n_tensors floats).  Waits for `hip_stream` first.  NOVAK_ERR_STATE on a single-pass handle. */
+ * memory `out` (n_tensors floats).  Waits for `hip_stream` first.  NOVAK_ERR_STATE on a handle with neither scaling. */
 int novak_copy_tensor_scales(novak_handle *h, float *out, void *hip_stream);
 
 /* True Nesterov, Eq. 10: writes the extrapolated parameters theta + beta_n * m of every tensor to the

@@ -69,6 +69,11 @@ struct LaunchCtx {
   int *d_first_chunk = nullptr;        // n_tensors + 1: chunk range of each tensor
   float *d_scale = nullptr;            // n_tensors: lambda_trust * alpha_auto
   float *d_gscale = nullptr;           // one float: gradient-clipping factor of the current step
+  // auto-LR without a trust ratio: global norms from pre-passes, the factor of Eq. 22 in one float
+  float *d_ascale = nullptr;
+  NormSums *d_chunk_sums_theta = nullptr;   // one per chunk: sums of squares of the parameters (in the g2 field)
+  NormSums *d_tensor_sums_theta = nullptr;  // one per tensor
+  const void **d_theta_ptrs = nullptr;      // n_tensors parameter pointers, for the pre-pass over theta
   // gradient centralization
   GcInfo *d_gc = nullptr;              // per tensor
   int *d_gc_tensor = nullptr;          // centralized tensors
@@ -166,12 +171,17 @@ Tables tables_of(const LaunchCtx *h) {
   tb.grad = reinterpret_cast<const void *const *>(base + n * sizeof(TensorPtrs));
   tb.gscale = h->d_gscale;
   tb.gc = h->d_gc;
+  tb.ascale = h->d_ascale;
   return tb;
 }
 
-bool two_pass(const LaunchCtx *h) { return h->hp.layer_adaptation || h->hp.auto_lr; }
+// The trust ratio needs per-tensor norms of the direction: two passes.  Auto-LR alone needs the global norms of the
+// gradients and the parameters as they are before the step: a pre-pass over each, then the single-pass step.
+bool two_pass(const LaunchCtx *h) { return h->hp.layer_adaptation != 0; }
+bool auto_only(const LaunchCtx *h) { return h->hp.auto_lr && !h->hp.layer_adaptation; }
+bool scaled(const LaunchCtx *h) { return h->hp.layer_adaptation || h->hp.auto_lr; }
 bool clipping(const LaunchCtx *h) { return h->hp.clip_threshold > 0.0; }
-bool needs_reductions(const LaunchCtx *h) { return two_pass(h) || clipping(h); }
+bool needs_reductions(const LaunchCtx *h) { return scaled(h) || clipping(h); }
 
 void free_device_tables(novak_handle *h) {
   if (h->d_chunks) (void)hipFree(h->d_chunks);
@@ -181,6 +191,12 @@ void free_device_tables(novak_handle *h) {
   if (h->d_first_chunk) (void)hipFree(h->d_first_chunk);
   if (h->d_scale) (void)hipFree(h->d_scale);
   if (h->d_gscale) (void)hipFree(h->d_gscale);
+  if (h->d_ascale) (void)hipFree(h->d_ascale);
+  if (h->d_chunk_sums_theta) (void)hipFree(h->d_chunk_sums_theta);
+  if (h->d_tensor_sums_theta) (void)hipFree(h->d_tensor_sums_theta);
+  h->d_ascale = nullptr;
+  h->d_chunk_sums_theta = nullptr;
+  h->d_tensor_sums_theta = nullptr;
   if (h->d_row_partials) (void)hipFree(h->d_row_partials);
   h->d_row_partials = nullptr;
   h->d_gscale = nullptr;
@@ -243,6 +259,12 @@ int build_chunk_table_unguarded(novak_handle *h) {
     NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_scale), nt * sizeof(float)));
     std::vector<float> ones(nt, 1.0f);
     NOVAK_HIP(h, hipMemcpy(h->d_scale, ones.data(), nt * sizeof(float), hipMemcpyHostToDevice));
+    if (auto_only(h)) {
+      NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_ascale), sizeof(float)));
+      NOVAK_HIP(h, hipMemcpy(h->d_ascale, &one, sizeof(float), hipMemcpyHostToDevice));
+      NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_tensor_sums_theta), nt * sizeof(NormSums)));
+      if (n > 0) NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_chunk_sums_theta), static_cast<size_t>(n) * sizeof(NormSums)));
+    }
     if (n > 0) {
       NOVAK_HIP(h, hipMalloc(reinterpret_cast<void **>(&h->d_chunk_sums), static_cast<size_t>(n) * sizeof(NormSums)));
       if (two_pass(h)) {   // one partial per wave of pass 1 (256 elements per wave); the pre-pass writes chunk sums itself
@@ -484,7 +506,7 @@ void launch_prepass_kernel(bool norm, bool gc, const dim3 &grid, unsigned lds, h
 }
 
 hipError_t launch_prepass(const LaunchCtx *h, int grad_dtype, hipStream_t s, const Tables &tb) {
-  const bool norm = clipping(h), gc = h->n_gc > 0;
+  const bool norm = clipping(h) || auto_only(h), gc = h->n_gc > 0;
   const bool bf16_g = grad_dtype == NOVAK_GRAD_BF16;
   Geometry g0;
   g0.sub_shift = log2_exact(h->chunk_elems / kPreSub);
@@ -511,7 +533,27 @@ hipError_t launch_prepass(const LaunchCtx *h, int grad_dtype, hipStream_t s, con
     const int nt_count = h->n_tensors;
     hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(kTensorReduceBlock), 0, s, h->d_first_chunk, h->d_chunk_sums,
                        h->d_tensor_sums, h->d_scale, sp);
-    hipLaunchKernelGGL(novak_clip_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, static_cast<float>(h->hp.clip_threshold), h->d_gscale);
+    if (clipping(h))
+      hipLaunchKernelGGL(novak_clip_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, static_cast<float>(h->hp.clip_threshold), h->d_gscale);
+    if (auto_only(h)) {
+      // the same kernel over the parameters (always fp32), then Eq. 20-22 from the two global norms
+      Tables over_theta = tb;
+      over_theta.grad = h->d_theta_ptrs;
+      const int w_th = h->prepass_waves_per_cu ? h->prepass_waves_per_cu : 6;
+      unsigned lds_th = w_th >= 32 ? 0u : (static_cast<unsigned>(h->lds_per_cu) / static_cast<unsigned>(w_th)) & ~511u;
+      if (lds_th > 65536u) lds_th = 65536u;
+      if (nt) launch_prepass_kernel<float, f32x4, true>(true, false, grid, lds_th, s, over_theta, g0.sub_shift, h->d_chunk_sums_theta, nullptr);
+      else launch_prepass_kernel<float, f32x4, false>(true, false, grid, lds_th, s, over_theta, g0.sub_shift, h->d_chunk_sums_theta, nullptr);
+      hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(kTensorReduceBlock), 0, s, h->d_first_chunk,
+                         h->d_chunk_sums_theta, h->d_tensor_sums_theta, h->d_scale, sp);
+      ScaleParams ap = sp;
+      ap.auto_lo = static_cast<float>(h->hp.auto_clip_lo);
+      ap.auto_hi = static_cast<float>(h->hp.auto_clip_hi);
+      ap.gamma = h->hp.auto_lr_gamma;
+      ap.auto_lr = 1;
+      hipLaunchKernelGGL(novak_auto_lr_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, h->d_scale, h->d_ema, ap,
+                         h->d_tensor_sums_theta, h->d_ascale);
+    }
   }
   return hipGetLastError();
 }
@@ -550,7 +592,8 @@ hipError_t launch_scaled_step(const LaunchCtx *h, int grad_dtype, int la, hipStr
   hipLaunchKernelGGL(novak_reduce_tensors_kernel, dim3(static_cast<unsigned>(nt_count)), dim3(kTensorReduceBlock), 0, s, h->d_first_chunk, h->d_chunk_sums,
                      h->d_tensor_sums, h->d_scale, sp);
   if (hp.auto_lr)
-    hipLaunchKernelGGL(novak_auto_lr_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, h->d_scale, h->d_ema, sp);
+    hipLaunchKernelGGL(novak_auto_lr_kernel, dim3(1), dim3(64), 0, s, nt_count, h->d_tensor_sums, h->d_scale, h->d_ema, sp,
+                       static_cast<const NormSums *>(nullptr), static_cast<float *>(nullptr));
   if ((e = hipGetLastError()) != hipSuccess) return e;
   int s2 = 3 + (bf16_m ? 0 : 1);                    // pass 2: theta, m, v read; theta written
   if (la_reads(la)) s2 += 1;
@@ -620,7 +663,8 @@ hipError_t enqueue_step(const LaunchCtx *cx, int grad_dtype, const StepPlan &pl,
   Consts c = pl.c;
   hipError_t e;
   if (cx->n_gc > 0) c.flags |= F_GC;
-  if ((clipping(cx) || cx->n_gc > 0) && (e = launch_prepass(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
+  if (auto_only(cx)) c.flags |= F_AUTO;
+  if ((clipping(cx) || cx->n_gc > 0 || auto_only(cx)) && (e = launch_prepass(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
   if (two_pass(cx)) {
     if ((e = launch_scaled_step(cx, grad_dtype, pl.la, stream, tables_of(cx), c)) != hipSuccess) return e;
   } else {
@@ -635,7 +679,7 @@ hipError_t enqueue_step(const LaunchCtx *cx, int grad_dtype, const StepPlan &pl,
 // and lookahead phase, then the kernels follow; which of them run does not depend on t.
 hipError_t enqueue_step_device(const LaunchCtx *cx, int grad_dtype, hipStream_t stream, int n_records) {
   hipError_t e;
-  const uint32_t extra = cx->n_gc > 0 ? F_GC : 0u;
+  const uint32_t extra = (cx->n_gc > 0 ? F_GC : 0u) | (auto_only(cx) ? F_AUTO : 0u);
   if (n_records > 0) {      // cx->d_step is the first of the n_records slots to fill
     hipLaunchKernelGGL(novak_prologue_kernel, dim3(1), dim3(kDeviceRing), 0, stream, cx->hp, extra, cx->d_counter, cx->d_step, n_records);
     if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -644,7 +688,7 @@ hipError_t enqueue_step_device(const LaunchCtx *cx, int grad_dtype, hipStream_t 
     hipLaunchKernelGGL(novak_count_kernel, dim3(1), dim3(64), 0, stream, cx->d_step);
     return hipGetLastError();
   }
-  if ((clipping(cx) || cx->n_gc > 0) && (e = launch_prepass(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
+  if ((clipping(cx) || cx->n_gc > 0 || auto_only(cx)) && (e = launch_prepass(cx, grad_dtype, stream, tables_of(cx))) != hipSuccess) return e;
   if (two_pass(cx)) {
     // the host does not know the step's lookahead phase: residency for the phase with the most streams
     const int la = cx->hp.lookahead_mode == NOVAK_LOOKAHEAD_MEMORY_EFFICIENT ? LA_MID : LA_OFF;
@@ -777,6 +821,12 @@ static int create_impl(novak_handle **out, const novak_hparams *hp, const novak_
     }
     if ((e = hipMemcpy(h->d_ptrs, host.data(), bytes, hipMemcpyHostToDevice)) != hipSuccess) return bail(fail_hip(h, e, "hipMemcpy(pointer tables)"));
     if ((e = hipMalloc(reinterpret_cast<void **>(&h->d_out_ptrs), n * sizeof(float *))) != hipSuccess) return bail(fail_hip(h, e, "hipMalloc(output pointers)"));
+    if (auto_only(h)) {      // the parameters' pointers as a plain list, for the pre-pass that takes their norm
+      std::vector<const void *> th(n, nullptr);
+      for (size_t i = 0; i < n; ++i) th[i] = tensors[i].param;
+      if ((e = hipMalloc(reinterpret_cast<void **>(&h->d_theta_ptrs), n * sizeof(void *))) != hipSuccess) return bail(fail_hip(h, e, "hipMalloc(parameter pointers)"));
+      if ((e = hipMemcpy(h->d_theta_ptrs, th.data(), n * sizeof(void *), hipMemcpyHostToDevice)) != hipSuccess) return bail(fail_hip(h, e, "hipMemcpy(parameter pointers)"));
+    }
     if ((e = hipHostMalloc(reinterpret_cast<void **>(&h->h_ring), (novak_handle::kRing + 1) * n * sizeof(void *), hipHostMallocDefault)) != hipSuccess)
       return bail(fail_hip(h, e, "hipHostMalloc(pointer staging ring)"));
     for (int r = 0; r < novak_handle::kRing; ++r)
@@ -955,6 +1005,7 @@ int novak_destroy(novak_handle *h) {
   if (h->d_ptrs) (void)hipFree(h->d_ptrs);
   if (h->d_ring) (void)hipFree(h->d_ring);
   if (h->d_out_ptrs) (void)hipFree(h->d_out_ptrs);
+  if (h->d_theta_ptrs) (void)hipFree(h->d_theta_ptrs);
   if (h->d_gc) (void)hipFree(h->d_gc);
   if (h->d_gc_tensor) (void)hipFree(h->d_gc_tensor);
   if (h->d_row_first) (void)hipFree(h->d_row_first);
@@ -1046,7 +1097,7 @@ int novak_set_step_counter(novak_handle *h, void *counter) {
 int novak_copy_tensor_scales(novak_handle *h, float *out, void *hip_stream) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
   if (h->broken) return fail(h, NOVAK_ERR_STATE, "the handle lost its tables in a failed novak_set_tuning; destroy it");
-  if (!two_pass(h)) return fail(h, NOVAK_ERR_STATE, "the handle runs the single-pass step: there are no per-tensor scales");
+  if (!scaled(h)) return fail(h, NOVAK_ERR_STATE, "neither layer adaptation nor auto-LR is on: there are no per-tensor scales");
   if (h->tensors.empty()) return NOVAK_OK;
   if (!out) return fail(h, NOVAK_ERR_NULL_POINTER, "out is NULL");
   DeviceScope scope;
@@ -1246,7 +1297,7 @@ static int step_static_impl(const novak_hparams *hp, const novak_tensor_desc *te
   uint32_t warn = 0;
   int rc = novak_validate_hparams(hp, &cx.hp, &warn);
   if (rc != NOVAK_OK) return fail(nullptr, rc, "hyper-parameters rejected (section 5.8 validation rules)");
-  if (two_pass(&cx) || cx.hp.use_gc)
+  if (scaled(&cx) || cx.hp.use_gc)
     return fail(nullptr, NOVAK_ERR_NOT_IMPLEMENTED, "the allocation-free step covers the single-pass update (with clipping and the sparse threshold); "
                                                     "layer adaptation, auto-LR and gradient centralization need a handle");
   if (cx.hp.device_step) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "the allocation-free step takes t as an argument: device_step must be 0");

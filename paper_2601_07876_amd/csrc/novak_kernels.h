@@ -44,7 +44,7 @@ enum : int {
 };
 constexpr bool la_runtime(int la) { return la >= LA_RUNTIME_ME; }
 
-enum : uint32_t { F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u, F_CLIP = 16u, F_SPARSE = 32u, F_GC = 64u };
+enum : uint32_t { F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u, F_CLIP = 16u, F_SPARSE = 32u, F_GC = 64u, F_AUTO = 128u };
 
 // The four state pointers of a tensor sit together so that one 32-byte scalar load fetches them.
 struct TensorPtrs {
@@ -71,6 +71,8 @@ struct Tables {
   const void *const *grad;
   const float *gscale;   // one float: the step's gradient-clipping factor (read only when F_CLIP is set)
   const GcInfo *gc;      // per tensor (read only when F_GC is set)
+  const float *ascale;   // one float: the step's auto-LR factor of Eq. 22 (read only when F_AUTO is set: auto-LR without
+                         // a trust ratio needs global norms only, which a pre-pass supplies to the single-pass step)
 };
 
 // idx / cols for 0 <= idx < 2^52 without an integer divide: double estimate, then one correction step
@@ -243,12 +245,12 @@ __device__ __forceinline__ void apply(float &th, float u, float m_hat, float &la
 }
 
 template <int LA, typename MomS = float>
-__device__ __forceinline__ void update_one(float &th, float g, float &m, float &v, float &la, const Consts &c, float gs, int la_rt = LA_OFF) {
+__device__ __forceinline__ void update_one(float &th, float g, float &m, float &v, float &la, const Consts &c, float gs, float step, int la_rt = LA_OFF) {
   moments(th, g, m, v, c, gs);
   m = round_mom<MomS>(m);          // the stored m_t is what the rest of the step uses
   float m_hat;
   const float u = direction(m, v, c, m_hat);
-  apply<LA>(th, u, m_hat, la, c, c.step_size, la_rt);
+  apply<LA>(th, u, m_hat, la, c, step, la_rt);
 }
 
 // Vector loads and stores of tensor data.  Every tensor pointer is device (global) memory, which the compiler cannot
@@ -281,11 +283,11 @@ __device__ __forceinline__ f32x4 grad_to_f32<u16x4>(u16x4 g) {
 }
 
 template <int LA, typename MomS = float>
-__device__ __forceinline__ void update_vec(f32x4 &th, f32x4 g, f32x4 &m, f32x4 &v, f32x4 &la, const Consts &c, float gs, int la_rt = LA_OFF) {
+__device__ __forceinline__ void update_vec(f32x4 &th, f32x4 g, f32x4 &m, f32x4 &v, f32x4 &la, const Consts &c, float gs, float step, int la_rt = LA_OFF) {
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     float th_k = th[k], m_k = m[k], v_k = v[k], la_k = la[k];
-    update_one<LA, MomS>(th_k, g[k], m_k, v_k, la_k, c, gs, la_rt);
+    update_one<LA, MomS>(th_k, g[k], m_k, v_k, la_k, c, gs, step, la_rt);
     th[k] = th_k; m[k] = m_k; v[k] = v_k; la[k] = la_k;
   }
 }
@@ -332,6 +334,7 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
   const int phase = la_runtime(LA) ? la_rt : LA;
   const bool reads = la_reads(phase), writes = la_writes(phase);
   const float gs = (c.flags & F_CLIP) ? *tb.gscale : 1.0f;
+  const float step = (c.flags & F_AUTO) ? c.step_size * *tb.ascale : c.step_size;     // Eq. 24a with lambda_trust = 1
   GcInfo gi;
   gi.cols = 0;
   if (GC) gi = tb.gc[ch.tensor];
@@ -377,7 +380,7 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
         f32x4 gf = grad_to_f32<GradV>(g[u]);
         if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(j), gi);
         f32x4 mf = mom_to_f32<MomV>(m[u]);
-        update_vec<LA, MomS>(th[u], gf, mf, v[u], la[u], c, gs, la_rt);
+        update_vec<LA, MomS>(th[u], gf, mf, v[u], la[u], c, gs, step, la_rt);
         st<NT>(th4 + j, th[u]);
         st<NT>(m4 + j, f32_to_mom<MomV>(mf));
         st<NT>(v4 + j, v[u]);
@@ -392,7 +395,7 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
       if (reads) la = ld<NT>(la4 + i);
       f32x4 gf = grad_to_f32<GradV>(g);
       if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(i), gi);
-      update_vec<LA, MomS>(th, gf, m, v, la, c, gs, la_rt);
+      update_vec<LA, MomS>(th, gf, m, v, la, c, gs, step, la_rt);
       st<NT>(th4 + i, th);
       st<NT>(m4 + i, f32_to_mom<MomV>(m));
       st<NT>(v4 + i, v);
@@ -407,7 +410,7 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
     else g = g_p[i];
     if (reads) la = la_p[i];
     if (GC && gi.cols) g = centralize_one(g, off + i, gi);
-    update_one<LA, MomS>(th, g, m, v, la, c, gs, la_rt);
+    update_one<LA, MomS>(th, g, m, v, la, c, gs, step, la_rt);
     th_p[i] = th;
     store_mom<MomS>(m_p + i, m);
     v_p[i] = v;
@@ -1071,12 +1074,13 @@ __global__ __launch_bounds__(kTensorReduceBlock) void novak_reduce_tensors_kerne
 }
 
 // one wave: global norms -> EMAs (Eq. 20-21, state in `ema`: g_bar, theta_bar) -> alpha_auto (Eq. 22),
-// folded into every tensor's scale
+// folded into every tensor's scale.  `theta_sums` (when given): the parameters' sums of squares come from a pre-pass of
+// their own, in its g2 field; `ascale` (when given) receives alpha_auto for the single-pass step.
 __global__ __launch_bounds__(64) void novak_auto_lr_kernel(int n_tensors, const NormSums *tensor_sums, float *scale,
-                                                           double *ema, ScaleParams sp) {
+                                                           double *ema, ScaleParams sp, const NormSums *theta_sums, float *ascale) {
   double a = 0.0, g = 0.0;
   for (int j = threadIdx.x; j < n_tensors; j += 64) {
-    a += tensor_sums[j].theta2;
+    a += theta_sums ? theta_sums[j].g2 : tensor_sums[j].theta2;
     g += tensor_sums[j].g2;
   }
   a = wave_sum(a); g = wave_sum(g);
@@ -1095,6 +1099,7 @@ __global__ __launch_bounds__(64) void novak_auto_lr_kernel(int n_tensors, const 
   if (threadIdx.x == 0) {
     ema[0] = g_bar;
     ema[1] = th_bar;
+    if (ascale) *ascale = ff;
   }
 }
 

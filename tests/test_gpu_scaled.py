@@ -234,3 +234,25 @@ def test_c3_vgg16_centralization_and_clipping_full_oracle():
 def test_c4_vit_b16_bf16_centralization_full_oracle():
     """bf16 gradients, rows of 768 and 3072 elements, one row of 151296 (position embedding), no clipping."""
     _full_size_scaled("c4_vit_b16_bf16", 2, layer=False, auto=False, use_gc=True)
+
+
+def test_auto_lr_alone_runs_the_single_pass_step_behind_a_norms_pre_pass():
+    """Auto-LR without a trust ratio needs the global norms of the gradients and of the parameters only: one pre-pass over
+    each, Eq. 20-22 on the device, then the single-pass step with alpha_auto.  Every element against the oracle at
+    full size (ResNet-50 list; ViT list with bf16 gradients, centralization and clipping sharing the gradient pre-pass)."""
+    _full_size_scaled("c2_resnet50", 6, layer=False, auto=True)
+    _full_size_scaled("c4_vit_b16_bf16", 3, layer=False, auto=True, use_gc=True, clip_threshold=1.0)
+
+
+def test_auto_lr_alone_reports_its_factor_and_launches_no_two_pass_kernels():
+    wl = W.get_workload("ragged")
+    hyper = dict(wl.hyper, auto_lr=True)
+    gpu, states, h = H.run_pair(wl.numels, hyper, 7, wl.grad_std, auto_sync=True)
+    try:
+        H.compare_states(gpu, states)
+        assert bool(gpu.info.auto_lr) and not bool(gpu.info.layer_adaptation)
+        scales = gpu.tensor_scales()
+        assert np.all(scales == scales[0]) and 0.1 <= scales[0] <= 2.0          # lambda_trust = 1: one factor for every tensor
+        np.testing.assert_allclose(scales[0], states[0].trace.scale, rtol=5e-6)
+    finally:
+        gpu.close()
