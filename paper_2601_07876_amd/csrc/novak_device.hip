@@ -743,6 +743,17 @@ int check_grads(const novak_tensor_desc *tensors, size_t n, void *const *grads, 
   return NOVAK_OK;
 }
 
+// No exception leaves the library: what can throw on the host side of an entry point is an allocation (an error
+// string, a staging vector), which becomes a status code.
+template <typename F>
+int guarded(F &&body) {
+  try {
+    return body();
+  } catch (...) {
+    return NOVAK_ERR_NO_MEMORY;
+  }
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
@@ -889,7 +900,7 @@ int novak_create(novak_handle **out, const novak_hparams *hp, const novak_tensor
   }
 }
 
-int novak_arena_alloc(int32_t device_id, size_t bytes, void **ptr, int32_t *contiguous) {
+static int arena_alloc_impl(int32_t device_id, size_t bytes, void **ptr, int32_t *contiguous) {
   if (!ptr) return fail(nullptr, NOVAK_ERR_NULL_POINTER, "ptr is NULL");
   *ptr = nullptr;
   if (contiguous) *contiguous = 0;
@@ -911,7 +922,7 @@ int novak_arena_alloc(int32_t device_id, size_t bytes, void **ptr, int32_t *cont
   return NOVAK_OK;
 }
 
-int novak_arena_free(int32_t device_id, void *ptr) {
+static int arena_free_impl(int32_t device_id, void *ptr) {
   if (!ptr) return NOVAK_OK;
   if (device_id < 0) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "device_id < 0");
   DeviceScope scope;
@@ -1039,7 +1050,7 @@ int novak_get_info(const novak_handle *h, novak_info *info) {
   return NOVAK_OK;
 }
 
-int novak_nesterov_extrapolate(novak_handle *h, void *const *out, void *hip_stream) {
+static int nesterov_extrapolate_impl(novak_handle *h, void *const *out, void *hip_stream) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
   if (h->broken) return fail(h, NOVAK_ERR_STATE, "the handle lost its tables in a failed novak_set_tuning; destroy it");
   const size_t n = h->tensors.size();
@@ -1076,7 +1087,7 @@ int novak_nesterov_extrapolate(novak_handle *h, void *const *out, void *hip_stre
   return NOVAK_OK;
 }
 
-int novak_set_auto_lr_state(novak_handle *h, void *ema) {
+static int set_auto_lr_state_impl(novak_handle *h, void *ema) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
   if (!h->hp.auto_lr) return fail(h, NOVAK_ERR_STATE, "auto_lr is off (or was disabled by the fast path)");
   if (!ema) return fail(h, NOVAK_ERR_NULL_POINTER, "ema is NULL");
@@ -1085,7 +1096,7 @@ int novak_set_auto_lr_state(novak_handle *h, void *ema) {
   return NOVAK_OK;
 }
 
-int novak_set_step_counter(novak_handle *h, void *counter) {
+static int set_step_counter_impl(novak_handle *h, void *counter) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
   if (!h->hp.device_step) return fail(h, NOVAK_ERR_STATE, "the handle counts steps on the host (device_step is off)");
   if (!counter) return fail(h, NOVAK_ERR_NULL_POINTER, "counter is NULL");
@@ -1094,7 +1105,7 @@ int novak_set_step_counter(novak_handle *h, void *counter) {
   return NOVAK_OK;
 }
 
-int novak_copy_tensor_scales(novak_handle *h, float *out, void *hip_stream) {
+static int copy_tensor_scales_impl(novak_handle *h, float *out, void *hip_stream) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
   if (h->broken) return fail(h, NOVAK_ERR_STATE, "the handle lost its tables in a failed novak_set_tuning; destroy it");
   if (!scaled(h)) return fail(h, NOVAK_ERR_STATE, "neither layer adaptation nor auto-LR is on: there are no per-tensor scales");
@@ -1152,14 +1163,10 @@ static int set_tuning_impl(novak_handle *h, int32_t key, int64_t value) {
 }
 
 int novak_set_tuning(novak_handle *h, int32_t key, int64_t value) {
-  try {
-    return set_tuning_impl(h, key, value);
-  } catch (...) {
-    return NOVAK_ERR_NO_MEMORY;
-  }
+  return guarded([&] { return set_tuning_impl(h, key, value); });
 }
 
-int novak_lookahead_init(novak_handle *h, void *hip_stream) {
+static int lookahead_init_impl(novak_handle *h, void *hip_stream) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
   if (h->broken) return fail(h, NOVAK_ERR_STATE, "the handle lost its tables in a failed novak_set_tuning; destroy it");
   if (h->hp.lookahead_mode == NOVAK_LOOKAHEAD_NONE) return fail(h, NOVAK_ERR_STATE, "lookahead is off");
@@ -1171,7 +1178,7 @@ int novak_lookahead_init(novak_handle *h, void *hip_stream) {
   return NOVAK_OK;
 }
 
-int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t step, void *hip_stream) {
+static int step_impl(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t step, void *hip_stream) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
   if (h->broken) return fail(h, NOVAK_ERR_STATE, "the handle lost its tables in a failed novak_set_tuning; destroy it");
   const size_t n = h->tensors.size();
@@ -1251,7 +1258,7 @@ int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t 
   return NOVAK_OK;
 }
 
-int novak_lookahead_sync(novak_handle *h, void *hip_stream) {
+static int lookahead_sync_impl(novak_handle *h, void *hip_stream) {
   if (!h) return NOVAK_ERR_NULL_POINTER;
   if (h->broken) return fail(h, NOVAK_ERR_STATE, "the handle lost its tables in a failed novak_set_tuning; destroy it");
   if (h->hp.lookahead_mode == NOVAK_LOOKAHEAD_NONE) return fail(h, NOVAK_ERR_STATE, "lookahead is off");
@@ -1374,11 +1381,44 @@ static int step_static_impl(const novak_hparams *hp, const novak_tensor_desc *te
 
 int novak_step_static(const novak_hparams *hp, const novak_tensor_desc *tensors, int32_t n_tensors, void *const *grads,
                       int32_t grad_dtype, int64_t step, int32_t device_id, void *hip_stream) {
-  try {
-    return step_static_impl(hp, tensors, n_tensors, grads, grad_dtype, step, device_id, hip_stream);
-  } catch (...) {      // a host-side string allocation failed
-    return NOVAK_ERR_NO_MEMORY;
-  }
+  return guarded([&] { return step_static_impl(hp, tensors, n_tensors, grads, grad_dtype, step, device_id, hip_stream); });
+}
+
+// The entry points whose bodies stand above as *_impl.
+int novak_arena_alloc(int32_t device_id, size_t bytes, void **ptr, int32_t *contiguous) {
+  return guarded([&] { return arena_alloc_impl(device_id, bytes, ptr, contiguous); });
+}
+
+int novak_arena_free(int32_t device_id, void *ptr) {
+  return guarded([&] { return arena_free_impl(device_id, ptr); });
+}
+
+int novak_nesterov_extrapolate(novak_handle *h, void *const *out, void *hip_stream) {
+  return guarded([&] { return nesterov_extrapolate_impl(h, out, hip_stream); });
+}
+
+int novak_set_auto_lr_state(novak_handle *h, void *ema) {
+  return guarded([&] { return set_auto_lr_state_impl(h, ema); });
+}
+
+int novak_set_step_counter(novak_handle *h, void *counter) {
+  return guarded([&] { return set_step_counter_impl(h, counter); });
+}
+
+int novak_copy_tensor_scales(novak_handle *h, float *out, void *hip_stream) {
+  return guarded([&] { return copy_tensor_scales_impl(h, out, hip_stream); });
+}
+
+int novak_lookahead_init(novak_handle *h, void *hip_stream) {
+  return guarded([&] { return lookahead_init_impl(h, hip_stream); });
+}
+
+int novak_step(novak_handle *h, void *const *grads, int32_t grad_dtype, int64_t step, void *hip_stream) {
+  return guarded([&] { return step_impl(h, grads, grad_dtype, step, hip_stream); });
+}
+
+int novak_lookahead_sync(novak_handle *h, void *hip_stream) {
+  return guarded([&] { return lookahead_sync_impl(h, hip_stream); });
 }
 
 }  // extern "C"
