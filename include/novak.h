@@ -48,7 +48,7 @@ enum {
   NOVAK_ERR_BAD_STEP = 4,         /* step < 1, or not last step + 1 on this handle */
   NOVAK_ERR_STATE = 5,            /* call not legal now (sync not due / sync pending / no lookahead) */
   NOVAK_ERR_HIP = 6,              /* a HIP runtime call failed; see novak_last_error() */
-  NOVAK_ERR_NOT_IMPLEMENTED = 7,  /* the entry point does not cover a requested feature (novak_step_static: two-pass scalings, centralization) */
+  NOVAK_ERR_NOT_IMPLEMENTED = 7,  /* the entry point does not cover a requested feature (novak_step_static: layer adaptation, auto-LR, centralization) */
   NOVAK_ERR_NO_MEMORY = 8
 };
 
@@ -332,7 +332,7 @@ int novak_set_auto_lr_state(novak_handle *h, void *ema);
  * lookahead phase with the most streams. */
 int novak_set_step_counter(novak_handle *h, void *counter);
 
-/* Monitoring: copies lambda_trust * alpha_auto of the last two-pass step, one float per tensor, to HOST
+/* Monitoring: copies lambda_trust * alpha_auto of the last step (a factor that is off counts as 1), one float per tensor, to HOST
  * memory `out` (n_tensors floats).  Waits for `hip_stream` first.  NOVAK_ERR_STATE on a handle with neither scaling. */
 int novak_copy_tensor_scales(novak_handle *h, float *out, void *hip_stream);
 

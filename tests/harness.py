@@ -176,11 +176,15 @@ def assert_close(name: str, got: np.ndarray, ref: np.ndarray, atol: float = ATOL
                              f"worst at {j}: got {got64[j]!r} ref {ref64[j]!r} err {err[j]:.3e}")
 
 
-def assert_close_strict(name: str, got: np.ndarray, ref: np.ndarray, rtol: float = 2e-6):
-    """Tighter, scale-aware check: |d| <= rtol * (|ref| + rms(ref)).  Keeps m and v meaningful even
-    where the benchmark's absolute floor of 1e-7 exceeds their magnitude."""
+STRICT_MIN_SIZE = 64      # below this many elements a tensor's own rms is no scale
+
+
+def assert_close_strict(name: str, got: np.ndarray, ref: np.ndarray, rtol: float = 2e-6, scale: Optional[float] = None):
+    """Tighter, scale-aware check: |d| <= rtol * (|ref| + scale), scale = rms(ref) unless given.  Keeps m and v
+    meaningful even where the benchmark's absolute floor of 1e-7 exceeds their magnitude."""
     got64, ref64 = got.astype(np.float64), ref.astype(np.float64)
-    scale = float(np.sqrt(np.mean(ref64 * ref64))) if ref64.size else 0.0
+    if scale is None:
+        scale = float(np.sqrt(np.mean(ref64 * ref64))) if ref64.size else 0.0
     err = np.abs(got64 - ref64)
     bound = rtol * (np.abs(ref64) + scale) + 1e-38
     bad = ~(err <= bound)
@@ -203,8 +207,9 @@ def assert_close_strict(name: str, got: np.ndarray, ref: np.ndarray, rtol: float
 #     decay, g + beta_N (g - m) in Eq. 13 - its fp32 evaluation is off by roundings at the magnitude of the TERMS
 #     (PRE_UNITS of them for the pre-processing, the oracle's trace.g_terms), and that moves u, and theta, by far
 #     more than the bound on about one element in 1e5.  Such runs (`steep`) therefore also step the oracle on
-#     gradients shifted by that error in both directions, and theta must lie in the interval the three results
-#     span (plus the bound).
+#     gradients shifted by that error in both directions (odd and even elements in opposite directions, so that
+#     the shift survives the row means of Eq. 26), and theta must lie in the interval the three results span (plus
+#     the bound).
 FP32_UNIT = 2.0 ** -24
 FP32_SLACK = 2.0
 PRE_UNITS = 3.0
@@ -339,6 +344,9 @@ class CheckedOracle:
                 if approx:      # Eq. 13 as fma(beta_N, g - m, g): the difference, beta_N and the result are rounded
                     e = e + (2.0 * h.beta_n * (np.abs(tr.g_processed) + np.abs(mp)) + np.abs(tr.g_tilde)) / (1.0 + h.beta_n)
                 d.append(FP32_SLACK * FP32_UNIT * e / gs)
+            # neighbouring elements are shifted in opposite directions: a shift that all elements of a row shared
+            # would drop out of Eq. 26 with the row's mean
+            d = [di * np.where(np.arange(di.size) % 2 == 0, 1.0, -1.0) for di in d]
             for sign in (1.0, -1.0):
                 g_shift = [np.asarray(g, dtype=np.float64).reshape(-1) + sign * di for g, di in zip(gh, d)]
                 shifted.append(self._variant(h, g_shift, t, stored)[0])
@@ -454,8 +462,14 @@ def compare_states(gpu: GpuNovak, states: List[O.TensorState], strict: bool = Tr
     """Every element of theta, m, v against the oracle's state: |d| <= 1e-7 + 1e-5 |ref|, plus the
     scale-aware check.  (After a step-by-step run the oracle's state is one step from the GPU's.)"""
     th, m, v = gpu.host("theta"), gpu.host("m"), gpu.host("v")
+    # the scale of a tensor too small to have one (a moment that has just cancelled would be its own yardstick) is the list's
+    whole = {}
+    for role, refs in (("theta", [st.theta for st in states]), ("m", [st.m for st in states]), ("v", [st.v for st in states])):
+        sq = sum(float(np.sum(r.astype(np.float64) ** 2)) for r in refs)
+        cnt = sum(r.size for r in refs)
+        whole[role] = (sq / cnt) ** 0.5 if cnt else 0.0
     for i, st in enumerate(states):
         for role, got, ref in (("theta", th[i], st.theta), ("m", m[i], st.m), ("v", v[i], st.v)):
             assert_close(f"{tag}{role}[{i}]", got, ref)
             if strict and ref.size:
-                assert_close_strict(f"{tag}{role}[{i}]", got, ref)
+                assert_close_strict(f"{tag}{role}[{i}]", got, ref, scale=whole[role] if ref.size < STRICT_MIN_SIZE else None)

@@ -5,6 +5,8 @@ is u = c1 g~ / (c2 |g~| + eps): a smoothed sign(g~) whose transition is ~eps wid
 cancellation (g + lambda*theta with coupled decay, Eq. 13's g + beta_N (g - m)), an fp32 evaluation carries an
 error of the size of the TERMS' roundings, and theta moves by far more than 1e-7 + 1e-5 |theta|.  The tests below
 show the effect with the oracle alone, then run an fp32 evaluation of the step through the harness's CheckedOracle."""
+import dataclasses
+
 import numpy as np
 import pytest
 
@@ -85,6 +87,37 @@ def test_interval_policy_accepts_an_fp32_evaluation_and_nothing_wider():
         bad[k] += f32(1e-4)
         with pytest.raises(AssertionError, match="theta"):
             check(bad)
+
+
+def test_interval_policy_survives_centralization():
+    """The same with Eq. 26 in front on a tensor that is one row: a shift that every element shared would vanish
+    with the row mean, so the policy shifts neighbouring elements in opposite directions."""
+    rng = np.random.default_rng(12)
+    n = 1 << 13
+    h = O.Hyper(lr=1e-2, weight_decay=1e-2, decoupled_decay=False, rectified=False, nesterov="none", lookahead="none", use_gc=True)
+    theta = rng.normal(0.0, 0.02, n).astype(f32)
+    left = np.sign(rng.normal(size=n)) * 10.0 ** rng.uniform(-9.0, -5.0, n)
+    c = left - h.weight_decay * theta.astype(np.float64)      # the centralized gradient that cancels against the decay
+    c[-1] = -np.sum(c[:-1])                                   # a centralized row has mean 0
+    g = (c + 3e-3).astype(f32)                                # the raw gradient: the same plus a row mean
+    mean = float(np.mean(g.astype(np.float64)))
+    gc = (g.astype(np.float64) - mean).astype(f32)            # Eq. 26 rounded once, then the step in fp32
+    th, m, v = _fp32_first_step(theta, gc, dataclasses.replace(h, use_gc=False))
+
+    states = [O.init_state(theta, h, rows=1)]
+    ck = H.CheckedOracle(states, h, "f32")
+    ck.load([theta], [np.zeros(n, f32)], [np.zeros(n, f32)])
+    ck.step([g], 1, [th], [m], [v])
+    nominal = O.init_state(theta, h, rows=1)
+    O.step(nominal, g, 1, h)
+    outside = ~H._close(th, nominal.theta)
+    assert outside.sum() > 100 and ck.in_interval == int(outside.sum())
+    # with one common shift for the whole row the interval collapses and the same evaluation is refused
+    d_common = 1e-9
+    a, b = O.init_state(theta, h, rows=1), O.init_state(theta, h, rows=1)
+    O.step(a, g.astype(np.float64) + d_common, 1, h)
+    O.step(b, g.astype(np.float64) - d_common, 1, h)
+    assert np.max(np.abs(a.theta.astype(np.float64) - b.theta)) < 1e-7      # the shift dropped out with the mean
 
 
 def test_which_runs_are_compared_step_by_step():
