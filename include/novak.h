@@ -384,8 +384,8 @@ int novak_get_info(const novak_handle *h, novak_info *info);
 
 /* Adjusts a launch parameter (NOVAK_TUNE_*); rebuilds the chunk table when needed (that waits for the
  * device).  It takes no stream: call it when the handle's earlier steps have finished (synchronise their
- * stream first).  Results do not depend on tuning values.  The bfloat16-moment and the centralizing step kernels
- * exist only in the default launch shape and ignore THREADS / VEC_PER_LANE.  If a table rebuild fails
+ * stream first).  Results do not depend on tuning values.  The bfloat16-moment, the centralizing and the adaptive-beta step
+ * kernels exist only in the default launch shape and ignore THREADS / VEC_PER_LANE.  If a table rebuild fails
  * after the old tables were released, the handle keeps none: every later call on it but novak_destroy,
  * novak_get_info and novak_last_error returns NOVAK_ERR_STATE. */
 int novak_set_tuning(novak_handle *h, int32_t key, int64_t value);

@@ -372,50 +372,63 @@ void launch_step_block(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s
   }
 }
 
-// Centralization and the bfloat16 first moment are compiled into the default launch shape only
-// (one wave64 per 256 elements).
-template <typename GradS, typename GradV, bool NT, bool GC, typename MomS, typename MomV>
+// Centralization, the bfloat16 first moment and the adaptive-beta moment updates are compiled into the default
+// launch shape only (one wave64 per 256 elements).
+template <typename GradS, typename GradV, bool NT, bool GC, typename MomS, typename MomV, bool AB>
 void launch_step_special(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
   const StreamCount n = step_streams(grad_dtype, la, sizeof(MomS) == 2);
   const Geometry gm = geometry_of(h, 256, 64, n.wide, n.narrow);
   const dim3 grid(gm.grid), block(64);
   switch (la) {
-    case LA_OFF: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_OFF, NT, 1, 64, GC, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
-    case LA_FIRST: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_FIRST, NT, 1, 64, GC, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
-    case LA_MID: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_MID, NT, 1, 64, GC, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
-    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_LAST_FUSED, NT, 1, 64, GC, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
-    default: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_BASIC_FUSED, NT, 1, 64, GC, MomS, MomV>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_OFF: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_OFF, NT, 1, 64, GC, MomS, MomV, AB>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_FIRST: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_FIRST, NT, 1, 64, GC, MomS, MomV, AB>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_MID: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_MID, NT, 1, 64, GC, MomS, MomV, AB>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    case LA_LAST_FUSED: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_LAST_FUSED, NT, 1, 64, GC, MomS, MomV, AB>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+    default: hipLaunchKernelGGL((novak_step_kernel<GradS, GradV, LA_BASIC_FUSED, NT, 1, 64, GC, MomS, MomV, AB>), grid, block, gm.lds, s, tb, c, gm.sub_shift); break;
+  }
+}
+
+template <bool GC, typename MomS, typename MomV, bool AB>
+void launch_step_special_dtype(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+  if (grad_dtype == NOVAK_GRAD_BF16) {
+    if (h->nontemporal) launch_step_special<unsigned short, u16x4, true, GC, MomS, MomV, AB>(h, grad_dtype, la, s, tb, c);
+    else launch_step_special<unsigned short, u16x4, false, GC, MomS, MomV, AB>(h, grad_dtype, la, s, tb, c);
+  } else {
+    if (h->nontemporal) launch_step_special<float, f32x4, true, GC, MomS, MomV, AB>(h, grad_dtype, la, s, tb, c);
+    else launch_step_special<float, f32x4, false, GC, MomS, MomV, AB>(h, grad_dtype, la, s, tb, c);
   }
 }
 
 template <bool GC, typename MomS, typename MomV>
-void launch_step_special_dtype(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
-  if (grad_dtype == NOVAK_GRAD_BF16) {
-    if (h->nontemporal) launch_step_special<unsigned short, u16x4, true, GC, MomS, MomV>(h, grad_dtype, la, s, tb, c);
-    else launch_step_special<unsigned short, u16x4, false, GC, MomS, MomV>(h, grad_dtype, la, s, tb, c);
-  } else {
-    if (h->nontemporal) launch_step_special<float, f32x4, true, GC, MomS, MomV>(h, grad_dtype, la, s, tb, c);
-    else launch_step_special<float, f32x4, false, GC, MomS, MomV>(h, grad_dtype, la, s, tb, c);
-  }
+void launch_step_special_ab(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
+  if (h->hp.adaptive_beta) launch_step_special_dtype<GC, MomS, MomV, true>(h, grad_dtype, la, s, tb, c);
+  else launch_step_special_dtype<GC, MomS, MomV, false>(h, grad_dtype, la, s, tb, c);
 }
 
 void launch_step(const LaunchCtx *h, int grad_dtype, int la, hipStream_t s, const Tables &tb, const Consts &c) {
   const bool gc = (c.flags & F_GC) != 0;
   const bool bf16_m = h->hp.moment_dtype == NOVAK_MOMENT_BF16_M;
-  if (gc && bf16_m) return launch_step_special_dtype<true, unsigned short, u16x4>(h, grad_dtype, la, s, tb, c);
-  if (bf16_m) return launch_step_special_dtype<false, unsigned short, u16x4>(h, grad_dtype, la, s, tb, c);
-  if (gc) return launch_step_special_dtype<true, float, f32x4>(h, grad_dtype, la, s, tb, c);
+  if (gc && bf16_m) return launch_step_special_ab<true, unsigned short, u16x4>(h, grad_dtype, la, s, tb, c);
+  if (bf16_m) return launch_step_special_ab<false, unsigned short, u16x4>(h, grad_dtype, la, s, tb, c);
+  if (gc) return launch_step_special_ab<true, float, f32x4>(h, grad_dtype, la, s, tb, c);
+  if (h->hp.adaptive_beta) return launch_step_special_dtype<false, float, f32x4, true>(h, grad_dtype, la, s, tb, c);
   if (h->nontemporal) launch_step_block<true>(h, grad_dtype, la, s, tb, c);
   else launch_step_block<false>(h, grad_dtype, la, s, tb, c);
 }
 
 // Device-step mode: the kernel that takes constants and lookahead phase from device memory (default shape).
+template <typename GradS, typename GradV, int LA, bool NT, bool GC, bool AB>
+void launch_step_device_ab(const LaunchCtx *h, const dim3 &grid, unsigned lds, int sub_shift, hipStream_t s, const Tables &tb) {
+  if (h->hp.moment_dtype == NOVAK_MOMENT_BF16_M)
+    hipLaunchKernelGGL((novak_step_device_kernel<GradS, GradV, LA, NT, GC, unsigned short, u16x4, AB>), grid, dim3(64), lds, s, tb, h->d_step, sub_shift);
+  else
+    hipLaunchKernelGGL((novak_step_device_kernel<GradS, GradV, LA, NT, GC, float, f32x4, AB>), grid, dim3(64), lds, s, tb, h->d_step, sub_shift);
+}
+
 template <typename GradS, typename GradV, int LA, bool NT, bool GC>
 void launch_step_device_mom(const LaunchCtx *h, const dim3 &grid, unsigned lds, int sub_shift, hipStream_t s, const Tables &tb) {
-  if (h->hp.moment_dtype == NOVAK_MOMENT_BF16_M)
-    hipLaunchKernelGGL((novak_step_device_kernel<GradS, GradV, LA, NT, GC, unsigned short, u16x4>), grid, dim3(64), lds, s, tb, h->d_step, sub_shift);
-  else
-    hipLaunchKernelGGL((novak_step_device_kernel<GradS, GradV, LA, NT, GC, float, f32x4>), grid, dim3(64), lds, s, tb, h->d_step, sub_shift);
+  if (h->hp.adaptive_beta) launch_step_device_ab<GradS, GradV, LA, NT, GC, true>(h, grid, lds, sub_shift, s, tb);
+  else launch_step_device_ab<GradS, GradV, LA, NT, GC, false>(h, grid, lds, sub_shift, s, tb);
 }
 
 template <typename GradS, typename GradV, int LA>
@@ -478,17 +491,23 @@ void launch_apply(int la, const Geometry &gm, hipStream_t s, const Tables &tb, c
   }
 }
 
-template <typename MomS, typename MomV>
-void launch_moments(const LaunchCtx *h, int grad_dtype, const Geometry &g1, hipStream_t s, const Tables &tb, const Consts &c) {
+template <typename MomS, typename MomV, bool AB>
+void launch_moments_ab(const LaunchCtx *h, int grad_dtype, const Geometry &g1, hipStream_t s, const Tables &tb, const Consts &c) {
   const dim3 grid1(g1.grid), block(kScaledBlock);
   const bool nt = h->nontemporal != 0;
   if (grad_dtype == NOVAK_GRAD_BF16) {
-    if (nt) hipLaunchKernelGGL((novak_moments_kernel<unsigned short, u16x4, true, MomS, MomV>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
-    else hipLaunchKernelGGL((novak_moments_kernel<unsigned short, u16x4, false, MomS, MomV>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
+    if (nt) hipLaunchKernelGGL((novak_moments_kernel<unsigned short, u16x4, true, MomS, MomV, AB>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
+    else hipLaunchKernelGGL((novak_moments_kernel<unsigned short, u16x4, false, MomS, MomV, AB>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
   } else {
-    if (nt) hipLaunchKernelGGL((novak_moments_kernel<float, f32x4, true, MomS, MomV>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
-    else hipLaunchKernelGGL((novak_moments_kernel<float, f32x4, false, MomS, MomV>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
+    if (nt) hipLaunchKernelGGL((novak_moments_kernel<float, f32x4, true, MomS, MomV, AB>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
+    else hipLaunchKernelGGL((novak_moments_kernel<float, f32x4, false, MomS, MomV, AB>), grid1, block, g1.lds, s, tb, c, g1.sub_shift, h->d_partials);
   }
+}
+
+template <typename MomS, typename MomV>
+void launch_moments(const LaunchCtx *h, int grad_dtype, const Geometry &g1, hipStream_t s, const Tables &tb, const Consts &c) {
+  if (h->hp.adaptive_beta) launch_moments_ab<MomS, MomV, true>(h, grad_dtype, g1, s, tb, c);
+  else launch_moments_ab<MomS, MomV, false>(h, grad_dtype, g1, s, tb, c);
 }
 
 // Gradient pre-pass: one read of the gradients gives each chunk's sum of squares (clipping) and the row sums
@@ -629,17 +648,23 @@ void launch_apply_device_la(const LaunchCtx *h, const Geometry &gm, hipStream_t 
   }
 }
 
-template <typename MomS, typename MomV>
-void launch_moments_device(const LaunchCtx *h, int grad_dtype, const Geometry &g1, hipStream_t s, const Tables &tb) {
+template <typename MomS, typename MomV, bool AB>
+void launch_moments_device_ab(const LaunchCtx *h, int grad_dtype, const Geometry &g1, hipStream_t s, const Tables &tb) {
   const dim3 grid1(g1.grid), block(kScaledBlock);
   const bool nt = h->nontemporal != 0;
   if (grad_dtype == NOVAK_GRAD_BF16) {
-    if (nt) hipLaunchKernelGGL((novak_moments_device_kernel<unsigned short, u16x4, true, MomS, MomV>), grid1, block, g1.lds, s, tb, h->d_step, g1.sub_shift, h->d_partials);
-    else hipLaunchKernelGGL((novak_moments_device_kernel<unsigned short, u16x4, false, MomS, MomV>), grid1, block, g1.lds, s, tb, h->d_step, g1.sub_shift, h->d_partials);
+    if (nt) hipLaunchKernelGGL((novak_moments_device_kernel<unsigned short, u16x4, true, MomS, MomV, AB>), grid1, block, g1.lds, s, tb, h->d_step, g1.sub_shift, h->d_partials);
+    else hipLaunchKernelGGL((novak_moments_device_kernel<unsigned short, u16x4, false, MomS, MomV, AB>), grid1, block, g1.lds, s, tb, h->d_step, g1.sub_shift, h->d_partials);
   } else {
-    if (nt) hipLaunchKernelGGL((novak_moments_device_kernel<float, f32x4, true, MomS, MomV>), grid1, block, g1.lds, s, tb, h->d_step, g1.sub_shift, h->d_partials);
-    else hipLaunchKernelGGL((novak_moments_device_kernel<float, f32x4, false, MomS, MomV>), grid1, block, g1.lds, s, tb, h->d_step, g1.sub_shift, h->d_partials);
+    if (nt) hipLaunchKernelGGL((novak_moments_device_kernel<float, f32x4, true, MomS, MomV, AB>), grid1, block, g1.lds, s, tb, h->d_step, g1.sub_shift, h->d_partials);
+    else hipLaunchKernelGGL((novak_moments_device_kernel<float, f32x4, false, MomS, MomV, AB>), grid1, block, g1.lds, s, tb, h->d_step, g1.sub_shift, h->d_partials);
   }
+}
+
+template <typename MomS, typename MomV>
+void launch_moments_device(const LaunchCtx *h, int grad_dtype, const Geometry &g1, hipStream_t s, const Tables &tb) {
+  if (h->hp.adaptive_beta) launch_moments_device_ab<MomS, MomV, true>(h, grad_dtype, g1, s, tb);
+  else launch_moments_device_ab<MomS, MomV, false>(h, grad_dtype, g1, s, tb);
 }
 
 hipError_t launch_sync(const LaunchCtx *h, hipStream_t s) {

@@ -44,7 +44,10 @@ enum : int {
 };
 constexpr bool la_runtime(int la) { return la >= LA_RUNTIME_ME; }
 
-enum : uint32_t { F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u, F_CLIP = 16u, F_SPARSE = 32u, F_GC = 64u, F_AUTO = 128u };
+enum : uint32_t {
+  F_APPROX = 1u, F_CLASSICAL = 2u, F_DENOM = 4u, F_COUPLED = 8u, F_CLIP = 16u, F_SPARSE = 32u, F_GC = 64u, F_AUTO = 128u,
+  F_LITERAL_M = 256u, F_LITERAL_V = 512u   // adaptive-beta kernels only: this step evaluates Eq. 1 / Eq. 2 as printed
+};
 
 // The four state pointers of a tensor sit together so that one 32-byte scalar load fetches them.
 struct TensorPtrs {
@@ -115,6 +118,7 @@ struct Consts {
   float la_c0, la_c1;    // lookahead blend coefficients (meaning depends on the LA phase)
   float sparse_tau;      // tau of Eq. 27 (used when F_SPARSE is set)
   float blend_w;         // 1-beta1 of Eq. 16 (base beta1; omb1 follows the schedule of Eq. 3)
+  float beta1_t, beta2_t;  // the scheduled betas of Eq. 3-4 (read by the adaptive-beta kernels only)
   uint32_t flags;
 };
 
@@ -126,7 +130,7 @@ struct DeviceStep {
   int la;              // LA_* phase of this step
   int64_t t;           // the step's number
   int64_t *counter;    // the caller's step counter: the step's last kernel stores t there
-  int pad[12];
+  int pad[10];
 };
 static_assert(sizeof(DeviceStep) == 128, "one record per 128 bytes");
 
@@ -190,6 +194,11 @@ __device__ __forceinline__ void store_mom(MomS *p, float m) {
 //   moments():   Phases 2 and 4 - gradient processing and the two EMAs (Eq. 13, 1, 2)
 //   direction(): Phases 5 and 8a - bias correction and the base direction u (Eq. 5, 17)
 //   apply():     Phases 8b, 9, 10 - classical blend, decay + update, lookahead (Eq. 16, 18, 24, 28-31)
+// AB: compiled for handles with the adaptive-beta schedule of Eq. 3-4, whose betas start near 0.  There the
+// difference form rounds at the magnitude of the OLD moment although the new one is ~beta(t) times smaller (an element
+// whose gradient has dropped keeps a relative error of 2^-24 / beta(t)), so while beta(t) <= 1/2 Eq. 1-2 are evaluated
+// as printed (the rounding of beta and 1 - beta, which do not add up to 1 exactly, is amplified by at most 2 there).
+template <bool AB = false>
 __device__ __forceinline__ void moments(float th_in, float g, float &m, float &v, const Consts &c, float gs) {
   if (c.flags & F_CLIP) g *= gs;                                        // global-norm clipping comes first
   if (c.flags & F_COUPLED) g = __builtin_fmaf(c.wd, th_in, g);          // classic L2 reading
@@ -197,6 +206,10 @@ __device__ __forceinline__ void moments(float th_in, float g, float &m, float &v
   const float m_in = m, v_in = v;
   m = __builtin_fmaf(c.omb1, g - m, m);                                 // Eq. 1:  m + (1-b1)(g - m)
   v = __builtin_fmaf(c.omb2, __builtin_fmaf(g, g, -v), v);              // Eq. 2:  v + (1-b2)(g^2 - v)
+  if constexpr (AB) {
+    if (c.flags & F_LITERAL_M) m = __builtin_fmaf(c.omb1, g, c.beta1_t * m_in);        // Eq. 1 as printed
+    if (c.flags & F_LITERAL_V) v = __builtin_fmaf(c.omb2, g * g, c.beta2_t * v_in);    // Eq. 2 as printed
+  }
   // A moment that has overflowed stays infinite under Eq. 1-2 as printed (beta*inf + finite); the
   // difference form above would turn it into inf - inf.  With v = inf the direction is 0 and theta only decays.
   const bool g_finite = __builtin_fabsf(g) < __builtin_inff();
@@ -244,9 +257,9 @@ __device__ __forceinline__ void apply(float &th, float u, float m_hat, float &la
   }
 }
 
-template <int LA, typename MomS = float>
+template <int LA, typename MomS = float, bool AB = false>
 __device__ __forceinline__ void update_one(float &th, float g, float &m, float &v, float &la, const Consts &c, float gs, float step, int la_rt = LA_OFF) {
-  moments(th, g, m, v, c, gs);
+  moments<AB>(th, g, m, v, c, gs);
   m = round_mom<MomS>(m);          // the stored m_t is what the rest of the step uses
   float m_hat;
   const float u = direction(m, v, c, m_hat);
@@ -282,12 +295,12 @@ __device__ __forceinline__ f32x4 grad_to_f32<u16x4>(u16x4 g) {
   return r;
 }
 
-template <int LA, typename MomS = float>
+template <int LA, typename MomS = float, bool AB = false>
 __device__ __forceinline__ void update_vec(f32x4 &th, f32x4 g, f32x4 &m, f32x4 &v, f32x4 &la, const Consts &c, float gs, float step, int la_rt = LA_OFF) {
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     float th_k = th[k], m_k = m[k], v_k = v[k], la_k = la[k];
-    update_one<LA, MomS>(th_k, g[k], m_k, v_k, la_k, c, gs, step, la_rt);
+    update_one<LA, MomS, AB>(th_k, g[k], m_k, v_k, la_k, c, gs, step, la_rt);
     th[k] = th_k; m[k] = m_k; v[k] = v_k; la[k] = la_k;
   }
 }
@@ -308,8 +321,9 @@ __host__ __device__ constexpr bool la_writes(int la) { return la == LA_FIRST || 
 // the default shape UN = 1, BLOCK = 64).
 // MomS / MomV: storage type of the first moment and its 4-vector (float / f32x4, or unsigned short /
 // u16x4 for bfloat16; the latter also only for UN = 1, BLOCK = 64).
+// AB: the adaptive-beta variant of the moment updates (see moments; also only for UN = 1, BLOCK = 64).
 template <typename GradS, typename GradV, int LA, bool NT, int UN, int BLOCK, bool GC = false, typename MomS = float,
-          typename MomV = f32x4, bool DEV = false>
+          typename MomV = f32x4, bool DEV = false, bool AB = false>
 __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg, int sub_shift, const DeviceStep *ds = nullptr) {
   constexpr int SUB = BLOCK * 4 * UN;
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
@@ -380,7 +394,7 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
         f32x4 gf = grad_to_f32<GradV>(g[u]);
         if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(j), gi);
         f32x4 mf = mom_to_f32<MomV>(m[u]);
-        update_vec<LA, MomS>(th[u], gf, mf, v[u], la[u], c, gs, step, la_rt);
+        update_vec<LA, MomS, AB>(th[u], gf, mf, v[u], la[u], c, gs, step, la_rt);
         st<NT>(th4 + j, th[u]);
         st<NT>(m4 + j, f32_to_mom<MomV>(mf));
         st<NT>(v4 + j, v[u]);
@@ -395,7 +409,7 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
       if (reads) la = ld<NT>(la4 + i);
       f32x4 gf = grad_to_f32<GradV>(g);
       if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(i), gi);
-      update_vec<LA, MomS>(th, gf, m, v, la, c, gs, step, la_rt);
+      update_vec<LA, MomS, AB>(th, gf, m, v, la, c, gs, step, la_rt);
       st<NT>(th4 + i, th);
       st<NT>(m4 + i, f32_to_mom<MomV>(m));
       st<NT>(v4 + i, v);
@@ -410,7 +424,7 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
     else g = g_p[i];
     if (reads) la = la_p[i];
     if (GC && gi.cols) g = centralize_one(g, off + i, gi);
-    update_one<LA, MomS>(th, g, m, v, la, c, gs, step, la_rt);
+    update_one<LA, MomS, AB>(th, g, m, v, la, c, gs, step, la_rt);
     th_p[i] = th;
     store_mom<MomS>(m_p + i, m);
     v_p[i] = v;
@@ -419,9 +433,9 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
 }
 
 template <typename GradS, typename GradV, int LA, bool NT, int UN, int BLOCK, bool GC = false, typename MomS = float,
-          typename MomV = f32x4>
+          typename MomV = f32x4, bool AB = false>
 __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, int sub_shift) {
-  step_body<GradS, GradV, LA, NT, UN, BLOCK, GC, MomS, MomV>(tb, c, sub_shift);
+  step_body<GradS, GradV, LA, NT, UN, BLOCK, GC, MomS, MomV, false, AB>(tb, c, sub_shift);
 }
 
 // Device-step mode: what the step is (constants, lookahead phase) was written to device memory by
@@ -429,9 +443,9 @@ __global__ __launch_bounds__(BLOCK) void novak_step_kernel(Tables tb, Consts c, 
 // LA_RUNTIME_ME or LA_RUNTIME_BASIC: one body in which the lookahead blend and store are selected by the wave-uniform
 // phase (compiling the phase bodies behind a switch made the compiler merge them and lose the "all loads first"
 // order: -10 %).  Default launch shape only (one wave64 per 256 elements).
-template <typename GradS, typename GradV, int LA, bool NT, bool GC, typename MomS, typename MomV>
+template <typename GradS, typename GradV, int LA, bool NT, bool GC, typename MomS, typename MomV, bool AB>
 __global__ __launch_bounds__(64) void novak_step_device_kernel(Tables tb, const DeviceStep *ds, int sub_shift) {
-  step_body<GradS, GradV, LA, NT, 1, 64, GC, MomS, MomV, true>(tb, Consts(), sub_shift, ds);
+  step_body<GradS, GradV, LA, NT, 1, 64, GC, MomS, MomV, true, AB>(tb, Consts(), sub_shift, ds);
 }
 
 // What step t does: the kernel constants (scalar prologue of Phases 5-6 rounded to fp32) and the lookahead
@@ -450,6 +464,8 @@ __host__ __device__ inline void plan_step(const novak_hparams &hp, int64_t step,
   Consts c = Consts();
   c.omb1 = static_cast<float>(1.0 - sc.beta1_t);      // the moment updates follow Eq. 3-4 when scheduled
   c.omb2 = static_cast<float>(1.0 - sc.beta2_t);
+  c.beta1_t = static_cast<float>(sc.beta1_t);
+  c.beta2_t = static_cast<float>(sc.beta2_t);
   c.blend_w = static_cast<float>(1.0 - hp.beta1);
   c.beta1 = static_cast<float>(hp.beta1);
   c.beta_n = static_cast<float>(hp.beta_n);
@@ -465,6 +481,8 @@ __host__ __device__ inline void plan_step(const novak_hparams &hp, int64_t step,
   if (sc.denom_on) c.flags |= F_DENOM;
   if (!hp.decoupled_decay && hp.weight_decay != 0.0) c.flags |= F_COUPLED;
   if (hp.clip_threshold > 0.0) c.flags |= F_CLIP;
+  if (hp.adaptive_beta && sc.beta1_t <= 0.5) c.flags |= F_LITERAL_M;
+  if (hp.adaptive_beta && sc.beta2_t <= 0.5) c.flags |= F_LITERAL_V;
   if (hp.sparse_threshold > 0.0) {
     c.flags |= F_SPARSE;
     c.sparse_tau = static_cast<float>(hp.sparse_threshold);
@@ -509,7 +527,7 @@ __global__ __launch_bounds__(kDeviceRing) void novak_prologue_kernel(novak_hpara
   d.t = t;
   d.counter = counter;
 #pragma unroll
-  for (int i = 0; i < 12; ++i) d.pad[i] = 0;
+  for (int i = 0; i < 10; ++i) d.pad[i] = 0;
   out[threadIdx.x] = d;
 }
 
@@ -637,7 +655,7 @@ __device__ __forceinline__ double wave_sum(double x) {
 }
 
 // `c_arg` holds the step's constants, or (DEV, device-step mode) `ds` points to them in device memory.
-template <typename GradS, typename GradV, bool NT, typename MomS, typename MomV, bool DEV>
+template <typename GradS, typename GradV, bool NT, typename MomS, typename MomV, bool DEV, bool AB>
 __device__ __forceinline__ void moments_body(const Tables &tb, const Consts &c_arg, int sub_shift, NormPartial *partials, const DeviceStep *ds) {
   const novak_chunk ch = tb.chunks[blockIdx.x >> sub_shift];
   const int start = static_cast<int>(blockIdx.x & ((1u << sub_shift) - 1u)) * kScaledSub;
@@ -681,7 +699,7 @@ __device__ __forceinline__ void moments_body(const Tables &tb, const Consts &c_a
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         float m_k = m[k], v_k = v[k], m_hat;
-        moments(th[k], g[k], m_k, v_k, c, gs);
+        moments<AB>(th[k], g[k], m_k, v_k, c, gs);
         m_k = round_mom<MomS>(m_k);
         const float u = direction(m_k, v_k, c, m_hat);
         s_th = __builtin_fmaf(th[k], th[k], s_th);
@@ -700,7 +718,7 @@ __device__ __forceinline__ void moments_body(const Tables &tb, const Consts &c_a
     else g = g_p[i];
     s_g = __builtin_fmaf(g, g, s_g);
     if (gi.cols) g = centralize_one(g, off + i, gi);
-    moments(th, g, m, v, c, gs);
+    moments<AB>(th, g, m, v, c, gs);
     m = round_mom<MomS>(m);
     const float u = direction(m, v, c, m_hat);
     s_th = __builtin_fmaf(th, th, s_th);
@@ -718,13 +736,13 @@ __device__ __forceinline__ void moments_body(const Tables &tb, const Consts &c_a
   }
 }
 
-template <typename GradS, typename GradV, bool NT, typename MomS = float, typename MomV = f32x4>
+template <typename GradS, typename GradV, bool NT, typename MomS, typename MomV, bool AB>
 __global__ __launch_bounds__(kScaledBlock) void novak_moments_kernel(Tables tb, Consts c, int sub_shift, NormPartial *partials) {
-  moments_body<GradS, GradV, NT, MomS, MomV, false>(tb, c, sub_shift, partials, nullptr);
+  moments_body<GradS, GradV, NT, MomS, MomV, false, AB>(tb, c, sub_shift, partials, nullptr);
 }
-template <typename GradS, typename GradV, bool NT, typename MomS = float, typename MomV = f32x4>
+template <typename GradS, typename GradV, bool NT, typename MomS, typename MomV, bool AB>
 __global__ __launch_bounds__(kScaledBlock) void novak_moments_device_kernel(Tables tb, const DeviceStep *ds, int sub_shift, NormPartial *partials) {
-  moments_body<GradS, GradV, NT, MomS, MomV, true>(tb, Consts(), sub_shift, partials, ds);
+  moments_body<GradS, GradV, NT, MomS, MomV, true, AB>(tb, Consts(), sub_shift, partials, ds);
 }
 
 // one wave per chunk: sums the chunk's per-wave partials in a fixed order

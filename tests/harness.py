@@ -346,7 +346,7 @@ class CheckedOracle:
                 d.append(FP32_SLACK * FP32_UNIT * e / gs)
             # neighbouring elements are shifted in opposite directions: a shift that all elements of a row shared
             # would drop out of Eq. 26 with the row's mean
-            d = [di * np.where(np.arange(di.size) % 2 == 0, 1.0, -1.0) for di in d]
+            d = [di * np.where(np.arange(st.theta.size) % 2 == 0, 1.0, -1.0) for di, st in zip(d, nominal)]
             for sign in (1.0, -1.0):
                 g_shift = [np.asarray(g, dtype=np.float64).reshape(-1) + sign * di for g, di in zip(gh, d)]
                 shifted.append(self._variant(h, g_shift, t, stored)[0])

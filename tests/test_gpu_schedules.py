@@ -33,6 +33,34 @@ def test_adaptive_beta(nesterov, lookahead, grad_dtype, two_pass):
         gpu.close()
 
 
+@pytest.mark.parametrize("variant", ["single_pass", "device_step", "two_pass", "bf16_m"])
+def test_adaptive_beta_keeps_a_small_second_moment_accurate(variant):
+    """While beta_2(t) is near 0 (t << tau_2) the new v is ~beta_2(t) times the old one wherever the gradient has
+    dropped; with gradients of order 1 that is far above the absolute floor of the bound, so v must be right in
+    RELATIVE terms on every element (an evaluation that rounds at the old moment's magnitude is off by
+    2^-24 / beta_2(t) ~ 1e-4 there)."""
+    numels = [70001, 4097, 255, 1]
+    # (no Nesterov term: the gradient that enters Eq. 2 is an input, so the EMA's own roundings are all there is)
+    hyper = dict(W.get_workload("ragged").hyper, adaptive_beta=True, lookahead="none", nesterov="none", mode="research",
+                 layer_adaptation=variant == "two_pass", moment_dtype="bf16_m" if variant == "bf16_m" else "f32",
+                 device_step=variant == "device_step")
+    steps = 6
+    gpu, states, h = H.run_pair(numels, hyper, steps, 1.0, auto_sync=True, seed=7)
+    try:
+        H.compare_states(gpu, states, strict=False)
+        b2 = O.scheduled_betas(h, steps)[1]
+        assert b2 < 2e-3
+        dropped = 0
+        for got, st in zip(gpu.host("v"), states):
+            ref = st.v.astype(np.float64)
+            assert np.all(ref > 0.0)
+            assert np.max(np.abs(got.astype(np.float64) - ref) / ref) < 1e-6
+            dropped += int((ref < 4.0 * b2).sum())                     # v_t ~ beta_2(t) v_{t-1}: the gradient dropped
+        assert dropped > 100
+    finally:
+        gpu.close()
+
+
 def test_true_nesterov_fallback_after_n_taylor_steps():
     wl = W.get_workload("ragged")
     hyper = dict(wl.hyper, nesterov="true", n_taylor=4, mode="research")
