@@ -165,14 +165,15 @@ class GpuNovak:
             self.handle = None
 
 
-def assert_close(name: str, got: np.ndarray, ref: np.ndarray, atol: float = ATOL, rtol: float = RTOL):
+def assert_close(name: str, got: np.ndarray, ref: np.ndarray, atol=ATOL, rtol: float = RTOL):
     got64, ref64 = got.astype(np.float64), ref.astype(np.float64)
     err = np.abs(got64 - ref64)
     bound = atol + rtol * np.abs(ref64)
     bad = ~(err <= bound)
     if bad.any():
         j = int(np.argmax(err - bound))
-        raise AssertionError(f"{name}: {int(bad.sum())}/{bad.size} elements outside |d| <= {atol} + {rtol}|ref|; "
+        a = float(np.asarray(atol).reshape(-1)[j]) if np.ndim(atol) else atol      # (a per-element floor: the worst element's)
+        raise AssertionError(f"{name}: {int(bad.sum())}/{bad.size} elements outside |d| <= {a} + {rtol}|ref|; "
                              f"worst at {j}: got {got64[j]!r} ref {ref64[j]!r} err {err[j]:.3e}")
 
 
@@ -210,6 +211,11 @@ def assert_close_strict(name: str, got: np.ndarray, ref: np.ndarray, rtol: float
 #     gradients shifted by that error in both directions (odd and even elements in opposite directions, so that
 #     the shift survives the row means of Eq. 26), and theta must lie in the interval the three results span (plus
 #     the bound).
+# (4) fp32 m where Eq. 1 cancels: beta1 m + (1-beta1) g~ can be far smaller than its terms, and ANY fp32 evaluation
+#     keeps an absolute error of a few roundings at the terms' magnitude - the same first-order model as in (1).  The
+#     step-by-step comparison therefore allows m that much on top of the bound.  With the workloads' gradients
+#     (1e-2 and below) the allowance is ~2e-9, a fiftieth of the bound's absolute floor; with gradients of order 1 and
+#     above, where the floor no longer hides anything, it is what makes the comparison of m possible at all.
 FP32_UNIT = 2.0 ** -24
 FP32_SLACK = 2.0
 PRE_UNITS = 3.0
@@ -367,7 +373,7 @@ class CheckedOracle:
                 self.resolved_total += int(resolved.sum())
                 self.either_way += int((gm != O.round_to_bf16(st.trace.m_exact)).sum())
             else:
-                assert_close(f"{name} m", got_m[i], st.m)
+                assert_close(f"{name} m", got_m[i], st.m, atol=ATOL + fp32_error_of_m(st.trace, m_prev[i], b1_t, preprocessed(h, st.rows)))
             self.elements_total += st.theta.size
             assert_close(f"{name} v", got_v[i], st.v)
             ok = _close(got_theta[i], st.theta)
@@ -423,19 +429,19 @@ def run_pair(numels: Sequence[int], hyper: Dict[str, object], steps: int, grad_s
              seed: int = 42, auto_sync: bool = False, chunk_elems: Optional[int] = None,
              nontemporal: Optional[bool] = None, misalign: int = 0, grad_misalign: int = 0, guard: int = 0,
              check_blend_at: Sequence[int] = (), vec_per_lane: Optional[int] = None, threads: Optional[int] = None,
-             rows: Optional[Sequence[int]] = None):
+             rows: Optional[Sequence[int]] = None, step_by_step: bool = False):
     """Runs GPU and oracle over host-generated inputs; returns (gpu, oracle states, oracle hyper) after `steps`.
 
     Plain runs are two independent trajectories compared at the end (compare_states).  Runs that take a
-    discontinuous decision (bfloat16 m, Eq. 27) are compared after EVERY step from a common state by a
-    CheckedOracle; compare_states then checks the final state once more."""
+    discontinuous decision (bfloat16 m, Eq. 27), or that ask for it (`step_by_step`), are compared after EVERY step
+    from a common state by a CheckedOracle; compare_states then checks the final state once more."""
     theta0 = W.host_params(numels, seed)
     gpu = GpuNovak(numels, hyper, grad_dtype, theta0, misalign=misalign, guard=guard, chunk_elems=chunk_elems,
                    nontemporal=nontemporal, auto_sync=auto_sync, vec_per_lane=vec_per_lane, threads=threads, rows=rows)
     h = oracle_hyper(hyper, gpu.eff_nesterov, gpu.eff_lookahead, gpu.info)
     states = [O.init_state(th, h, rows=gpu.rows[i]) for i, th in enumerate(theta0)]
     aux = O.AutoLrState()
-    checked = CheckedOracle(states, h, grad_dtype, aux) if needs_common_state(h) else None
+    checked = CheckedOracle(states, h, grad_dtype, aux) if (needs_common_state(h) or step_by_step) else None
     for t in range(1, steps + 1):
         gh = W.host_grads(numels, t, grad_std, seed, bf16=(grad_dtype == "bf16"))
         gd = gpu.upload_grads(gh, misalign=grad_misalign)

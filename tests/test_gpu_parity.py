@@ -554,3 +554,25 @@ def test_retuning_between_steps_changes_no_result(extra):
         assert gpu.guards_intact()
     finally:
         gpu.close()
+
+
+@pytest.mark.parametrize("two_pass", [False, True])
+@pytest.mark.parametrize("grad_std", [1.0, 100.0])
+def test_gradient_scales_far_above_the_absolute_floor(grad_std, two_pass):
+    """The workloads' gradients (1e-2 and below) leave v, and partly m, under the bound's absolute floor of 1e-7.
+    With gradients of order 1 and 100 nothing hides there: theta and v must meet the bound on every element after
+    every step (from a common state), and m the bound plus what any fp32 evaluation of Eq. 13 + Eq. 1 is off by
+    where the sum cancels (policy (4) of the harness)."""
+    wl = W.get_workload("ragged")
+    hyper = dict(wl.hyper, mode="research", layer_adaptation=two_pass)
+    gpu, states, h = H.run_pair(wl.numels, hyper, 11, grad_std, auto_sync=True, guard=8, step_by_step=True)
+    try:
+        th, v = gpu.host("theta"), gpu.host("v")
+        for i, st in enumerate(states):
+            H.assert_close(f"theta[{i}]", th[i], st.theta)
+            H.assert_close(f"v[{i}]", v[i], st.v)
+            if st.v.size:
+                assert np.median(st.v) > 1e-5                        # nothing under the floor
+        assert gpu.guards_intact()
+    finally:
+        gpu.close()
