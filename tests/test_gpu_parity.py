@@ -160,14 +160,16 @@ def test_resume_is_bitwise():
         part.close()
 
 
+@pytest.mark.parametrize("device_step", [False, True])
 @pytest.mark.parametrize("t0", [995, 9_995, 999_995, 49_999_995])
-def test_late_steps_start_from_a_given_state(t0):
+def test_late_steps_start_from_a_given_state(t0, device_step):
     """Steps far into a run (a fresh handle accepts any first step): the bias corrections go through
     expm1(t log beta) (section 5.8), r_t approaches 1 (Eq. 9) and the window position is t mod k.  Both sides
-    start from the same theta, m, v at step t0 (a multiple of k, so a window opens) and take 11 steps."""
+    start from the same theta, m, v at step t0 (a multiple of k, so a window opens) and take 11 steps.  With
+    `device_step` the count starts in device memory at t0 and the prologue is the device's own double arithmetic."""
     wl = W.get_workload("ragged")
     numels = wl.numels
-    hyper = dict(wl.hyper, nesterov="classical")
+    hyper = dict(wl.hyper, nesterov="classical", device_step=device_step)
     theta0 = W.host_params(numels, 100)
     rng = np.random.default_rng(t0)
     m0 = [rng.normal(0, 3e-3, n).astype(np.float32) for n in numels]
@@ -180,6 +182,8 @@ def test_late_steps_start_from_a_given_state(t0):
             st.m, st.v = m0[i].copy(), v0[i].copy()
             gpu.m[i].copy_(torch.from_numpy(m0[i]))
             gpu.v[i].copy_(torch.from_numpy(v0[i]))
+        if device_step:
+            gpu.counter.fill_(t0)
         for t in range(t0 + 1, t0 + 12):
             gh = W.host_grads(numels, t - t0, wl.grad_std, 100)
             N.check(gpu.step(t, gpu.upload_grads(gh)), f"step {t}", gpu.handle)
@@ -189,6 +193,8 @@ def test_late_steps_start_from_a_given_state(t0):
                     O.lookahead_sync(st, h)
         H.compare_states(gpu, states)
         assert gpu.guards_intact()
+        if device_step:
+            assert int(gpu.counter.item()) == t0 + 11
         rc, sc = N.novak_compute_step_scalars(N.make_hparams(**hyper), t0 + 11)
         assert sc.r_t == pytest.approx(O.step_scalars(h, t0 + 11).r_t, rel=1e-13) and sc.r_t > 0.64
     finally:
