@@ -45,6 +45,7 @@ def parse_args():
     ap.add_argument("--use-gc", action="store_true", help="research mode: gradient centralization of the multi-dimensional tensors")
     ap.add_argument("--clip", type=float, default=0.0, help="global-norm gradient clipping threshold (0 = off)")
     ap.add_argument("--sparse", type=float, default=0.0, help="sparse threshold tau of Eq. 27 (0 = off)")
+    ap.add_argument("--adaptive-beta", action="store_true", help="beta schedule of Eq. 3-4 (tau = 1000, 5000)")
     ap.add_argument("--moment-dtype", default="f32", choices=("f32", "bf16_m"),
                     help="storage of the first moment: fp32, or bfloat16 (reduced-precision state; not the headline configuration)")
     ap.add_argument("--layout", default="arena", choices=("arena", "torch_one", "separate", "separate_contiguous", "torch_pool"),
@@ -425,6 +426,8 @@ def main():
     if args.layer_adaptation or args.auto_lr or args.use_gc:
         hyper.update(mode="research", layer_adaptation=args.layer_adaptation, auto_lr=args.auto_lr, use_gc=args.use_gc)
     hyper.update(clip_threshold=args.clip, sparse_threshold=args.sparse, moment_dtype=args.moment_dtype)
+    if args.adaptive_beta:
+        hyper.update(adaptive_beta=True)
     fused = not args.separate_sync
     p = wl.total
 
@@ -458,7 +461,7 @@ def main():
                    "nesterov": nest_name, "lookahead": la_name, "la_k": k, "sync": "fused" if fused else "separate",
                    "mode": hyper["mode"], "rectified": bool(hyper["rectified"]),
                    "layer_adaptation": bool(info.layer_adaptation), "auto_lr": bool(info.auto_lr),
-                   "use_gc": bool(info.use_gc), "moment_dtype": args.moment_dtype, "clip_threshold": args.clip, "sparse_threshold": args.sparse,
+                   "use_gc": bool(info.use_gc), "moment_dtype": args.moment_dtype, "clip_threshold": args.clip, "sparse_threshold": args.sparse, "adaptive_beta": bool(args.adaptive_beta),
                    "step_count": "device" if args.device_step else "host", "graph_steps": int(args.graph_steps) if args.device_step else 0,
                    "chunk_elems": int(info.chunk_elems), "chunks": int(info.n_chunks), "layout": args.layout,
                    "arena_contiguous": bool(arena_contiguous)},
