@@ -439,7 +439,7 @@ def main():
     run.close()
     kernels, dominant = res["kernels"], res["dominant"]
     dk = kernels[dominant]
-    running = profiled_config_of(args, fused)
+    running = profiled_config_of(args, fused, int(info.chunk_elems))
     traffic, traffic_file = measured_traffic(args.workload, dominant, running)
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": dk["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": dk["GBps"] / HBM_PEAK_GBS, "avg_kernel_ms": dk["avg_ms"],
@@ -505,13 +505,13 @@ def main():
     print(json.dumps(result))
 
 
-def profiled_config_of(args, fused) -> str:
+def profiled_config_of(args, fused, chunk_elems: int) -> str:
     """The launch configuration as the profiles/ summaries state it (a counter figure is only carried over
     to a run of the same configuration)."""
     auto = lambda x, d: d if x is None else x
     if args.device_step:
         return "device_step"          # another kernel variant than the one the counters were taken on
-    return (f"layout={args.layout} chunk_elems={auto(args.chunk_elems, 16384)} waves_per_cu={auto(args.waves_per_cu, 0)} "
+    return (f"layout={args.layout} chunk_elems={chunk_elems} waves_per_cu={auto(args.waves_per_cu, 0)} "
             f"nontemporal={auto(args.nontemporal, 1)} vec_per_lane={auto(args.vec_per_lane, 1)} threads={auto(args.threads, 64)} "
             f"sync={'fused' if fused else 'separate'}")
 
