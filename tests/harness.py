@@ -298,6 +298,8 @@ class CheckedOracle:
       * coupled decay, adaptive beta: the oracle also runs on gradients shifted by -/+ the fp32 error of the
         gradient that feeds the moments; theta must meet the bound against the nominal result or lie in the
         interval the three results span;
+      * fp32 m: the bound plus the first-order error of an fp32 evaluation of Eq. 13 + Eq. 1 (policy (4): ~2e-9 at the
+        workloads' gradient scale, what the cancellation in Eq. 1 leaves at gradient scales of order 1 and above);
       * everything else: |got - ref| <= 1e-7 + 1e-5 |ref|.
     The state that continues (lookahead window included) is the variant the implementation agreed with.
     """
