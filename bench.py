@@ -15,6 +15,7 @@ from __future__ import annotations
 
 import argparse
 import ctypes as C
+import dataclasses
 import json
 import os
 import sys
@@ -45,6 +46,7 @@ def parse_args():
     ap.add_argument("--use-gc", action="store_true", help="research mode: gradient centralization of the multi-dimensional tensors")
     ap.add_argument("--clip", type=float, default=0.0, help="global-norm gradient clipping threshold (0 = off)")
     ap.add_argument("--sparse", type=float, default=0.0, help="sparse threshold tau of Eq. 27 (0 = off)")
+    ap.add_argument("--grad-dtype", default=None, choices=("f32", "bf16"), help="override the workload's gradient type")
     ap.add_argument("--adaptive-beta", action="store_true", help="beta schedule of Eq. 3-4 (tau = 1000, 5000)")
     ap.add_argument("--moment-dtype", default="f32", choices=("f32", "bf16_m"),
                     help="storage of the first moment: fp32, or bfloat16 (reduced-precision state; not the headline configuration)")
@@ -414,6 +416,8 @@ def main():
     torch.cuda.set_device(torch.device("cuda:0"))
 
     wl = W.get_workload(args.workload)
+    if args.grad_dtype:
+        wl = dataclasses.replace(wl, grad_dtype=args.grad_dtype)
     hyper = dict(wl.hyper)
     if args.lookahead:
         hyper["lookahead"] = args.lookahead

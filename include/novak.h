@@ -192,8 +192,8 @@ typedef struct novak_info {
 
 /* tuning keys for novak_set_tuning */
 enum {
-  NOVAK_TUNE_CHUNK_ELEMS = 0,   /* elements per chunk-table entry; a power of two in [4096, 2^24] (default 16384; 65536 for
-                                   lists of 2^29 elements and more that run a gradient pre-pass) */
+  NOVAK_TUNE_CHUNK_ELEMS = 0,   /* elements per chunk-table entry; a power of two in [4096, 2^24] (default 16384; a handle that
+                                   runs a gradient pre-pass starts with 65536, 16384 or 4096 by the size of its list) */
   NOVAK_TUNE_NONTEMPORAL = 1,   /* 0/1: non-temporal hints on the streaming loads and stores */
   NOVAK_TUNE_VEC_PER_LANE = 2,  /* 1, 2 or 4: 128-bit accesses per stream per lane */
   NOVAK_TUNE_THREADS = 3,       /* 64, 128 or 256 threads per workgroup; a workgroup covers threads*4*vec_per_lane elements */

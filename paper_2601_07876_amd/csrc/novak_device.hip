@@ -210,7 +210,6 @@ void free_device_tables(novak_handle *h) {
 
 int build_chunk_table_unguarded(novak_handle *h);
 bool fits_one_launch(int64_t n_chunks, int64_t chunk_elems);
-constexpr int64_t kLargeList = int64_t{1} << 29, kLargeListChunk = 65536;
 constexpr const char *kTooLarge = "the tensor list needs more than 2^32 - 1 threads in one launch (about 1.7e10 elements); split it over several handles";
 
 // (Re)build and upload the chunk table for the current chunk_elems.  Synchronous.  If it fails after the
@@ -903,13 +902,23 @@ static int create_impl(novak_handle **out, const novak_hparams *hp, const novak_
         return bail(fail_hip(h, e, "gradient-centralization tables"));
     }
   }
-  // Large lists that run a gradient pre-pass start with 65536-element entries: the pre-pass (one wave per entry) and
-  // the step kernels behind it measured 1.0 - 1.6 % more on the 1.3e9-parameter list, and nothing either way at 1.4e8;
-  // a list of small tensors would lose the pre-pass's parallelism (one fifth of the waves; -27 % at 2.6e7 parameters).
-  if ((clipping(h) || h->n_gc > 0 || auto_only(h)) && h->total_numel >= kLargeList) {
-    int64_t planned = 0;
-    if (novak_plan_chunks(h->numels.data(), n_tensors, kLargeListChunk, nullptr, 0, &planned) == NOVAK_OK && fits_one_launch(planned, kLargeListChunk))
-      h->chunk_elems = kLargeListChunk;
+  // Handles that run a gradient pre-pass (one wave per chunk-table entry, 6 resident per compute unit) start with the
+  // largest entry size of 65536 / 16384 / 4096 elements that still gives the pre-pass four rounds of waves.  Long
+  // entries amortise a wave's start-up (1.3e9 parameters: +1.0 ... 1.6 % of the whole step at 65536 against 16384); a
+  // short list needs the waves more: with centralization its pre-pass waves are latency-bound row reductions, and one
+  // round of them took 80 us where four rounds of a quarter the size take 27 (2.6e7 parameters: +32 % at 4096).
+  if (clipping(h) || h->n_gc > 0 || auto_only(h)) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device_id) != hipSuccess || cus < 1) cus = 256;
+    const int64_t rounds_of_four = int64_t{4} * 6 * cus;
+    for (const int64_t c : {int64_t{65536}, int64_t{16384}, int64_t{4096}}) {
+      int64_t planned = 0;
+      if (novak_plan_chunks(h->numels.data(), n_tensors, c, nullptr, 0, &planned) != NOVAK_OK || !fits_one_launch(planned, c)) continue;
+      if (planned >= rounds_of_four || c == 4096) {
+        h->chunk_elems = c;
+        break;
+      }
+    }
   }
   rc = build_chunk_table(h);
   if (rc != NOVAK_OK) return bail(rc);

@@ -283,6 +283,30 @@ __device__ __forceinline__ void st(T *p, T x) {
   else *q = x;
 }
 
+// The row means that 4 consecutive elements starting at e0 need, for rows of at least 4 elements (then the 4 lie in at
+// most two rows): both loads are unconditional, so they can be issued together with the step's own loads, before any
+// gradient value has arrived.  (Behind the branches of `centralize` the loads waited for the gradient wherever it has
+// to be converted first: the bfloat16-gradient kernels paid a second memory round trip per wave, 12-14 % of their time.)
+struct RowMeans4 {
+  double first, second;   // mean of the row of element e0, and of the next row if the 4 elements reach into it
+  int split;              // elements k < split belong to the first row
+};
+__device__ __forceinline__ RowMeans4 load_row_means(int64_t e0, const GcInfo &gc) {
+  const int64_t row = row_of(e0, gc.cols, gc.inv_cols);
+  const int64_t left = (row + 1) * gc.cols - e0;          // elements of that row from e0 on (>= 1)
+  const NOVAK_GLOBAL double *means = (const NOVAK_GLOBAL double *)gc.means;
+  RowMeans4 r;
+  r.split = left < 4 ? static_cast<int>(left) : 4;
+  r.first = means[row];
+  r.second = means[row + (left < 4 ? 1 : 0)];
+  return r;
+}
+template <typename V>
+__device__ __forceinline__ void centralize4(V &g, const RowMeans4 &r) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) g[k] = static_cast<float>(static_cast<double>(g[k]) - (k < r.split ? r.first : r.second));
+}
+
 template <typename GradV>
 __device__ __forceinline__ f32x4 grad_to_f32(GradV g);
 template <>
@@ -388,11 +412,17 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
         v[u] = ld<NT>(v4 + j);
         if (load_la) la[u] = ld<NT>(la_src + j);
       }
+      RowMeans4 rm[UN];
+      if (GC && gi.cols >= 4) {
+#pragma unroll
+        for (int u = 0; u < UN; ++u) rm[u] = load_row_means(off + 4 * static_cast<int64_t>(threadIdx.x + u * BLOCK), gi);
+      }
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
         const int j = threadIdx.x + u * BLOCK;
         f32x4 gf = grad_to_f32<GradV>(g[u]);
-        if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(j), gi);
+        if (GC && gi.cols >= 4) centralize4(gf, rm[u]);
+        else if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(j), gi);
         f32x4 mf = mom_to_f32<MomV>(m[u]);
         update_vec<LA, MomS, AB>(th[u], gf, mf, v[u], la[u], c, gs, step, la_rt);
         st<NT>(th4 + j, th[u]);
@@ -407,8 +437,11 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
       f32x4 th = ld<NT>(th4 + i), m = mom_to_f32<MomV>(ld<NT>(m4 + i)), v = ld<NT>(v4 + i), la;
       GradV g = ld<NT>(g4 + i);
       if (reads) la = ld<NT>(la4 + i);
+      RowMeans4 rm;
+      if (GC && gi.cols >= 4) rm = load_row_means(off + 4 * static_cast<int64_t>(i), gi);
       f32x4 gf = grad_to_f32<GradV>(g);
-      if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(i), gi);
+      if (GC && gi.cols >= 4) centralize4(gf, rm);
+      else if (GC && gi.cols) centralize(gf, 4, off + 4 * static_cast<int64_t>(i), gi);
       update_vec<LA, MomS, AB>(th, gf, m, v, la, c, gs, step, la_rt);
       st<NT>(th4 + i, th);
       st<NT>(m4 + i, f32_to_mom<MomV>(m));
@@ -691,11 +724,17 @@ __device__ __forceinline__ void moments_body(const Tables &tb, const Consts &c_a
     const int i = threadIdx.x;
     if (i < nvec) {
       const f32x4 th = ld<NT>(th4 + i);
-      f32x4 g = grad_to_f32<GradV>(ld<NT>(g4 + i));
-      f32x4 m = mom_to_f32<MomV>(ld<NT>(m4 + i)), v = ld<NT>(v4 + i);
+      const GradV g_raw = ld<NT>(g4 + i);
+      const MomV m_raw = ld<NT>(m4 + i);
+      f32x4 v = ld<NT>(v4 + i);
+      RowMeans4 rm;
+      if (gi.cols >= 4) rm = load_row_means(off + 4 * static_cast<int64_t>(i), gi);
+      f32x4 g = grad_to_f32<GradV>(g_raw);
+      f32x4 m = mom_to_f32<MomV>(m_raw);
 #pragma unroll
       for (int k = 0; k < 4; ++k) s_g = __builtin_fmaf(g[k], g[k], s_g);     // norm of the gradient as handed in
-      if (gi.cols) centralize(g, 4, off + 4 * static_cast<int64_t>(i), gi);
+      if (gi.cols >= 4) centralize4(g, rm);
+      else if (gi.cols) centralize(g, 4, off + 4 * static_cast<int64_t>(i), gi);
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         float m_k = m[k], v_k = v[k], m_hat;
