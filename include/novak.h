@@ -363,7 +363,8 @@ int novak_lookahead_sync(novak_handle *h, void *hip_stream);
  *     auto_sync = 1).  layer_adaptation, auto_lr, use_gc (after the fast-path downgrade) return
  *     NOVAK_ERR_NOT_IMPLEMENTED; lookahead with auto_sync = 0 returns NOVAK_ERR_INVALID_ARG.
  *   Limits: n_tensors <= NOVAK_STATIC_MAX_TENSORS and at most NOVAK_STATIC_MAX_CHUNKS chunk-table entries
- *     (sum over tensors of ceil(numel / 16384), i.e. up to 2^28 elements); beyond them NOVAK_ERR_INVALID_ARG.
+ *     (sum over tensors of ceil(numel / 16384), i.e. up to 2^29 elements; with clipping the entry size follows the
+ *     rule of NOVAK_TUNE_CHUNK_ELEMS, the same as a handle's, and may be 65536 or 4096); beyond them NOVAK_ERR_INVALID_ARG.
  *   No state is kept between calls: `step` is not checked against an earlier call, and the lookahead buffers
  *     must have been initialised by the caller (copy of theta) before the first step of the first window.
  *   All calls on one GPU share that GPU's array.  A call writes every entry it later reads, so nothing
@@ -371,7 +372,7 @@ int novak_lookahead_sync(novak_handle *h, void *hip_stream);
  *     run at the same time on one GPU (different streams without an event dependency) race on it.
  *   Errors are reported through the return code and novak_last_error(NULL). */
 #define NOVAK_STATIC_MAX_TENSORS 1024
-#define NOVAK_STATIC_MAX_CHUNKS 16384
+#define NOVAK_STATIC_MAX_CHUNKS 32768
 #define NOVAK_STATIC_SCRATCH_BYTES (2u << 20)
 int novak_step_static(const novak_hparams *hp, const novak_tensor_desc *tensors, int32_t n_tensors, void *const *grads,
                       int32_t grad_dtype, int64_t step, int32_t device_id, void *hip_stream);

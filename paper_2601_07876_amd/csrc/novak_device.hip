@@ -733,6 +733,33 @@ bool fits_one_launch(int64_t n_chunks, int64_t chunk_elems) {
   return n_chunks <= (int64_t{0xffffffffLL} / 64) / (chunk_elems / kMinSub);
 }
 
+// The chunk-table entry size a list starts with.  Without a gradient pre-pass: NOVAK_CHUNK_DEFAULT (the step kernels do
+// not depend on it).  With one (one wave per entry, 6 resident per compute unit): the largest of 65536 / 16384 / 4096
+// elements that still gives the pre-pass four rounds of waves.  Long entries amortise a wave's start-up (1.3e9
+// parameters: +1.0 ... 1.6 % of the whole step at 65536 against 16384); a short list needs the waves more: with
+// centralization its pre-pass waves are chains of latency-bound row reductions, and one round of them took 80 us where
+// four rounds of a quarter the size take 27 (2.6e7 parameters: +32 % at 4096).  `max_chunks` bounds the table (the
+// allocation-free step's static array); the handle path and that step share this function, so the same list is cut
+// the same way by both.
+int64_t initial_chunk_elems(const novak_tensor_desc *tensors, int32_t n_tensors, bool prepass, int32_t device_id, int64_t max_chunks) {
+  if (!prepass) return NOVAK_CHUNK_DEFAULT;
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device_id) != hipSuccess || cus < 1) {
+    (void)hipGetLastError();
+    cus = 256;
+  }
+  const int64_t rounds_of_four = int64_t{4} * 6 * cus;
+  int64_t pick = NOVAK_CHUNK_DEFAULT;
+  for (const int64_t c : {int64_t{65536}, int64_t{16384}, int64_t{4096}}) {
+    int64_t planned = 0;
+    for (int32_t i = 0; i < n_tensors; ++i) planned += (tensors[i].numel + c - 1) / c;
+    if (planned > max_chunks || !fits_one_launch(planned, c)) continue;
+    pick = c;
+    if (planned >= rounds_of_four) break;
+  }
+  return pick;
+}
+
 // Descriptor checks shared by novak_create and the allocation-free step.  On failure writes the reason.
 int check_descs(const novak_hparams &eff, const novak_tensor_desc *tensors, int32_t n_tensors, std::string *why) {
   for (int32_t i = 0; i < n_tensors; ++i) {
@@ -902,24 +929,7 @@ static int create_impl(novak_handle **out, const novak_hparams *hp, const novak_
         return bail(fail_hip(h, e, "gradient-centralization tables"));
     }
   }
-  // Handles that run a gradient pre-pass (one wave per chunk-table entry, 6 resident per compute unit) start with the
-  // largest entry size of 65536 / 16384 / 4096 elements that still gives the pre-pass four rounds of waves.  Long
-  // entries amortise a wave's start-up (1.3e9 parameters: +1.0 ... 1.6 % of the whole step at 65536 against 16384); a
-  // short list needs the waves more: with centralization its pre-pass waves are latency-bound row reductions, and one
-  // round of them took 80 us where four rounds of a quarter the size take 27 (2.6e7 parameters: +32 % at 4096).
-  if (clipping(h) || h->n_gc > 0 || auto_only(h)) {
-    int cus = 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device_id) != hipSuccess || cus < 1) cus = 256;
-    const int64_t rounds_of_four = int64_t{4} * 6 * cus;
-    for (const int64_t c : {int64_t{65536}, int64_t{16384}, int64_t{4096}}) {
-      int64_t planned = 0;
-      if (novak_plan_chunks(h->numels.data(), n_tensors, c, nullptr, 0, &planned) != NOVAK_OK || !fits_one_launch(planned, c)) continue;
-      if (planned >= rounds_of_four || c == 4096) {
-        h->chunk_elems = c;
-        break;
-      }
-    }
-  }
+  h->chunk_elems = initial_chunk_elems(tensors, n_tensors, clipping(h) || h->n_gc > 0 || auto_only(h), device_id, INT64_MAX);
   rc = build_chunk_table(h);
   if (rc != NOVAK_OK) return bail(rc);
   guard.h = nullptr;
@@ -1360,11 +1370,12 @@ static int step_static_impl(const novak_hparams *hp, const novak_tensor_desc *te
   if (rc != NOVAK_OK) return fail(nullptr, rc, why);
   if (step < 1) return fail(nullptr, NOVAK_ERR_BAD_STEP, "step must be >= 1 (Eq. 5 is undefined at t = 0)");
   if (n_tensors > NOVAK_STATIC_MAX_TENSORS) return fail(nullptr, NOVAK_ERR_INVALID_ARG, "more than NOVAK_STATIC_MAX_TENSORS tensors");
+  cx.chunk_elems = initial_chunk_elems(tensors, n_tensors, clipping(&cx), device_id, NOVAK_STATIC_MAX_CHUNKS);
   int64_t n_chunks = 0;
   for (int32_t i = 0; i < n_tensors; ++i) {
-    n_chunks += (tensors[i].numel + NOVAK_CHUNK_DEFAULT - 1) / NOVAK_CHUNK_DEFAULT;
+    n_chunks += (tensors[i].numel + cx.chunk_elems - 1) / cx.chunk_elems;
     if (n_chunks > NOVAK_STATIC_MAX_CHUNKS)
-      return fail(nullptr, NOVAK_ERR_INVALID_ARG, "the list needs more than NOVAK_STATIC_MAX_CHUNKS chunk-table entries (16384 elements each)");
+      return fail(nullptr, NOVAK_ERR_INVALID_ARG, "the list needs more than NOVAK_STATIC_MAX_CHUNKS chunk-table entries");
   }
   StepPlan pl;
   plan_step(cx.hp, step, &pl);
@@ -1401,7 +1412,7 @@ static int step_static_impl(const novak_hparams *hp, const novak_tensor_desc *te
     b.first_tensor = first;
     b.n_tensors = n_tensors;
     b.n_chunks = static_cast<int32_t>(n_chunks);
-    b.chunk_elems = NOVAK_CHUNK_DEFAULT;
+    b.chunk_elems = cx.chunk_elems;
     for (int32_t j = 0; j < b.count; ++j) {
       const novak_tensor_desc &d = tensors[first + j];
       FillTensor &ft = b.t[j];
@@ -1412,7 +1423,7 @@ static int step_static_impl(const novak_hparams *hp, const novak_tensor_desc *te
       ft.grad = grads[first + j];
       ft.numel = d.numel;
       ft.first_chunk = next_chunk;
-      next_chunk += (d.numel + NOVAK_CHUNK_DEFAULT - 1) / NOVAK_CHUNK_DEFAULT;
+      next_chunk += (d.numel + cx.chunk_elems - 1) / cx.chunk_elems;
     }
     hipLaunchKernelGGL(novak_fill_tables_kernel, dim3(static_cast<unsigned>(b.count)), dim3(64), 0, stream, b, cx.d_chunks, d_tensors, d_grad,
                        cx.d_first_chunk);

@@ -28,7 +28,7 @@ NOVAK_WARN_LAYER_ADAPTATION_DISABLED, NOVAK_WARN_AUTO_LR_DISABLED, NOVAK_WARN_GC
 NOVAK_TUNE_CHUNK_ELEMS, NOVAK_TUNE_NONTEMPORAL, NOVAK_TUNE_VEC_PER_LANE, NOVAK_TUNE_THREADS, NOVAK_TUNE_WAVES_PER_CU = 0, 1, 2, 3, 4
 NOVAK_TUNE_PREPASS_WAVES_PER_CU = 5
 
-NOVAK_STATIC_MAX_TENSORS, NOVAK_STATIC_MAX_CHUNKS, NOVAK_STATIC_SCRATCH_BYTES = 1024, 16384, 2 << 20
+NOVAK_STATIC_MAX_TENSORS, NOVAK_STATIC_MAX_CHUNKS, NOVAK_STATIC_SCRATCH_BYTES = 1024, 32768, 2 << 20
 NOVAK_ARENA_TENSOR_ALIGN, NOVAK_ARENA_ROLE_PERIOD, NOVAK_ARENA_ROLE_SKEW = 256, 8192, 2048
 
 NESTEROV = {"none": 0, "approx": 1, "classical": 2, "true": 3}

@@ -121,4 +121,4 @@ def test_limits_and_unsupported_options_are_refused_with_a_reason():
     assert call(ok, [N.novak_tensor_desc(4098, 8192, 12288, 16384, 64)]) == N.NOVAK_ERR_MISALIGNED
     assert call(ok, []) == N.NOVAK_OK and call(ok, [desc(0)]) == N.NOVAK_OK          # nothing to do
     # exactly at the limit the sizes are accepted by the checks (not launched here: the addresses are made up)
-    assert N.NOVAK_STATIC_MAX_CHUNKS * 16384 == 1 << 28
+    assert N.NOVAK_STATIC_MAX_CHUNKS * 16384 == 1 << 29
