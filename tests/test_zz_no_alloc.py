@@ -98,6 +98,19 @@ def test_variants(grad_dtype, moment_dtype, lookahead, k):
     _run_both(rag.numels + [0], hyper, steps=2 * k + 1, grad_dtype=grad_dtype)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_clipped_lists_are_cut_the_same_way_as_by_a_handle(seed):
+    """With clipping the chunk-table entry size depends on the list (short lists get short entries); the handle and
+    this entry point must choose alike, or the chunks' sums of squares add up in another order and the clip factor
+    can differ in its last bit.  Random short lists, bit-identical results."""
+    rng = np.random.default_rng(1000 + seed)
+    sizes = [0, 1, 3, 64, 255, 256, 257, 1023, 4096, 4097, 16383, 16384, 16385, 20000, 70001, 131075]
+    numels = [int(rng.choice(sizes)) if rng.random() < 0.8 else int(rng.integers(1, 40000)) for _ in range(int(rng.choice([1, 2, 5, 63, 64, 65])))]
+    hyper = dict(W.get_workload("ragged").hyper, mode="research", clip_threshold=0.3, nesterov=["none", "approx", "classical"][seed % 3],
+                 lookahead=["none", "memory_efficient", "basic"][(seed // 3) % 3], la_k=3, moment_dtype=["f32", "bf16_m"][seed % 2])
+    _run_both(numels, hyper, steps=4, grad_dtype=["f32", "bf16"][(seed // 2) % 2], seed=seed)
+
+
 def test_limits_and_unsupported_options_are_refused_with_a_reason():
     """Nothing is dereferenced before these checks, so made-up addresses do."""
     def desc(n):
