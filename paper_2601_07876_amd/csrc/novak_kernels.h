@@ -359,16 +359,11 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
   const void *const g_base = tb.grad[ch.tensor];
   // Device-step mode (DEV): constants and lookahead phase come from device memory; their scalar load is issued
   // here, together with the two table loads above, so that the wave waits once for all three.
-  Consts c_dev;
-  int la_rt = LA_OFF;
-  if constexpr (DEV) {
-    const DeviceStep d = *ds;
-    c_dev = d.c;
-    la_rt = d.la;
-    device_step_done(d);
-  }
-  const Consts &c = DEV ? c_dev : c_arg;
+  DeviceStep d;
+  if constexpr (DEV) d = *ds;
+  const Consts &c = DEV ? d.c : c_arg;
   // which lookahead stream this step reads / writes: compiled in, or a wave-uniform run-time value
+  const int la_rt = DEV ? d.la : LA_OFF;
   const int phase = la_runtime(LA) ? la_rt : LA;
   const bool reads = la_reads(phase), writes = la_writes(phase);
   const float gs = (c.flags & F_CLIP) ? *tb.gscale : 1.0f;
@@ -376,6 +371,10 @@ __device__ __forceinline__ void step_body(const Tables &tb, const Consts &c_arg,
   GcInfo gi;
   gi.cols = 0;
   if (GC) gi = tb.gc[ch.tensor];
+  // The counter's store comes after every wave-uniform load: behind a store that may alias them the compiler reads
+  // such values with vector loads and waits for them together with the step's own loads (the centralizing device-step
+  // kernels then issued the row-mean loads a memory round trip late: -7 ... -9 %).
+  if constexpr (DEV) device_step_done(d);
   float *__restrict__ th_p = tp.param + off;
   MomS *__restrict__ m_p = reinterpret_cast<MomS *>(tp.m) + off;
   float *__restrict__ v_p = tp.v + off;
@@ -1169,18 +1168,14 @@ __device__ __forceinline__ void apply_body(const Tables &tb, const Consts &c_arg
   const int n = min(kScaledSub, ch.len - start);
   const int64_t off = ch.offset + start;
   const TensorPtrs tp = tb.tensors[ch.tensor];
-  Consts c_dev;
-  int la_rt = LA_OFF;
-  if constexpr (DEV) {
-    const DeviceStep d = *ds;
-    c_dev = d.c;
-    la_rt = d.la;
-    device_step_done(d);
-  }
-  const Consts &c = DEV ? c_dev : c_arg;
+  DeviceStep d;
+  if constexpr (DEV) d = *ds;
+  const Consts &c = DEV ? d.c : c_arg;
+  const int la_rt = DEV ? d.la : LA_OFF;
   const int phase = la_runtime(LA) ? la_rt : LA;
   const bool reads = la_reads(phase), writes = la_writes(phase);
   const float step = c.step_size * scale[ch.tensor];                    // Eq. 24a
+  if constexpr (DEV) device_step_done(d);      // (after the wave-uniform loads: see step_body)
   float *__restrict__ th_p = tp.param + off;
   const MomS *__restrict__ m_p = reinterpret_cast<const MomS *>(tp.m) + off;
   const float *__restrict__ v_p = tp.v + off;
