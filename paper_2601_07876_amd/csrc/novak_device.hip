@@ -307,8 +307,8 @@ Geometry geometry_of(const LaunchCtx *h, int sub_elems, int threads, int wide, i
     const double per_wave = static_cast<double>(wide > 0 ? wide : 1) * h->vec_per_lane;
     waves = static_cast<int>(budget / per_wave + 0.5);
     // with a narrow array in the mix there is no gain beyond these (the two kernels of the two-pass step with a
-    // bfloat16 m plateau at 22 - 28 waves, the single-pass kernels at 14 - 16)
-    const int cap = budget == kTwoPassBudget ? 24 : (budget > kStepBudget ? 16 : 14);
+    // bfloat16 m plateau at 22 - 28 waves; the single-pass kernels at 14 with five wide arrays, at 16 - 18 with four)
+    const int cap = budget == kTwoPassBudget ? 24 : ((budget > kStepBudget || wide <= 4) ? 16 : 14);
     if (narrow > 0 && waves > cap) waves = cap;
   }
   const int waves_per_wg = threads / 64;
