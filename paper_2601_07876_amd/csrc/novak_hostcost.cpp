@@ -1,6 +1,6 @@
 // novak_hostcost: how long the library itself keeps the host busy per novak_step, without Python in the way.
 //
-//   novak_hostcost NUMELS_FILE [STEPS [GRAPH_STEPS]]
+//   novak_hostcost NUMELS_FILE [STEPS [GRAPH_STEPS [WAVES_PER_CU]]]
 //
 // NUMELS_FILE lists one tensor size per line (the shape lists of the benchmark workloads can be written with
 // `python -c "import workloads as W; print(*W.get_workload('c2_resnet50').numels, sep='\n')"`).  The tensors
@@ -13,6 +13,7 @@
 // With GRAPH_STEPS > 0 (a multiple of 5 that divides STEPS) the handle runs in device-step mode (step count in
 // device memory) on a stream of its own: the same two figures for the eager loop, then GRAPH_STEPS steps are
 // captured once into a HIP graph and replayed STEPS / GRAPH_STEPS times: graph_us_per_step.
+// WAVES_PER_CU > 0 overrides the residency cap of the step kernels (NOVAK_TUNE_WAVES_PER_CU).
 #include <hip/hip_runtime_api.h>
 
 #include <chrono>
@@ -42,11 +43,12 @@
 
 int main(int argc, char **argv) {
   if (argc < 2) {
-    std::fprintf(stderr, "usage: %s NUMELS_FILE [STEPS [GRAPH_STEPS]]\n", argv[0]);
+    std::fprintf(stderr, "usage: %s NUMELS_FILE [STEPS [GRAPH_STEPS [WAVES_PER_CU]]]\n", argv[0]);
     return 2;
   }
   const int steps = argc > 2 ? std::atoi(argv[2]) : 2000;
   const int graph_steps = argc > 3 ? std::atoi(argv[3]) : 0;
+  const int waves_per_cu = argc > 4 ? std::atoi(argv[4]) : 0;
   if (graph_steps < 0 || (graph_steps > 0 && (graph_steps % 5 != 0 || steps % graph_steps != 0))) {
     std::fprintf(stderr, "GRAPH_STEPS must be a multiple of the lookahead window (5) that divides STEPS\n");
     return 2;
@@ -90,6 +92,7 @@ int main(int argc, char **argv) {
     total += numels[static_cast<size_t>(i)];
   }
   NK(novak_create(&h, &hp, descs.data(), n, 0));
+  if (waves_per_cu > 0) NK(novak_set_tuning(h, NOVAK_TUNE_WAVES_PER_CU, waves_per_cu));
   hipStream_t stream = nullptr;                 // the legacy default stream cannot be captured
   int64_t *counter = nullptr;
   if (graph_steps > 0) {
